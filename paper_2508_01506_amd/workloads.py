@@ -1,0 +1,219 @@
+"""Seeded synthetic workloads for the factored transformer layer.
+
+This module only draws numbers and shapes them into the inputs of one layer
+(activations X, rank-r factor pairs (U, V, b), LayerNorm parameters, key
+lengths).  It contains none of the layer's arithmetic: no projection,
+attention, activation or normalisation is evaluated here, so both the CPU
+oracle's tests and the GPU path can consume exactly the same arrays.
+
+Every array is generated in float64, cast to float32 and then rounded ONCE to
+the 16-bit storage type of the workload (fp16 or bf16), so that the values a
+GPU kernel reads from its 16-bit buffers and the values the oracle reads from
+the float arrays are identical real numbers.
+
+Factor format (Methodology, "Optimal Low-Rank Factorization via SVD"): a dense
+projection W [in, out] is stored as U [in, r] and V [r, out] with the singular
+values split evenly, U = A_r diag(sigma)^1/2, V = diag(sigma)^1/2 B_r^T, plus a
+dense bias b [out].
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field, replace
+from typing import Dict, Optional
+
+import numpy as np
+
+__all__ = ["Workload", "WORKLOADS", "get_workload", "make_inputs", "round_to_storage",
+           "to_storage_bits", "spectrum_factors"]
+
+
+@dataclass(frozen=True)
+class Workload:
+    """Shape and recipe of one synthetic layer."""
+    name: str
+    B: int
+    M: int
+    D: int
+    H: int
+    F: int
+    r_attn: int                 # rank of the four attention projections
+    r_ffn: int                  # rank of the two FFN projections
+    dtype: str                  # storage type of X and of every parameter: "fp16" | "bf16"
+    mask: str = "none"          # "none" | "padding" | "causal"
+    norm: str = "post_ln"       # "post_ln" | "pre_ln" | "none"
+    factors: str = "gaussian"   # "gaussian" | "spectrum" | "spectrum_unit"
+    min_len: int = 0            # padding mask: key_len ~ integers U[min_len, M]
+    seed: int = 1506
+    ln_eps: float = 1e-5
+
+    @property
+    def T(self) -> int:
+        return self.B * self.M
+
+    @property
+    def d_h(self) -> int:
+        return self.D // self.H
+
+
+def _wl(index: int, sub: int = 0, **kw) -> Workload:
+    return Workload(seed=1506 + 1000 * index + sub, **kw)
+
+
+# The five benchmark configurations plus small shapes used by the tests.
+WORKLOADS: Dict[str, Workload] = {}
+
+
+def _register(w: Workload) -> None:
+    WORKLOADS[w.name] = w
+
+
+_register(_wl(1, name="cfg1_bert_base_b2_m128", B=2, M=128, D=768, H=12, F=3072,
+              r_attn=192, r_ffn=384, dtype="fp16"))
+_register(_wl(2, name="cfg2_bert_base_b16_m512_pad", B=16, M=512, D=768, H=12, F=3072,
+              r_attn=384, r_ffn=768, dtype="fp16", mask="padding", min_len=256,
+              factors="spectrum"))
+_register(_wl(2, 1, name="cfg2u_bert_base_b16_m512_pad_unit", B=16, M=512, D=768, H=12, F=3072,
+              r_attn=384, r_ffn=768, dtype="fp16", mask="padding", min_len=256,
+              factors="spectrum_unit"))
+for _i, _r in enumerate((128, 256, 512)):
+    _register(_wl(3, _i, name=f"cfg3_bert_large_b32_m512_r{_r}", B=32, M=512, D=1024, H=16,
+                  F=4096, r_attn=_r, r_ffn=_r, dtype="bf16"))
+_register(_wl(4, name="cfg4_long_b4_m8192", B=4, M=8192, D=768, H=12, F=3072,
+              r_attn=256, r_ffn=512, dtype="fp16"))
+_register(_wl(5, name="cfg5_llm_b1_m4096_causal", B=1, M=4096, D=4096, H=32, F=16384,
+              r_attn=1024, r_ffn=2048, dtype="bf16", mask="causal", norm="pre_ln"))
+
+# Small shapes: a few tiles plus ragged tails, cheap for the oracle.
+_register(_wl(7, name="tiny_h2_d64", B=2, M=80, D=128, H=2, F=256, r_attn=48, r_ffn=80,
+              dtype="fp16"))
+_register(_wl(7, 1, name="tiny_pad", B=3, M=200, D=128, H=2, F=384, r_attn=64, r_ffn=96,
+              dtype="fp16", mask="padding", min_len=1))
+_register(_wl(7, 2, name="tiny_causal_d128", B=2, M=333, D=256, H=2, F=512, r_attn=80,
+              r_ffn=144, dtype="bf16", mask="causal", norm="pre_ln"))
+_register(_wl(7, 3, name="small_multi_qblock", B=2, M=1100, D=192, H=3, F=768, r_attn=96,
+              r_ffn=208, dtype="fp16", mask="padding", min_len=300))
+_register(_wl(7, 4, name="small_causal_d64", B=1, M=700, D=256, H=4, F=1024, r_attn=112,
+              r_ffn=272, dtype="bf16", mask="causal", norm="none"))
+
+
+def get_workload(name: str, **overrides) -> Workload:
+    w = WORKLOADS[name]
+    return replace(w, **overrides) if overrides else w
+
+
+# ---------------------------------------------------------------------------
+# rounding to the 16-bit storage types
+# ---------------------------------------------------------------------------
+
+def _bf16_bits(x32: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even float32 -> bfloat16, returned as uint16 bit patterns."""
+    u = np.ascontiguousarray(x32, dtype=np.float32).view(np.uint32)
+    rounded = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+    return (rounded >> np.uint32(16)).astype(np.uint16)
+
+
+def to_storage_bits(x: np.ndarray, dtype: str) -> np.ndarray:
+    """16-bit patterns (uint16 array) of ``x`` in storage type ``dtype``."""
+    x32 = np.asarray(x, dtype=np.float32)
+    if dtype == "fp16":
+        return x32.astype(np.float16).view(np.uint16)
+    if dtype == "bf16":
+        return _bf16_bits(x32)
+    raise ValueError(f"unknown storage dtype {dtype!r}")
+
+
+def round_to_storage(x: np.ndarray, dtype: str) -> np.ndarray:
+    """``x`` rounded once to ``dtype`` and returned as float32 (exactly representable)."""
+    x32 = np.asarray(x, dtype=np.float32)
+    if dtype == "fp16":
+        return x32.astype(np.float16).astype(np.float32)
+    if dtype == "bf16":
+        bits = _bf16_bits(x32).astype(np.uint32) << np.uint32(16)
+        return bits.view(np.float32).reshape(x32.shape)
+    if dtype == "fp32":
+        return x32
+    raise ValueError(f"unknown storage dtype {dtype!r}")
+
+
+# ---------------------------------------------------------------------------
+# factor generators
+# ---------------------------------------------------------------------------
+
+def _orthonormal(rng: np.random.Generator, rows: int, cols: int) -> np.ndarray:
+    """Seeded matrix with orthonormal columns (QR of a Gaussian, signs fixed)."""
+    q, r = np.linalg.qr(rng.standard_normal((rows, cols)))
+    return q * np.sign(np.diag(r))[None, :]
+
+
+def spectrum_factors(rng: np.random.Generator, n_in: int, n_out: int, rank: int,
+                     unit: bool):
+    """Rank-``rank`` truncation of W = A diag(sigma) B^T with sigma_i = c * i^-1/2.
+
+    A [n_in, n], B [n_out, n] have orthonormal columns (n = min(n_in, n_out)),
+    so the construction *is* the SVD of W and the best rank-r factors are known
+    without calling an SVD routine.  ``unit`` chooses c so that X W has unit
+    variance per element for X ~ N(0, 1) (c^2 = n_out / sum_i 1/i); otherwise c = 1.
+    Returns (U, V, sigma) in float64, with sigma the full spectrum.
+    """
+    n = min(n_in, n_out)
+    a = _orthonormal(rng, n_in, n)
+    b = _orthonormal(rng, n_out, n)
+    sigma = np.arange(1, n + 1, dtype=np.float64) ** -0.5
+    if unit:
+        sigma = sigma * np.sqrt(n_out / np.sum(1.0 / np.arange(1, n + 1)))
+    root = np.sqrt(sigma[:rank])
+    u = a[:, :rank] * root[None, :]
+    v = root[:, None] * b[:, :rank].T
+    return u, v, sigma
+
+
+def _gaussian_factors(rng: np.random.Generator, n_in: int, n_out: int, rank: int):
+    """U ~ N(0, 1/n_in), V ~ N(0, 1/rank): variance 1/fan_in of each factor."""
+    u = rng.standard_normal((n_in, rank)) / np.sqrt(n_in)
+    v = rng.standard_normal((rank, n_out)) / np.sqrt(rank)
+    return u, v
+
+
+def make_inputs(w: Workload) -> dict:
+    """Draw every input of one layer for workload ``w``.
+
+    Draw order: X; (U, V, b) for q, k, v, o; ln1 gamma, beta; (U, V, b) for
+    w1, w2; ln2 gamma, beta; key_len.  Returns float32 arrays already rounded
+    to ``w.dtype`` (key_len: int32 or None) and, for spectrum workloads, the
+    float64 spectra under ``"sigma"``.
+    """
+    rng = np.random.Generator(np.random.PCG64(w.seed))
+    st = w.dtype
+    out: dict = {"workload": w}
+    out["X"] = round_to_storage(rng.standard_normal((w.B, w.M, w.D)), st)
+
+    sigma = {}
+
+    def factor(name: str, n_in: int, n_out: int, rank: int):
+        if w.factors == "gaussian":
+            u, v = _gaussian_factors(rng, n_in, n_out, rank)
+        else:
+            u, v, s = spectrum_factors(rng, n_in, n_out, rank, unit=(w.factors == "spectrum_unit"))
+            sigma[name] = s
+        b = 0.02 * rng.standard_normal(n_out)
+        out[name] = {"U": round_to_storage(u, st), "V": round_to_storage(v, st),
+                     "b": round_to_storage(b, st)}
+
+    def ln(name: str):
+        out[name + "_gamma"] = round_to_storage(1.0 + 0.02 * rng.standard_normal(w.D), st)
+        out[name + "_beta"] = round_to_storage(0.02 * rng.standard_normal(w.D), st)
+
+    for a in ("q", "k", "v", "o"):
+        factor(a, w.D, w.D, w.r_attn)
+    ln("ln1")
+    factor("w1", w.D, w.F, w.r_ffn)
+    factor("w2", w.F, w.D, w.r_ffn)
+    ln("ln2")
+    if w.mask == "padding":
+        out["key_len"] = rng.integers(max(w.min_len, 1), w.M + 1, size=w.B).astype(np.int32)
+    else:
+        out["key_len"] = None
+    out["causal"] = (w.mask == "causal")
+    if sigma:
+        out["sigma"] = sigma
+    return out

@@ -1,0 +1,367 @@
+"""Pins of the CPU oracle against things other than itself (no GPU needed).
+
+Each test fixes the oracle to a closed form, a library routine used in a
+different formulation, a brute-force evaluation with python loops, or a value
+printed in the paper, so that a dropped term, a wrong sign or index or a
+transposed operand in the oracle fails at least one of them.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as TF
+
+from oracle import fsvd_oracle as O
+from paper_2508_01506_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def full_rank_factors(rng, n_in, n_out, bias=True):
+    """Dense W with its exact full-rank factorisation U = A S^1/2, V = S^1/2 B^T."""
+    Wd = rng.standard_normal((n_in, n_out)) / np.sqrt(n_in)
+    a, s, bt = np.linalg.svd(Wd, full_matrices=False)
+    fac = {"U": a * np.sqrt(s)[None, :], "V": np.sqrt(s)[:, None] * bt,
+           "b": 0.1 * rng.standard_normal(n_out) if bias else None}
+    return Wd, fac
+
+
+def torch_dense_layer(X, Ws, bs, ln1, ln2, H, norm, causal, key_len, eps):
+    """Dense layer written with torch's library routines (independent of the oracle)."""
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    X = t(X)
+    B, M, D = X.shape
+    d_h = D // H
+
+    def attn(x):
+        q, k, v = (TF.linear(x, t(Ws[n]).T, t(bs[n])).view(B, M, H, d_h).transpose(1, 2)
+                   for n in "qkv")
+        mask = torch.ones(B, 1, M, M, dtype=torch.bool)
+        if causal:
+            mask &= torch.tril(torch.ones(M, M, dtype=torch.bool))
+        if key_len is not None:
+            mask &= (torch.arange(M)[None, :] < torch.as_tensor(key_len)[:, None])[:, None, None, :]
+        c = TF.scaled_dot_product_attention(q, k, v, attn_mask=mask)
+        return TF.linear(c.transpose(1, 2).reshape(B, M, D), t(Ws["o"]).T, t(bs["o"]))
+
+    def ffn(x):
+        return TF.linear(TF.gelu(TF.linear(x, t(Ws["w1"]).T, t(bs["w1"]))), t(Ws["w2"]).T, t(bs["w2"]))
+
+    ln = lambda x, p: TF.layer_norm(x, (D,), t(p[0]), t(p[1]), eps)
+    if norm == "post_ln":
+        y1 = ln(X + attn(X), ln1)
+        return ln(y1 + ffn(y1), ln2).numpy()
+    if norm == "pre_ln":
+        x1 = X + attn(ln(X, ln1))
+        return (x1 + ffn(ln(x1, ln2))).numpy()
+    return ffn(attn(X)).numpy()
+
+
+@pytest.mark.parametrize("norm", ["post_ln", "pre_ln", "none"])
+@pytest.mark.parametrize("mask", ["none", "causal", "padding", "both"])
+def test_full_rank_identity_equals_dense_layer(norm, mask):
+    """U V = W at full rank, so the factored layer equals the dense layer."""
+    rng = np.random.default_rng(11)
+    B, M, D, H, F = 2, 9, 16, 2, 40
+    X = rng.standard_normal((B, M, D))
+    Ws, bs, fac = {}, {}, {}
+    for n, (i, o) in {"q": (D, D), "k": (D, D), "v": (D, D), "o": (D, D), "w1": (D, F), "w2": (F, D)}.items():
+        Ws[n], fac[n] = full_rank_factors(rng, i, o)
+        bs[n] = fac[n]["b"]
+    ln1 = (1 + 0.1 * rng.standard_normal(D), 0.1 * rng.standard_normal(D))
+    ln2 = (1 + 0.1 * rng.standard_normal(D), 0.1 * rng.standard_normal(D))
+    causal = mask in ("causal", "both")
+    key_len = np.array([5, 9]) if mask in ("padding", "both") else None
+    got = O.layer(X, fac["q"], fac["k"], fac["v"], fac["o"], ln1, fac["w1"], fac["w2"], ln2, H,
+                  norm=norm, causal=causal, key_len=key_len, eps=1e-5)
+    ref = torch_dense_layer(X, Ws, bs, ln1, ln2, H, norm, causal, key_len, 1e-5)
+    np.testing.assert_allclose(got, ref, rtol=1e-9, atol=1e-10)
+
+
+def test_eckart_young_truncation_error():
+    """||W - U_r V_r||_F^2 = sum_{i>r} sigma_i^2 and spectral norm sigma_{r+1}."""
+    rng = np.random.default_rng(5)
+    n_in, n_out, r = 48, 80, 17
+    U, V, sigma = W.spectrum_factors(rng, n_in, n_out, n_in, unit=False)
+    W_full = U @ V
+    Ur, Vr, _ = U[:, :r], V[:r], sigma
+    W_r = O.factored_linear(np.eye(n_in), {"U": Ur, "V": Vr, "b": None})
+    np.testing.assert_allclose(np.sum((W_full - W_r) ** 2), np.sum(sigma[r:] ** 2), rtol=1e-10)
+    np.testing.assert_allclose(np.linalg.norm(W_full - W_r, 2), sigma[r], rtol=1e-10)
+    # numpy's own SVD of the full matrix recovers the constructed spectrum i^-1/2
+    np.testing.assert_allclose(np.linalg.svd(W_full, compute_uv=False), sigma, rtol=1e-9)
+    np.testing.assert_allclose(sigma, np.arange(1, n_in + 1) ** -0.5)
+    # statistical form: E||X (W - W_r)||_F^2 = T sum_{i>r} sigma_i^2 for X ~ N(0, 1)
+    T = 4000
+    X = rng.standard_normal((T, n_in))
+    err = X @ W_full - O.factored_linear(X, {"U": Ur, "V": Vr, "b": None})
+    expect = T * np.sum(sigma[r:] ** 2)
+    assert abs(np.sum(err ** 2) / expect - 1) < 0.05
+
+
+def brute_attention(x, q, k, v, o, H, causal, key_len, scale=None):
+    """Attention of one sequence with python loops and math.exp only."""
+    M, D = len(x), len(x[0])
+    d_h = D // H
+
+    def lin(row, fac):
+        r = len(fac["U"][0])
+        p = [sum(row[i] * fac["U"][i][j] for i in range(len(row))) for j in range(r)]
+        n = len(fac["V"][0])
+        return [sum(p[j] * fac["V"][j][c] for j in range(r)) + fac["b"][c] for c in range(n)]
+
+    Q = [lin(x[i], q) for i in range(M)]
+    K = [lin(x[i], k) for i in range(M)]
+    V = [lin(x[i], v) for i in range(M)]
+    sc = (1.0 / math.sqrt(d_h)) if scale is None else scale
+    out = []
+    for i in range(M):
+        ctx = [0.0] * D
+        for h in range(H):
+            cols = range(h * d_h, (h + 1) * d_h)
+            keys = [j for j in range(M) if (key_len is None or j < key_len) and (not causal or j <= i)]
+            s = [sum(Q[i][c] * K[j][c] for c in cols) * sc for j in keys]
+            mx = max(s)
+            e = [math.exp(t - mx) for t in s]
+            z = sum(e)
+            for c in cols:
+                ctx[c] = sum(e[n] / z * V[j][c] for n, j in enumerate(keys))
+        out.append(lin(ctx, o))
+    return out
+
+
+@pytest.mark.parametrize("causal,key_len,scale", [(False, None, None), (True, None, None), (False, 4, None),
+                                                  (True, 3, None), (False, 1, None), (False, None, 0.37)])
+def test_attention_brute_force_tiny(causal, key_len, scale):
+    rng = np.random.default_rng(3)
+    M, D, H, r = 7, 8, 2, 3
+    x = rng.standard_normal((M, D))
+    fac = {n: {"U": rng.standard_normal((D, r)), "V": rng.standard_normal((r, D)),
+               "b": rng.standard_normal(D)} for n in "qkvo"}
+    kl = None if key_len is None else np.array([key_len])
+    got = O.attention(x[None], fac["q"], fac["k"], fac["v"], fac["o"], H, causal, kl, scale)[0]
+    tl = lambda f: {a: f[a].tolist() for a in f}
+    ref = brute_attention(x.tolist(), tl(fac["q"]), tl(fac["k"]), tl(fac["v"]), tl(fac["o"]), H,
+                          causal, key_len, scale)
+    np.testing.assert_allclose(got, np.array(ref), rtol=1e-10, atol=1e-12)
+
+
+def _rand_layer(rng, B, M, D, H, F, r, rf):
+    fac = {}
+    for n, (i, o, rk) in {"q": (D, D, r), "k": (D, D, r), "v": (D, D, r), "o": (D, D, r),
+                          "w1": (D, F, rf), "w2": (F, D, rf)}.items():
+        fac[n] = {"U": rng.standard_normal((i, rk)) / np.sqrt(i), "V": rng.standard_normal((rk, o)) / np.sqrt(rk),
+                  "b": 0.3 * rng.standard_normal(o)}
+    X = rng.standard_normal((B, M, D))
+    return X, fac
+
+
+def test_attention_special_cases():
+    rng = np.random.default_rng(8)
+    D, H, r = 12, 3, 5
+    X, fac = _rand_layer(rng, 2, 6, D, H, 24, r, 4)
+    ident_o = {"U": np.eye(D), "V": np.eye(D), "b": None}
+    # one token: the context is that token's value vector
+    C = O.attention(X[:, :1], fac["q"], fac["k"], fac["v"], ident_o, H)
+    np.testing.assert_allclose(C, O.factored_linear(X[:, :1], fac["v"]), rtol=1e-12)
+    # causal: row 0 sees only key 0
+    C = O.attention(X, fac["q"], fac["k"], fac["v"], ident_o, H, causal=True)
+    np.testing.assert_allclose(C[:, 0], O.factored_linear(X[:, 0], fac["v"]), rtol=1e-12)
+    # all keys equal (zero key factor): uniform weights -> mean of the valid value rows
+    zero_k = {"U": fac["k"]["U"], "V": np.zeros_like(fac["k"]["V"]), "b": fac["k"]["b"]}
+    key_len = np.array([4, 6])
+    C = O.attention(X, fac["q"], zero_k, fac["v"], ident_o, H, key_len=key_len)
+    Vfull = O.factored_linear(X, fac["v"])
+    for b in range(2):
+        mean_v = Vfull[b, :key_len[b]].mean(axis=0)
+        np.testing.assert_allclose(C[b], np.broadcast_to(mean_v, C[b].shape), rtol=1e-12)
+    # causal with equal keys: row i is the running mean of the first i+1 value rows
+    C = O.attention(X, fac["q"], zero_k, fac["v"], ident_o, H, causal=True)
+    run = np.cumsum(Vfull, axis=1) / np.arange(1, 7)[None, :, None]
+    np.testing.assert_allclose(C, run, rtol=1e-12)
+
+
+def test_attention_invariants():
+    rng = np.random.default_rng(9)
+    B, M, D, H, r = 2, 10, 16, 4, 6
+    X, fac = _rand_layer(rng, B, M, D, H, 32, r, 4)
+    args = lambda **kw: (fac["q"], kw.get("k", fac["k"]), kw.get("v", fac["v"]), fac["o"], H)
+    base = O.attention(X, *args())
+    # the key bias shifts every score of a row by the same amount: no effect
+    k2 = dict(fac["k"], b=fac["k"]["b"] + rng.standard_normal(D))
+    np.testing.assert_allclose(O.attention(X, *args(k=k2)), base, rtol=1e-9, atol=1e-12)
+    # the value bias passes straight through the weighted mean, then through U_o V_o
+    db = rng.standard_normal(D)
+    v2 = dict(fac["v"], b=fac["v"]["b"] + db)
+    shift = (db @ fac["o"]["U"]) @ fac["o"]["V"]
+    np.testing.assert_allclose(O.attention(X, *args(v=v2)), base + shift, rtol=1e-9, atol=1e-12)
+    # zero-padding the rank dimension changes nothing (padded rank of LOAD_TILES)
+    pad = lambda f: {"U": np.pad(f["U"], ((0, 0), (0, 5))), "V": np.pad(f["V"], ((0, 5), (0, 0))), "b": f["b"]}
+    np.testing.assert_allclose(O.attention(X, pad(fac["q"]), pad(fac["k"]), pad(fac["v"]), pad(fac["o"]), H),
+                               base, rtol=1e-12)
+    # no mask: permuting the tokens permutes the outputs
+    perm = rng.permutation(M)
+    np.testing.assert_allclose(O.attention(X[:, perm], *args()), base[:, perm], rtol=1e-9, atol=1e-12)
+    # causal: outputs at positions <= i ignore later tokens
+    X2 = X.copy()
+    X2[:, 6:] = rng.standard_normal((B, M - 6, D))
+    c1 = O.attention(X, *args(), causal=True)
+    c2 = O.attention(X2, *args(), causal=True)
+    np.testing.assert_allclose(c1[:, :6], c2[:, :6], rtol=1e-12)
+    assert np.abs(c1[:, 6:] - c2[:, 6:]).max() > 1e-3
+    # padding: keys beyond key_len do not influence any row; query rows there are still computed
+    kl = np.array([4, 7])
+    X3 = X.copy()
+    X3[0, 4:] += 1.0
+    X3[1, 7:] -= 2.0
+    p1 = O.attention(X, *args(), key_len=kl)
+    p3 = O.attention(X3, *args(), key_len=kl)
+    np.testing.assert_allclose(p1[0, :4], p3[0, :4], rtol=1e-12)
+    np.testing.assert_allclose(p1[1, :7], p3[1, :7], rtol=1e-12)
+    assert np.isfinite(p1).all()
+    # heads are independent column blocks: changing V_q columns of head 1 leaves other heads' context alone
+    ident_o = {"U": np.eye(D), "V": np.eye(D), "b": None}
+    q2 = {"U": fac["q"]["U"], "V": fac["q"]["V"].copy(), "b": fac["q"]["b"]}
+    q2["V"][:, 4:8] *= -1.5
+    ca = O.attention(X, fac["q"], fac["k"], fac["v"], ident_o, H)
+    cb = O.attention(X, q2, fac["k"], fac["v"], ident_o, H)
+    np.testing.assert_allclose(np.delete(ca, np.s_[4:8], axis=2), np.delete(cb, np.s_[4:8], axis=2), rtol=1e-12)
+    assert np.abs(ca[..., 4:8] - cb[..., 4:8]).max() > 1e-3
+
+
+def test_softmax_rows():
+    rng = np.random.default_rng(1)
+    s = rng.standard_normal((5, 9)) * 4
+    s[:, 6:] = -np.inf
+    a = O.softmax_rows(s)
+    np.testing.assert_allclose(a.sum(-1), 1.0, rtol=1e-14)
+    assert (a[:, 6:] == 0).all()
+    np.testing.assert_allclose(O.softmax_rows(s + 123.0), a, rtol=1e-12)
+    np.testing.assert_allclose(a[0, :6], [math.exp(v) / sum(math.exp(u) for u in s[0, :6]) for v in s[0, :6]],
+                               rtol=1e-12)
+
+
+def test_gelu_and_activations():
+    xs = np.linspace(-9, 9, 721)
+    ref = np.array([0.5 * x * (1 + math.erf(x / math.sqrt(2))) for x in xs])
+    np.testing.assert_allclose(O.gelu_erf(xs), ref, rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(O.gelu_erf(xs) - O.gelu_erf(-xs), xs, atol=1e-13)
+    assert O.gelu_erf(0.0) == 0.0
+    np.testing.assert_allclose(O.gelu_erf(np.array([12.0, -12.0])), [12.0, 0.0], atol=1e-12)
+    # standard normal CDF values: Phi(1) = 0.841344746..., Phi(-2) = 0.0227501319...
+    np.testing.assert_allclose(O.gelu_erf(1.0), 0.8413447460685429, rtol=1e-13)
+    np.testing.assert_allclose(O.gelu_erf(-2.0), -2 * 0.022750131948179195, rtol=1e-12)
+    assert np.abs(O.gelu_tanh(xs) - O.gelu_erf(xs)).max() < 5e-3
+    np.testing.assert_array_equal(O.activation(xs, "relu"), np.maximum(xs, 0))
+
+
+def test_layer_norm_statistics():
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((6, 32)) * 3 + 1.5
+    eps = 1e-5
+    y = O.layer_norm(x, np.ones(32), np.zeros(32), eps)
+    np.testing.assert_allclose(y.mean(-1), 0, atol=1e-14)
+    var = x.var(-1)
+    np.testing.assert_allclose(y.var(-1), var / (var + eps), rtol=1e-12)
+    g, b = rng.standard_normal(32), rng.standard_normal(32)
+    np.testing.assert_allclose(O.layer_norm(x, g, b, eps), y * g + b, rtol=1e-12)
+    np.testing.assert_allclose(O.layer_norm(x, g, b, eps),
+                               TF.layer_norm(torch.from_numpy(x), (32,), torch.from_numpy(g), torch.from_numpy(b), eps).numpy(),
+                               rtol=1e-10)
+
+
+def test_ffn_rowwise_and_padding():
+    rng = np.random.default_rng(4)
+    X, fac = _rand_layer(rng, 2, 9, 16, 2, 40, 4, 7)
+    full = O.ffn(X, fac["w1"], fac["w2"])
+    idx = [7, 2, 4]
+    np.testing.assert_allclose(O.ffn(X[:, idx], fac["w1"], fac["w2"]), full[:, idx], rtol=1e-12)
+    pad = lambda f: {"U": np.pad(f["U"], ((0, 0), (0, 9))), "V": np.pad(f["V"], ((0, 9), (0, 0))), "b": f["b"]}
+    np.testing.assert_allclose(O.ffn(X, pad(fac["w1"]), pad(fac["w2"])), full, rtol=1e-12)
+    # definition with an explicit dense hidden activation and math.erf
+    Wi = fac["w1"]["U"] @ fac["w1"]["V"]
+    Wo = fac["w2"]["U"] @ fac["w2"]["V"]
+    hid = X[0, 0] @ Wi + fac["w1"]["b"]
+    hid = np.array([0.5 * h * (1 + math.erf(h / math.sqrt(2))) for h in hid])
+    np.testing.assert_allclose(full[0, 0], hid @ Wo + fac["w2"]["b"], rtol=1e-10)
+
+
+@pytest.mark.parametrize("norm", ["post_ln", "pre_ln", "none"])
+@pytest.mark.parametrize("part", ["layer", "attention", "ffn"])
+def test_sampled_rows_equal_full_evaluation(norm, part):
+    """The row-sampled evaluation used at benchmark sizes agrees with the full one."""
+    rng = np.random.default_rng(6)
+    B, M, D, H, F = 2, 12, 16, 2, 24
+    X, fac = _rand_layer(rng, B, M, D, H, F, 5, 6)
+    ln1 = (1 + 0.1 * rng.standard_normal(D), 0.1 * rng.standard_normal(D))
+    ln2 = (1 + 0.1 * rng.standard_normal(D), 0.1 * rng.standard_normal(D))
+    kl = np.array([8, 12])
+    a = (fac["q"], fac["k"], fac["v"], fac["o"])
+    if part == "layer":
+        full = O.layer(X, *a, ln1, fac["w1"], fac["w2"], ln2, H, norm=norm, causal=True, key_len=kl)
+    elif part == "attention":
+        full = O.attention(X, *a, H, True, kl)
+    else:
+        full = O.ffn(X, fac["w1"], fac["w2"])
+    rows = [0, 5, 11]
+    for b in range(B):
+        got = O.layer_rows(X, b, rows, *a, ln1, fac["w1"], fac["w2"], ln2, H, norm=norm, causal=True,
+                           key_len=kl, part=part)
+        np.testing.assert_allclose(got, full[b, rows], rtol=1e-12, atol=1e-13)
+
+
+def test_paper_parameter_counts():
+    """Factor bookkeeping reproduces the parameter counts printed in the attention ablation."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "attention_param_counts.txt")) if l[0] not in "#\n"]
+    for rank, params_k in rows:
+        r = None if rank == "dense" else int(rank)
+        n = O.attention_param_count(768, 12, r, per_head=True, dense_out=True)
+        assert abs(n / 1000.0 - float(params_k)) <= 0.51, (rank, n)
+    # break-even ranks: whole matrix r < D/2, per head r < D/(H+1)
+    assert 2 * 768 * 383 < 768 * 768 < 2 * 768 * 385
+    assert 12 * (768 + 64) * 59 < 768 * 768 < 12 * (768 + 64) * 60
+
+
+def test_transient_memory_closed_forms():
+    """3 B M r for streaming attention, 2 B M r for the FFN; unfused adds 3 B M D (+ B H M^2) and B M F."""
+    B, M, D, H, F, r = 16, 512, 768, 12, 3072, 384
+    assert O.attention_transient_scalars(B, M, D, H, r, True) == 3 * B * M * r
+    assert O.attention_transient_scalars(B, M, D, H, r, False) == 3 * B * M * r + 3 * B * M * D
+    assert O.attention_transient_scalars(B, M, D, H, r, False, True) == 3 * B * M * (r + D) + B * H * M * M
+    assert O.ffn_transient_scalars(B, M, F, r, True) == 2 * B * M * r
+    assert O.ffn_transient_scalars(B, M, F, r, False) == 2 * B * M * r + B * M * F
+    for w in W.WORKLOADS.values():
+        assert O.attention_transient_scalars(w.B, w.M, w.D, w.H, w.r_attn, True) < \
+            O.attention_transient_scalars(w.B, w.M, w.D, w.H, w.r_attn, False)
+
+
+def test_workload_generator_is_seeded_and_exactly_representable():
+    w = W.get_workload("tiny_pad")
+    a, b = W.make_inputs(w), W.make_inputs(w)
+    np.testing.assert_array_equal(a["X"], b["X"])
+    np.testing.assert_array_equal(a["q"]["U"], b["q"]["U"])
+    np.testing.assert_array_equal(a["key_len"], b["key_len"])
+    assert a["key_len"].min() >= 1 and a["key_len"].max() <= w.M
+    np.testing.assert_array_equal(a["X"], a["X"].astype(np.float16).astype(np.float32))
+    wb = W.get_workload("tiny_causal_d128")
+    c = W.make_inputs(wb)
+    bits = c["X"].view(np.uint32)
+    assert (bits & 0xFFFF == 0).all()          # bf16-representable
+    np.testing.assert_array_equal(W.round_to_storage(c["X"], "bf16"), c["X"])
+    np.testing.assert_array_equal(W.to_storage_bits(c["X"], "bf16"), (bits >> 16).astype(np.uint16))
+    tb = torch.from_numpy(np.random.default_rng(0).standard_normal(1000).astype(np.float32))
+    np.testing.assert_array_equal(W.round_to_storage(tb.numpy(), "bf16"), tb.to(torch.bfloat16).float().numpy())
+
+
+def test_spectrum_workload_matches_recipe():
+    w = W.get_workload("cfg2_bert_base_b16_m512_pad", B=1, M=8, min_len=1)
+    inp = W.make_inputs(w)
+    s = inp["sigma"]["q"]
+    np.testing.assert_allclose(s, np.arange(1, 769) ** -0.5)
+    Wq = inp["q"]["U"].astype(np.float64) @ inp["q"]["V"].astype(np.float64)
+    sv = np.linalg.svd(Wq, compute_uv=False)
+    np.testing.assert_allclose(sv[:w.r_attn], s[:w.r_attn], rtol=2e-3)   # fp16 rounding of the factors
+    assert sv[w.r_attn:].max() < 1e-3
+    assert inp["key_len"].min() >= 1
