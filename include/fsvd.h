@@ -1,0 +1,188 @@
+/*
+ * fsvd — rank-aware streaming execution of one SVD-compressed transformer layer
+ * on AMD MI355X (gfx950).  C ABI.
+ *
+ * Every projection matrix W [in, out] of the layer is given as a rank-r factor
+ * pair W ~= U V with U [in, r], V [r, out] and a dense bias b [out]
+ * (Methodology, "Optimal Low-Rank Factorization via SVD": W^[r] = U~ V~^T with
+ * the singular values split evenly into both factors).  The library evaluates
+ * the layer so that the full-width intermediates — the [B*M, D] query, key and
+ * value tensors, the [B, H, M, M] scores and the [B*M, F] FFN hidden
+ * activation — are rebuilt tile by tile on chip and never written to device
+ * memory; only rank-space tensors ([B*M, r]) and model-width block
+ * inputs/outputs ([B*M, D]) pass through the caller's workspace.
+ *
+ * Conventions shared by all entry points
+ *  - Pointers.  Every data pointer (X, factors, biases, LayerNorm parameters,
+ *    key_len, out, workspace) is a DEVICE pointer owned by the caller and only
+ *    borrowed for the duration of the call.  The descriptor and fsvd_factor
+ *    structs themselves are HOST memory.  The library never allocates or frees
+ *    device memory and keeps no state between calls; all scratch is carved
+ *    from `workspace`, which must be 256-byte aligned and at least as large as
+ *    the matching fsvd_*_workspace() value.  The transient activation memory
+ *    of a call is therefore exactly `workspace_bytes`.
+ *  - Layouts.  Row-major, contiguous.  X and out are [B, M, D]; U is
+ *    [in, rank]; V is [rank, out]; bias is [out] (or NULL for no bias).  Head h
+ *    of an attention projection owns output columns [h*d_h, (h+1)*d_h) of V,
+ *    d_h = D / H (Definition "Attention Activation Approximation").
+ *  - Types.  X, U, V, bias, gamma and beta are stored in `io_dtype` (FSVD_F16
+ *    or FSVD_BF16).  All contractions run on the fp16 matrix cores with fp32
+ *    accumulation; bf16 inputs are widened to fp16 on load, which is exact for
+ *    2^-14 <= |x| <= 65504 and loses at most 2^-25 absolute below that.  `out`
+ *    is written in `out_dtype` (FSVD_F16, FSVD_BF16 or FSVD_F32).
+ *  - Streams.  All work is enqueued on `hip_stream` (a hipStream_t passed as
+ *    void*; NULL is the default stream).  No call synchronises the host.
+ *  - Errors.  Arguments are validated before anything is launched; a call
+ *    either enqueues the whole computation and returns FSVD_OK or enqueues
+ *    nothing and returns an error code.  Nothing aborts or throws.  The
+ *    *_workspace() functions return 0 for an invalid descriptor.
+ *  - Limits.  D % H == 0 and d_h in {64, 128}; D, F and every rank are
+ *    multiples of 16 (a rank that is not can be zero-padded by the caller,
+ *    which leaves the result unchanged: Alg. 1 Part I pads the rank the same
+ *    way); B*M < 2^31 / max(D, F); key_len[b] in [1, M].
+ */
+#ifndef FSVD_H
+#define FSVD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FSVD_OK = 0,
+  FSVD_ERR_INVALID_ARG = 1,  /* null pointer, non-positive size, inconsistent factor shapes */
+  FSVD_ERR_UNSUPPORTED = 2,  /* valid request outside the supported limits listed above */
+  FSVD_ERR_WORKSPACE = 3,    /* workspace NULL, misaligned or too small */
+  FSVD_ERR_DEVICE = 4        /* a HIP launch failed; hipGetLastError() has the detail */
+} fsvd_status;
+
+typedef enum { FSVD_F16 = 0, FSVD_BF16 = 1, FSVD_F32 = 2 } fsvd_dtype;
+typedef enum { FSVD_ACT_GELU_ERF = 0, FSVD_ACT_GELU_TANH = 1, FSVD_ACT_RELU = 2 } fsvd_act;
+typedef enum { FSVD_NORM_NONE = 0, FSVD_NORM_POST_LN = 1, FSVD_NORM_PRE_LN = 2 } fsvd_norm;
+
+/* One factored projection W ~= U V (+ bias).  U [in_dim, rank], V [rank, out_dim],
+ * bias [out_dim] or NULL; device pointers in the descriptor's io_dtype. */
+typedef struct {
+  const void *U;
+  const void *V;
+  const void *bias;
+  int32_t in_dim;
+  int32_t rank;
+  int32_t out_dim;
+} fsvd_factor;
+
+/* Problem descriptor (host memory). */
+typedef struct {
+  int32_t B;             /* sequences */
+  int32_t M;             /* tokens per sequence */
+  int32_t D;             /* model width */
+  int32_t H;             /* attention heads, d_h = D / H */
+  int32_t F;             /* FFN hidden width (ignored by fsvd_attention) */
+  fsvd_dtype io_dtype;   /* storage type of X and of all parameters: F16 or BF16 */
+  fsvd_dtype out_dtype;  /* type of `out`: F16, BF16 or F32 */
+  int32_t causal;        /* non-zero: key j is visible to query i only if j <= i */
+  const int32_t *key_len;/* device int32[B] or NULL: keys j >= key_len[b] are masked for every
+                            query of sequence b (all M query rows are still computed) */
+  float softmax_scale;   /* 0 selects 1/sqrt(d_h) (Alg. 1 Part II) */
+  fsvd_act act;          /* FFN non-linearity phi */
+  fsvd_norm norm;        /* residual / LayerNorm wiring of fsvd_layer */
+  float ln_eps;          /* LayerNorm epsilon (biased variance) */
+} fsvd_desc;
+
+/* Workspace sizes in bytes (multiples of 256); 0 if the request is invalid or unsupported.
+ * Pure host functions: they touch no device. */
+size_t fsvd_attention_workspace(const fsvd_desc *desc, int32_t r_q, int32_t r_k, int32_t r_v, int32_t r_o);
+size_t fsvd_ffn_workspace(const fsvd_desc *desc, int32_t r_1, int32_t r_2);
+size_t fsvd_layer_workspace(const fsvd_desc *desc, int32_t r_q, int32_t r_k, int32_t r_v, int32_t r_o,
+                            int32_t r_1, int32_t r_2);
+
+/* Validation only (what the compute entry points run before launching); touches no device.
+ * Useful to check a configuration without a GPU. */
+fsvd_status fsvd_attention_check(const fsvd_desc *desc, const fsvd_factor *q, const fsvd_factor *k,
+                                 const fsvd_factor *v, const fsvd_factor *o);
+fsvd_status fsvd_ffn_check(const fsvd_desc *desc, const fsvd_factor *w1, const fsvd_factor *w2);
+
+/*
+ * Attention block, FlashSVDAttention (Alg. 1; section "FlashSVDAttention"):
+ *   P_a = X U_a for a in {q, k, v}                       (rank space, workspace)
+ *   per (sequence, head, query block): rebuild Q = P_q V_q[:, head] + b_q on chip; for every
+ *   key block rebuild K and V the same way, scores = Q K^T * softmax_scale, masks,
+ *   streaming softmax, context += alpha V                (Alg. 1 Part I + II)
+ *   out = (context U_o) V_o + b_o                        (output projection in factored form)
+ * X [B, M, D] -> out [B, M, D].  q, k, v, o: in_dim = out_dim = D, ranks free.
+ */
+fsvd_status fsvd_attention(const fsvd_desc *desc, const void *X, const fsvd_factor *q, const fsvd_factor *k,
+                           const fsvd_factor *v, const fsvd_factor *o, void *out, void *workspace,
+                           size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Feed-forward block, FlashSVDFFN V1 (Alg. 2; section "FlashSVDFFN V1"):
+ *   P = X U_1                                            (rank space, workspace)
+ *   per row block, streaming over F: Y = phi(P V_1[:, chunk] + b_1[chunk]) on chip,
+ *   Z += Y U_2[chunk, :]                                 (rank space, workspace)
+ *   out = Z V_2 + b_2
+ * X [B, M, D] -> out [B, M, D].  w1: D -> F, w2: F -> D.
+ */
+fsvd_status fsvd_ffn(const fsvd_desc *desc, const void *X, const fsvd_factor *w1, const fsvd_factor *w2,
+                     void *out, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * One transformer layer built from the two blocks above.  The residual / LayerNorm wiring is
+ * not part of the paper's method (it only notes that these ops remain once the blocks are fused,
+ * section "FlashSVDFFN V2"); desc->norm selects
+ *   POST_LN: Y1 = LN1(X + Attn(X));      out = LN2(Y1 + FFN(Y1))
+ *   PRE_LN : X1 = X + Attn(LN1(X));      out = X1 + FFN(LN2(X1))
+ *   NONE   : out = FFN(Attn(X))          (ln*_gamma / ln*_beta may be NULL)
+ * LN(x) = gamma (x - mean) / sqrt(var + ln_eps) + beta per token, biased variance, fp32 statistics.
+ */
+fsvd_status fsvd_layer(const fsvd_desc *desc, const void *X, const fsvd_factor *q, const fsvd_factor *k,
+                       const fsvd_factor *v, const fsvd_factor *o, const void *ln1_gamma, const void *ln1_beta,
+                       const fsvd_factor *w1, const fsvd_factor *w2, const void *ln2_gamma, const void *ln2_beta,
+                       void *out, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+
+/* ------------------------------------------------------------------------------------------
+ * Building blocks.  The three entry points above are sequences of these steps; they are exported
+ * so that each kernel can be checked and timed on its own.  Same pointer, stream and error
+ * conventions; tensors are contiguous (row stride = number of columns); none needs a workspace.
+ * ------------------------------------------------------------------------------------------ */
+
+/* C[T, N] = A[T, K] W[K, N] (+ bias[N]) (+ residual[T, N]): the rank projection P = X U, the
+ * up-projections (.) V + b and the factored output projection are all this (Alg. 2 "GEMM 1st" and
+ * "GEMM 2nd"; FlashSVDAttention text, P_a = X U_a).  a_dtype: F16, BF16 or F32; w_dtype (W and bias):
+ * F16 or BF16; residual may be NULL, else it is read in r_dtype; C is written in c_dtype.
+ * K and N must be multiples of 16. */
+fsvd_status fsvd_linear(int32_t T, int32_t K, int32_t N, const void *A, fsvd_dtype a_dtype, const void *W,
+                        const void *bias, fsvd_dtype w_dtype, const void *residual, fsvd_dtype r_dtype,
+                        void *C, fsvd_dtype c_dtype, void *hip_stream);
+
+/* Alg. 1 Part II on rank-space inputs: Pq [B*M, q->rank], Pk, Pv (fp16) and the V / bias members of
+ * q, k, v (their U members are ignored) -> context [B*M, D] (fp16, heads concatenated). */
+fsvd_status fsvd_attention_core(const fsvd_desc *desc, const void *Pq, const void *Pk, const void *Pv,
+                                const fsvd_factor *q, const fsvd_factor *k, const fsvd_factor *v,
+                                void *context, void *hip_stream);
+
+/* The on-chip loops of Alg. 2: P1 [B*M, w1->rank] (fp16), V / bias of w1 and U of w2 -> Z [B*M, w2->rank]
+ * (fp16) with Z = phi(P1 V_1 + b_1) U_2. */
+fsvd_status fsvd_ffn_core(const fsvd_desc *desc, const void *P1, const fsvd_factor *w1, const fsvd_factor *w2,
+                          void *Z, void *hip_stream);
+
+/* Y[T, D] = gamma (X - mean) / sqrt(var + eps) + beta per row; X in x_dtype, gamma / beta in p_dtype,
+ * Y in y_dtype (any of F16, BF16, F32).  D <= 8192. */
+fsvd_status fsvd_layernorm(int32_t T, int32_t D, const void *X, fsvd_dtype x_dtype, const void *gamma,
+                           const void *beta, fsvd_dtype p_dtype, float eps, void *Y, fsvd_dtype y_dtype,
+                           void *hip_stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char *fsvd_status_string(fsvd_status status);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int32_t fsvd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FSVD_H */

@@ -1,0 +1,258 @@
+"""ctypes binding of libfsvd.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (include/fsvd.h)
+and does nothing but turn torch tensors into device pointers, allocate the
+output and the workspace with torch (device memory plumbing) and check the
+returned status.  All arithmetic happens in the library's HIP kernels; there is
+no fallback: if the shared library is missing the import of the native handle
+raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfsvd.so")
+
+FSVD_F16, FSVD_BF16, FSVD_F32 = 0, 1, 2
+ACT = {"gelu_erf": 0, "gelu_tanh": 1, "relu": 2}
+NORM = {"none": 0, "post_ln": 1, "pre_ln": 2}
+STATUS = {0: "FSVD_OK", 1: "FSVD_ERR_INVALID_ARG", 2: "FSVD_ERR_UNSUPPORTED", 3: "FSVD_ERR_WORKSPACE",
+          4: "FSVD_ERR_DEVICE"}
+_TORCH2FSVD = {torch.float16: FSVD_F16, torch.bfloat16: FSVD_BF16, torch.float32: FSVD_F32}
+
+EXPORTS = ["fsvd_attention_workspace", "fsvd_ffn_workspace", "fsvd_layer_workspace", "fsvd_attention_check",
+           "fsvd_ffn_check", "fsvd_attention", "fsvd_ffn", "fsvd_layer", "fsvd_linear", "fsvd_attention_core",
+           "fsvd_ffn_core", "fsvd_layernorm", "fsvd_status_string", "fsvd_version"]
+
+
+class FsvdError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {STATUS.get(status, status)}")
+
+
+class fsvd_factor(C.Structure):
+    _fields_ = [("U", C.c_void_p), ("V", C.c_void_p), ("bias", C.c_void_p),
+                ("in_dim", C.c_int32), ("rank", C.c_int32), ("out_dim", C.c_int32)]
+
+
+class fsvd_desc(C.Structure):
+    _fields_ = [("B", C.c_int32), ("M", C.c_int32), ("D", C.c_int32), ("H", C.c_int32), ("F", C.c_int32),
+                ("io_dtype", C.c_int), ("out_dtype", C.c_int), ("causal", C.c_int32), ("key_len", C.c_void_p),
+                ("softmax_scale", C.c_float), ("act", C.c_int), ("norm", C.c_int), ("ln_eps", C.c_float)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -m paper_2508_01506_amd.build` "
+                                    "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        P, F, D = C.c_void_p, C.POINTER(fsvd_factor), C.POINTER(fsvd_desc)
+        i32, sz = C.c_int32, C.c_size_t
+        L.fsvd_attention_workspace.restype = sz
+        L.fsvd_attention_workspace.argtypes = [D, i32, i32, i32, i32]
+        L.fsvd_ffn_workspace.restype = sz
+        L.fsvd_ffn_workspace.argtypes = [D, i32, i32]
+        L.fsvd_layer_workspace.restype = sz
+        L.fsvd_layer_workspace.argtypes = [D, i32, i32, i32, i32, i32, i32]
+        L.fsvd_attention_check.restype = C.c_int
+        L.fsvd_attention_check.argtypes = [D, F, F, F, F]
+        L.fsvd_ffn_check.restype = C.c_int
+        L.fsvd_ffn_check.argtypes = [D, F, F]
+        L.fsvd_attention.restype = C.c_int
+        L.fsvd_attention.argtypes = [D, P, F, F, F, F, P, P, sz, P]
+        L.fsvd_ffn.restype = C.c_int
+        L.fsvd_ffn.argtypes = [D, P, F, F, P, P, sz, P]
+        L.fsvd_layer.restype = C.c_int
+        L.fsvd_layer.argtypes = [D, P, F, F, F, F, P, P, F, F, P, P, P, P, sz, P]
+        L.fsvd_linear.restype = C.c_int
+        L.fsvd_linear.argtypes = [i32, i32, i32, P, C.c_int, P, P, C.c_int, P, C.c_int, P, C.c_int, P]
+        L.fsvd_attention_core.restype = C.c_int
+        L.fsvd_attention_core.argtypes = [D, P, P, P, F, F, F, P, P]
+        L.fsvd_ffn_core.restype = C.c_int
+        L.fsvd_ffn_core.argtypes = [D, P, F, F, P, P]
+        L.fsvd_layernorm.restype = C.c_int
+        L.fsvd_layernorm.argtypes = [i32, i32, P, C.c_int, P, P, C.c_int, C.c_float, P, C.c_int, P]
+        L.fsvd_status_string.restype = C.c_char_p
+        L.fsvd_status_string.argtypes = [C.c_int]
+        L.fsvd_version.restype = i32
+        L.fsvd_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+# ---------------------------------------------------------------------------------------------
+# marshalling helpers
+# ---------------------------------------------------------------------------------------------
+
+@dataclass
+class Factor:
+    """Device tensors of one factored projection (U [in, r], V [r, out], b [out] or None)."""
+    U: torch.Tensor
+    V: torch.Tensor
+    b: Optional[torch.Tensor] = None
+
+    def c(self) -> fsvd_factor:
+        for t in (self.U, self.V, self.b):
+            assert t is None or (t.is_contiguous() and t.is_cuda)
+        return fsvd_factor(self.U.data_ptr(), self.V.data_ptr(), 0 if self.b is None else self.b.data_ptr(),
+                           self.U.shape[0], self.U.shape[1], self.V.shape[1])
+
+    @property
+    def rank(self) -> int:
+        return self.U.shape[1]
+
+
+def _ptr(t: Optional[torch.Tensor]) -> int:
+    if t is None:
+        return 0
+    assert t.is_cuda and t.is_contiguous()
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def make_desc(B, M, D, H, F, io_dtype, out_dtype=torch.float32, causal=False, key_len=None, softmax_scale=0.0,
+              act="gelu_erf", norm="post_ln", ln_eps=1e-5) -> fsvd_desc:
+    if key_len is not None:
+        assert key_len.dtype == torch.int32 and key_len.is_cuda and key_len.is_contiguous()
+    return fsvd_desc(B, M, D, H, F, _TORCH2FSVD[io_dtype], _TORCH2FSVD[out_dtype], int(bool(causal)),
+                     _ptr(key_len), float(softmax_scale), ACT[act], NORM[norm], float(ln_eps))
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise FsvdError(status, where)
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    if nbytes == 0:
+        raise FsvdError(2, "workspace size query rejected the configuration")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def _out_dtype(desc: fsvd_desc):
+    return {FSVD_F16: torch.float16, FSVD_BF16: torch.bfloat16, FSVD_F32: torch.float32}[desc.out_dtype]
+
+
+# ---------------------------------------------------------------------------------------------
+# entry points (same names as the C ABI)
+# ---------------------------------------------------------------------------------------------
+
+def fsvd_attention_workspace(desc, r_q, r_k, r_v, r_o) -> int:
+    return lib().fsvd_attention_workspace(C.byref(desc), r_q, r_k, r_v, r_o)
+
+
+def fsvd_ffn_workspace(desc, r_1, r_2) -> int:
+    return lib().fsvd_ffn_workspace(C.byref(desc), r_1, r_2)
+
+
+def fsvd_layer_workspace(desc, r_q, r_k, r_v, r_o, r_1, r_2) -> int:
+    return lib().fsvd_layer_workspace(C.byref(desc), r_q, r_k, r_v, r_o, r_1, r_2)
+
+
+def fsvd_attention(desc, X, q: Factor, k: Factor, v: Factor, o: Factor, out=None, workspace=None):
+    if out is None:
+        out = torch.empty(X.shape, dtype=_out_dtype(desc), device=X.device)
+    if workspace is None:
+        workspace = _workspace(fsvd_attention_workspace(desc, q.rank, k.rank, v.rank, o.rank), X.device)
+    fq, fk, fv, fo = q.c(), k.c(), v.c(), o.c()
+    _check(lib().fsvd_attention(C.byref(desc), _ptr(X), C.byref(fq), C.byref(fk), C.byref(fv), C.byref(fo),
+                                _ptr(out), _ptr(workspace), workspace.numel(), _stream()), "fsvd_attention")
+    return out
+
+
+def fsvd_ffn(desc, X, w1: Factor, w2: Factor, out=None, workspace=None):
+    if out is None:
+        out = torch.empty(X.shape, dtype=_out_dtype(desc), device=X.device)
+    if workspace is None:
+        workspace = _workspace(fsvd_ffn_workspace(desc, w1.rank, w2.rank), X.device)
+    f1, f2 = w1.c(), w2.c()
+    _check(lib().fsvd_ffn(C.byref(desc), _ptr(X), C.byref(f1), C.byref(f2), _ptr(out), _ptr(workspace),
+                          workspace.numel(), _stream()), "fsvd_ffn")
+    return out
+
+
+def fsvd_layer(desc, X, q, k, v, o, ln1_gamma, ln1_beta, w1, w2, ln2_gamma, ln2_beta, out=None, workspace=None):
+    if out is None:
+        out = torch.empty(X.shape, dtype=_out_dtype(desc), device=X.device)
+    if workspace is None:
+        workspace = _workspace(fsvd_layer_workspace(desc, q.rank, k.rank, v.rank, o.rank, w1.rank, w2.rank), X.device)
+    fq, fk, fv, fo, f1, f2 = q.c(), k.c(), v.c(), o.c(), w1.c(), w2.c()
+    _check(lib().fsvd_layer(C.byref(desc), _ptr(X), C.byref(fq), C.byref(fk), C.byref(fv), C.byref(fo),
+                            _ptr(ln1_gamma), _ptr(ln1_beta), C.byref(f1), C.byref(f2), _ptr(ln2_gamma),
+                            _ptr(ln2_beta), _ptr(out), _ptr(workspace), workspace.numel(), _stream()), "fsvd_layer")
+    return out
+
+
+def fsvd_linear(A, W, bias=None, residual=None, out_dtype=torch.float16, out=None):
+    T, K = A.shape
+    N = W.shape[1]
+    if out is None:
+        out = torch.empty((T, N), dtype=out_dtype, device=A.device)
+    _check(lib().fsvd_linear(T, K, N, _ptr(A), _TORCH2FSVD[A.dtype], _ptr(W), _ptr(bias), _TORCH2FSVD[W.dtype],
+                             _ptr(residual), 0 if residual is None else _TORCH2FSVD[residual.dtype], _ptr(out),
+                             _TORCH2FSVD[out.dtype], _stream()), "fsvd_linear")
+    return out
+
+
+def fsvd_attention_core(desc, Pq, Pk, Pv, q: Factor, k: Factor, v: Factor, out=None):
+    if out is None:
+        out = torch.empty((desc.B, desc.M, desc.D), dtype=torch.float16, device=Pq.device)
+    fq, fk, fv = q.c(), k.c(), v.c()
+    _check(lib().fsvd_attention_core(C.byref(desc), _ptr(Pq), _ptr(Pk), _ptr(Pv), C.byref(fq), C.byref(fk),
+                                     C.byref(fv), _ptr(out), _stream()), "fsvd_attention_core")
+    return out
+
+
+def fsvd_ffn_core(desc, P1, w1: Factor, w2: Factor, out=None):
+    if out is None:
+        out = torch.empty((desc.B * desc.M, w2.rank), dtype=torch.float16, device=P1.device)
+    f1, f2 = w1.c(), w2.c()
+    _check(lib().fsvd_ffn_core(C.byref(desc), _ptr(P1), C.byref(f1), C.byref(f2), _ptr(out), _stream()),
+           "fsvd_ffn_core")
+    return out
+
+
+def fsvd_layernorm(X, gamma, beta, eps, out_dtype=torch.float32, out=None):
+    T, D = X.shape
+    if out is None:
+        out = torch.empty((T, D), dtype=out_dtype, device=X.device)
+    _check(lib().fsvd_layernorm(T, D, _ptr(X), _TORCH2FSVD[X.dtype], _ptr(gamma), _ptr(beta),
+                                _TORCH2FSVD[gamma.dtype], float(eps), _ptr(out), _TORCH2FSVD[out.dtype], _stream()),
+           "fsvd_layernorm")
+    return out
+
+
+# ---------------------------------------------------------------------------------------------
+# workload plumbing: numpy inputs (already rounded to the storage type) -> device tensors
+# ---------------------------------------------------------------------------------------------
+
+def to_device(inp: dict, device="cuda:0"):
+    """Upload the arrays of workloads.make_inputs() in the workload's storage type."""
+    w = inp["workload"]
+    dt = torch.float16 if w.dtype == "fp16" else torch.bfloat16
+    up = lambda a: torch.from_numpy(a).to(device=device, dtype=dt).contiguous()
+    dev = {"X": up(inp["X"])}
+    for n in ("q", "k", "v", "o", "w1", "w2"):
+        dev[n] = Factor(up(inp[n]["U"]), up(inp[n]["V"]), up(inp[n]["b"]))
+    for n in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta"):
+        dev[n] = up(inp[n])
+    dev["key_len"] = None if inp["key_len"] is None else torch.from_numpy(inp["key_len"]).to(device)
+    dev["desc"] = make_desc(w.B, w.M, w.D, w.H, w.F, dt, torch.float32, inp["causal"], dev["key_len"], 0.0,
+                            "gelu_erf", w.norm, w.ln_eps)
+    return dev

@@ -1,0 +1,422 @@
+// Streaming attention over rank-space inputs (Alg. 1): Q, K and V tiles are rebuilt on chip from
+// P_q, P_k, P_v [T, r] and the head's columns of V_q, V_k, V_v [r, D] (Alg. 1 Part I), scores and the
+// streaming softmax never leave registers (Part II), and only the context C [T, D] is written.
+//
+// One workgroup (4 wavefronts) owns one (sequence, head, block of BQ = 128*QT queries).
+//   Q phase : every wavefront rebuilds Q^T [d_h, 32*QT] for its own queries, contraction over r_q
+//             in 64-wide chunks, pre-scaled by softmax_scale*log2(e), and keeps it as MFMA operands.
+//   KV loop : per step of 128 keys, wavefront w rebuilds 64 keys of K (w even) or V (w odd) — weight
+//             chunks are transposed into LDS (double-buffered) and shared, P rows are read straight
+//             from global memory — adds the bias and publishes the fp16 tile in LDS in operand order.
+//             Then every wavefront computes S^T = K Q^T for its queries, masks, updates the running
+//             row maximum / sum and accumulates O^T += V^T P~^T.
+// All products are arranged "transposed" (keys or features along accumulator rows, queries along
+// lanes), so the accumulators of one product are, after rounding to fp16, exactly the operand
+// registers of the next one: no activation ever needs a transpose or an LDS round trip except the
+// K/V tile exchange between wavefronts, and the softmax row statistics are per-lane scalars.
+#include "fsvd_common.h"
+#include "fsvd_kernels.h"
+
+namespace fsvd {
+
+namespace {
+
+constexpr int kAttnWaves = 4;
+constexpr int kBKV = 128;            // keys per step (two 64-key slabs, each rebuilt by a K and a V wavefront)
+constexpr float kLog2e = 1.4426950408889634f;
+
+__device__ __forceinline__ h8 pack8(const f16v& x, int t, float add) {
+  h8 r;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r[i] = (_Float16)(x[8 * t + i] + add);
+  return r;
+}
+
+template <int DH, int QT, int WT>
+__global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int nqb) {
+  constexpr int DT32 = DH / 32;             // 32-wide feature tiles
+  constexpr int DST = DH / 16;              // 16-wide contraction steps over d_h
+  constexpr int BQ = kAttnWaves * QT * 32;  // queries per workgroup
+  constexpr int WBUF = DH * kLdsRow;        // halves per staged weight chunk (one matrix)
+  constexpr int NBM = 16 * (DH / 8);        // 4x8 staging blocks per matrix chunk
+  constexpr int NBLK = (2 * NBM) / 256;     // staging blocks per thread in the KV loop (1 or 2)
+
+  __shared__ __attribute__((aligned(16))) _Float16 wbuf[2][2][WBUF];   // [parity][K|V weights]
+  __shared__ __attribute__((aligned(16))) h8 ktile[kBKV / 32][DST][64];
+  __shared__ __attribute__((aligned(16))) h8 vtile[kBKV / 32][DT32][2][64];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+  const int BH = a.B * a.H;
+  const int bh = blockIdx.x % BH;
+  const int qb = nqb - 1 - blockIdx.x / BH;   // late query blocks (most keys under a causal mask) first
+  const int b = bh / a.H, h = bh % a.H;
+  const int M = a.M;
+  const int q0 = qb * BQ;
+  const int qw = q0 + wave * QT * 32;         // first query of this wavefront
+  int kv_len = a.key_len ? a.key_len[b] : M;
+  kv_len = kv_len < 1 ? 1 : (kv_len > M ? M : kv_len);
+  int kv_end = kv_len;
+  if (a.causal && q0 + BQ < kv_end) kv_end = q0 + BQ;
+  const int nsteps = (kv_end + kBKV - 1) / kBKV;
+  const size_t tok0 = (size_t)b * M;
+  const size_t col0 = (size_t)h * DH;         // this head's columns in V_a, b_a and C
+
+  // ---- weight staging: thread -> 4 (rank) x 8 (feature) block
+  auto stage_coords = [&](int bid, int& mat, int& q4, int& ng) {
+    mat = bid / NBM;
+    const int w = bid % NBM;
+    q4 = (w >> 2) & 15;
+    ng = (w & 3) + 4 * (w >> 6);
+  };
+
+  // =================================== Q phase ===================================
+  h8 qf[DST][QT];
+  {
+    f16v acc[DT32][QT];
+#pragma unroll
+    for (int dt = 0; dt < DT32; ++dt)
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) acc[dt][qt] = zero16();
+    const _Float16* prow[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+      int q = qw + 32 * qt + l32;
+      q = q < M ? q : M - 1;
+      prow[qt] = a.Pq + (tok0 + q) * a.ldpq;
+    }
+    const int rq = a.rq;
+    const int nc = (rq + kChunkK - 1) / kChunkK;
+    int s_mat, s_q4, s_ng;
+    stage_coords(tid, s_mat, s_q4, s_ng);
+    const bool stager = tid < NBM;
+    u4 w_raw[4];
+    h8 p_cur[QT][4], p_nxt[QT][4];
+    auto load_p = [&](int c, h8 (&dst)[QT][4]) {
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const int k = c * kChunkK + chunk_off(kk, g);
+          u4 raw = {0u, 0u, 0u, 0u};
+          if (k < rq) raw = *(const u4*)(prow[qt] + k);
+          dst[qt][kk] = __builtin_bit_cast(h8, raw);
+        }
+    };
+    auto issue_w = [&](int c) {
+      if (stager) load_w4x8<WT>((const uint16_t*)a.Vq + col0, (size_t)a.D, c * kChunkK + 4 * s_q4, 8 * s_ng, rq, DH, w_raw);
+    };
+    auto commit_w = [&](int p) {
+      if (stager) {
+        u2 t[8];
+        transpose_w4x8<WT>(w_raw, t);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) *(u2*)&wbuf[p][0][(8 * s_ng + j) * kLdsRow + 4 * s_q4] = t[j];
+      }
+    };
+    issue_w(0);
+    load_p(0, p_cur);
+    commit_w(0);
+    __syncthreads();
+    for (int c = 0; c < nc; ++c) {
+      const bool more = c + 1 < nc;
+      if (more) { issue_w(c + 1); load_p(c + 1, p_nxt); }
+      const _Float16* wb = wbuf[c & 1][0];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        h8 wf[DT32];
+#pragma unroll
+        for (int dt = 0; dt < DT32; ++dt) wf[dt] = *(const h8*)&wb[(32 * dt + l32) * kLdsRow + chunk_off(kk, g)];
+#pragma unroll
+        for (int dt = 0; dt < DT32; ++dt)
+#pragma unroll
+          for (int qt = 0; qt < QT; ++qt) acc[dt][qt] = mfma32(wf[dt], p_cur[qt][kk], acc[dt][qt]);
+      }
+      if (more) {
+        commit_w((c + 1) & 1);
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) p_cur[qt][kk] = p_nxt[qt][kk];
+      }
+      __syncthreads();
+    }
+    // bias, softmax scale (log2 domain), round to fp16 operands
+    const float qs = a.scale * kLog2e;
+#pragma unroll
+    for (int dt = 0; dt < DT32; ++dt) {
+      float bias[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        bias[v] = a.bq ? load_param(a.bq, col0 + 32 * dt + 8 * (v >> 2) + 4 * g + (v & 3), a.w_dt) : 0.f;
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          h8 r;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) r[i] = (_Float16)((acc[dt][qt][8 * t + i] + bias[8 * t + i]) * qs);
+          qf[2 * dt + t][qt] = r;
+        }
+    }
+  }
+
+  // =================================== KV loop ===================================
+  f16v o[DT32][QT];
+  float m_run[QT], l_run[QT];
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    m_run[qt] = -1e30f;
+    l_run[qt] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < DT32; ++dt) o[dt][qt] = zero16();
+  }
+
+  const int kvt = wave >> 1;        // which 64-key slab of the step this wavefront rebuilds
+  const int which = wave & 1;       // 0: keys, 1: values
+  const _Float16* Psrc = which ? a.Pv : a.Pk;
+  const int ldp = which ? a.ldpv : a.ldpk;
+  const int rr = which ? a.rv : a.rk;
+  const int rmax = a.rk > a.rv ? a.rk : a.rv;
+  const int nc = (rmax + kChunkK - 1) / kChunkK;
+  const int total = nsteps * nc;
+
+  int s_mat[NBLK], s_q4[NBLK], s_ng[NBLK];
+#pragma unroll
+  for (int i = 0; i < NBLK; ++i) stage_coords(tid + 256 * i, s_mat[i], s_q4[i], s_ng[i]);
+  u4 w_raw[NBLK][4];
+  auto issue_w = [&](int c) {
+#pragma unroll
+    for (int i = 0; i < NBLK; ++i) {
+      const void* W = s_mat[i] ? a.Vv : a.Vk;
+      const int r = s_mat[i] ? a.rv : a.rk;
+      load_w4x8<WT>((const uint16_t*)W + col0, (size_t)a.D, c * kChunkK + 4 * s_q4[i], 8 * s_ng[i], r, DH, w_raw[i]);
+    }
+  };
+  auto commit_w = [&](int p) {
+#pragma unroll
+    for (int i = 0; i < NBLK; ++i) {
+      u2 t[8];
+      transpose_w4x8<WT>(w_raw[i], t);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) *(u2*)&wbuf[p][s_mat[i]][(8 * s_ng[i] + j) * kLdsRow + 4 * s_q4[i]] = t[j];
+    }
+  };
+  h8 p_cur[2][4], p_nxt[2][4];
+  auto load_p = [&](int step, int c, h8 (&dst)[2][4]) {
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      int key = step * kBKV + 64 * kvt + 32 * kt + l32;
+      key = key < M ? key : M - 1;
+      const _Float16* row = Psrc + (tok0 + key) * ldp;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const int k = c * kChunkK + chunk_off(kk, g);
+        u4 raw = {0u, 0u, 0u, 0u};
+        if (k < rr) raw = *(const u4*)(row + k);
+        dst[kt][kk] = __builtin_bit_cast(h8, raw);
+      }
+    }
+  };
+
+  f16v acc[DT32][2];
+#pragma unroll
+  for (int dt = 0; dt < DT32; ++dt) { acc[dt][0] = zero16(); acc[dt][1] = zero16(); }
+
+  if (total > 0) {
+    issue_w(0);
+    load_p(0, 0, p_cur);
+    commit_w(0);
+  }
+  __syncthreads();
+
+  int step = 0, c = 0;
+  for (int it = 0; it < total; ++it) {
+    const bool more = it + 1 < total;
+    int nstep = step, ncn = c + 1;
+    if (ncn == nc) { ncn = 0; nstep = step + 1; }
+    if (more) { issue_w(ncn); load_p(nstep, ncn, p_nxt); }
+    {
+      const _Float16* wb = wbuf[it & 1][which];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        h8 wf[DT32];
+#pragma unroll
+        for (int dt = 0; dt < DT32; ++dt) wf[dt] = *(const h8*)&wb[(32 * dt + l32) * kLdsRow + chunk_off(kk, g)];
+        if (which == 0) {
+#pragma unroll
+          for (int dt = 0; dt < DT32; ++dt)
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt) acc[dt][kt] = mfma32(wf[dt], p_cur[kt][kk], acc[dt][kt]);   // K^T: rows d, cols keys
+        } else {
+#pragma unroll
+          for (int dt = 0; dt < DT32; ++dt)
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt) acc[dt][kt] = mfma32(p_cur[kt][kk], wf[dt], acc[dt][kt]);   // V: rows keys, cols d
+        }
+      }
+    }
+    if (more) {
+      commit_w((it + 1) & 1);
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) p_cur[kt][kk] = p_nxt[kt][kk];
+    }
+    __syncthreads();
+
+    if (c == nc - 1) {
+      // ---- publish the rebuilt tile (bias added, fp16, operand order)
+      if (which == 0) {
+#pragma unroll
+        for (int dt = 0; dt < DT32; ++dt) {
+          float bias[16];
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            bias[v] = a.bk ? load_param(a.bk, col0 + 32 * dt + 8 * (v >> 2) + 4 * g + (v & 3), a.w_dt) : 0.f;
+#pragma unroll
+          for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+              h8 r;
+#pragma unroll
+              for (int i = 0; i < 8; ++i) r[i] = (_Float16)(acc[dt][kt][8 * t + i] + bias[8 * t + i]);
+              ktile[2 * kvt + kt][2 * dt + t][lane] = r;
+            }
+        }
+      } else {
+#pragma unroll
+        for (int dt = 0; dt < DT32; ++dt) {
+          const float bias = a.bv ? load_param(a.bv, col0 + 32 * dt + l32, a.w_dt) : 0.f;
+#pragma unroll
+          for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) vtile[2 * kvt + kt][dt][t][lane] = pack8(acc[dt][kt], t, bias);
+        }
+      }
+#pragma unroll
+      for (int dt = 0; dt < DT32; ++dt) { acc[dt][0] = zero16(); acc[dt][1] = zero16(); }
+      __syncthreads();
+
+      // ---- scores, streaming softmax, context for this wavefront's queries
+      const int qlast = qw + 32 * QT - 1;
+#pragma unroll 1
+      for (int ks = 0; ks < kBKV / 32; ++ks) {
+        const int key0 = step * kBKV + 32 * ks;
+        if (key0 >= kv_end) break;
+        if (a.causal && key0 > qlast) break;
+        f16v s[QT];
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) s[qt] = zero16();
+#pragma unroll
+        for (int ds = 0; ds < DST; ++ds) {
+          const h8 kf = ktile[ks][ds][lane];
+#pragma unroll
+          for (int qt = 0; qt < QT; ++qt) s[qt] = mfma32(kf, qf[ds][qt], s[qt]);   // S^T: rows keys, cols queries
+        }
+        const bool need_mask = (key0 + 32 > kv_len) || (a.causal && key0 + 31 > qw);
+        if (need_mask) {
+#pragma unroll
+          for (int qt = 0; qt < QT; ++qt) {
+            const int q = qw + 32 * qt + l32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int key = key0 + 8 * (v >> 2) + 4 * g + (v & 3);
+              if (key >= kv_len || (a.causal && key > q)) s[qt][v] = -INFINITY;
+            }
+          }
+        }
+        h8 pf[QT][2];
+        float alpha[QT];
+        bool rescale = false;
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
+          float mx = s[qt][0];
+#pragma unroll
+          for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[qt][v]);
+          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+          const float m_new = fmaxf(m_run[qt], mx);
+          alpha[qt] = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
+          m_run[qt] = m_new;
+          float sum = 0.f;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const float p = __builtin_amdgcn_exp2f(s[qt][v] - m_new);
+            s[qt][v] = p;
+            sum += p;
+          }
+          l_run[qt] = l_run[qt] * alpha[qt] + sum;
+          rescale = rescale || (alpha[qt] != 1.0f);
+          pf[qt][0] = pack8(s[qt], 0, 0.f);
+          pf[qt][1] = pack8(s[qt], 1, 0.f);
+        }
+        if (__any(rescale)) {
+#pragma unroll
+          for (int dt = 0; dt < DT32; ++dt)
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+              for (int v = 0; v < 16; ++v) o[dt][qt][v] *= alpha[qt];
+        }
+#pragma unroll
+        for (int dt = 0; dt < DT32; ++dt)
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            const h8 vf = vtile[ks][dt][t][lane];
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) o[dt][qt] = mfma32(vf, pf[qt][t], o[dt][qt]);   // O^T: rows d, cols queries
+          }
+      }
+    }
+    step = nstep;
+    c = ncn;
+  }
+
+  // ---- normalise and write the context (fp16), 4 consecutive features per store
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    const int q = qw + 32 * qt + l32;
+    const float l = l_run[qt] + __shfl_xor(l_run[qt], 32, 64);
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
+    if (q < M) {
+      _Float16* crow = a.C + (tok0 + q) * a.ldc + col0;
+#pragma unroll
+      for (int dt = 0; dt < DT32; ++dt)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          h4 r;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) r[i] = (_Float16)(o[dt][qt][4 * jj + i] * inv);
+          *(h4*)(crow + 32 * dt + 8 * jj + 4 * g) = r;
+        }
+    }
+  }
+}
+
+template <int DH, int QT>
+hipError_t launch_qt(const AttnCoreArgs& a, hipStream_t s) {
+  constexpr int BQ = kAttnWaves * QT * 32;
+  const int nqb = (a.M + BQ - 1) / BQ;
+  const dim3 grid(a.B * a.H * nqb), block(256);
+  if (a.w_dt == DT_F16) hipLaunchKernelGGL((attn_core_kernel<DH, QT, DT_F16>), grid, block, 0, s, a, nqb);
+  else hipLaunchKernelGGL((attn_core_kernel<DH, QT, DT_BF16>), grid, block, 0, s, a, nqb);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_attn_core(const AttnCoreArgs& a, hipStream_t s) {
+  const int dh = a.D / a.H;
+  if (dh == 64) {
+    if (a.M <= 128) return launch_qt<64, 1>(a, s);
+    if (a.M <= 256) return launch_qt<64, 2>(a, s);
+    return launch_qt<64, 4>(a, s);
+  }
+  if (dh == 128) {
+    if (a.M <= 128) return launch_qt<128, 1>(a, s);
+    return launch_qt<128, 2>(a, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace fsvd

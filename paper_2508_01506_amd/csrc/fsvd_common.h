@@ -1,0 +1,167 @@
+// Device-side building blocks shared by the fsvd kernels (gfx950 only).
+//
+// Matrix-core convention used everywhere (v_mfma_f32_32x32x16_f16, one wavefront of 64 lanes):
+//   A operand: lane l supplies 8 halves of row (l % 32), contraction slots 8*(l / 32) .. +7
+//   B operand: lane l supplies 8 halves of column (l % 32), same contraction slots
+//   accumulator register v (0..15) of lane l holds row 8*(v/4) + 4*(l/32) + (v%4), column l % 32
+// Which logical index a contraction slot stands for is free as long as A and B agree; the kernels
+// use that freedom to feed accumulators of one product straight into the next product.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fsvd {
+
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+typedef float f8v __attribute__((ext_vector_type(8)));
+typedef float f4v __attribute__((ext_vector_type(4)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+
+enum : int { DT_F16 = 0, DT_BF16 = 1, DT_F32 = 2 };
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ f16v mfma32(h8 a, h8 b, f16v c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ f16v zero16() {
+  f16v z;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) z[i] = 0.f;
+  return z;
+}
+
+// two bf16 packed in one dword -> two fp16 packed in one dword (exact in fp16's normal range)
+__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t w) {
+  float lo = __uint_as_float(w << 16);
+  float hi = __uint_as_float(w & 0xffff0000u);
+  auto p = __builtin_amdgcn_cvt_pkrtz(lo, hi);
+  return __builtin_bit_cast(uint32_t, p);
+}
+
+// 8 stored 16-bit values (one 16-byte load) -> 8 halves
+template <int DT>
+__device__ __forceinline__ h8 raw_to_h8(u4 raw) {
+  if constexpr (DT == DT_BF16) {
+    u4 c;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) c[i] = bf16x2_to_f16x2(raw[i]);
+    return __builtin_bit_cast(h8, c);
+  } else {
+    return __builtin_bit_cast(h8, raw);
+  }
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// scalar read of a stored parameter (bias, gamma, beta) as float
+__device__ __forceinline__ float load_param(const void* p, size_t i, int dt) {
+  if (dt == DT_F16) return (float)((const _Float16*)p)[i];
+  if (dt == DT_BF16) return bf16_bits_to_float(((const uint16_t*)p)[i]);
+  return ((const float*)p)[i];
+}
+
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ void store_out(void* p, size_t i, float v, int dt) {
+  if (dt == DT_F32) ((float*)p)[i] = v;
+  else if (dt == DT_F16) ((_Float16*)p)[i] = (_Float16)v;
+  else ((uint16_t*)p)[i] = float_to_bf16_bits(v);
+}
+
+// 8 consecutive elements of a row-major activation (row pointer already applied) as an MFMA fragment.
+// AT: storage type of the activation.  `ok` false yields zeros (ragged contraction tails).
+template <int AT>
+__device__ __forceinline__ h8 load_act8(const void* base, size_t elem_off, bool ok) {
+  if constexpr (AT == DT_F32) {
+    f4v lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+    if (ok) {
+      const f4v* p = (const f4v*)((const float*)base + elem_off);
+      lo = p[0];
+      hi = p[1];
+    }
+    h8 r;
+    r[0] = (_Float16)lo[0]; r[1] = (_Float16)lo[1]; r[2] = (_Float16)lo[2]; r[3] = (_Float16)lo[3];
+    r[4] = (_Float16)hi[0]; r[5] = (_Float16)hi[1]; r[6] = (_Float16)hi[2]; r[7] = (_Float16)hi[3];
+    return r;
+  } else {
+    u4 raw = {0u, 0u, 0u, 0u};
+    if (ok) raw = *(const u4*)((const uint16_t*)base + elem_off);
+    return raw_to_h8<AT>(raw);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Transposed staging of a weight tile.  Weights are row-major [K, N] with the contraction index K
+// as the slow axis, while an MFMA operand wants 8 consecutive contraction slots per lane, so a
+// tile is transposed in registers on its way into LDS: a thread loads a 4 (k) x 8 (n) block with
+// four 16-byte loads and emits, for each of the 8 columns, the 4 k-values as one 8-byte LDS store.
+// ---------------------------------------------------------------------------------------------
+template <int WT>
+__device__ __forceinline__ void load_w4x8(const void* W, size_t ldw, int k, int n, int K, int N, u4 raw[4]) {
+  const uint16_t* w = (const uint16_t*)W;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    u4 z = {0u, 0u, 0u, 0u};
+    raw[i] = z;
+    if (k + i < K && n < N) raw[i] = *(const u4*)(w + (size_t)(k + i) * ldw + n);
+  }
+}
+
+// out[j] = { W[k..k+3][n+j] } as 4 halves
+template <int WT>
+__device__ __forceinline__ void transpose_w4x8(const u4 raw[4], u2 out[8]) {
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    uint32_t r0 = raw[0][d], r1 = raw[1][d], r2 = raw[2][d], r3 = raw[3][d];
+    if constexpr (WT == DT_BF16) {
+      float l0 = __uint_as_float(r0 << 16), l1 = __uint_as_float(r1 << 16);
+      float l2 = __uint_as_float(r2 << 16), l3 = __uint_as_float(r3 << 16);
+      float g0 = __uint_as_float(r0 & 0xffff0000u), g1 = __uint_as_float(r1 & 0xffff0000u);
+      float g2 = __uint_as_float(r2 & 0xffff0000u), g3 = __uint_as_float(r3 & 0xffff0000u);
+      out[2 * d][0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(l0, l1));
+      out[2 * d][1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(l2, l3));
+      out[2 * d + 1][0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(g0, g1));
+      out[2 * d + 1][1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(g2, g3));
+    } else {
+      out[2 * d][0] = (r0 & 0xffffu) | (r1 << 16);
+      out[2 * d][1] = (r2 & 0xffffu) | (r3 << 16);
+      out[2 * d + 1][0] = (r0 >> 16) | (r1 & 0xffff0000u);
+      out[2 * d + 1][1] = (r2 >> 16) | (r3 & 0xffff0000u);
+    }
+  }
+}
+
+// LDS weight tiles are stored [n][k] with a row of kLdsK halves of payload plus 8 halves of padding,
+// so that 16 lanes reading 16 bytes from 16 consecutive rows hit distinct banks.
+constexpr int kChunkK = 64;             // contraction chunk staged per step
+constexpr int kLdsRow = kChunkK + 8;    // halves per LDS row
+
+// Contraction-slot mapping inside one 64-wide chunk: MFMA step kk (0..3), lane group g (0..1),
+// slot s (0..7) stand for chunk offset 32*g + 8*kk + s.  An activation lane therefore reads 64
+// contiguous bytes of its row over the four steps of a chunk.
+__device__ __forceinline__ int chunk_off(int kk, int g) { return 32 * g + 8 * kk; }
+
+// blockIdx -> tile index so that each of the 8 XCDs (round-robin workgroup dispatch) walks a
+// contiguous range of tiles and its L2 sees neighbouring tiles.
+__device__ __forceinline__ int xcd_tile(int linear, int total) {
+  if ((total & 7) != 0) return linear;
+  return (linear & 7) * (total >> 3) + (linear >> 3);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+}  // namespace fsvd

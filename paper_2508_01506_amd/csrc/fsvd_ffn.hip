@@ -1,0 +1,273 @@
+// Fused FFN core (Alg. 2, the on-chip loops): Z[T, r2] = phi(P1[T, r1] V_1[r1, F] + b_1) U_2[F, r2].
+// The hidden activation phi(...) [T, F] exists only as 128-wide slabs in registers / LDS.
+//
+// One workgroup (4 wavefronts) owns 128 tokens and one slice of at most 512 output ranks; the
+// accumulator Z^T [slice, 128 tokens] stays in registers for the whole sweep over F.  Per 128-wide
+// chunk of F:
+//   phase A  Y^T[128 f, 128 tok] = V_1[:, chunk]^T P1^T, contraction over r1 in 128-wide stages;
+//            wavefront (wt, wr) computes features 64*wr.. for tokens 64*wt.. (P1 rows come straight
+//            from global memory), adds b_1, applies phi, rounds to fp16 and hands the result to its
+//            partner wavefront through LDS in MFMA operand order;
+//   phase B  Z^T[128*s + 64*wr.., tokens 64*wt..] += U_2[chunk, :]^T Y^T, one 128-rank sub-stage s at a
+//            time.
+// Every weight tile (128 contraction rows x 128 output columns) is transposed in registers on its
+// way into a double-buffered LDS tile; tile i+1 is fetched from global memory while tile i is used.
+// When r2 > 512 the slices are separate workgroups and phase A is recomputed per slice.
+#include "fsvd_common.h"
+#include "fsvd_kernels.h"
+
+namespace fsvd {
+
+namespace {
+
+constexpr int kFfnBT = 128;                 // tokens per workgroup
+constexpr int kFfnBF = 128;                 // F chunk
+constexpr int kTile = 128;                  // weight tile edge
+constexpr int kTileRow = kTile + 8;         // halves per LDS tile row (16-lane conflict-free 16-byte reads)
+constexpr int kMaxSlice = 512;
+
+// exact-GELU via the Abramowitz-Stegun 7.1.26 rational approximation of erf (|error| <= 1.5e-7),
+// written so that the negative tail does not cancel.
+__device__ __forceinline__ float gelu_erf_f(float x) {
+  const float z = fabsf(x) * 0.70710678118654752f;
+  const float t = __frcp_rn(1.0f + 0.3275911f * z);
+  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+  const float tail = 0.5f * poly * __builtin_amdgcn_exp2f(-z * z * 1.4426950408889634f);   // 0.5 * erfc(|x|/sqrt2)
+  return x >= 0.f ? x * (1.0f - tail) : x * tail;
+}
+__device__ __forceinline__ float gelu_tanh_f(float x) {
+  const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+  return x * __frcp_rn(1.0f + __builtin_amdgcn_exp2f(-2.0f * u * 1.4426950408889634f));
+}
+__device__ __forceinline__ float act_f(float x, int act) {
+  if (act == 0) return gelu_erf_f(x);
+  if (act == 1) return gelu_tanh_f(x);
+  return fmaxf(x, 0.f);
+}
+
+// contraction-slot offset inside a 128-wide stage: step kk (0..7), lane group g
+__device__ __forceinline__ int stage_off(int kk, int g) { return 64 * (kk >> 2) + 32 * g + 8 * (kk & 3); }
+
+template <int NS, int WT>
+__global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nslices, int slice_w) {
+  __shared__ __attribute__((aligned(16))) _Float16 wt_lds[2][kTile * kTileRow];
+  __shared__ __attribute__((aligned(16))) h8 gtile[2][4][2][2][64];   // [token half][f tile][t][token tile][lane]
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+  const int wt = wave >> 1, wr = wave & 1;
+  const int slice = blockIdx.x % nslices;
+  const int tb = blockIdx.x / nslices;
+  const int t0 = tb * kFfnBT;
+  const int s0 = slice * slice_w;                               // first output rank of this slice
+  const int s_end = (s0 + slice_w < a.r2) ? s0 + slice_w : a.r2;
+  const int r1 = a.r1, F = a.F;
+  const int nA = (r1 + kTile - 1) / kTile;
+  const int nchunks = (F + kFfnBF - 1) / kFfnBF;
+
+  // ---- weight tile staging: each thread moves two 4 (k) x 8 (n) blocks
+  int sq[2], sng[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int bid = tid + 256 * i;
+    sng[i] = (bid & 3) + 4 * ((bid >> 6) & 3);
+    sq[i] = ((bid >> 2) & 15) + 16 * (bid >> 8);
+  }
+  u4 w_raw[2][4];
+  // kind 0: V_1 rows r (stage ra), columns f of chunk c.  kind 1: U_2 rows f of chunk c, columns s0 + 128*s.
+  auto issue_tile = [&](int kind, int c, int idx) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      if (kind == 0) {
+        load_w4x8<WT>((const uint16_t*)a.V1 + (size_t)c * kFfnBF, (size_t)F, idx * kTile + 4 * sq[i], 8 * sng[i],
+                      r1, F - c * kFfnBF, w_raw[i]);
+      } else {
+        const int n0 = s0 + idx * kTile;
+        load_w4x8<WT>((const uint16_t*)a.U2 + n0, (size_t)a.r2, c * kFfnBF + 4 * sq[i], 8 * sng[i],
+                      F, s_end - n0, w_raw[i]);
+      }
+    }
+  };
+  // kind 1 tiles store their 4-row groups in accumulator order (0-3, 8-11, 4-7, 12-15 of every 16)
+  auto commit_tile = [&](int kind, int p) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      u2 t[8];
+      transpose_w4x8<WT>(w_raw[i], t);
+      int q = sq[i];
+      if (kind == 1) q = (q & ~3) | ((q & 1) << 1) | ((q >> 1) & 1);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) *(u2*)&wt_lds[p][(8 * sng[i] + j) * kTileRow + 4 * q] = t[j];
+    }
+  };
+
+  // ---- P1 rows of this wavefront's tokens
+  const _Float16* prow[2];
+#pragma unroll
+  for (int tt = 0; tt < 2; ++tt) {
+    int tok = t0 + 64 * wt + 32 * tt + l32;
+    tok = tok < a.T ? tok : a.T - 1;
+    prow[tt] = a.P1 + (size_t)tok * a.ldp;
+  }
+  h8 p_cur[2][4], p_nxt[2][4];
+  auto load_p = [&](int half, h8 (&dst)[2][4]) {   // half: 64-wide piece of r1
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const int k = half * 64 + 32 * g + 8 * kk;
+        u4 raw = {0u, 0u, 0u, 0u};
+        if (k < r1) raw = *(const u4*)(prow[tt] + k);
+        dst[tt][kk] = __builtin_bit_cast(h8, raw);
+      }
+  };
+  const int nhalf = 2 * nA;
+
+  f16v z[NS][2][2];
+#pragma unroll
+  for (int s = 0; s < NS; ++s)
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) { z[s][rt][0] = zero16(); z[s][rt][1] = zero16(); }
+
+  int parity = 0;
+  issue_tile(0, 0, 0);
+  load_p(0, p_cur);
+  commit_tile(0, 0);
+  __syncthreads();
+
+  for (int c = 0; c < nchunks; ++c) {
+    // ================= phase A =================
+    f16v y[2][2];
+#pragma unroll
+    for (int ft = 0; ft < 2; ++ft) { y[ft][0] = zero16(); y[ft][1] = zero16(); }
+    for (int ra = 0; ra < nA; ++ra) {
+      const bool lastA = ra + 1 == nA;
+      if (!lastA) issue_tile(0, c, ra + 1); else issue_tile(1, c, 0);
+      const _Float16* wb = wt_lds[parity];
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        const int half = 2 * ra + hh;
+        int nh = half + 1;
+        if (nh == nhalf) nh = 0;
+        load_p(nh, p_nxt);
+        if (half * 64 < r1) {
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) {
+            h8 wf[2];
+#pragma unroll
+            for (int ft = 0; ft < 2; ++ft)
+              wf[ft] = *(const h8*)&wb[(64 * wr + 32 * ft + l32) * kTileRow + 64 * hh + 32 * g + 8 * kk];
+#pragma unroll
+            for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+              for (int tt = 0; tt < 2; ++tt) y[ft][tt] = mfma32(wf[ft], p_cur[tt][kk], y[ft][tt]);   // rows f, cols tokens
+          }
+        }
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) p_cur[tt][kk] = p_nxt[tt][kk];
+      }
+      if (lastA) {
+        // bias, phi, fp16, publish in operand order for phase B
+#pragma unroll
+        for (int ft = 0; ft < 2; ++ft) {
+          float bias[16];
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int f = c * kFfnBF + 64 * wr + 32 * ft + 8 * (v >> 2) + 4 * g + (v & 3);
+            bias[v] = (a.b1 && f < F) ? load_param(a.b1, f, a.w_dt) : 0.f;
+          }
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+              h8 r;
+#pragma unroll
+              for (int i = 0; i < 8; ++i) r[i] = (_Float16)act_f(y[ft][tt][8 * t + i] + bias[8 * t + i], a.act);
+              gtile[wt][2 * wr + ft][t][tt][lane] = r;
+            }
+        }
+      }
+      commit_tile(lastA ? 1 : 0, parity ^ 1);
+      __syncthreads();
+      parity ^= 1;
+    }
+    // ================= phase B =================
+    h8 gq[8][2];
+#pragma unroll
+    for (int fs = 0; fs < 8; ++fs)
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) gq[fs][tt] = gtile[wt][fs >> 1][fs & 1][tt][lane];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const bool lastB = s + 1 == NS;
+      const bool more = !lastB || (c + 1 < nchunks);
+      if (more) { if (!lastB) issue_tile(1, c, s + 1); else issue_tile(0, c + 1, 0); }
+      const _Float16* wb = wt_lds[parity];
+      if (s0 + s * kTile < s_end) {
+#pragma unroll
+        for (int fs = 0; fs < 8; ++fs) {
+          h8 wf[2];
+#pragma unroll
+          for (int rt = 0; rt < 2; ++rt) wf[rt] = *(const h8*)&wb[(64 * wr + 32 * rt + l32) * kTileRow + 16 * fs + 8 * g];
+#pragma unroll
+          for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) z[s][rt][tt] = mfma32(wf[rt], gq[fs][tt], z[s][rt][tt]);   // rows ranks, cols tokens
+        }
+      }
+      if (more) commit_tile(lastB ? 0 : 1, parity ^ 1);
+      __syncthreads();
+      parity ^= 1;
+    }
+  }
+
+  // ---- write Z (fp16), 4 consecutive ranks per store
+#pragma unroll
+  for (int tt = 0; tt < 2; ++tt) {
+    const int tok = t0 + 64 * wt + 32 * tt + l32;
+    if (tok >= a.T) continue;
+    _Float16* zrow = a.Z + (size_t)tok * a.ldz;
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const int r = s0 + s * kTile + 64 * wr + 32 * rt + 8 * jj + 4 * g;
+          if (r < s_end) {
+            h4 o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = (_Float16)z[s][rt][tt][4 * jj + i];
+            *(h4*)(zrow + r) = o;
+          }
+        }
+  }
+}
+
+template <int NS>
+hipError_t launch_ns(const FfnCoreArgs& a, int nslices, int slice_w, hipStream_t s) {
+  const dim3 grid(((a.T + kFfnBT - 1) / kFfnBT) * nslices), block(256);
+  if (a.w_dt == DT_F16) hipLaunchKernelGGL((ffn_core_kernel<NS, DT_F16>), grid, block, 0, s, a, nslices, slice_w);
+  else hipLaunchKernelGGL((ffn_core_kernel<NS, DT_BF16>), grid, block, 0, s, a, nslices, slice_w);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_ffn_core(const FfnCoreArgs& a, hipStream_t s) {
+  const int nslices = (a.r2 + kMaxSlice - 1) / kMaxSlice;
+  int slice_w = (a.r2 + nslices - 1) / nslices;
+  slice_w = (slice_w + 15) / 16 * 16;
+  const int ns = (slice_w + kTile - 1) / kTile;
+  switch (ns) {
+    case 1: return launch_ns<1>(a, nslices, slice_w, s);
+    case 2: return launch_ns<2>(a, nslices, slice_w, s);
+    case 3: return launch_ns<3>(a, nslices, slice_w, s);
+    case 4: return launch_ns<4>(a, nslices, slice_w, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace fsvd
