@@ -110,7 +110,8 @@ def attention_context_one_sequence(x, q, k, v, H, causal=False, key_len=None, sc
     checked without forming every M x M score matrix.
     """
     x = _f64(x)
-    M, D = x.shape
+    M = x.shape[0]
+    D = np.shape(q["V"])[1]          # width of the rebuilt Q/K/V (x itself may be any width)
     d_h = D // H
     if scale is None or scale == 0:
         scale = 1.0 / np.sqrt(d_h)

@@ -1,0 +1,303 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle, element by element, on the
+same seeded inputs.  Metric: max|err| / RMS(ref).
+
+Tolerances (derivation in DESIGN.md, "Numerics"):
+  * fsvd_layer with LayerNorm (the five benchmark configurations): 2e-3, the stated gate.
+  * single blocks without the residual stream: every fp16 hand-off between two matrix-core
+    contractions adds about 2.8e-4 (= 2^-11 / sqrt 3) of RMS-relative noise and the maximum over
+    10^5..10^8 outputs sits 4.5-5 sigma out; attention has five hand-offs plus the score path
+    (non-causal 6e-3), and under a causal mask the first rows are not averaged while RMS(ref) is
+    (2e-2); the FFN has three hand-offs (3e-3); FFN(Attn(X)) without any LayerNorm compounds both
+    (3e-2).
+"""
+import numpy as np
+import pytest
+import torch
+
+from fsvd_testing import gpu_call, oracle_call, oracle_rows, rel_err, sample_rows
+from oracle import fsvd_oracle as O
+from paper_2508_01506_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL_LAYER = 2e-3
+TOL = {"layer": TOL_LAYER, "ffn": 3e-3, "attention": 6e-3, "attention_causal": 2e-2, "layer_none": 3e-2}
+
+
+@pytest.fixture(scope="module")
+def fb():
+    from paper_2508_01506_amd import binding
+    binding.lib()
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return binding
+
+
+def tol_for(w, part):
+    if part == "attention":
+        return TOL["attention_causal"] if w.mask == "causal" else TOL["attention"]
+    if part == "layer" and w.norm == "none":
+        return TOL["layer_none"]
+    return TOL[part]
+
+
+DEV = "cuda:0"
+_cache = {}
+
+
+def workload(name, fb):
+    if name not in _cache:
+        _cache.clear()
+        w = W.get_workload(name)
+        inp = W.make_inputs(w)
+        _cache[name] = (w, inp, fb.to_device(inp, DEV))
+    return _cache[name]
+
+
+# ------------------------------------------------------------------ building blocks
+@pytest.mark.parametrize("T,K,N,adt,wdt,odt", [
+    (70, 64, 48, torch.float16, torch.float16, torch.float32),
+    (300, 192, 272, torch.bfloat16, torch.bfloat16, torch.float32),
+    (513, 208, 128, torch.float32, torch.float16, torch.float32),
+    (256, 768, 576, torch.float16, torch.float16, torch.float16),
+    (1, 16, 16, torch.float16, torch.float16, torch.float32),
+    (1000, 1024, 80, torch.bfloat16, torch.bfloat16, torch.bfloat16),
+    (2049, 2048, 3072, torch.float16, torch.bfloat16, torch.float32),
+])
+def test_linear(fb, T, K, N, adt, wdt, odt):
+    g = torch.Generator().manual_seed(T + K + N)
+    A = torch.randn(T, K, generator=g).to(adt)
+    Wt = (torch.randn(K, N, generator=g) / K ** 0.5).to(wdt)
+    b = torch.randn(N, generator=g).to(wdt)
+    R = torch.randn(T, N, generator=g)
+    # operands are exact in their storage type; an fp32 activation is rounded to fp16 by the kernel
+    A_used = A.to(torch.float16) if adt == torch.float32 else A
+    ref = O.rank_projection(A_used.double().numpy(), Wt.double().numpy()) + b.double().numpy() + R.double().numpy()
+    got = fb.fsvd_linear(A.to(DEV), Wt.to(DEV), b.to(DEV), R.to(DEV), out_dtype=odt).float().cpu().numpy()
+    out_eps = {torch.float32: 2e-6, torch.float16: 2.0 ** -11, torch.bfloat16: 2.0 ** -8}[odt]
+    assert np.abs(got - ref).max() <= out_eps * (np.abs(ref).max() + 1) + 1e-5
+    plain = fb.fsvd_linear(A.to(DEV), Wt.to(DEV), out_dtype=torch.float32).cpu().numpy()
+    ref_plain = O.rank_projection(A_used.double().numpy(), Wt.double().numpy())
+    assert rel_err(plain, ref_plain) < 5e-6
+
+
+@pytest.mark.parametrize("T,D,xdt,ydt", [(37, 768, torch.float32, torch.float32), (5, 64, torch.float16, torch.float16),
+                                         (130, 4096, torch.bfloat16, torch.float32), (3, 1104, torch.float32, torch.bfloat16)])
+def test_layernorm(fb, T, D, xdt, ydt):
+    g = torch.Generator().manual_seed(D)
+    X = (torch.randn(T, D, generator=g) * 2 + 1).to(xdt)
+    gm = torch.randn(D, generator=g).half()
+    bt = torch.randn(D, generator=g).half()
+    ref = O.layer_norm(X.double().numpy(), gm.double().numpy(), bt.double().numpy(), 1e-5)
+    got = fb.fsvd_layernorm(X.to(DEV), gm.to(DEV), bt.to(DEV), 1e-5, out_dtype=ydt).float().cpu().numpy()
+    eps = {torch.float32: 3e-6, torch.float16: 2.0 ** -11, torch.bfloat16: 2.0 ** -8}[ydt]
+    assert np.abs(got - ref).max() <= eps * (np.abs(ref).max() + 1)
+
+
+def _selector(total, start, width):
+    S = np.zeros((total, width))
+    S[np.arange(start, start + width), np.arange(width)] = 1.0
+    return S
+
+
+@pytest.mark.parametrize("name", ["tiny_h2_d64", "tiny_pad", "tiny_causal_d128", "small_multi_qblock"])
+def test_attention_core_from_rank_space_inputs(fb, name):
+    """Alg. 1 Part II alone: P_q, P_k, P_v (already fp16) -> context, against the oracle fed the same P."""
+    w, inp, dev = workload(name, fb)
+    r = w.r_attn
+    P = {a: O.rank_projection(inp["X"], inp[a]["U"]).astype(np.float16) for a in "qkv"}
+    Pd = {a: torch.from_numpy(P[a].reshape(w.T, r)).to(DEV) for a in "qkv"}
+    got = fb.fsvd_attention_core(dev["desc"], Pd["q"], Pd["k"], Pd["v"], dev["q"], dev["k"], dev["v"]).float().cpu().numpy()
+    # oracle on x = [P_q | P_k | P_v] with 0/1 selector matrices as the U factors
+    xcat = np.concatenate([P[a].astype(np.float64) for a in "qkv"], axis=-1)
+    fac = {a: {"U": _selector(3 * r, i * r, r), "V": inp[a]["V"], "b": inp[a]["b"]} for i, a in enumerate("qkv")}
+    ref = np.stack([O.attention_context_one_sequence(xcat[b], fac["q"], fac["k"], fac["v"], w.H, inp["causal"],
+                                                     None if inp["key_len"] is None else inp["key_len"][b])
+                    for b in range(w.B)])
+    # hand-offs left: Q/K/V tiles, probabilities, and the fp16 context itself, whose final rounding is
+    # not averaged by any later contraction (half an ulp of a 4.5-sigma element is 2.2e-3 of the RMS)
+    assert rel_err(got, ref) < (2e-2 if inp["causal"] else 8e-3)
+
+
+@pytest.mark.parametrize("name,act", [("tiny_h2_d64", "gelu_erf"), ("tiny_pad", "gelu_tanh"), ("tiny_causal_d128", "relu"),
+                                      ("small_causal_d64", "gelu_erf")])
+def test_ffn_core_from_rank_space_input(fb, name, act):
+    """The on-chip loops of Alg. 2 alone: P1 (fp16) -> Z = phi(P1 V_1 + b_1) U_2."""
+    w, inp, dev = workload(name, fb)
+    P1 = O.rank_projection(inp["X"], inp["w1"]["U"]).astype(np.float16).reshape(w.T, w.r_ffn)
+    d = fb.make_desc(w.B, w.M, w.D, w.H, w.F, dev["X"].dtype, act=act)
+    got = fb.fsvd_ffn_core(d, torch.from_numpy(P1).to(DEV), dev["w1"], dev["w2"]).float().cpu().numpy()
+    hidden = O.activation(P1.astype(np.float64) @ inp["w1"]["V"].astype(np.float64) + inp["w1"]["b"], act)
+    ref = O.rank_projection(hidden, inp["w2"]["U"])
+    assert rel_err(got, ref) < 2.5e-3      # fp16 hidden activation + fp16 Z
+
+
+# ------------------------------------------------------------------ entry points, small shapes, every element
+SMALL = ["tiny_h2_d64", "tiny_pad", "tiny_causal_d128", "small_multi_qblock", "small_causal_d64"]
+
+
+@pytest.mark.parametrize("part", ["attention", "ffn", "layer"])
+@pytest.mark.parametrize("name", SMALL)
+def test_entry_points_small(fb, name, part):
+    w, inp, dev = workload(name, fb)
+    got = gpu_call(dev, part).cpu().numpy()
+    assert np.isfinite(got).all()
+    assert rel_err(got, oracle_call(inp, part)) < tol_for(w, part)
+
+
+@pytest.mark.parametrize("norm", ["post_ln", "pre_ln"])
+@pytest.mark.parametrize("name", SMALL)
+def test_layer_gate_on_small_shapes_both_norms(fb, name, norm):
+    w = W.get_workload(name, norm=norm)
+    inp = W.make_inputs(w)
+    dev = fb.to_device(inp, DEV)
+    assert rel_err(gpu_call(dev, "layer").cpu().numpy(), oracle_call(inp, "layer")) < TOL_LAYER
+
+
+# ------------------------------------------------------------------ benchmark sizes, sampled rows
+FULL = ["cfg1_bert_base_b2_m128", "cfg2_bert_base_b16_m512_pad", "cfg2u_bert_base_b16_m512_pad_unit",
+        "cfg3_bert_large_b32_m512_r128", "cfg3_bert_large_b32_m512_r256", "cfg3_bert_large_b32_m512_r512",
+        "cfg4_long_b4_m8192", "cfg5_llm_b1_m4096_causal"]
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_sampled_rows(fb, name):
+    """At the benchmark sizes, in the launch configuration bench.py times, on rows the oracle computes one by one."""
+    w, inp, dev = workload(name, fb)
+    outs = {part: gpu_call(dev, part).cpu().numpy() for part in ("layer", "attention", "ffn")}
+    for part, got in outs.items():
+        assert np.isfinite(got).all()
+        num, den, cnt = 0.0, 0.0, 0
+        for b in sorted({0, w.B // 2, w.B - 1}):
+            rows = sample_rows(w, 12, seed=b)
+            ref = oracle_rows(inp, b, rows, part)
+            num = max(num, float(np.abs(got[b, rows] - ref).max()))
+            den += float(np.sum(ref ** 2))
+            cnt += ref.size
+        err = num / np.sqrt(den / cnt)
+        assert err < tol_for(w, part), (name, part, err)
+
+
+def test_full_size_padding_property(fb):
+    """Tokens at masked key positions cannot influence the context of any row (bitwise)."""
+    w, inp, dev = workload("cfg2u_bert_base_b16_m512_pad_unit", fb)
+    a = gpu_call(dev, "attention")
+    X2 = dev["X"].clone()
+    kl = inp["key_len"]
+    for b in range(w.B):
+        X2[b, kl[b]:] = torch.randn_like(X2[b, kl[b]:])
+    dev2 = dict(dev, X=X2)
+    a2 = gpu_call(dev2, "attention")
+    for b in range(w.B):
+        assert torch.equal(a[b, :kl[b]], a2[b, :kl[b]])
+
+
+def test_full_size_causal_prefix_property(fb):
+    """Under the causal mask, outputs at positions < p do not depend on tokens >= p (bitwise)."""
+    w, inp, dev = workload("cfg5_llm_b1_m4096_causal", fb)
+    a = gpu_call(dev, "layer")
+    p = 1500
+    X2 = dev["X"].clone()
+    X2[:, p:] = torch.randn_like(X2[:, p:])
+    a2 = gpu_call(dict(dev, X=X2), "layer")
+    assert torch.equal(a[:, :p], a2[:, :p])
+    assert not torch.equal(a[:, p:], a2[:, p:])
+
+
+# ------------------------------------------------------------------ edge cases
+def _run_custom(fb, w, mutate=None, **desc_kw):
+    inp = W.make_inputs(w)
+    if mutate:
+        mutate(inp)
+    dev = fb.to_device(inp, DEV)
+    if desc_kw:
+        base = dict(B=w.B, M=w.M, D=w.D, H=w.H, F=w.F, io_dtype=dev["X"].dtype, causal=inp["causal"],
+                    key_len=dev["key_len"], norm=w.norm, ln_eps=w.ln_eps)
+        base.update(desc_kw)
+        dev["desc"] = fb.make_desc(**base)
+    return inp, dev
+
+
+def test_single_token_sequences(fb):
+    w = W.get_workload("tiny_h2_d64", B=3, M=1)
+    inp, dev = _run_custom(fb, w)
+    for part in ("attention", "ffn", "layer"):
+        assert rel_err(gpu_call(dev, part).cpu().numpy(), oracle_call(inp, part)) < tol_for(w, part) * 2
+
+
+def test_key_len_one_and_full(fb):
+    w = W.get_workload("tiny_pad")
+    def mut(inp):
+        inp["key_len"][:] = [1, w.M, 97]
+    inp, dev = _run_custom(fb, w, mut)
+    got = gpu_call(dev, "attention").cpu().numpy()
+    ref = oracle_call(inp, "attention")
+    assert rel_err(got, ref) < TOL["attention"]
+    # with a single visible key every context row is that key's value vector
+    v0 = O.factored_linear(O.factored_linear(inp["X"][0, 0], inp["v"]), inp["o"])
+    assert np.abs(got[0] - v0[None, :]).max() < 5e-3 * np.abs(v0).max()
+
+
+def test_causal_and_padding_combined(fb):
+    w = W.get_workload("small_multi_qblock", mask="padding")
+    inp = W.make_inputs(w)
+    inp["causal"] = True
+    dev = fb.to_device(inp, DEV)
+    got = gpu_call(dev, "attention").cpu().numpy()
+    assert rel_err(got, oracle_call(inp, "attention")) < TOL["attention_causal"]
+
+
+def test_ragged_lengths_and_minimum_rank(fb):
+    for M, r in ((33, 16), (129, 16), (257, 32)):
+        w = W.get_workload("tiny_h2_d64", M=M, r_attn=r, r_ffn=16, B=1)
+        inp, dev = _run_custom(fb, w)
+        assert rel_err(gpu_call(dev, "layer").cpu().numpy(), oracle_call(inp, "layer")) < TOL_LAYER
+
+
+def test_no_bias_custom_scale_and_activations(fb):
+    w = W.get_workload("tiny_h2_d64")
+    inp = W.make_inputs(w)
+    dev = fb.to_device(inp, DEV)
+    for n in ("q", "k", "v", "o", "w1", "w2"):
+        inp[n]["b"] = None
+        dev[n].b = None
+    for act in ("gelu_tanh", "relu"):
+        d = fb.make_desc(w.B, w.M, w.D, w.H, w.F, dev["X"].dtype, softmax_scale=0.05, act=act, norm=w.norm)
+        dev["desc"] = d
+        got = gpu_call(dev, "layer").cpu().numpy()
+        a = (inp["q"], inp["k"], inp["v"], inp["o"])
+        ref = O.layer(inp["X"], *a, (inp["ln1_gamma"], inp["ln1_beta"]), inp["w1"], inp["w2"],
+                      (inp["ln2_gamma"], inp["ln2_beta"]), w.H, norm=w.norm, scale=0.05, act=act, eps=w.ln_eps)
+        assert rel_err(got, ref) < TOL_LAYER
+
+
+@pytest.mark.parametrize("odt,eps", [(torch.float16, 2.0 ** -11), (torch.bfloat16, 2.0 ** -8)])
+def test_sixteen_bit_outputs_round_the_fp32_result(fb, odt, eps):
+    w, inp, dev = workload("tiny_pad", fb)
+    ref32 = gpu_call(dev, "layer")
+    d = dev["desc"]
+    d16 = fb.make_desc(w.B, w.M, w.D, w.H, w.F, dev["X"].dtype, out_dtype=odt, key_len=dev["key_len"], norm=w.norm,
+                       ln_eps=w.ln_eps)
+    got = gpu_call(dict(dev, desc=d16), "layer")
+    assert got.dtype == odt
+    assert torch.equal(got, ref32.to(odt))
+
+
+def test_run_to_run_determinism(fb):
+    """No atomics anywhere: two runs are bitwise equal."""
+    w, inp, dev = workload("small_multi_qblock", fb)
+    for part in ("attention", "ffn", "layer"):
+        assert torch.equal(gpu_call(dev, part), gpu_call(dev, part))
+
+
+def test_rank_padding_invariance(fb):
+    """Zero-padding every rank to a larger multiple of 16 leaves the result bitwise unchanged."""
+    w = W.get_workload("tiny_h2_d64")
+    inp = W.make_inputs(w)
+    dev = fb.to_device(inp, DEV)
+    base = gpu_call(dev, "layer")
+    pad = 32
+    for n in ("q", "k", "v", "o", "w1", "w2"):
+        f = dev[n]
+        f.U = torch.nn.functional.pad(f.U, (0, pad)).contiguous()
+        f.V = torch.nn.functional.pad(f.V, (0, 0, 0, pad)).contiguous()
+    assert torch.equal(gpu_call(dev, "layer"), base)

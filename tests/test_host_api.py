@@ -1,0 +1,129 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, validates arguments before touching a device, and sizes workspaces as documented."""
+import ctypes as C
+import os
+import re
+
+import pytest
+import torch
+
+from paper_2508_01506_amd import binding as fb
+from paper_2508_01506_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, INVALID, UNSUPPORTED, WORKSPACE, DEVICE = range(5)
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "fsvd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fsvd_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = fb.lib()
+    names = declared_symbols()
+    assert len(names) >= 14
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in fsvd.h but not exported"
+    assert sorted(fb.EXPORTS) == names
+    assert L.fsvd_version() >= 100
+    for code, frag in [(0, b"ok"), (1, b"invalid"), (2, b"unsupported"), (3, b"workspace"), (4, b"device")]:
+        assert frag in L.fsvd_status_string(code)
+
+
+def desc(**kw):
+    base = dict(B=2, M=128, D=768, H=12, F=3072, io_dtype=torch.float16)
+    base.update(kw)
+    return fb.make_desc(**base)
+
+
+def test_workspace_sizes_follow_the_documented_plan():
+    up = lambda n: (n + 255) // 256 * 256
+    for w in W.WORKLOADS.values():
+        d = fb.make_desc(w.B, w.M, w.D, w.H, w.F, torch.float16, norm=w.norm)
+        T, D, ra, rf = w.T, w.D, w.r_attn, w.r_ffn
+        attn = up(T * D * 2) + max(up(T * 3 * ra * 2), up(T * ra * 2))
+        ffn = up(T * rf * 2) + up(T * rf * 2)
+        assert fb.fsvd_attention_workspace(d, ra, ra, ra, ra) == attn
+        assert fb.fsvd_ffn_workspace(d, rf, rf) == ffn
+        stream = up(T * D * (2 if w.norm == "none" else 4))
+        layer = stream + up(T * D * 2) + max(up(T * 3 * ra * 2), up(T * ra * 2), ffn)
+        assert fb.fsvd_layer_workspace(d, ra, ra, ra, ra, rf, rf) == layer
+        # strictly below the unfused factored layer's transient buffers (same fp16 storage, same reuse):
+        # that path also materialises Q, K, V [T, D] next to P and the hidden [T, F] next to P1 and Z
+        unfused_attn = attn + 3 * T * D * 2
+        unfused_ffn = ffn + T * w.F * 2
+        assert attn < unfused_attn and ffn < unfused_ffn
+        assert layer < stream + up(T * D * 2) + max(up(T * 3 * ra * 2) + 3 * T * D * 2, unfused_ffn)
+
+
+def test_workspace_query_rejects_bad_configurations():
+    assert fb.fsvd_attention_workspace(desc(H=7), 64, 64, 64, 64) == 0          # D % H != 0
+    assert fb.fsvd_attention_workspace(desc(D=96, H=3), 64, 64, 64, 64) == 0    # d_h = 32
+    assert fb.fsvd_attention_workspace(desc(), 60, 64, 64, 64) == 0             # rank not a multiple of 16
+    assert fb.fsvd_ffn_workspace(desc(F=0), 64, 64) == 0
+    assert fb.fsvd_ffn_workspace(desc(B=0), 64, 64) == 0
+    assert fb.fsvd_layer_workspace(desc(), 64, 64, 64, 64, 64, 0) == 0
+    assert fb.fsvd_attention_workspace(desc(), 64, 64, 64, 64) > 0
+
+
+def fac(i, r, o, U=1, V=1):
+    return fb.fsvd_factor(U, V, 0, i, r, o)
+
+
+def test_checks_report_the_documented_status_codes():
+    L = fb.lib()
+    d = desc()
+    good = fac(768, 64, 768)
+    chk = lambda dd, q, k, v, o: L.fsvd_attention_check(C.byref(dd), C.byref(q), C.byref(k), C.byref(v), C.byref(o))
+    assert chk(d, good, good, good, good) == OK
+    assert chk(d, fac(768, 64, 512), good, good, good) == INVALID        # wrong out_dim
+    assert chk(d, good, fac(512, 64, 768), good, good) == INVALID        # wrong in_dim
+    assert chk(d, good, good, fac(768, 0, 768), good) == INVALID         # rank 0
+    assert chk(d, good, good, good, fac(768, 24, 768)) == UNSUPPORTED    # rank % 16
+    assert chk(desc(D=96, H=3), fac(96, 16, 96), fac(96, 16, 96), fac(96, 16, 96), fac(96, 16, 96)) == UNSUPPORTED
+    assert chk(desc(H=5), good, good, good, good) == INVALID
+    assert chk(desc(B=-1), good, good, good, good) == INVALID
+    bad_dtype = desc()
+    bad_dtype.io_dtype = 2
+    assert chk(bad_dtype, good, good, good, good) == INVALID
+    big = desc(B=1 << 15, M=1 << 15)
+    assert chk(big, good, good, good, good) == UNSUPPORTED
+    w1, w2 = fac(768, 64, 3072), fac(3072, 64, 768)
+    assert L.fsvd_ffn_check(C.byref(d), C.byref(w1), C.byref(w2)) == OK
+    assert L.fsvd_ffn_check(C.byref(d), C.byref(w2), C.byref(w1)) == INVALID
+    assert L.fsvd_ffn_check(C.byref(desc(F=3080)), C.byref(fac(768, 64, 3080)), C.byref(fac(3080, 64, 768))) == UNSUPPORTED
+
+
+def test_compute_entry_points_validate_before_any_launch():
+    """Null pointers, short or misaligned workspaces are rejected on the host (no GPU is needed to see it)."""
+    L = fb.lib()
+    d = desc()
+    q = fac(768, 64, 768)
+    need = fb.fsvd_attention_workspace(d, 64, 64, 64, 64)
+    call = lambda X, out, ws, n: L.fsvd_attention(C.byref(d), X, C.byref(q), C.byref(q), C.byref(q), C.byref(q), out, ws, n, None)
+    assert call(None, 256, 256, need) == INVALID
+    assert call(256, None, 256, need) == INVALID
+    assert call(256, 256, None, need) == WORKSPACE
+    assert call(256, 256, 256, need - 1) == WORKSPACE
+    assert call(256, 256, 257, need) == WORKSPACE               # not 256-byte aligned
+    nullU = fac(768, 64, 768, U=0)
+    assert L.fsvd_attention(C.byref(d), 256, C.byref(nullU), C.byref(q), C.byref(q), C.byref(q), 256, 256, need, None) == INVALID
+    w1, w2 = fac(768, 64, 3072), fac(3072, 64, 768)
+    assert L.fsvd_ffn(C.byref(d), 256, C.byref(w1), C.byref(w2), 256, 256, 16, None) == WORKSPACE
+    lneed = fb.fsvd_layer_workspace(d, 64, 64, 64, 64, 64, 64)
+    layer = lambda g1: L.fsvd_layer(C.byref(d), 256, C.byref(q), C.byref(q), C.byref(q), C.byref(q), g1, 256,
+                                    C.byref(w1), C.byref(w2), 256, 256, 256, 256, lneed, None)
+    assert layer(None) == INVALID                               # LayerNorm parameters required unless norm == NONE
+    assert L.fsvd_linear(16, 40, 16, 256, 0, 256, None, 0, None, 0, 256, 0, None) == UNSUPPORTED   # K % 16
+    assert L.fsvd_linear(0, 32, 16, 256, 0, 256, None, 0, None, 0, 256, 0, None) == INVALID
+    assert L.fsvd_layernorm(4, 16384, 256, 0, 256, 256, 0, 1e-5, 256, 2, None) == UNSUPPORTED
+    assert L.fsvd_layernorm(4, 64, None, 0, 256, 256, 0, 1e-5, 256, 2, None) == INVALID
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(fb, "_lib", None)
+    monkeypatch.setattr(fb, "LIB_PATH", "/nonexistent/libfsvd.so")
+    with pytest.raises(FileNotFoundError):
+        fb.lib()
