@@ -1,0 +1,172 @@
+"""Benchmark of the fused low-rank layer on one MI355X.
+
+A step is one pass of the whole hot path — rank projections, streaming attention, factored output
+projection, residual + LayerNorm, fused FFN, residual (+ LayerNorm) — i.e. one fsvd_layer call on one
+batch of synthetic inputs that are already resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+PEAK_MFMA_TFLOPS = 2500.0   # MI355X dense fp16 / bf16 matrix peak
+PEAK_HBM_GBS = 8000.0
+DEFAULT_WORKLOAD = "cfg5_llm_b1_m4096_causal"   # the largest configuration: the one the MFMA-peak target is stated on
+
+
+def useful_flops(w, mean_pairs):
+    """Algorithmic FLOPs of one layer, every tile built once (no recompute counted)."""
+    T, D, F, ra, rf = w.T, w.D, w.F, w.r_attn, w.r_ffn
+    f = {
+        "rank_proj_qkv": 6.0 * T * D * ra,
+        "rebuild_qkv": 6.0 * T * ra * D,
+        "attn_core": 4.0 * D * mean_pairs,
+        "out_proj": 4.0 * T * D * ra,
+        "ffn_in": 2.0 * T * D * rf,
+        "ffn_core": 4.0 * T * rf * F,
+        "ffn_out": 2.0 * T * rf * D,
+    }
+    f["total"] = sum(f.values())
+    return f
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding or collectives exist); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2508_01506_amd import binding as fb
+    from paper_2508_01506_amd import workloads as W
+
+    fb.lib()   # fails loudly if the HIP library is missing
+    w = W.get_workload(args.workload)
+    inp = W.make_inputs(w)
+    dev = fb.to_device(inp, "cuda:0")
+    d = dev["desc"]
+    ra, rf = w.r_attn, w.r_ffn
+    ws_bytes = fb.fsvd_layer_workspace(d, ra, ra, ra, ra, rf, rf)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
+    out = torch.empty((w.B, w.M, w.D), dtype=torch.float32, device="cuda:0")
+
+    def step():
+        fb.fsvd_layer(d, dev["X"], dev["q"], dev["k"], dev["v"], dev["o"], dev["ln1_gamma"], dev["ln1_beta"],
+                      dev["w1"], dev["w2"], dev["ln2_gamma"], dev["ln2_beta"], out=out, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    tokens_per_s = w.T / (ms * 1e-3)
+
+    # ---- attended (query, key) pairs, for the FLOP model
+    if inp["causal"]:
+        pairs = w.B * w.M * (w.M + 1) / 2
+    elif inp["key_len"] is not None:
+        pairs = float(w.M * inp["key_len"].astype(np.int64).sum())
+    else:
+        pairs = float(w.B) * w.M * w.M
+    fl = useful_flops(w, pairs)
+
+    # ---- dominant kernels, timed alone with events on the launch stream, in the launch configuration
+    # the layer uses (same shapes, same dispatch): the fused FFN core and the streaming attention core
+    def timed(fn, n):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    g = torch.Generator(device="cuda:0").manual_seed(1)
+    P1 = torch.randn((w.T, rf), generator=g, device="cuda:0", dtype=torch.float16)
+    Z = torch.empty((w.T, rf), device="cuda:0", dtype=torch.float16)
+    Pq, Pk, Pv = (torch.randn((w.T, ra), generator=g, device="cuda:0", dtype=torch.float16) for _ in range(3))
+    Cx = torch.empty((w.B, w.M, w.D), device="cuda:0", dtype=torch.float16)
+    n_k = max(3, min(args.steps, 20))
+    ffn_ms = timed(lambda: fb.fsvd_ffn_core(d, P1, dev["w1"], dev["w2"], out=Z), n_k)
+    attn_ms = timed(lambda: fb.fsvd_attention_core(d, Pq, Pk, Pv, dev["q"], dev["k"], dev["v"], out=Cx), n_k)
+    if ffn_ms >= attn_ms:
+        kname, kflops, kms = "ffn_core_kernel", fl["ffn_core"], ffn_ms
+    else:
+        kname, kflops, kms = "attn_core_kernel", fl["rebuild_qkv"] + fl["attn_core"], attn_ms
+    achieved = kflops / (kms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": kname, "achieved": round(achieved, 2), "peak": PEAK_MFMA_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_TFLOPS, 4), "traffic": None,
+                "kernel_ms": round(kms, 4), "algorithmic_flops": kflops,
+                "other_kernel_ms": {"ffn_core_kernel": round(ffn_ms, 4), "attn_core_kernel": round(attn_ms, 4)}}
+
+    # ---- transient memory: the caller's workspace is the only scratch the library uses
+    T, D, F = w.T, w.D, w.F
+    stream_bytes = T * D * (2 if w.norm == "none" else 4)
+    unfused = stream_bytes + T * D * 2 + max(T * 3 * ra * 2 + 3 * T * D * 2, 2 * T * rf * 2 + T * F * 2)
+    result = {
+        "metric": "fused low-rank layer tokens/s + peak transient activation MB; % MFMA peak",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "M": w.M, "D": w.D, "H": w.H, "F": w.F, "r_attn": ra, "r_ffn": rf,
+                   "storage": w.dtype, "mask": w.mask, "norm": w.norm},
+        "useful_tflops": round(fl["total"] / (ms * 1e-3) / 1e12, 2),
+        "mfma_peak_frac": round(fl["total"] / (ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS, 4),
+        "transient_mb": round(ws_bytes / 2 ** 20, 2), "unfused_transient_mb": round(unfused / 2 ** 20, 2),
+        "roofline": roofline,
+    }
+
+    # ---- the CPU oracle on a bounded sample of the same workload (a reported baseline, not the target)
+    if not args.no_cpu_baseline:
+        from fsvd_testing import oracle_rows
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            threads = len(os.sched_getaffinity(0))
+        n_rows = w.M if w.M <= 4096 else 1024
+        rows = np.arange(w.M - n_rows, w.M)
+        done, dt, err, seqs = 0, 0.0, 0.0, []
+        for b in range(w.B - 1, -1, -1):        # whole sequences until about 10 s of CPU work are spent
+            t0 = time.perf_counter()
+            ref = oracle_rows(inp, b, rows, "layer")
+            dt += time.perf_counter() - t0
+            got = out[b, w.M - n_rows:].cpu().numpy()
+            err = max(err, float(np.abs(got - ref).max() / np.sqrt(np.mean(ref ** 2))))
+            done += n_rows
+            seqs.append(b)
+            if dt > 10.0:
+                break
+        result["cpu_baseline"] = {"value": round(done / dt, 1), "unit": "tokens/s", "cores": int(threads),
+                                  "kind": "oracle",
+                                  "sample": f"last {n_rows} query rows (keys/values of the whole sequence) of "
+                                            f"{len(seqs)} sequence(s) {seqs[-1]}..{seqs[0]}, fp64 numpy, {dt:.1f} s"}
+        result["max_err_over_rms_vs_oracle_sample"] = float(f"{err:.3e}")
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
