@@ -39,7 +39,8 @@
  *  - Limits.  D % H == 0 and d_h in {64, 128}; D, F and every rank are
  *    multiples of 16 (a rank that is not can be zero-padded by the caller,
  *    which leaves the result unchanged: Alg. 1 Part I pads the rank the same
- *    way); B*M < 2^31 / max(D, F); key_len[b] in [1, M].
+ *    way); B*M*max(D, F) < 2^29 and every tensor smaller than 2 GiB;
+ *    key_len[b] in [1, M].
  */
 #ifndef FSVD_H
 #define FSVD_H
@@ -147,7 +148,7 @@ fsvd_status fsvd_layer(const fsvd_desc *desc, const void *X, const fsvd_factor *
 /* ------------------------------------------------------------------------------------------
  * Building blocks.  The three entry points above are sequences of these steps; they are exported
  * so that each kernel can be checked and timed on its own.  Same pointer, stream and error
- * conventions; tensors are contiguous (row stride = number of columns); none needs a workspace.
+ * conventions; row-major tensors are contiguous (row stride = number of columns); none needs a workspace.
  * ------------------------------------------------------------------------------------------ */
 
 /* C[T, N] = A[T, K] W[K, N] (+ bias[N]) (+ residual[T, N]): the rank projection P = X U, the
@@ -159,19 +160,33 @@ fsvd_status fsvd_linear(int32_t T, int32_t K, int32_t N, const void *A, fsvd_dty
                         const void *bias, fsvd_dtype w_dtype, const void *residual, fsvd_dtype r_dtype,
                         void *C, fsvd_dtype c_dtype, void *hip_stream);
 
-/* Alg. 1 Part II on rank-space inputs: Pq [B*M, q->rank], Pk, Pv (fp16) and the V / bias members of
- * q, k, v (their U members are ignored) -> context [B*M, D] (fp16, heads concatenated). */
+/*
+ * Fragment-major ("FM") layout.  Inside the library every activation that feeds a matrix-core
+ * contraction is fp16 in this layout, and the two kernels below take and return it.  For A [T, K]:
+ * tokens are grouped in tiles of 32 and the contraction axis in chunks of 64 (both zero- or
+ * garbage-padded); block (tile, chunk) occupies 4 KiB at ((tile * ceil(K/64)) + chunk) * 4096 and holds,
+ * for step kk = 0..3, 64 units of 16 bytes: unit kk * 64 + 32 g + (t % 32) stores
+ * A[t, 64 chunk + 32 g + 8 kk + 0..7].  fsvd_fm_bytes gives the buffer size (0 if K % 8 != 0);
+ * fsvd_pack_fm converts a contiguous row-major [T, K] tensor (F16, BF16 or F32) and zero-fills the
+ * padding; fsvd_unpack_fm converts back to row-major (F16, BF16 or F32).
+ */
+size_t fsvd_fm_bytes(int32_t T, int32_t K);
+fsvd_status fsvd_pack_fm(int32_t T, int32_t K, const void *src, fsvd_dtype src_dtype, void *dst_fm, void *hip_stream);
+fsvd_status fsvd_unpack_fm(int32_t T, int32_t K, const void *src_fm, void *dst, fsvd_dtype dst_dtype, void *hip_stream);
+
+/* Alg. 1 Part II on rank-space inputs: Pq [B*M, q->rank], Pk, Pv (FM) and the V / bias members of
+ * q, k, v (their U members are ignored) -> context [B*M, D] (FM, heads concatenated). */
 fsvd_status fsvd_attention_core(const fsvd_desc *desc, const void *Pq, const void *Pk, const void *Pv,
                                 const fsvd_factor *q, const fsvd_factor *k, const fsvd_factor *v,
                                 void *context, void *hip_stream);
 
-/* The on-chip loops of Alg. 2: P1 [B*M, w1->rank] (fp16), V / bias of w1 and U of w2 -> Z [B*M, w2->rank]
- * (fp16) with Z = phi(P1 V_1 + b_1) U_2. */
+/* The on-chip loops of Alg. 2: P1 [B*M, w1->rank] (FM), V / bias of w1 and U of w2 -> Z [B*M, w2->rank]
+ * (FM) with Z = phi(P1 V_1 + b_1) U_2. */
 fsvd_status fsvd_ffn_core(const fsvd_desc *desc, const void *P1, const fsvd_factor *w1, const fsvd_factor *w2,
                           void *Z, void *hip_stream);
 
 /* Y[T, D] = gamma (X - mean) / sqrt(var + eps) + beta per row; X in x_dtype, gamma / beta in p_dtype,
- * Y in y_dtype (any of F16, BF16, F32).  D <= 8192. */
+ * Y in y_dtype (any of F16, BF16, F32).  D <= 8192, D % 8 == 0. */
 fsvd_status fsvd_layernorm(int32_t T, int32_t D, const void *X, fsvd_dtype x_dtype, const void *gamma,
                            const void *beta, fsvd_dtype p_dtype, float eps, void *Y, fsvd_dtype y_dtype,
                            void *hip_stream);

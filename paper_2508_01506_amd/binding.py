@@ -28,7 +28,8 @@ _TORCH2FSVD = {torch.float16: FSVD_F16, torch.bfloat16: FSVD_BF16, torch.float32
 
 EXPORTS = ["fsvd_attention_workspace", "fsvd_ffn_workspace", "fsvd_layer_workspace", "fsvd_attention_check",
            "fsvd_ffn_check", "fsvd_attention", "fsvd_ffn", "fsvd_layer", "fsvd_linear", "fsvd_attention_core",
-           "fsvd_ffn_core", "fsvd_layernorm", "fsvd_status_string", "fsvd_version"]
+           "fsvd_ffn_core", "fsvd_layernorm", "fsvd_status_string", "fsvd_version", "fsvd_fm_bytes", "fsvd_pack_fm",
+           "fsvd_unpack_fm"]
 
 
 class FsvdError(RuntimeError):
@@ -85,6 +86,12 @@ def lib():
         L.fsvd_ffn_core.argtypes = [D, P, F, F, P, P]
         L.fsvd_layernorm.restype = C.c_int
         L.fsvd_layernorm.argtypes = [i32, i32, P, C.c_int, P, P, C.c_int, C.c_float, P, C.c_int, P]
+        L.fsvd_fm_bytes.restype = sz
+        L.fsvd_fm_bytes.argtypes = [i32, i32]
+        L.fsvd_pack_fm.restype = C.c_int
+        L.fsvd_pack_fm.argtypes = [i32, i32, P, C.c_int, P, P]
+        L.fsvd_unpack_fm.restype = C.c_int
+        L.fsvd_unpack_fm.argtypes = [i32, i32, P, P, C.c_int, P]
         L.fsvd_status_string.restype = C.c_char_p
         L.fsvd_status_string.argtypes = [C.c_int]
         L.fsvd_version.restype = i32
@@ -210,9 +217,30 @@ def fsvd_linear(A, W, bias=None, residual=None, out_dtype=torch.float16, out=Non
     return out
 
 
-def fsvd_attention_core(desc, Pq, Pk, Pv, q: Factor, k: Factor, v: Factor, out=None):
+def fsvd_fm_bytes(T, K) -> int:
+    return lib().fsvd_fm_bytes(T, K)
+
+
+def fsvd_pack_fm(src, out=None):
+    """Row-major [T, K] (fp16 / bf16 / fp32) -> fragment-major fp16 buffer (uint8 tensor)."""
+    T, K = src.shape
     if out is None:
-        out = torch.empty((desc.B, desc.M, desc.D), dtype=torch.float16, device=Pq.device)
+        out = torch.empty(fsvd_fm_bytes(T, K), dtype=torch.uint8, device=src.device)
+    _check(lib().fsvd_pack_fm(T, K, _ptr(src), _TORCH2FSVD[src.dtype], _ptr(out), _stream()), "fsvd_pack_fm")
+    return out
+
+
+def fsvd_unpack_fm(src_fm, T, K, out_dtype=torch.float16, out=None):
+    if out is None:
+        out = torch.empty((T, K), dtype=out_dtype, device=src_fm.device)
+    _check(lib().fsvd_unpack_fm(T, K, _ptr(src_fm), _ptr(out), _TORCH2FSVD[out.dtype], _stream()), "fsvd_unpack_fm")
+    return out
+
+
+def fsvd_attention_core(desc, Pq, Pk, Pv, q: Factor, k: Factor, v: Factor, out=None):
+    """Pq, Pk, Pv and the returned context are fragment-major buffers (see fsvd_pack_fm / fsvd_unpack_fm)."""
+    if out is None:
+        out = torch.empty(fsvd_fm_bytes(desc.B * desc.M, desc.D), dtype=torch.uint8, device=Pq.device)
     fq, fk, fv = q.c(), k.c(), v.c()
     _check(lib().fsvd_attention_core(C.byref(desc), _ptr(Pq), _ptr(Pk), _ptr(Pv), C.byref(fq), C.byref(fk),
                                      C.byref(fv), _ptr(out), _stream()), "fsvd_attention_core")
@@ -220,8 +248,9 @@ def fsvd_attention_core(desc, Pq, Pk, Pv, q: Factor, k: Factor, v: Factor, out=N
 
 
 def fsvd_ffn_core(desc, P1, w1: Factor, w2: Factor, out=None):
+    """P1 and the returned Z are fragment-major buffers."""
     if out is None:
-        out = torch.empty((desc.B * desc.M, w2.rank), dtype=torch.float16, device=P1.device)
+        out = torch.empty(fsvd_fm_bytes(desc.B * desc.M, w2.rank), dtype=torch.uint8, device=P1.device)
     f1, f2 = w1.c(), w2.c()
     _check(lib().fsvd_ffn_core(C.byref(desc), _ptr(P1), C.byref(f1), C.byref(f2), _ptr(out), _stream()),
            "fsvd_ffn_core")

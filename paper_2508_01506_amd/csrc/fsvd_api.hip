@@ -28,7 +28,7 @@ fsvd_status check_desc(const fsvd_desc* d, bool need_ffn) {
   if (d->D % 16 != 0 || d->D > 8192) return FSVD_ERR_UNSUPPORTED;
   if (need_ffn && d->F % 16 != 0) return FSVD_ERR_UNSUPPORTED;
   const long long widest = need_ffn && d->F > d->D ? d->F : d->D;
-  if ((long long)d->B * d->M * widest >= (1LL << 31)) return FSVD_ERR_UNSUPPORTED;
+  if ((long long)d->B * d->M * widest >= (1LL << 29)) return FSVD_ERR_UNSUPPORTED;   // every tensor < 2 GiB
   return FSVD_OK;
 }
 
@@ -44,6 +44,8 @@ fsvd_status check_factor(const fsvd_factor* f, int in_dim, int out_dim, bool nee
   if (f->in_dim != in_dim || f->out_dim != out_dim) return FSVD_ERR_INVALID_ARG;
   fsvd_status s = check_rank(f->rank);
   if (s != FSVD_OK) return s;
+  const long long widest = in_dim > out_dim ? in_dim : out_dim;
+  if ((long long)f->rank * widest >= (1LL << 29)) return FSVD_ERR_UNSUPPORTED;   // each factor < 1 GiB
   if (need_u && !f->U) return FSVD_ERR_INVALID_ARG;
   if (need_v && !f->V) return FSVD_ERR_INVALID_ARG;
   return FSVD_OK;
@@ -72,22 +74,27 @@ fsvd_status check_ws(const void* ws, size_t have, size_t need) {
   return FSVD_OK;
 }
 
-// ---- workspace plans (bytes); all intermediates are fp16 except the fp32 residual stream
-struct AttnPlan { size_t c, p, to, total; };   // offsets of C, P (packed q|k|v), T_o; T_o aliases P
+// ---- workspace plans (bytes).  Every intermediate that feeds a matrix-core contraction is fp16 in the
+// fragment-major layout (fm_bytes pads tokens to 32 and the contraction axis to 64); the residual stream is fp32.
+struct AttnPlan { size_t c, p, pq, pk, pv, to, total; };   // C (also the packed X); P_q | P_k | P_v; T_o aliases P
 AttnPlan plan_attn(size_t T, size_t D, size_t rq, size_t rk, size_t rv, size_t ro) {
   AttnPlan pl;
   pl.c = 0;
-  pl.p = align_up(T * D * 2);
+  pl.p = align_up(fm_bytes(T, D));
+  pl.pq = pl.p;
+  pl.pk = pl.pq + align_up(fm_bytes(T, rq));
+  pl.pv = pl.pk + align_up(fm_bytes(T, rk));
+  const size_t p_end = pl.pv + align_up(fm_bytes(T, rv));
   pl.to = pl.p;
-  pl.total = pl.p + smax(align_up(T * (rq + rk + rv) * 2), align_up(T * ro * 2));
+  pl.total = smax(p_end, pl.to + align_up(fm_bytes(T, ro)));
   return pl;
 }
 struct FfnPlan { size_t p1, z, total; };
 FfnPlan plan_ffn(size_t T, size_t r1, size_t r2) {
   FfnPlan pl;
   pl.p1 = 0;
-  pl.z = align_up(T * r1 * 2);
-  pl.total = pl.z + align_up(T * r2 * 2);
+  pl.z = align_up(fm_bytes(T, r1));
+  pl.total = pl.z + align_up(fm_bytes(T, r2));
   return pl;
 }
 
@@ -95,87 +102,92 @@ float resolve_scale(const fsvd_desc* d) {
   return d->softmax_scale > 0.f ? d->softmax_scale : 1.0f / sqrtf((float)(d->D / d->H));
 }
 
-// Attention block on `A_in` (a_dt) -> `out` (c_dt), optional residual added in the last epilogue.
-// `scratch` holds C | max(P, T_o); `c_buf` overrides the location of C when non-null.
-fsvd_status run_attention(const fsvd_desc* d, const void* A_in, int a_dt, const fsvd_factor* q, const fsvd_factor* k,
+// Attention block.  `x_fm`: the block input, fragment-major fp16 [T, D] (it may live in c_buf: the context
+// overwrites it only after the rank projection has consumed it).  c_buf: FM [T, D]; rank_buf: P_q | P_k | P_v, later T_o.
+// The last GEMM writes `out` row-major in c_dt (+ residual) or, when out_fm is set, fragment-major fp16.
+fsvd_status run_attention(const fsvd_desc* d, const void* x_fm, const fsvd_factor* q, const fsvd_factor* k,
                           const fsvd_factor* v, const fsvd_factor* o, const void* residual, int r_dt, void* out,
-                          int c_dt, char* c_buf, char* rank_buf, hipStream_t s) {
+                          int c_dt, bool out_fm, char* c_buf, char* rank_buf, hipStream_t s) {
   const int T = d->B * d->M, D = d->D;
-  const int rtot = q->rank + k->rank + v->rank;
-  _Float16* P = (_Float16*)rank_buf;
-  _Float16* C = (_Float16*)c_buf;
-  _Float16* To = (_Float16*)rank_buf;   // P is dead once the context is complete
+  const AttnPlan pl = plan_attn(T, D, q->rank, k->rank, v->rank, o->rank);
+  char* Pq = rank_buf;
+  char* Pk = rank_buf + (pl.pk - pl.p);
+  char* Pv = rank_buf + (pl.pv - pl.p);
+  char* To = rank_buf;   // P is dead once the context is complete
 
   LinearArgs h1{};
-  h1.A = A_in; h1.lda = D; h1.a_dt = a_dt; h1.T = T; h1.K = D; h1.w_dt = d->io_dtype; h1.c_dt = DT_F16;
-  h1.R = nullptr; h1.ngroups = 3;
-  h1.g[0] = {q->U, nullptr, P, q->rank, q->rank, rtot};
-  h1.g[1] = {k->U, nullptr, P + q->rank, k->rank, k->rank, rtot};
-  h1.g[2] = {v->U, nullptr, P + q->rank + k->rank, v->rank, v->rank, rtot};
+  h1.A = x_fm; h1.a_layout = LAYOUT_FM; h1.lda = D; h1.a_dt = DT_F16; h1.T = T; h1.K = D; h1.w_dt = d->io_dtype;
+  h1.c_layout = LAYOUT_FM; h1.c_dt = DT_F16; h1.R = nullptr; h1.ngroups = 3;
+  h1.g[0] = {q->U, nullptr, Pq, q->rank, q->rank, 0};
+  h1.g[1] = {k->U, nullptr, Pk, k->rank, k->rank, 0};
+  h1.g[2] = {v->U, nullptr, Pv, v->rank, v->rank, 0};
   FSVD_HIP(launch_linear(h1, s));
 
   AttnCoreArgs ca{};
-  ca.Pq = P; ca.Pk = P + q->rank; ca.Pv = P + q->rank + k->rank;
-  ca.ldpq = ca.ldpk = ca.ldpv = rtot;
+  ca.Pq = Pq; ca.Pk = Pk; ca.Pv = Pv;
   ca.rq = q->rank; ca.rk = k->rank; ca.rv = v->rank;
   ca.Vq = q->V; ca.Vk = k->V; ca.Vv = v->V;
   ca.bq = q->bias; ca.bk = k->bias; ca.bv = v->bias;
   ca.w_dt = d->io_dtype;
   ca.B = d->B; ca.M = d->M; ca.D = D; ca.H = d->H;
   ca.causal = d->causal; ca.key_len = d->key_len; ca.scale = resolve_scale(d);
-  ca.C = C; ca.ldc = D;
+  ca.C = c_buf;
   FSVD_HIP(launch_attn_core(ca, s));
 
   LinearArgs h3a{};
-  h3a.A = C; h3a.lda = D; h3a.a_dt = DT_F16; h3a.T = T; h3a.K = D; h3a.w_dt = d->io_dtype; h3a.c_dt = DT_F16;
-  h3a.ngroups = 1;
-  h3a.g[0] = {o->U, nullptr, To, o->rank, o->rank, o->rank};
+  h3a.A = c_buf; h3a.a_layout = LAYOUT_FM; h3a.lda = D; h3a.a_dt = DT_F16; h3a.T = T; h3a.K = D; h3a.w_dt = d->io_dtype;
+  h3a.c_layout = LAYOUT_FM; h3a.c_dt = DT_F16; h3a.ngroups = 1;
+  h3a.g[0] = {o->U, nullptr, To, o->rank, o->rank, 0};
   FSVD_HIP(launch_linear(h3a, s));
 
   LinearArgs h3b{};
-  h3b.A = To; h3b.lda = o->rank; h3b.a_dt = DT_F16; h3b.T = T; h3b.K = o->rank; h3b.w_dt = d->io_dtype; h3b.c_dt = c_dt;
+  h3b.A = To; h3b.a_layout = LAYOUT_FM; h3b.lda = o->rank; h3b.a_dt = DT_F16; h3b.T = T; h3b.K = o->rank;
+  h3b.w_dt = d->io_dtype; h3b.c_layout = out_fm ? LAYOUT_FM : LAYOUT_ROW; h3b.c_dt = c_dt;
   h3b.R = residual; h3b.ldr = D; h3b.r_dt = r_dt; h3b.ngroups = 1;
   h3b.g[0] = {o->V, o->bias, out, D, D, D};
   FSVD_HIP(launch_linear(h3b, s));
   return FSVD_OK;
 }
 
-fsvd_status run_ffn(const fsvd_desc* d, const void* A_in, int a_dt, const fsvd_factor* w1, const fsvd_factor* w2,
-                    const void* residual, int r_dt, void* out, int c_dt, char* scratch, hipStream_t s) {
+// FFN block on `A_in` (fragment-major fp16, or row-major in a_dt) -> row-major `out` in c_dt (+ residual).
+fsvd_status run_ffn(const fsvd_desc* d, const void* A_in, int a_layout, int a_dt, const fsvd_factor* w1,
+                    const fsvd_factor* w2, const void* residual, int r_dt, void* out, int c_dt, char* scratch,
+                    hipStream_t s) {
   const int T = d->B * d->M, D = d->D;
   const FfnPlan pl = plan_ffn(T, w1->rank, w2->rank);
-  _Float16* P1 = (_Float16*)(scratch + pl.p1);
-  _Float16* Z = (_Float16*)(scratch + pl.z);
+  char* P1 = scratch + pl.p1;
+  char* Z = scratch + pl.z;
 
   LinearArgs h5{};
-  h5.A = A_in; h5.lda = D; h5.a_dt = a_dt; h5.T = T; h5.K = D; h5.w_dt = d->io_dtype; h5.c_dt = DT_F16; h5.ngroups = 1;
-  h5.g[0] = {w1->U, nullptr, P1, w1->rank, w1->rank, w1->rank};
+  h5.A = A_in; h5.a_layout = a_layout; h5.lda = D; h5.a_dt = a_dt; h5.T = T; h5.K = D; h5.w_dt = d->io_dtype;
+  h5.c_layout = LAYOUT_FM; h5.c_dt = DT_F16; h5.ngroups = 1;
+  h5.g[0] = {w1->U, nullptr, P1, w1->rank, w1->rank, 0};
   FSVD_HIP(launch_linear(h5, s));
 
   FfnCoreArgs fa{};
-  fa.P1 = P1; fa.ldp = w1->rank; fa.r1 = w1->rank; fa.V1 = w1->V; fa.b1 = w1->bias; fa.U2 = w2->U; fa.r2 = w2->rank;
-  fa.w_dt = d->io_dtype; fa.T = T; fa.F = d->F; fa.act = d->act; fa.Z = Z; fa.ldz = w2->rank;
+  fa.P1 = P1; fa.r1 = w1->rank; fa.V1 = w1->V; fa.b1 = w1->bias; fa.U2 = w2->U; fa.r2 = w2->rank;
+  fa.w_dt = d->io_dtype; fa.T = T; fa.F = d->F; fa.act = d->act; fa.Z = Z;
   FSVD_HIP(launch_ffn_core(fa, s));
 
   LinearArgs h7{};
-  h7.A = Z; h7.lda = w2->rank; h7.a_dt = DT_F16; h7.T = T; h7.K = w2->rank; h7.w_dt = d->io_dtype; h7.c_dt = c_dt;
-  h7.R = residual; h7.ldr = D; h7.r_dt = r_dt; h7.ngroups = 1;
+  h7.A = Z; h7.a_layout = LAYOUT_FM; h7.lda = w2->rank; h7.a_dt = DT_F16; h7.T = T; h7.K = w2->rank; h7.w_dt = d->io_dtype;
+  h7.c_layout = LAYOUT_ROW; h7.c_dt = c_dt; h7.R = residual; h7.ldr = D; h7.r_dt = r_dt; h7.ngroups = 1;
   h7.g[0] = {w2->V, w2->bias, out, D, D, D};
   FSVD_HIP(launch_linear(h7, s));
   return FSVD_OK;
 }
 
-// layer workspace: [stream: fp32 [T, D] (POST_LN, PRE_LN) or fp16 [T, D] (NONE)] [C / normalised copy: fp16 [T, D]]
-//                  [rank scratch: max(P, T_o, P1 + Z)]
+// layer workspace: [residual stream: fp32 [T, D] row-major (absent for NORM_NONE)] [FM [T, D]: packed input / context /
+// normalised copy] [rank scratch: max(P_q|P_k|P_v, T_o, P1 + Z)]
 struct LayerPlan { size_t stream, c, rank, total; };
 LayerPlan plan_layer(const fsvd_desc* d, size_t rq, size_t rk, size_t rv, size_t ro, size_t r1, size_t r2) {
   const size_t T = (size_t)d->B * d->M, D = d->D;
   LayerPlan pl;
   pl.stream = 0;
-  pl.c = align_up(T * D * (d->norm == FSVD_NORM_NONE ? 2 : 4));
-  pl.rank = pl.c + align_up(T * D * 2);
-  const size_t attn_rank = smax(align_up(T * (rq + rk + rv) * 2), align_up(T * ro * 2));
-  pl.total = pl.rank + smax(attn_rank, plan_ffn(T, r1, r2).total);
+  pl.c = d->norm == FSVD_NORM_NONE ? 0 : align_up(T * D * 4);
+  pl.rank = pl.c + align_up(fm_bytes(T, D));
+  const AttnPlan ap = plan_attn(T, D, rq, rk, rv, ro);
+  pl.total = pl.rank + smax(ap.total - ap.p, plan_ffn(T, r1, r2).total);
   return pl;
 }
 
@@ -224,10 +236,13 @@ fsvd_status fsvd_attention(const fsvd_desc* d, const void* X, const fsvd_factor*
                            const fsvd_factor* v, const fsvd_factor* o, void* out, void* ws, size_t ws_bytes, void* stream) {
   FSVD_TRY(check_attn(d, q, k, v, o, true));
   if (!X || !out) return FSVD_ERR_INVALID_ARG;
-  const AttnPlan pl = plan_attn((size_t)d->B * d->M, d->D, q->rank, k->rank, v->rank, o->rank);
+  const int T = d->B * d->M;
+  const AttnPlan pl = plan_attn(T, d->D, q->rank, k->rank, v->rank, o->rank);
   FSVD_TRY(check_ws(ws, ws_bytes, pl.total));
+  hipStream_t s = (hipStream_t)stream;
   char* w = (char*)ws;
-  return run_attention(d, X, d->io_dtype, q, k, v, o, nullptr, 0, out, d->out_dtype, w + pl.c, w + pl.p, (hipStream_t)stream);
+  FSVD_HIP(launch_pack_fm(X, d->io_dtype, T, d->D, w + pl.c, s));
+  return run_attention(d, w + pl.c, q, k, v, o, nullptr, 0, out, d->out_dtype, false, w + pl.c, w + pl.p, s);
 }
 
 fsvd_status fsvd_ffn(const fsvd_desc* d, const void* X, const fsvd_factor* w1, const fsvd_factor* w2, void* out,
@@ -235,7 +250,7 @@ fsvd_status fsvd_ffn(const fsvd_desc* d, const void* X, const fsvd_factor* w1, c
   FSVD_TRY(check_ffn(d, w1, w2, true));
   if (!X || !out) return FSVD_ERR_INVALID_ARG;
   FSVD_TRY(check_ws(ws, ws_bytes, plan_ffn((size_t)d->B * d->M, w1->rank, w2->rank).total));
-  return run_ffn(d, X, d->io_dtype, w1, w2, nullptr, 0, out, d->out_dtype, (char*)ws, (hipStream_t)stream);
+  return run_ffn(d, X, LAYOUT_ROW, d->io_dtype, w1, w2, nullptr, 0, out, d->out_dtype, (char*)ws, (hipStream_t)stream);
 }
 
 fsvd_status fsvd_layer(const fsvd_desc* d, const void* X, const fsvd_factor* q, const fsvd_factor* k,
@@ -256,31 +271,32 @@ fsvd_status fsvd_layer(const fsvd_desc* d, const void* X, const fsvd_factor* q, 
   const int T = d->B * d->M, D = d->D;
   const int io = d->io_dtype;
 
-  auto ln = [&](const void* x, int x_dt, const void* gm, const void* bt, void* y, int y_dt) -> fsvd_status {
+  auto ln = [&](const void* x, int x_dt, const void* gm, const void* bt, void* y_row, int y_dt, void* y_fm) -> fsvd_status {
     LayerNormArgs la{};
-    la.X = x; la.x_dt = x_dt; la.ldx = D; la.gamma = gm; la.beta = bt; la.p_dt = io; la.eps = d->ln_eps;
-    la.T = T; la.D = D; la.Y0 = y; la.y0_dt = y_dt; la.ldy0 = D; la.Y1 = nullptr;
+    la.X = x; la.x_dt = x_dt; la.gamma = gm; la.beta = bt; la.p_dt = io; la.eps = d->ln_eps;
+    la.T = T; la.D = D; la.Yrow = y_row; la.yrow_dt = y_dt; la.Yfm = y_fm;
     FSVD_HIP(launch_layernorm(la, s));
     return FSVD_OK;
   };
 
   if (d->norm == FSVD_NORM_POST_LN) {
-    // S1 = X + Attn(X) -> Y1 = LN1(S1) in place (fp32); S2 = Y1 + FFN(Y1) in place; out = LN2(S2)
-    FSVD_TRY(run_attention(d, X, io, q, k, v, o, X, io, stream_buf, DT_F32, c_buf, rank_buf, s));
-    FSVD_TRY(ln(stream_buf, DT_F32, g1, b1, stream_buf, DT_F32));
-    FSVD_TRY(run_ffn(d, stream_buf, DT_F32, w1, w2, stream_buf, DT_F32, stream_buf, DT_F32, rank_buf, s));
-    FSVD_TRY(ln(stream_buf, DT_F32, g2, b2, out, d->out_dtype));
+    // S1 = X + Attn(X) (fp32 stream) -> Y1 = LN1(S1) in place + FM copy -> S2 = Y1 + FFN(Y1) in place -> out = LN2(S2)
+    FSVD_HIP(launch_pack_fm(X, io, T, D, c_buf, s));
+    FSVD_TRY(run_attention(d, c_buf, q, k, v, o, X, io, stream_buf, DT_F32, false, c_buf, rank_buf, s));
+    FSVD_TRY(ln(stream_buf, DT_F32, g1, b1, stream_buf, DT_F32, c_buf));
+    FSVD_TRY(run_ffn(d, c_buf, LAYOUT_FM, DT_F16, w1, w2, stream_buf, DT_F32, stream_buf, DT_F32, rank_buf, s));
+    FSVD_TRY(ln(stream_buf, DT_F32, g2, b2, out, d->out_dtype, nullptr));
   } else if (d->norm == FSVD_NORM_PRE_LN) {
-    // N1 = LN1(X) (fp16, in the context buffer, dead before the context is written)
-    // X1 = X + Attn(N1) (fp32 stream); N2 = LN2(X1) (fp16, context buffer again); out = X1 + FFN(N2)
-    FSVD_TRY(ln(X, io, g1, b1, c_buf, DT_F16));
-    // the attention core overwrites c_buf with the context only after the rank projection has consumed N1
-    FSVD_TRY(run_attention(d, c_buf, DT_F16, q, k, v, o, X, io, stream_buf, DT_F32, c_buf, rank_buf, s));
-    FSVD_TRY(ln(stream_buf, DT_F32, g2, b2, c_buf, DT_F16));
-    FSVD_TRY(run_ffn(d, c_buf, DT_F16, w1, w2, stream_buf, DT_F32, out, d->out_dtype, rank_buf, s));
+    // N1 = LN1(X) (FM) -> X1 = X + Attn(N1) (fp32 stream) -> N2 = LN2(X1) (FM) -> out = X1 + FFN(N2)
+    FSVD_TRY(ln(X, io, g1, b1, nullptr, 0, c_buf));
+    FSVD_TRY(run_attention(d, c_buf, q, k, v, o, X, io, stream_buf, DT_F32, false, c_buf, rank_buf, s));
+    FSVD_TRY(ln(stream_buf, DT_F32, g2, b2, nullptr, 0, c_buf));
+    FSVD_TRY(run_ffn(d, c_buf, LAYOUT_FM, DT_F16, w1, w2, stream_buf, DT_F32, out, d->out_dtype, rank_buf, s));
   } else {
-    FSVD_TRY(run_attention(d, X, io, q, k, v, o, nullptr, 0, stream_buf, DT_F16, c_buf, rank_buf, s));
-    FSVD_TRY(run_ffn(d, stream_buf, DT_F16, w1, w2, nullptr, 0, out, d->out_dtype, rank_buf, s));
+    // out = FFN(Attn(X)): the attention output goes straight into the FM buffer that feeds the FFN
+    FSVD_HIP(launch_pack_fm(X, io, T, D, c_buf, s));
+    FSVD_TRY(run_attention(d, c_buf, q, k, v, o, nullptr, 0, c_buf, DT_F16, true, c_buf, rank_buf, s));
+    FSVD_TRY(run_ffn(d, c_buf, LAYOUT_FM, DT_F16, w1, w2, nullptr, 0, out, d->out_dtype, rank_buf, s));
   }
   return FSVD_OK;
 }
@@ -292,12 +308,31 @@ fsvd_status fsvd_linear(int32_t T, int32_t K, int32_t N, const void* A, fsvd_dty
   if (T <= 0 || K <= 0 || N <= 0 || !A || !W || !C) return FSVD_ERR_INVALID_ARG;
   if (!dtype_ok(a_dtype) || !dtype_ok16(w_dtype) || !dtype_ok(c_dtype) || (residual && !dtype_ok(r_dtype))) return FSVD_ERR_INVALID_ARG;
   if (K % 16 != 0 || N % 16 != 0) return FSVD_ERR_UNSUPPORTED;
-  if ((long long)T * (K > N ? K : N) >= (1LL << 31)) return FSVD_ERR_UNSUPPORTED;
+  if ((long long)T * (K > N ? K : N) >= (1LL << 29)) return FSVD_ERR_UNSUPPORTED;
   LinearArgs a{};
-  a.A = A; a.lda = K; a.a_dt = a_dtype; a.T = T; a.K = K; a.w_dt = w_dtype; a.c_dt = c_dtype;
-  a.R = residual; a.ldr = N; a.r_dt = r_dtype; a.ngroups = 1;
+  a.A = A; a.a_layout = LAYOUT_ROW; a.lda = K; a.a_dt = a_dtype; a.T = T; a.K = K; a.w_dt = w_dtype;
+  a.c_layout = LAYOUT_ROW; a.c_dt = c_dtype; a.R = residual; a.ldr = N; a.r_dt = r_dtype; a.ngroups = 1;
   a.g[0] = {W, bias, C, N, N, N};
   FSVD_HIP(launch_linear(a, (hipStream_t)stream));
+  return FSVD_OK;
+}
+
+size_t fsvd_fm_bytes(int32_t T, int32_t K) {
+  if (T <= 0 || K <= 0 || K % 8 != 0) return 0;
+  return fm_bytes((size_t)T, (size_t)K);
+}
+
+fsvd_status fsvd_pack_fm(int32_t T, int32_t K, const void* src, fsvd_dtype src_dtype, void* dst_fm, void* stream) {
+  if (T <= 0 || K <= 0 || !src || !dst_fm || !dtype_ok(src_dtype)) return FSVD_ERR_INVALID_ARG;
+  if (K % 8 != 0 || fm_bytes(T, K) >= (1ULL << 31)) return FSVD_ERR_UNSUPPORTED;
+  FSVD_HIP(launch_pack_fm(src, src_dtype, T, K, dst_fm, (hipStream_t)stream));
+  return FSVD_OK;
+}
+
+fsvd_status fsvd_unpack_fm(int32_t T, int32_t K, const void* src_fm, void* dst, fsvd_dtype dst_dtype, void* stream) {
+  if (T <= 0 || K <= 0 || !src_fm || !dst || !dtype_ok(dst_dtype)) return FSVD_ERR_INVALID_ARG;
+  if (K % 8 != 0 || fm_bytes(T, K) >= (1ULL << 31)) return FSVD_ERR_UNSUPPORTED;
+  FSVD_HIP(launch_unpack_fm(src_fm, T, K, dst, dst_dtype, (hipStream_t)stream));
   return FSVD_OK;
 }
 
@@ -309,13 +344,12 @@ fsvd_status fsvd_attention_core(const fsvd_desc* d, const void* Pq, const void* 
   FSVD_TRY(check_factor(v, d->D, d->D, false, true));
   if (!Pq || !Pk || !Pv || !context) return FSVD_ERR_INVALID_ARG;
   AttnCoreArgs ca{};
-  ca.Pq = (const _Float16*)Pq; ca.Pk = (const _Float16*)Pk; ca.Pv = (const _Float16*)Pv;
-  ca.ldpq = q->rank; ca.ldpk = k->rank; ca.ldpv = v->rank;
+  ca.Pq = Pq; ca.Pk = Pk; ca.Pv = Pv;
   ca.rq = q->rank; ca.rk = k->rank; ca.rv = v->rank;
   ca.Vq = q->V; ca.Vk = k->V; ca.Vv = v->V; ca.bq = q->bias; ca.bk = k->bias; ca.bv = v->bias;
   ca.w_dt = d->io_dtype; ca.B = d->B; ca.M = d->M; ca.D = d->D; ca.H = d->H;
   ca.causal = d->causal; ca.key_len = d->key_len; ca.scale = resolve_scale(d);
-  ca.C = (_Float16*)context; ca.ldc = d->D;
+  ca.C = context;
   FSVD_HIP(launch_attn_core(ca, (hipStream_t)stream));
   return FSVD_OK;
 }
@@ -327,9 +361,9 @@ fsvd_status fsvd_ffn_core(const fsvd_desc* d, const void* P1, const fsvd_factor*
   FSVD_TRY(check_factor(w2, d->F, d->D, true, false));
   if (!P1 || !Z) return FSVD_ERR_INVALID_ARG;
   FfnCoreArgs fa{};
-  fa.P1 = (const _Float16*)P1; fa.ldp = w1->rank; fa.r1 = w1->rank; fa.V1 = w1->V; fa.b1 = w1->bias; fa.U2 = w2->U;
+  fa.P1 = P1; fa.r1 = w1->rank; fa.V1 = w1->V; fa.b1 = w1->bias; fa.U2 = w2->U;
   fa.r2 = w2->rank; fa.w_dt = d->io_dtype; fa.T = d->B * d->M; fa.F = d->F; fa.act = d->act;
-  fa.Z = (_Float16*)Z; fa.ldz = w2->rank;
+  fa.Z = Z;
   FSVD_HIP(launch_ffn_core(fa, (hipStream_t)stream));
   return FSVD_OK;
 }
@@ -338,11 +372,11 @@ fsvd_status fsvd_layernorm(int32_t T, int32_t D, const void* X, fsvd_dtype x_dty
                            fsvd_dtype p_dtype, float eps, void* Y, fsvd_dtype y_dtype, void* stream) {
   if (T <= 0 || D <= 0 || !X || !gamma || !beta || !Y) return FSVD_ERR_INVALID_ARG;
   if (!dtype_ok(x_dtype) || !dtype_ok(p_dtype) || !dtype_ok(y_dtype) || !(eps >= 0.f)) return FSVD_ERR_INVALID_ARG;
-  if (D > 8192) return FSVD_ERR_UNSUPPORTED;
+  if (D > 8192 || D % 8 != 0) return FSVD_ERR_UNSUPPORTED;
   if ((long long)T * D >= (1LL << 31)) return FSVD_ERR_UNSUPPORTED;
   LayerNormArgs la{};
-  la.X = X; la.x_dt = x_dtype; la.ldx = D; la.gamma = gamma; la.beta = beta; la.p_dt = p_dtype; la.eps = eps;
-  la.T = T; la.D = D; la.Y0 = Y; la.y0_dt = y_dtype; la.ldy0 = D; la.Y1 = nullptr;
+  la.X = X; la.x_dt = x_dtype; la.gamma = gamma; la.beta = beta; la.p_dt = p_dtype; la.eps = eps;
+  la.T = T; la.D = D; la.Yrow = Y; la.yrow_dt = y_dtype; la.Yfm = nullptr;
   FSVD_HIP(launch_layernorm(la, (hipStream_t)stream));
   return FSVD_OK;
 }

@@ -1,6 +1,6 @@
 // Streaming attention over rank-space inputs (Alg. 1): Q, K and V tiles are rebuilt on chip from
-// P_q, P_k, P_v [T, r] and the head's columns of V_q, V_k, V_v [r, D] (Alg. 1 Part I), scores and the
-// streaming softmax never leave registers (Part II), and only the context C [T, D] is written.
+// P_q, P_k, P_v [T, r] (fragment-major fp16) and the head's columns of V_q, V_k, V_v [r, D] (Alg. 1 Part I), scores and the
+// streaming softmax never leave registers (Part II), and only the context C [T, D] is written (fragment-major fp16).
 //
 // One workgroup (4 wavefronts) owns one (sequence, head, block of BQ = 128*QT queries).
 //   Q phase : every wavefront rebuilds Q^T [d_h, 32*QT] for its own queries, contraction over r_q
@@ -51,7 +51,7 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
   const int bh = blockIdx.x % BH;
   const int qb = nqb - 1 - blockIdx.x / BH;   // late query blocks (most keys under a causal mask) first
   const int b = bh / a.H, h = bh % a.H;
-  const int M = a.M;
+  const int M = a.M, D = a.D, T = a.B * a.M;
   const int q0 = qb * BQ;
   const int qw = q0 + wave * QT * 32;         // first query of this wavefront
   int kv_len = a.key_len ? a.key_len[b] : M;
@@ -59,15 +59,20 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
   int kv_end = kv_len;
   if (a.causal && q0 + BQ < kv_end) kv_end = q0 + BQ;
   const int nsteps = (kv_end + kBKV - 1) / kBKV;
-  const size_t tok0 = (size_t)b * M;
-  const size_t col0 = (size_t)h * DH;         // this head's columns in V_a, b_a and C
+  const int tok0 = b * M;
+  const int col0 = h * DH;                    // this head's columns in V_a, b_a and C
 
-  // ---- weight staging: thread -> 4 (rank) x 8 (feature) block
+  // ---- weight staging: block id -> matrix, 4-row group, 8-column group
   auto stage_coords = [&](int bid, int& mat, int& q4, int& ng) {
     mat = bid / NBM;
     const int w = bid % NBM;
     q4 = (w >> 2) & 15;
     ng = (w & 3) + 4 * (w >> 6);
+  };
+  // 4 consecutive bias entries of this head, as floats
+  auto bias4 = [&](const void* bp, int d) -> f4v {
+    const rsrc_t r = rsrc_at(bp, bp ? (long long)D * 2 : 0, 0);
+    return raw_to_f4<WT>(buf_load8(r, (col0 + d) * 2));
   };
 
   // =================================== Q phase ===================================
@@ -78,33 +83,32 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
     for (int dt = 0; dt < DT32; ++dt)
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt) acc[dt][qt] = zero16();
-    const _Float16* prow[QT];
+    const int rq = a.rq;
+    const int nc = (rq + kChunkK - 1) / kChunkK;
+    const long long p_total = (long long)fm_bytes(T, rq);
+    const long long w_total = (long long)rq * D * 2;
+    int voffP[QT];
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
       int q = qw + 32 * qt + l32;
       q = q < M ? q : M - 1;
-      prow[qt] = a.Pq + (tok0 + q) * a.ldpq;
+      voffP[qt] = fm_voff(tok0 + q, nc, g);
     }
-    const int rq = a.rq;
-    const int nc = (rq + kChunkK - 1) / kChunkK;
     int s_mat, s_q4, s_ng;
     stage_coords(tid, s_mat, s_q4, s_ng);
     const bool stager = tid < NBM;
+    const int voffW = (4 * s_q4 * D + 8 * s_ng) * 2;
     u4 w_raw[4];
-    h8 p_cur[QT][4], p_nxt[QT][4];
-    auto load_p = [&](int c, h8 (&dst)[QT][4]) {
+    h8 pfr[QT][4];
+    auto load_p = [&](int c, int kk) {
+      const rsrc_t r = rsrc_at(a.Pq, p_total, (long long)c * kFmChunkBytes);
+      const bool ok = c * kChunkK + 32 * g + 8 * kk < rq;
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          const int k = c * kChunkK + chunk_off(kk, g);
-          u4 raw = {0u, 0u, 0u, 0u};
-          if (k < rq) raw = *(const u4*)(prow[qt] + k);
-          dst[qt][kk] = __builtin_bit_cast(h8, raw);
-        }
+        pfr[qt][kk] = __builtin_bit_cast(h8, buf_load16(r, (ok ? voffP[qt] : kOobOffset) + kk * kFmStepBytes));
     };
     auto issue_w = [&](int c) {
-      if (stager) load_w4x8<WT>((const uint16_t*)a.Vq + col0, (size_t)a.D, c * kChunkK + 4 * s_q4, 8 * s_ng, rq, DH, w_raw);
+      if (stager) buf_load_w4x8(rsrc_at(a.Vq, w_total, ((long long)c * kChunkK * D + col0) * 2), voffW, D * 2, w_raw);
     };
     auto commit_w = [&](int p) {
       if (stager) {
@@ -115,12 +119,13 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
       }
     };
     issue_w(0);
-    load_p(0, p_cur);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) load_p(0, kk);
     commit_w(0);
     __syncthreads();
     for (int c = 0; c < nc; ++c) {
       const bool more = c + 1 < nc;
-      if (more) { issue_w(c + 1); load_p(c + 1, p_nxt); }
+      if (more) issue_w(c + 1);
       const _Float16* wb = wbuf[c & 1][0];
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
@@ -130,32 +135,26 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
 #pragma unroll
         for (int dt = 0; dt < DT32; ++dt)
 #pragma unroll
-          for (int qt = 0; qt < QT; ++qt) acc[dt][qt] = mfma32(wf[dt], p_cur[qt][kk], acc[dt][qt]);
+          for (int qt = 0; qt < QT; ++qt) acc[dt][qt] = mfma32(wf[dt], pfr[qt][kk], acc[dt][qt]);
+        if (more) load_p(c + 1, kk);     // refill the operand registers just consumed
       }
-      if (more) {
-        commit_w((c + 1) & 1);
-#pragma unroll
-        for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-          for (int kk = 0; kk < 4; ++kk) p_cur[qt][kk] = p_nxt[qt][kk];
-      }
+      if (more) commit_w((c + 1) & 1);
       __syncthreads();
     }
     // bias, softmax scale (log2 domain), round to fp16 operands
     const float qs = a.scale * kLog2e;
 #pragma unroll
     for (int dt = 0; dt < DT32; ++dt) {
-      float bias[16];
+      f4v bias[4];
 #pragma unroll
-      for (int v = 0; v < 16; ++v)
-        bias[v] = a.bq ? load_param(a.bq, col0 + 32 * dt + 8 * (v >> 2) + 4 * g + (v & 3), a.w_dt) : 0.f;
+      for (int jj = 0; jj < 4; ++jj) bias[jj] = bias4(a.bq, 32 * dt + 8 * jj + 4 * g);
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           h8 r;
 #pragma unroll
-          for (int i = 0; i < 8; ++i) r[i] = (_Float16)((acc[dt][qt][8 * t + i] + bias[8 * t + i]) * qs);
+          for (int i = 0; i < 8; ++i) r[i] = (_Float16)((acc[dt][qt][8 * t + i] + bias[2 * t + (i >> 2)][i & 3]) * qs);
           qf[2 * dt + t][qt] = r;
         }
     }
@@ -174,23 +173,27 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
 
   const int kvt = wave >> 1;        // which 64-key slab of the step this wavefront rebuilds
   const int which = wave & 1;       // 0: keys, 1: values
-  const _Float16* Psrc = which ? a.Pv : a.Pk;
-  const int ldp = which ? a.ldpv : a.ldpk;
+  const void* Psrc = which ? a.Pv : a.Pk;
   const int rr = which ? a.rv : a.rk;
+  const int pch = (rr + kChunkK - 1) / kChunkK;
+  const long long p_total = (long long)fm_bytes(T, rr);
   const int rmax = a.rk > a.rv ? a.rk : a.rv;
   const int nc = (rmax + kChunkK - 1) / kChunkK;
   const int total = nsteps * nc;
 
-  int s_mat[NBLK], s_q4[NBLK], s_ng[NBLK];
+  int s_mat[NBLK], s_q4[NBLK], s_ng[NBLK], voffW[NBLK];
 #pragma unroll
-  for (int i = 0; i < NBLK; ++i) stage_coords(tid + 256 * i, s_mat[i], s_q4[i], s_ng[i]);
+  for (int i = 0; i < NBLK; ++i) {
+    stage_coords(tid + 256 * i, s_mat[i], s_q4[i], s_ng[i]);
+    voffW[i] = (4 * s_q4[i] * D + 8 * s_ng[i]) * 2;
+  }
   u4 w_raw[NBLK][4];
   auto issue_w = [&](int c) {
 #pragma unroll
     for (int i = 0; i < NBLK; ++i) {
       const void* W = s_mat[i] ? a.Vv : a.Vk;
-      const int r = s_mat[i] ? a.rv : a.rk;
-      load_w4x8<WT>((const uint16_t*)W + col0, (size_t)a.D, c * kChunkK + 4 * s_q4[i], 8 * s_ng[i], r, DH, w_raw[i]);
+      const long long tot = (long long)(s_mat[i] ? a.rv : a.rk) * D * 2;
+      buf_load_w4x8(rsrc_at(W, tot, ((long long)c * kChunkK * D + col0) * 2), voffW[i], D * 2, w_raw[i]);
     }
   };
   auto commit_w = [&](int p) {
@@ -202,20 +205,16 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
       for (int j = 0; j < 8; ++j) *(u2*)&wbuf[p][s_mat[i]][(8 * s_ng[i] + j) * kLdsRow + 4 * s_q4[i]] = t[j];
     }
   };
-  h8 p_cur[2][4], p_nxt[2][4];
-  auto load_p = [&](int step, int c, h8 (&dst)[2][4]) {
+  h8 pfr[2][4];
+  auto load_p = [&](int step, int c, int kk) {
+    const rsrc_t r = rsrc_at(Psrc, p_total, (long long)c * kFmChunkBytes);
+    const bool ok = c * kChunkK + 32 * g + 8 * kk < rr;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
       int key = step * kBKV + 64 * kvt + 32 * kt + l32;
       key = key < M ? key : M - 1;
-      const _Float16* row = Psrc + (tok0 + key) * ldp;
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const int k = c * kChunkK + chunk_off(kk, g);
-        u4 raw = {0u, 0u, 0u, 0u};
-        if (k < rr) raw = *(const u4*)(row + k);
-        dst[kt][kk] = __builtin_bit_cast(h8, raw);
-      }
+      const int v = ok ? fm_voff(tok0 + key, pch, g) : kOobOffset;
+      pfr[kt][kk] = __builtin_bit_cast(h8, buf_load16(r, v + kk * kFmStepBytes));
     }
   };
 
@@ -225,7 +224,8 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
 
   if (total > 0) {
     issue_w(0);
-    load_p(0, 0, p_cur);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) load_p(0, 0, kk);
     commit_w(0);
   }
   __syncthreads();
@@ -235,7 +235,7 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
     const bool more = it + 1 < total;
     int nstep = step, ncn = c + 1;
     if (ncn == nc) { ncn = 0; nstep = step + 1; }
-    if (more) { issue_w(ncn); load_p(nstep, ncn, p_nxt); }
+    if (more) issue_w(ncn);
     {
       const _Float16* wb = wbuf[it & 1][which];
 #pragma unroll
@@ -247,22 +247,17 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
 #pragma unroll
           for (int dt = 0; dt < DT32; ++dt)
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt) acc[dt][kt] = mfma32(wf[dt], p_cur[kt][kk], acc[dt][kt]);   // K^T: rows d, cols keys
+            for (int kt = 0; kt < 2; ++kt) acc[dt][kt] = mfma32(wf[dt], pfr[kt][kk], acc[dt][kt]);   // K^T: rows d, cols keys
         } else {
 #pragma unroll
           for (int dt = 0; dt < DT32; ++dt)
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt) acc[dt][kt] = mfma32(p_cur[kt][kk], wf[dt], acc[dt][kt]);   // V: rows keys, cols d
+            for (int kt = 0; kt < 2; ++kt) acc[dt][kt] = mfma32(pfr[kt][kk], wf[dt], acc[dt][kt]);   // V: rows keys, cols d
         }
+        if (more) load_p(nstep, ncn, kk);   // refill the operand registers just consumed
       }
     }
-    if (more) {
-      commit_w((it + 1) & 1);
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) p_cur[kt][kk] = p_nxt[kt][kk];
-    }
+    if (more) commit_w((it + 1) & 1);
     __syncthreads();
 
     if (c == nc - 1) {
@@ -270,17 +265,16 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
       if (which == 0) {
 #pragma unroll
         for (int dt = 0; dt < DT32; ++dt) {
-          float bias[16];
+          f4v bias[4];
 #pragma unroll
-          for (int v = 0; v < 16; ++v)
-            bias[v] = a.bk ? load_param(a.bk, col0 + 32 * dt + 8 * (v >> 2) + 4 * g + (v & 3), a.w_dt) : 0.f;
+          for (int jj = 0; jj < 4; ++jj) bias[jj] = bias4(a.bk, 32 * dt + 8 * jj + 4 * g);
 #pragma unroll
           for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
               h8 r;
 #pragma unroll
-              for (int i = 0; i < 8; ++i) r[i] = (_Float16)(acc[dt][kt][8 * t + i] + bias[8 * t + i]);
+              for (int i = 0; i < 8; ++i) r[i] = (_Float16)(acc[dt][kt][8 * t + i] + bias[2 * t + (i >> 2)][i & 3]);
               ktile[2 * kvt + kt][2 * dt + t][lane] = r;
             }
         }
@@ -372,23 +366,30 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
     c = ncn;
   }
 
-  // ---- normalise and write the context (fp16), 4 consecutive features per store
+  // ---- normalise and write the context, fragment-major: 4 consecutive features per 8-byte store
+  {
+    _Float16* C = (_Float16*)a.C;
+    const int cch = D / 64;
 #pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    const int q = qw + 32 * qt + l32;
-    const float l = l_run[qt] + __shfl_xor(l_run[qt], 32, 64);
-    const float inv = l > 0.f ? 1.0f / l : 0.f;
-    if (q < M) {
-      _Float16* crow = a.C + (tok0 + q) * a.ldc + col0;
+    for (int qt = 0; qt < QT; ++qt) {
+      const int q = qw + 32 * qt + l32;
+      const float l = l_run[qt] + __shfl_xor(l_run[qt], 32, 64);
+      const float inv = l > 0.f ? 1.0f / l : 0.f;
+      if (q < M) {
+        const int tok = tok0 + q;
 #pragma unroll
-      for (int dt = 0; dt < DT32; ++dt)
+        for (int dt = 0; dt < DT32; ++dt) {
+          const int dabs = col0 + 32 * dt;
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-          h4 r;
+          for (int jj = 0; jj < 4; ++jj) {
+            const size_t unit = ((size_t)((tok >> 5) * cch + (dabs >> 6)) * 4 + jj) * 64 + ((dabs >> 5) & 1) * 32 + (tok & 31);
+            h4 r;
 #pragma unroll
-          for (int i = 0; i < 4; ++i) r[i] = (_Float16)(o[dt][qt][4 * jj + i] * inv);
-          *(h4*)(crow + 32 * dt + 8 * jj + 4 * g) = r;
+            for (int i = 0; i < 4; ++i) r[i] = (_Float16)(o[dt][qt][4 * jj + i] * inv);
+            *(h4*)(C + unit * 8 + 4 * g) = r;
+          }
         }
+      }
     }
   }
 }

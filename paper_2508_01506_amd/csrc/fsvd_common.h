@@ -141,6 +141,68 @@ __device__ __forceinline__ void transpose_w4x8(const u4 raw[4], u2 out[8]) {
   }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Buffer addressing.  A tensor (or the part of it that starts at some scalar byte offset) is
+// described by a 128-bit resource held in scalar registers; an access is resource + one 32-bit
+// per-lane byte offset (+ immediate), and an access whose per-lane offset reaches the resource's
+// size returns zero instead of touching memory.  Only the per-lane offset takes part in that
+// range check, so a tile base is folded into the resource itself (rsrc_at) rather than passed as
+// a scalar offset; row tails of a contraction (k >= K) then need no code, and a lane that must
+// read nothing passes kOobOffset.  Tensors addressed this way must be smaller than 2 GiB.
+// ---------------------------------------------------------------------------------------------
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr int kOobOffset = 0x7fff0000;   // plus any immediate it stays above every resource size and below 2^31
+
+// resource covering [base + off, base + total)
+__device__ __forceinline__ rsrc_t rsrc_at(const void* base, long long total, long long off) {
+  long long left = total - off;
+  left = left < 0 ? 0 : left;
+  return __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)base + (left > 0 ? off : 0)), 0, (int)left, 0x00020000);
+}
+__device__ __forceinline__ u4 buf_load16(rsrc_t r, int voff) { return __builtin_amdgcn_raw_buffer_load_b128(r, voff, 0, 0); }
+__device__ __forceinline__ u2 buf_load8(rsrc_t r, int voff) { return __builtin_amdgcn_raw_buffer_load_b64(r, voff, 0, 0); }
+
+// 4 consecutive stored parameters (e.g. bias) as floats
+template <int WT>
+__device__ __forceinline__ f4v raw_to_f4(u2 raw) {
+  f4v o;
+  if constexpr (WT == DT_BF16) {
+    o[0] = __uint_as_float(raw[0] << 16); o[1] = __uint_as_float(raw[0] & 0xffff0000u);
+    o[2] = __uint_as_float(raw[1] << 16); o[3] = __uint_as_float(raw[1] & 0xffff0000u);
+  } else {
+    h4 h = __builtin_bit_cast(h4, raw);
+    o[0] = (float)h[0]; o[1] = (float)h[1]; o[2] = (float)h[2]; o[3] = (float)h[3];
+  }
+  return o;
+}
+
+// 4 (k) x 8 (n) weight block: rows start at voff + i * row_bytes.  K is a multiple of 4 and blocks
+// start at multiples of 4, so a block is in range as a whole or not at all: the range check of
+// row 0 (voff against the resource size) is applied to every row.
+__device__ __forceinline__ void buf_load_w4x8(rsrc_t r, int voff, int row_bytes, u4 raw[4]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) raw[i] = __builtin_amdgcn_raw_buffer_load_b128(r, voff, i * row_bytes, 0);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Fragment-major ("FM") layout of an fp16 activation A[T, K] that will be an MFMA operand.
+// Tokens are grouped in tiles of 32 and the contraction axis in chunks of 64; one (tile, chunk)
+// block is 4 KiB holding, for MFMA step kk = 0..3, the 64 lanes' 16-byte operand registers in
+// lane order: lane (t % 32) + 32 g owns k = 64 c + 32 g + 8 kk + 0..7 of token t.  A wavefront
+// therefore fetches an operand with ONE fully contiguous 1 KiB load, and a producer whose
+// accumulators hold 4 consecutive k per lane writes contiguous 512-byte runs.
+// ---------------------------------------------------------------------------------------------
+__host__ __device__ __forceinline__ size_t fm_bytes(size_t T, size_t K) {
+  return ((T + 31) / 32) * ((K + 63) / 64) * 4096;
+}
+// byte offset of the 16-byte unit of (token t, lane group g) inside block (t / 32, chunk 0), step 0
+__device__ __forceinline__ int fm_voff(int t, int kchunks, int g) {
+  return (((t >> 5) * kchunks) * 256 + g * 32 + (t & 31)) * 16;
+}
+constexpr int kFmChunkBytes = 4096;
+constexpr int kFmStepBytes = 1024;
+
 // LDS weight tiles are stored [n][k] with a row of kLdsK halves of payload plus 8 halves of padding,
 // so that 16 lanes reading 16 bytes from 16 consecutive rows hit distinct banks.
 constexpr int kChunkK = 64;             // contraction chunk staged per step

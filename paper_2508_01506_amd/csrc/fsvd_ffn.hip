@@ -1,7 +1,7 @@
 // Fused FFN core (Alg. 2, the on-chip loops): Z[T, r2] = phi(P1[T, r1] V_1[r1, F] + b_1) U_2[F, r2].
 // The hidden activation phi(...) [T, F] exists only as 128-wide slabs in registers / LDS.
 //
-// One workgroup (4 wavefronts) owns 128 tokens and one slice of at most 512 output ranks; the
+// One workgroup (4 wavefronts) owns 128 (or 64) tokens and one slice of at most 512 output ranks; the
 // accumulator Z^T [slice, 128 tokens] stays in registers for the whole sweep over F.  Per 128-wide
 // chunk of F:
 //   phase A  Y^T[128 f, 128 tok] = V_1[:, chunk]^T P1^T, contraction over r1 in 128-wide stages;
@@ -20,7 +20,6 @@ namespace fsvd {
 
 namespace {
 
-constexpr int kFfnBT = 128;                 // tokens per workgroup
 constexpr int kFfnBF = 128;                 // F chunk
 constexpr int kTile = 128;                  // weight tile edge
 constexpr int kTileRow = kTile + 8;         // halves per LDS tile row (16-lane conflict-free 16-byte reads)
@@ -39,31 +38,29 @@ __device__ __forceinline__ float gelu_tanh_f(float x) {
   const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
   return x * __frcp_rn(1.0f + __builtin_amdgcn_exp2f(-2.0f * u * 1.4426950408889634f));
 }
-__device__ __forceinline__ float act_f(float x, int act) {
-  if (act == 0) return gelu_erf_f(x);
-  if (act == 1) return gelu_tanh_f(x);
-  return fmaxf(x, 0.f);
-}
 
-// contraction-slot offset inside a 128-wide stage: step kk (0..7), lane group g
-__device__ __forceinline__ int stage_off(int kk, int g) { return 64 * (kk >> 2) + 32 * g + 8 * (kk & 3); }
-
-template <int NS, int WT>
+template <int NS, int WT, int TG>
 __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nslices, int slice_w) {
+  constexpr int WRN = 4 / TG;          // wavefronts sharing one 64-token group, splitting features / ranks
+  constexpr int FT = 4 / WRN;          // 32-wide feature (phase A) and rank (phase B) tiles per wavefront
+  constexpr int ROWS = 128 / WRN;      // rows of a 128-wide tile owned by one wavefront
   __shared__ __attribute__((aligned(16))) _Float16 wt_lds[2][kTile * kTileRow];
-  __shared__ __attribute__((aligned(16))) h8 gtile[2][4][2][2][64];   // [token half][f tile][t][token tile][lane]
+  __shared__ __attribute__((aligned(16))) h8 gtile[TG][4][2][2][64];   // [token group][f tile][t][token tile][lane]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
-  const int wt = wave >> 1, wr = wave & 1;
+  const int wt = wave / WRN, wr = wave % WRN;
   const int slice = blockIdx.x % nslices;
   const int tb = blockIdx.x / nslices;
-  const int t0 = tb * kFfnBT;
+  const int t0 = tb * (64 * TG);
   const int s0 = slice * slice_w;                               // first output rank of this slice
-  const int s_end = (s0 + slice_w < a.r2) ? s0 + slice_w : a.r2;
-  const int r1 = a.r1, F = a.F;
+  const int r1 = a.r1, F = a.F, r2 = a.r2, T = a.T;
+  const int s_end = (s0 + slice_w < r2) ? s0 + slice_w : r2;
   const int nA = (r1 + kTile - 1) / kTile;
   const int nchunks = (F + kFfnBF - 1) / kFfnBF;
+  const int pch = (r1 + 63) / 64, zch = (r2 + 63) / 64;
+  const long long p_total = (long long)fm_bytes(T, r1);
+  const long long v1_total = (long long)r1 * F * 2, u2_total = (long long)F * r2 * 2;
 
   // ---- weight tile staging: each thread moves two 4 (k) x 8 (n) blocks
   int sq[2], sng[2];
@@ -74,18 +71,19 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
     sq[i] = ((bid >> 2) & 15) + 16 * (bid >> 8);
   }
   u4 w_raw[2][4];
-  // kind 0: V_1 rows r (stage ra), columns f of chunk c.  kind 1: U_2 rows f of chunk c, columns s0 + 128*s.
+  // kind 0: V_1 rows r of stage idx, columns f of chunk c.  kind 1: U_2 rows f of chunk c, columns s0 + 128*idx.
   auto issue_tile = [&](int kind, int c, int idx) {
+    if (kind == 0) {
+      const rsrc_t r = rsrc_at(a.V1, v1_total, ((long long)idx * kTile * F + c * kFfnBF) * 2);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      if (kind == 0) {
-        load_w4x8<WT>((const uint16_t*)a.V1 + (size_t)c * kFfnBF, (size_t)F, idx * kTile + 4 * sq[i], 8 * sng[i],
-                      r1, F - c * kFfnBF, w_raw[i]);
-      } else {
-        const int n0 = s0 + idx * kTile;
-        load_w4x8<WT>((const uint16_t*)a.U2 + n0, (size_t)a.r2, c * kFfnBF + 4 * sq[i], 8 * sng[i],
-                      F, s_end - n0, w_raw[i]);
-      }
+      for (int i = 0; i < 2; ++i)
+        buf_load_w4x8(r, (c * kFfnBF + 8 * sng[i] < F) ? (4 * sq[i] * F + 8 * sng[i]) * 2 : kOobOffset, F * 2, w_raw[i]);
+    } else {
+      const int n0 = s0 + idx * kTile;
+      const rsrc_t r = rsrc_at(a.U2, u2_total, ((long long)c * kFfnBF * r2 + n0) * 2);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        buf_load_w4x8(r, (n0 + 8 * sng[i] < s_end) ? (4 * sq[i] * r2 + 8 * sng[i]) * 2 : kOobOffset, r2 * 2, w_raw[i]);
     }
   };
   // kind 1 tiles store their 4-row groups in accumulator order (0-3, 8-11, 4-7, 12-15 of every 16)
@@ -101,45 +99,42 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
     }
   };
 
-  // ---- P1 rows of this wavefront's tokens
-  const _Float16* prow[2];
+  // ---- P1 operands of this wavefront's tokens (fragment-major: one contiguous 1 KiB load each)
+  int voffP[2];
 #pragma unroll
   for (int tt = 0; tt < 2; ++tt) {
     int tok = t0 + 64 * wt + 32 * tt + l32;
-    tok = tok < a.T ? tok : a.T - 1;
-    prow[tt] = a.P1 + (size_t)tok * a.ldp;
+    tok = tok < T ? tok : T - 1;
+    voffP[tt] = fm_voff(tok, pch, g);
   }
-  h8 p_cur[2][4], p_nxt[2][4];
-  auto load_p = [&](int half, h8 (&dst)[2][4]) {   // half: 64-wide piece of r1
+  h8 pfr[2][4];
+  auto load_p = [&](int half, int kk) {   // half: 64-wide piece of r1
+    const rsrc_t r = rsrc_at(a.P1, p_total, (long long)half * kFmChunkBytes);
+    const bool ok = half * 64 + 32 * g + 8 * kk < r1;
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const int k = half * 64 + 32 * g + 8 * kk;
-        u4 raw = {0u, 0u, 0u, 0u};
-        if (k < r1) raw = *(const u4*)(prow[tt] + k);
-        dst[tt][kk] = __builtin_bit_cast(h8, raw);
-      }
+      pfr[tt][kk] = __builtin_bit_cast(h8, buf_load16(r, (ok ? voffP[tt] : kOobOffset) + kk * kFmStepBytes));
   };
   const int nhalf = 2 * nA;
 
-  f16v z[NS][2][2];
+  f16v z[NS][FT][2];
 #pragma unroll
   for (int s = 0; s < NS; ++s)
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt) { z[s][rt][0] = zero16(); z[s][rt][1] = zero16(); }
+    for (int rt = 0; rt < FT; ++rt) { z[s][rt][0] = zero16(); z[s][rt][1] = zero16(); }
 
   int parity = 0;
   issue_tile(0, 0, 0);
-  load_p(0, p_cur);
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) load_p(0, kk);
   commit_tile(0, 0);
   __syncthreads();
 
   for (int c = 0; c < nchunks; ++c) {
     // ================= phase A =================
-    f16v y[2][2];
+    f16v y[FT][2];
 #pragma unroll
-    for (int ft = 0; ft < 2; ++ft) { y[ft][0] = zero16(); y[ft][1] = zero16(); }
+    for (int ft = 0; ft < FT; ++ft) { y[ft][0] = zero16(); y[ft][1] = zero16(); }
     for (int ra = 0; ra < nA; ++ra) {
       const bool lastA = ra + 1 == nA;
       if (!lastA) issue_tile(0, c, ra + 1); else issue_tile(1, c, 0);
@@ -149,45 +144,42 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
         const int half = 2 * ra + hh;
         int nh = half + 1;
         if (nh == nhalf) nh = 0;
-        load_p(nh, p_nxt);
-        if (half * 64 < r1) {
 #pragma unroll
-          for (int kk = 0; kk < 4; ++kk) {
-            h8 wf[2];
+        for (int kk = 0; kk < 4; ++kk) {
+          h8 wf[FT];
 #pragma unroll
-            for (int ft = 0; ft < 2; ++ft)
-              wf[ft] = *(const h8*)&wb[(64 * wr + 32 * ft + l32) * kTileRow + 64 * hh + 32 * g + 8 * kk];
+          for (int ft = 0; ft < FT; ++ft)
+            wf[ft] = *(const h8*)&wb[(ROWS * wr + 32 * ft + l32) * kTileRow + 64 * hh + 32 * g + 8 * kk];
 #pragma unroll
-            for (int ft = 0; ft < 2; ++ft)
+          for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
-              for (int tt = 0; tt < 2; ++tt) y[ft][tt] = mfma32(wf[ft], p_cur[tt][kk], y[ft][tt]);   // rows f, cols tokens
-          }
+            for (int tt = 0; tt < 2; ++tt) y[ft][tt] = mfma32(wf[ft], pfr[tt][kk], y[ft][tt]);   // rows f, cols tokens
+          load_p(nh, kk);                 // refill the operand registers just consumed
         }
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-          for (int kk = 0; kk < 4; ++kk) p_cur[tt][kk] = p_nxt[tt][kk];
       }
       if (lastA) {
         // bias, phi, fp16, publish in operand order for phase B
+        const rsrc_t rB = rsrc_at(a.b1, a.b1 ? (long long)F * 2 : 0, (long long)c * kFfnBF * 2);
+        auto publish = [&](auto phi) {
 #pragma unroll
-        for (int ft = 0; ft < 2; ++ft) {
-          float bias[16];
+          for (int ft = 0; ft < FT; ++ft) {
+            f4v bias[4];
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int f = c * kFfnBF + 64 * wr + 32 * ft + 8 * (v >> 2) + 4 * g + (v & 3);
-            bias[v] = (a.b1 && f < F) ? load_param(a.b1, f, a.w_dt) : 0.f;
+            for (int jj = 0; jj < 4; ++jj) bias[jj] = raw_to_f4<WT>(buf_load8(rB, (ROWS * wr + 32 * ft + 8 * jj + 4 * g) * 2));
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+              for (int t = 0; t < 2; ++t) {
+                h8 r;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) r[i] = (_Float16)phi(y[ft][tt][8 * t + i] + bias[2 * t + (i >> 2)][i & 3]);
+                gtile[wt][FT * wr + ft][t][tt][lane] = r;
+              }
           }
-#pragma unroll
-          for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-              h8 r;
-#pragma unroll
-              for (int i = 0; i < 8; ++i) r[i] = (_Float16)act_f(y[ft][tt][8 * t + i] + bias[8 * t + i], a.act);
-              gtile[wt][2 * wr + ft][t][tt][lane] = r;
-            }
-        }
+        };
+        if (a.act == 0) publish([](float x) { return gelu_erf_f(x); });
+        else if (a.act == 1) publish([](float x) { return gelu_tanh_f(x); });
+        else publish([](float x) { return fmaxf(x, 0.f); });
       }
       commit_tile(lastA ? 1 : 0, parity ^ 1);
       __syncthreads();
@@ -208,11 +200,11 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
       if (s0 + s * kTile < s_end) {
 #pragma unroll
         for (int fs = 0; fs < 8; ++fs) {
-          h8 wf[2];
+          h8 wf[FT];
 #pragma unroll
-          for (int rt = 0; rt < 2; ++rt) wf[rt] = *(const h8*)&wb[(64 * wr + 32 * rt + l32) * kTileRow + 16 * fs + 8 * g];
+          for (int rt = 0; rt < FT; ++rt) wf[rt] = *(const h8*)&wb[(ROWS * wr + 32 * rt + l32) * kTileRow + 16 * fs + 8 * g];
 #pragma unroll
-          for (int rt = 0; rt < 2; ++rt)
+          for (int rt = 0; rt < FT; ++rt)
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) z[s][rt][tt] = mfma32(wf[rt], gq[fs][tt], z[s][rt][tt]);   // rows ranks, cols tokens
         }
@@ -223,35 +215,47 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
     }
   }
 
-  // ---- write Z (fp16), 4 consecutive ranks per store
+  // ---- write Z fragment-major (fp16), 4 consecutive ranks per 8-byte store
+  _Float16* Z = (_Float16*)a.Z;
 #pragma unroll
   for (int tt = 0; tt < 2; ++tt) {
     const int tok = t0 + 64 * wt + 32 * tt + l32;
-    if (tok >= a.T) continue;
-    _Float16* zrow = a.Z + (size_t)tok * a.ldz;
+    if (tok >= T) continue;
 #pragma unroll
     for (int s = 0; s < NS; ++s)
 #pragma unroll
-      for (int rt = 0; rt < 2; ++rt)
+      for (int rt = 0; rt < FT; ++rt)
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
-          const int r = s0 + s * kTile + 64 * wr + 32 * rt + 8 * jj + 4 * g;
+          const int r = s0 + s * kTile + ROWS * wr + 32 * rt + 8 * jj + 4 * g;
           if (r < s_end) {
+            const size_t unit = ((size_t)((tok >> 5) * zch + (r >> 6)) * 4 + ((r >> 3) & 3)) * 64 + ((r >> 5) & 1) * 32 + (tok & 31);
             h4 o;
 #pragma unroll
             for (int i = 0; i < 4; ++i) o[i] = (_Float16)z[s][rt][tt][4 * jj + i];
-            *(h4*)(zrow + r) = o;
+            *(h4*)(Z + unit * 8 + 4 * ((r >> 2) & 1)) = o;
           }
         }
   }
 }
 
-template <int NS>
+template <int NS, int TG>
 hipError_t launch_ns(const FfnCoreArgs& a, int nslices, int slice_w, hipStream_t s) {
-  const dim3 grid(((a.T + kFfnBT - 1) / kFfnBT) * nslices), block(256);
-  if (a.w_dt == DT_F16) hipLaunchKernelGGL((ffn_core_kernel<NS, DT_F16>), grid, block, 0, s, a, nslices, slice_w);
-  else hipLaunchKernelGGL((ffn_core_kernel<NS, DT_BF16>), grid, block, 0, s, a, nslices, slice_w);
+  const dim3 grid(((a.T + 64 * TG - 1) / (64 * TG)) * nslices), block(256);
+  if (a.w_dt == DT_F16) hipLaunchKernelGGL((ffn_core_kernel<NS, DT_F16, TG>), grid, block, 0, s, a, nslices, slice_w);
+  else hipLaunchKernelGGL((ffn_core_kernel<NS, DT_BF16, TG>), grid, block, 0, s, a, nslices, slice_w);
   return hipGetLastError();
+}
+
+template <int TG>
+hipError_t launch_tg(const FfnCoreArgs& a, int nslices, int slice_w, hipStream_t s) {
+  switch ((slice_w + kTile - 1) / kTile) {
+    case 1: return launch_ns<1, TG>(a, nslices, slice_w, s);
+    case 2: return launch_ns<2, TG>(a, nslices, slice_w, s);
+    case 3: return launch_ns<3, TG>(a, nslices, slice_w, s);
+    case 4: return launch_ns<4, TG>(a, nslices, slice_w, s);
+  }
+  return hipErrorInvalidValue;
 }
 
 }  // namespace
@@ -259,15 +263,10 @@ hipError_t launch_ns(const FfnCoreArgs& a, int nslices, int slice_w, hipStream_t
 hipError_t launch_ffn_core(const FfnCoreArgs& a, hipStream_t s) {
   const int nslices = (a.r2 + kMaxSlice - 1) / kMaxSlice;
   int slice_w = (a.r2 + nslices - 1) / nslices;
-  slice_w = (slice_w + 15) / 16 * 16;
-  const int ns = (slice_w + kTile - 1) / kTile;
-  switch (ns) {
-    case 1: return launch_ns<1>(a, nslices, slice_w, s);
-    case 2: return launch_ns<2>(a, nslices, slice_w, s);
-    case 3: return launch_ns<3>(a, nslices, slice_w, s);
-    case 4: return launch_ns<4>(a, nslices, slice_w, s);
-  }
-  return hipErrorInvalidValue;
+  slice_w = (slice_w + 63) / 64 * 64;
+  // 128-token workgroups halve the weight traffic; 64-token ones fill the chip when tokens are few
+  const long wg128 = (long)((a.T + 127) / 128) * nslices;
+  return wg128 >= 224 ? launch_tg<2>(a, nslices, slice_w, s) : launch_tg<1>(a, nslices, slice_w, s);
 }
 
 }  // namespace fsvd

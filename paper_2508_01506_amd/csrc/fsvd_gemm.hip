@@ -3,48 +3,45 @@
 // (Alg. 2 "GEMM 1st" / "GEMM 2nd").
 //
 // One workgroup = 4 wavefronts stacked along the rows: a 256 x BN output tile, each wavefront a
-// 64 x BN slab held as 32x32 MFMA accumulators.  Activation fragments are loaded straight from
-// global memory into registers (every lane reads 64 contiguous bytes of its own row per 64-wide
-// contraction chunk; no other wavefront needs them), weight tiles are transposed in registers and
-// double-buffered in LDS, where all four wavefronts read them.  LDS read traffic is 0.5 KiB per MFMA.
+// 64 x BN slab held as 32x32 MFMA accumulators.  Activation operands go from global memory straight
+// into registers (no other wavefront needs them); in the fragment-major layout that is one
+// contiguous 1 KiB load per operand.  Weight tiles are transposed in registers and double-buffered
+// in LDS, where all four wavefronts read them: 0.5 KiB of LDS reads per MFMA.
+// A fragment-major output is produced with the operand roles swapped (rows = output columns,
+// lanes = tokens), so that each lane owns 4 consecutive output columns of one token and a wavefront
+// writes contiguous 512-byte runs of the destination layout.
 #include "fsvd_common.h"
 #include "fsvd_kernels.h"
 
 namespace fsvd {
 
-template <int AT> struct RawAct { u4 v; };
-template <> struct RawAct<DT_F32> { f4v lo, hi; };
+namespace {
 
-template <int AT>
-__device__ __forceinline__ RawAct<AT> load_raw_act(const void* row, int k, bool ok) {
-  RawAct<AT> r;
-  if constexpr (AT == DT_F32) {
-    f4v z = {0.f, 0.f, 0.f, 0.f};
-    r.lo = z; r.hi = z;
-    if (ok) { const f4v* p = (const f4v*)((const float*)row + k); r.lo = p[0]; r.hi = p[1]; }
-  } else {
-    u4 z = {0u, 0u, 0u, 0u};
-    r.v = z;
-    if (ok) r.v = *(const u4*)((const uint16_t*)row + k);
-  }
-  return r;
-}
-template <int AT>
-__device__ __forceinline__ h8 cvt_raw_act(const RawAct<AT>& r) {
-  if constexpr (AT == DT_F32) {
+enum : int { AM_ROW_F16 = 0, AM_ROW_BF16 = 1, AM_ROW_F32 = 2, AM_FM = 3 };
+
+template <int AM> struct RawAct { u4 v; };
+template <> struct RawAct<AM_ROW_F32> { u4 lo, hi; };
+
+template <int AM>
+__device__ __forceinline__ h8 cvt_raw_act(const RawAct<AM>& r) {
+  if constexpr (AM == AM_ROW_F32) {
+    f4v lo = __builtin_bit_cast(f4v, r.lo), hi = __builtin_bit_cast(f4v, r.hi);
     h8 o;
-    o[0] = (_Float16)r.lo[0]; o[1] = (_Float16)r.lo[1]; o[2] = (_Float16)r.lo[2]; o[3] = (_Float16)r.lo[3];
-    o[4] = (_Float16)r.hi[0]; o[5] = (_Float16)r.hi[1]; o[6] = (_Float16)r.hi[2]; o[7] = (_Float16)r.hi[3];
+    o[0] = (_Float16)lo[0]; o[1] = (_Float16)lo[1]; o[2] = (_Float16)lo[2]; o[3] = (_Float16)lo[3];
+    o[4] = (_Float16)hi[0]; o[5] = (_Float16)hi[1]; o[6] = (_Float16)hi[2]; o[7] = (_Float16)hi[3];
     return o;
+  } else if constexpr (AM == AM_ROW_BF16) {
+    return raw_to_h8<DT_BF16>(r.v);
   } else {
-    return raw_to_h8<AT>(r.v);
+    return __builtin_bit_cast(h8, r.v);
   }
 }
 
-template <int AT, int WT, int BN>
-__global__ void __launch_bounds__(256, (AT == DT_F32 && BN == 128) ? 1 : 2) linear_kernel(LinearArgs a, int tiles_m, int tiles_n) {
-  constexpr int NT = BN / 32;                       // 32-column MFMA tiles per wavefront
-  constexpr int STAGE_WAVES = BN / 32;              // wavefronts that stage the weight tile
+template <int AM, int WT, int BN, bool CFM>
+__global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel(LinearArgs a, int tiles_m, int tiles_n) {
+  constexpr int NT = BN / 32;            // 32-column MFMA tiles per wavefront
+  constexpr int STAGE_WAVES = BN / 32;   // wavefronts that stage the weight tile
+  constexpr int ESZ = (AM == AM_ROW_F32) ? 4 : 2;
   __shared__ __attribute__((aligned(16))) _Float16 lds[2][BN * kLdsRow];
 
   const int tile = xcd_tile(blockIdx.x, tiles_m * tiles_n);
@@ -61,21 +58,28 @@ __global__ void __launch_bounds__(256, (AT == DT_F32 && BN == 128) ? 1 : 2) line
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int l32 = lane & 31, g = lane >> 5;
   const int m0 = tm * 256 + wave * 64;
-  const int K = a.K;
+  const int K = a.K, T = a.T;
+  const int kchunks = (K + kChunkK - 1) / kChunkK;
 
-  // activation row pointers (rows beyond T are clamped; their results are never stored)
-  const char* arow[2];
-  const size_t esz = (AT == DT_F32) ? 4 : 2;
+  // ---- activation addressing: one 32-bit offset per 32-row tile
+  const long long a_total = (AM == AM_FM) ? (long long)fm_bytes(T, K) : (long long)T * a.lda * ESZ;
+  int voffA[2];
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt) {
     int r = m0 + 32 * mt + l32;
-    r = r < a.T ? r : a.T - 1;
-    arow[mt] = (const char*)a.A + (size_t)r * a.lda * esz;
+    if constexpr (AM == AM_FM) {
+      voffA[mt] = fm_voff(r, kchunks, g);                 // rows past the last tile fall outside the resource
+    } else {
+      r = r < T ? r : T - 1;                              // clamped; their results are never stored
+      voffA[mt] = (r * a.lda + 32 * g) * ESZ;
+    }
   }
-  // weight staging coordinates
-  const int s_ng = (lane & 3) + 4 * wave;   // 8-column group inside the tile
-  const int s_q = lane >> 2;                // 4-row group inside the chunk
+  // ---- weight staging: thread -> 4 (k) x 8 (n) block
+  const int s_ng = (lane & 3) + 4 * wave;
+  const int s_q = lane >> 2;
   const bool stager = wave < STAGE_WAVES;
+  const long long w_total = (long long)K * G.ldw * 2;
+  const int voffW = (n0 + 8 * s_ng < G.N) ? (4 * s_q * G.ldw + 8 * s_ng) * 2 : kOobOffset;
 
   f16v acc[2][NT];
 #pragma unroll
@@ -83,29 +87,33 @@ __global__ void __launch_bounds__(256, (AT == DT_F32 && BN == 128) ? 1 : 2) line
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = zero16();
 
-  RawAct<AT> a_raw[2][4];
-  h8 a_frag[2][4];
+  RawAct<AM> rawA[2][2][4];   // [ping-pong][row tile][step]
   u4 w_raw[4];
 
-  const int nchunks = (K + kChunkK - 1) / kChunkK;
-
-  auto load_a = [&](int c) {
+  auto load_a = [&](int c, RawAct<AM> (&dst)[2][4]) {
+    const int kleft = K - c * kChunkK;
+    const rsrc_t r = (AM == AM_FM) ? rsrc_at(a.A, a_total, (long long)c * kFmChunkBytes)
+                                   : rsrc_at(a.A, a_total, (long long)c * kChunkK * ESZ);
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
-        int k = c * kChunkK + chunk_off(kk, g);
-        a_raw[mt][kk] = load_raw_act<AT>(arow[mt], k, k < K);
+        const int v = (32 * g + 8 * kk < kleft) ? voffA[mt] : kOobOffset;
+        if constexpr (AM == AM_FM) {
+          dst[mt][kk].v = buf_load16(r, v + kk * kFmStepBytes);
+        } else if constexpr (AM == AM_ROW_F32) {
+          dst[mt][kk].lo = buf_load16(r, v + kk * 32);
+          dst[mt][kk].hi = buf_load16(r, v + kk * 32 + 16);
+        } else {
+          dst[mt][kk].v = buf_load16(r, v + kk * 16);
+        }
       }
   };
-  auto cvt_a = [&]() {
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) a_frag[mt][kk] = cvt_raw_act<AT>(a_raw[mt][kk]);
-  };
   auto load_w = [&](int c) {
-    if (stager) load_w4x8<WT>(G.W, (size_t)G.ldw, c * kChunkK + 4 * s_q, n0 + 8 * s_ng, K, G.N, w_raw);
+    if (stager) {
+      const rsrc_t r = rsrc_at(G.W, w_total, ((long long)c * kChunkK * G.ldw + n0) * 2);
+      buf_load_w4x8(r, voffW, G.ldw * 2, w_raw);
+    }
   };
   auto store_w = [&](int buf) {
     if (stager) {
@@ -115,76 +123,120 @@ __global__ void __launch_bounds__(256, (AT == DT_F32 && BN == 128) ? 1 : 2) line
       for (int j = 0; j < 8; ++j) *(u2*)&lds[buf][(8 * s_ng + j) * kLdsRow + 4 * s_q] = t[j];
     }
   };
-
-  load_a(0);
-  load_w(0);
-  cvt_a();
-  store_w(0);
-  __syncthreads();
-
-  for (int c = 0; c < nchunks; ++c) {
-    const bool more = c + 1 < nchunks;
-    if (more) { load_a(c + 1); load_w(c + 1); }
-    const _Float16* wt = lds[c & 1];
+  auto compute = [&](const RawAct<AM> (&ra)[2][4], const _Float16* wt) {
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      h8 bf[NT];
+      h8 bf[NT], af[2];
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) bf[nt] = *(const h8*)&wt[(32 * nt + l32) * kLdsRow + chunk_off(kk, g)];
 #pragma unroll
+      for (int mt = 0; mt < 2; ++mt) af[mt] = cvt_raw_act<AM>(ra[mt][kk]);
+#pragma unroll
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = mfma32(a_frag[mt][kk], bf[nt], acc[mt][nt]);
+        for (int nt = 0; nt < NT; ++nt) {
+          if constexpr (CFM) acc[mt][nt] = mfma32(bf[nt], af[mt], acc[mt][nt]);   // rows n, cols tokens
+          else acc[mt][nt] = mfma32(af[mt], bf[nt], acc[mt][nt]);                 // rows tokens, cols n
+        }
     }
-    if (more) { store_w((c + 1) & 1); cvt_a(); }
+  };
+
+  load_a(0, rawA[0]);
+  load_w(0);
+  store_w(0);
+  __syncthreads();
+  for (int c = 0; c < kchunks; c += 2) {
+    const bool more1 = c + 1 < kchunks;
+    if (more1) { load_a(c + 1, rawA[1]); load_w(c + 1); }
+    compute(rawA[0], lds[0]);
+    if (more1) store_w(1);
+    __syncthreads();
+    if (!more1) break;
+    const bool more2 = c + 2 < kchunks;
+    if (more2) { load_a(c + 2, rawA[0]); load_w(c + 2); }
+    compute(rawA[1], lds[1]);
+    if (more2) store_w(0);
     __syncthreads();
   }
 
-  // epilogue
+  // ---- epilogue
+  if constexpr (CFM) {
+    // lane = token, registers = 4 consecutive output columns: 8-byte stores into the fragment-major output
+    const int nch = (G.N + 63) / 64;
+    const rsrc_t rB = rsrc_at(G.bias, G.bias ? (long long)G.N * 2 : 0, 0);
+    _Float16* C = (_Float16*)G.C;
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    const int col = n0 + 32 * nt + l32;
-    if (col >= G.N) continue;
-    const float bias = G.bias ? load_param(G.bias, col, a.w_dt) : 0.f;
+    for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+      for (int jj = 0; jj < 4; ++jj) {
+        const int n = n0 + 32 * nt + 8 * jj + 4 * g;   // first of 4 columns
+        if (n >= G.N) continue;
+        const f4v bias = raw_to_f4<WT>(buf_load8(rB, n * 2));
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = m0 + 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
-        if (row < a.T) {
-          float x = acc[mt][nt][v] + bias;
-          if (a.R) x += load_param(a.R, (size_t)row * a.ldr + col, a.r_dt);
-          store_out(G.C, (size_t)row * G.ldc + col, x, a.c_dt);
+        for (int mt = 0; mt < 2; ++mt) {
+          const int tok = m0 + 32 * mt + l32;
+          if (tok < T) {
+            const size_t unit = ((size_t)((tok >> 5) * nch + (n >> 6)) * 4 + jj) * 64 + ((n >> 5) & 1) * 32 + (tok & 31);
+            h4 o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = (_Float16)(acc[mt][nt][4 * jj + i] + bias[i]);
+            *(h4*)(C + unit * 8 + 4 * g) = o;
+          }
         }
       }
+  } else {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int col = n0 + 32 * nt + l32;
+      if (col >= G.N) continue;
+      const float bias = G.bias ? load_param(G.bias, col, a.w_dt) : 0.f;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
+          if (row < T) {
+            float x = acc[mt][nt][v] + bias;
+            if (a.R) x += load_param(a.R, (size_t)row * a.ldr + col, a.r_dt);
+            store_out(G.C, (size_t)row * G.ldc + col, x, a.c_dt);
+          }
+        }
+    }
   }
 }
 
-template <int AT, int WT>
-static hipError_t launch_bn(const LinearArgs& a, hipStream_t s) {
+template <int AM, int WT, bool CFM>
+hipError_t launch_bn(const LinearArgs& a, hipStream_t s) {
   const int tiles_m = (a.T + 255) / 256;
   int n128 = 0, n64 = 0;
   for (int i = 0; i < a.ngroups; ++i) { n128 += (a.g[i].N + 127) / 128; n64 += (a.g[i].N + 63) / 64; }
   // narrow tiles when the wide ones would leave compute units idle
   const bool narrow = (long)tiles_m * n128 < 320;
   if (narrow) {
-    hipLaunchKernelGGL((linear_kernel<AT, WT, 64>), dim3(tiles_m * n64), dim3(256), 0, s, a, tiles_m, n64);
+    hipLaunchKernelGGL((linear_kernel<AM, WT, 64, CFM>), dim3(tiles_m * n64), dim3(256), 0, s, a, tiles_m, n64);
   } else {
-    hipLaunchKernelGGL((linear_kernel<AT, WT, 128>), dim3(tiles_m * n128), dim3(256), 0, s, a, tiles_m, n128);
+    hipLaunchKernelGGL((linear_kernel<AM, WT, 128, CFM>), dim3(tiles_m * n128), dim3(256), 0, s, a, tiles_m, n128);
   }
   return hipGetLastError();
 }
 
+template <int AM, int WT>
+hipError_t launch_c(const LinearArgs& a, hipStream_t s) {
+  return a.c_layout == LAYOUT_FM ? launch_bn<AM, WT, true>(a, s) : launch_bn<AM, WT, false>(a, s);
+}
+
+template <int WT>
+hipError_t launch_a(const LinearArgs& a, hipStream_t s) {
+  if (a.a_layout == LAYOUT_FM) return launch_c<AM_FM, WT>(a, s);
+  if (a.a_dt == DT_F16) return launch_c<AM_ROW_F16, WT>(a, s);
+  if (a.a_dt == DT_BF16) return launch_c<AM_ROW_BF16, WT>(a, s);
+  return launch_c<AM_ROW_F32, WT>(a, s);
+}
+
+}  // namespace
+
 hipError_t launch_linear(const LinearArgs& a, hipStream_t s) {
-  if (a.w_dt == DT_F16) {
-    if (a.a_dt == DT_F16) return launch_bn<DT_F16, DT_F16>(a, s);
-    if (a.a_dt == DT_F32) return launch_bn<DT_F32, DT_F16>(a, s);
-    return launch_bn<DT_BF16, DT_F16>(a, s);
-  } else {
-    if (a.a_dt == DT_F16) return launch_bn<DT_F16, DT_BF16>(a, s);
-    if (a.a_dt == DT_F32) return launch_bn<DT_F32, DT_BF16>(a, s);
-    return launch_bn<DT_BF16, DT_BF16>(a, s);
-  }
+  return a.w_dt == DT_F16 ? launch_a<DT_F16>(a, s) : launch_a<DT_BF16>(a, s);
 }
 
 }  // namespace fsvd

@@ -1,4 +1,7 @@
 // Host-side launch interface of the fsvd kernels (internal to the library).
+//
+// "FM" below is the fragment-major fp16 activation layout defined in fsvd_common.h: every
+// intermediate activation that feeds a matrix-core contraction is kept in it.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stddef.h>
@@ -6,24 +9,28 @@
 
 namespace fsvd {
 
+enum : int { LAYOUT_ROW = 0, LAYOUT_FM = 1 };
+
 // ---- C[T, N] = A[T, K] W[K, N] (+ bias[N]) (+ R[T, N]) for up to three weight matrices sharing A
 struct LinearGroup {
   const void* W;     // [K, N] row-major, stored in w_dt
   const void* bias;  // [N] in w_dt, or nullptr
-  void* C;           // [T, N] with row stride ldc
+  void* C;           // ROW: [T, N] with row stride ldc; FM: fragment-major [T, N] (fp16)
   int N;
   int ldw;
   int ldc;
 };
 struct LinearArgs {
-  const void* A;  // [T, K] row stride lda, stored in a_dt (F16, BF16 or F32)
+  const void* A;  // ROW: [T, K] row stride lda in a_dt (F16, BF16 or F32); FM: fragment-major fp16 [T, K]
+  int a_layout;
   int lda;
   int a_dt;
   int T;
   int K;
   int w_dt;       // F16 or BF16
-  int c_dt;       // F16, BF16 or F32
-  const void* R;  // residual added in the epilogue (group 0 indexing), or nullptr
+  int c_layout;   // LAYOUT_ROW or LAYOUT_FM
+  int c_dt;       // ROW only: F16, BF16 or F32
+  const void* R;  // ROW only: residual [T, N] row stride ldr, added in the epilogue, or nullptr
   int ldr;
   int r_dt;
   int ngroups;
@@ -31,10 +38,9 @@ struct LinearArgs {
 };
 hipError_t launch_linear(const LinearArgs& a, hipStream_t s);
 
-// ---- streaming attention core (Alg. 1 Part II): rank-space P_q, P_k, P_v -> context C [T, D] (fp16)
+// ---- streaming attention core (Alg. 1 Part II): FM P_q, P_k, P_v -> FM context C [T, D]
 struct AttnCoreArgs {
-  const _Float16* Pq; const _Float16* Pk; const _Float16* Pv;  // [B*M, r_x], row strides ldpq/ldpk/ldpv
-  int ldpq, ldpk, ldpv;
+  const void* Pq; const void* Pk; const void* Pv;   // FM [B*M, r_x]
   int rq, rk, rv;
   const void* Vq; const void* Vk; const void* Vv;   // [r_x, D] stored in w_dt
   const void* bq; const void* bk; const void* bv;   // [D] in w_dt or nullptr
@@ -43,14 +49,13 @@ struct AttnCoreArgs {
   int causal;
   const int32_t* key_len;  // device [B] or nullptr
   float scale;             // softmax scale (already resolved, > 0)
-  _Float16* C;             // [B*M, D]
-  int ldc;
+  void* C;                 // FM [B*M, D]
 };
 hipError_t launch_attn_core(const AttnCoreArgs& a, hipStream_t s);
 
-// ---- fused FFN core (Alg. 2 inner loops): P1 [T, r1] -> Z [T, r2] = phi(P1 V1 + b1) U2
+// ---- fused FFN core (Alg. 2 inner loops): FM P1 [T, r1] -> FM Z [T, r2] = phi(P1 V1 + b1) U2
 struct FfnCoreArgs {
-  const _Float16* P1; int ldp; int r1;
+  const void* P1; int r1;
   const void* V1;    // [r1, F] in w_dt
   const void* b1;    // [F] in w_dt or nullptr
   const void* U2;    // [F, r2] in w_dt
@@ -58,19 +63,23 @@ struct FfnCoreArgs {
   int w_dt;
   int T, F;
   int act;
-  _Float16* Z; int ldz;  // [T, r2]
+  void* Z;
 };
 hipError_t launch_ffn_core(const FfnCoreArgs& a, hipStream_t s);
 
-// ---- LayerNorm over the last axis of [T, D]; writes up to two copies
+// ---- LayerNorm over the last axis of a row-major [T, D]; writes a row-major copy and/or an FM copy
 struct LayerNormArgs {
-  const void* X; int x_dt; int ldx;   // input in F16 / BF16 / F32
+  const void* X; int x_dt;            // row-major, F16 / BF16 / F32
   const void* gamma; const void* beta; int p_dt;
   float eps;
   int T, D;
-  void* Y0; int y0_dt; int ldy0;      // first output (required)
-  void* Y1; int y1_dt; int ldy1;      // optional second copy (nullptr to skip)
+  void* Yrow; int yrow_dt;            // row-major output or nullptr
+  void* Yfm;                          // FM fp16 output or nullptr
 };
 hipError_t launch_layernorm(const LayerNormArgs& a, hipStream_t s);
+
+// ---- layout conversion: row-major [T, K] (F16 / BF16 / F32) <-> FM fp16
+hipError_t launch_pack_fm(const void* src, int src_dt, int T, int K, void* dst_fm, hipStream_t s);
+hipError_t launch_unpack_fm(const void* src_fm, int T, int K, void* dst, int dst_dt, hipStream_t s);
 
 }  // namespace fsvd

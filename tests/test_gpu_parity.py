@@ -93,6 +93,27 @@ def test_layernorm(fb, T, D, xdt, ydt):
     assert np.abs(got - ref).max() <= eps * (np.abs(ref).max() + 1)
 
 
+@pytest.mark.parametrize("T,K,dt", [(70, 48, torch.float16), (257, 208, torch.bfloat16), (64, 64, torch.float32), (1, 16, torch.float16)])
+def test_fragment_major_pack_unpack_roundtrip(fb, T, K, dt):
+    """pack places element (t, k) where the documented layout says, zero-fills the padding, and unpack inverts it."""
+    g = torch.Generator().manual_seed(T * K)
+    A = torch.randn(T, K, generator=g).to(dt)
+    fm = fb.fsvd_pack_fm(A.to(DEV))
+    assert fm.numel() == ((T + 31) // 32) * ((K + 63) // 64) * 4096
+    halves = fm.cpu().view(torch.float16).numpy()
+    ref = np.zeros_like(halves)
+    A16 = A.to(torch.float16).numpy()
+    kc = (K + 63) // 64
+    for t in range(T):
+        for k in range(K):
+            c, gg, kk, s = k // 64, (k // 32) % 2, (k // 8) % 4, k % 8
+            unit = (((t // 32) * kc + c) * 4 + kk) * 64 + gg * 32 + t % 32
+            ref[unit * 8 + s] = A16[t, k]
+    np.testing.assert_array_equal(halves, ref)
+    back = fb.fsvd_unpack_fm(fm, T, K, torch.float32).cpu().numpy()
+    np.testing.assert_array_equal(back, A16.astype(np.float32))
+
+
 def _selector(total, start, width):
     S = np.zeros((total, width))
     S[np.arange(start, start + width), np.arange(width)] = 1.0
@@ -105,8 +126,9 @@ def test_attention_core_from_rank_space_inputs(fb, name):
     w, inp, dev = workload(name, fb)
     r = w.r_attn
     P = {a: O.rank_projection(inp["X"], inp[a]["U"]).astype(np.float16) for a in "qkv"}
-    Pd = {a: torch.from_numpy(P[a].reshape(w.T, r)).to(DEV) for a in "qkv"}
-    got = fb.fsvd_attention_core(dev["desc"], Pd["q"], Pd["k"], Pd["v"], dev["q"], dev["k"], dev["v"]).float().cpu().numpy()
+    Pd = {a: fb.fsvd_pack_fm(torch.from_numpy(P[a].reshape(w.T, r)).to(DEV)) for a in "qkv"}
+    ctx = fb.fsvd_attention_core(dev["desc"], Pd["q"], Pd["k"], Pd["v"], dev["q"], dev["k"], dev["v"])
+    got = fb.fsvd_unpack_fm(ctx, w.T, w.D, torch.float32).cpu().numpy().reshape(w.B, w.M, w.D)
     # oracle on x = [P_q | P_k | P_v] with 0/1 selector matrices as the U factors
     xcat = np.concatenate([P[a].astype(np.float64) for a in "qkv"], axis=-1)
     fac = {a: {"U": _selector(3 * r, i * r, r), "V": inp[a]["V"], "b": inp[a]["b"]} for i, a in enumerate("qkv")}
@@ -125,7 +147,8 @@ def test_ffn_core_from_rank_space_input(fb, name, act):
     w, inp, dev = workload(name, fb)
     P1 = O.rank_projection(inp["X"], inp["w1"]["U"]).astype(np.float16).reshape(w.T, w.r_ffn)
     d = fb.make_desc(w.B, w.M, w.D, w.H, w.F, dev["X"].dtype, act=act)
-    got = fb.fsvd_ffn_core(d, torch.from_numpy(P1).to(DEV), dev["w1"], dev["w2"]).float().cpu().numpy()
+    Zfm = fb.fsvd_ffn_core(d, fb.fsvd_pack_fm(torch.from_numpy(P1).to(DEV)), dev["w1"], dev["w2"])
+    got = fb.fsvd_unpack_fm(Zfm, w.T, w.r_ffn, torch.float32).cpu().numpy()
     hidden = O.activation(P1.astype(np.float64) @ inp["w1"]["V"].astype(np.float64) + inp["w1"]["b"], act)
     ref = O.rank_projection(hidden, inp["w2"]["U"])
     assert rel_err(got, ref) < 2.5e-3      # fp16 hidden activation + fp16 Z
