@@ -6,8 +6,8 @@
 //   Q phase : every wavefront rebuilds Q^T [d_h, 32*QT] for its own queries, contraction over r_q
 //             in 64-wide chunks, pre-scaled by softmax_scale*log2(e), and keeps it as MFMA operands.
 //   KV loop : per step of 128 keys, wavefront w rebuilds 64 keys of K (w even) or V (w odd) — weight
-//             chunks are transposed into LDS (double-buffered) and shared, P rows are read straight
-//             from global memory — adds the bias and publishes the fp16 tile in LDS in operand order.
+//             chunks are copied into LDS (double-buffered), shared, and read back transposed; P operands
+//             come straight from global memory — adds the bias and publishes the fp16 tile in LDS in operand order.
 //             Then every wavefront computes S^T = K Q^T for its queries, masks, updates the running
 //             row maximum / sum and accumulates O^T += V^T P~^T.
 // All products are arranged "transposed" (keys or features along accumulator rows, queries along
@@ -37,9 +37,11 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
   constexpr int DT32 = DH / 32;             // 32-wide feature tiles
   constexpr int DST = DH / 16;              // 16-wide contraction steps over d_h
   constexpr int BQ = kAttnWaves * QT * 32;  // queries per workgroup
-  constexpr int WBUF = DH * kLdsRow;        // halves per staged weight chunk (one matrix)
-  constexpr int NBM = 16 * (DH / 8);        // 4x8 staging blocks per matrix chunk
-  constexpr int NBLK = (2 * NBM) / 256;     // staging blocks per thread in the KV loop (1 or 2)
+  constexpr int WS = wtile_stride(DH);      // halves per LDS row of a staged weight chunk [64 ranks][DH]
+  constexpr int WBUF = kChunkK * WS;        // halves per staged weight chunk (one matrix)
+  constexpr int LPR = DH / 8;               // lanes per chunk row while staging (16 bytes each)
+  constexpr int RPP = 256 / LPR;            // chunk rows staged per pass
+  constexpr int NP = kChunkK / RPP;         // passes (loads per thread) per matrix chunk
 
   __shared__ __attribute__((aligned(16))) _Float16 wbuf[2][2][WBUF];   // [parity][K|V weights]
   __shared__ __attribute__((aligned(16))) h8 ktile[kBKV / 32][DST][64];
@@ -62,13 +64,9 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
   const int tok0 = b * M;
   const int col0 = h * DH;                    // this head's columns in V_a, b_a and C
 
-  // ---- weight staging: block id -> matrix, 4-row group, 8-column group
-  auto stage_coords = [&](int bid, int& mat, int& q4, int& ng) {
-    mat = bid / NBM;
-    const int w = bid % NBM;
-    q4 = (w >> 2) & 15;
-    ng = (w & 3) + 4 * (w >> 6);
-  };
+  // ---- weight staging: thread -> chunk row s_r (+ RPP per pass), 8 head columns from s_c
+  const int s_r = tid / LPR, s_c = 8 * (tid % LPR);
+  const int trA = tr_lane_off(lane, WS) + 32 * g * WS;   // transposing-read base of this lane (halves)
   // 4 consecutive bias entries of this head, as floats
   auto bias4 = [&](const void* bp, int d) -> f4v {
     const rsrc_t r = rsrc_at(bp, bp ? (long long)D * 2 : 0, 0);
@@ -94,29 +92,21 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
       q = q < M ? q : M - 1;
       voffP[qt] = fm_voff(tok0 + q, nc, g);
     }
-    int s_mat, s_q4, s_ng;
-    stage_coords(tid, s_mat, s_q4, s_ng);
-    const bool stager = tid < NBM;
-    const int voffW = (4 * s_q4 * D + 8 * s_ng) * 2;
-    u4 w_raw[4];
+    u4 w_raw[NP];
     h8 pfr[QT][4];
-    auto load_p = [&](int c, int kk) {
+    auto load_p = [&](int c, int kk) {   // the rank padding of an FM tensor holds zeros: no tail handling
       const rsrc_t r = rsrc_at(a.Pq, p_total, (long long)c * kFmChunkBytes);
-      const bool ok = c * kChunkK + 32 * g + 8 * kk < rq;
 #pragma unroll
-      for (int qt = 0; qt < QT; ++qt)
-        pfr[qt][kk] = __builtin_bit_cast(h8, buf_load16(r, (ok ? voffP[qt] : kOobOffset) + kk * kFmStepBytes));
+      for (int qt = 0; qt < QT; ++qt) pfr[qt][kk] = __builtin_bit_cast(h8, buf_load16(r, voffP[qt] + kk * kFmStepBytes));
     };
     auto issue_w = [&](int c) {
-      if (stager) buf_load_w4x8(rsrc_at(a.Vq, w_total, ((long long)c * kChunkK * D + col0) * 2), voffW, D * 2, w_raw);
-    };
-    auto commit_w = [&](int p) {
-      if (stager) {
-        u2 t[8];
-        transpose_w4x8<WT>(w_raw, t);
+      const rsrc_t r = rsrc_at(a.Vq, w_total, ((long long)c * kChunkK * D + col0) * 2);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) *(u2*)&wbuf[p][0][(8 * s_ng + j) * kLdsRow + 4 * s_q4] = t[j];
-      }
+      for (int p = 0; p < NP; ++p) w_raw[p] = buf_load16(r, ((s_r + p * RPP) * D + s_c) * 2);   // rows past r_q: 0
+    };
+    auto commit_w = [&](int pb) {
+#pragma unroll
+      for (int p = 0; p < NP; ++p) stage_store16<WT>(&wbuf[pb][0][(s_r + p * RPP) * WS + s_c], w_raw[p]);
     };
     issue_w(0);
 #pragma unroll
@@ -131,7 +121,10 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
       for (int kk = 0; kk < 4; ++kk) {
         h8 wf[DT32];
 #pragma unroll
-        for (int dt = 0; dt < DT32; ++dt) wf[dt] = *(const h8*)&wb[(32 * dt + l32) * kLdsRow + chunk_off(kk, g)];
+        for (int dt = 0; dt < DT32; ++dt) {
+          const _Float16* q = wb + trA + 8 * kk * WS + 32 * dt;
+          wf[dt] = tr_frag(q, q + 4 * WS);
+        }
 #pragma unroll
         for (int dt = 0; dt < DT32; ++dt)
 #pragma unroll
@@ -181,41 +174,35 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
   const int nc = (rmax + kChunkK - 1) / kChunkK;
   const int total = nsteps * nc;
 
-  int s_mat[NBLK], s_q4[NBLK], s_ng[NBLK], voffW[NBLK];
-#pragma unroll
-  for (int i = 0; i < NBLK; ++i) {
-    stage_coords(tid + 256 * i, s_mat[i], s_q4[i], s_ng[i]);
-    voffW[i] = (4 * s_q4[i] * D + 8 * s_ng[i]) * 2;
-  }
-  u4 w_raw[NBLK][4];
+  u4 w_raw[2][NP];
   auto issue_w = [&](int c) {
 #pragma unroll
-    for (int i = 0; i < NBLK; ++i) {
-      const void* W = s_mat[i] ? a.Vv : a.Vk;
-      const long long tot = (long long)(s_mat[i] ? a.rv : a.rk) * D * 2;
-      buf_load_w4x8(rsrc_at(W, tot, ((long long)c * kChunkK * D + col0) * 2), voffW[i], D * 2, w_raw[i]);
+    for (int m = 0; m < 2; ++m) {
+      const rsrc_t r = rsrc_at(m ? a.Vv : a.Vk, (long long)(m ? a.rv : a.rk) * D * 2, ((long long)c * kChunkK * D + col0) * 2);
+#pragma unroll
+      for (int p = 0; p < NP; ++p) w_raw[m][p] = buf_load16(r, ((s_r + p * RPP) * D + s_c) * 2);   // rows past the rank: 0
     }
   };
-  auto commit_w = [&](int p) {
+  auto commit_w = [&](int pb) {
 #pragma unroll
-    for (int i = 0; i < NBLK; ++i) {
-      u2 t[8];
-      transpose_w4x8<WT>(w_raw[i], t);
+    for (int m = 0; m < 2; ++m)
 #pragma unroll
-      for (int j = 0; j < 8; ++j) *(u2*)&wbuf[p][s_mat[i]][(8 * s_ng[i] + j) * kLdsRow + 4 * s_q4[i]] = t[j];
-    }
+      for (int p = 0; p < NP; ++p) stage_store16<WT>(&wbuf[pb][m][(s_r + p * RPP) * WS + s_c], w_raw[m][p]);
   };
   h8 pfr[2][4];
-  auto load_p = [&](int step, int c, int kk) {
-    const rsrc_t r = rsrc_at(Psrc, p_total, (long long)c * kFmChunkBytes);
-    const bool ok = c * kChunkK + 32 * g + 8 * kk < rr;
+  int voffKV[2];
+  auto set_keys = [&](int step) {
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
       int key = step * kBKV + 64 * kvt + 32 * kt + l32;
       key = key < M ? key : M - 1;
-      const int v = ok ? fm_voff(tok0 + key, pch, g) : kOobOffset;
-      pfr[kt][kk] = __builtin_bit_cast(h8, buf_load16(r, v + kk * kFmStepBytes));
+      voffKV[kt] = fm_voff(tok0 + key, pch, g);
     }
+  };
+  auto load_p = [&](int c, int kk) {      // chunks past this matrix's rank fall outside the resource: 0
+    const rsrc_t r = rsrc_at(Psrc, (c < pch) ? p_total : 0, (long long)c * kFmChunkBytes);
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) pfr[kt][kk] = __builtin_bit_cast(h8, buf_load16(r, voffKV[kt] + kk * kFmStepBytes));
   };
 
   f16v acc[DT32][2];
@@ -224,8 +211,9 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
 
   if (total > 0) {
     issue_w(0);
+    set_keys(0);
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) load_p(0, 0, kk);
+    for (int kk = 0; kk < 4; ++kk) load_p(0, kk);
     commit_w(0);
   }
   __syncthreads();
@@ -236,13 +224,17 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
     int nstep = step, ncn = c + 1;
     if (ncn == nc) { ncn = 0; nstep = step + 1; }
     if (more) issue_w(ncn);
+    if (ncn == 0) set_keys(nstep);          // the refills below already belong to the next step
     {
       const _Float16* wb = wbuf[it & 1][which];
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
         h8 wf[DT32];
 #pragma unroll
-        for (int dt = 0; dt < DT32; ++dt) wf[dt] = *(const h8*)&wb[(32 * dt + l32) * kLdsRow + chunk_off(kk, g)];
+        for (int dt = 0; dt < DT32; ++dt) {
+          const _Float16* q = wb + trA + 8 * kk * WS + 32 * dt;
+          wf[dt] = tr_frag(q, q + 4 * WS);
+        }
         if (which == 0) {
 #pragma unroll
           for (int dt = 0; dt < DT32; ++dt)
@@ -254,7 +246,7 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt) acc[dt][kt] = mfma32(pfr[kt][kk], wf[dt], acc[dt][kt]);   // V: rows keys, cols d
         }
-        if (more) load_p(nstep, ncn, kk);   // refill the operand registers just consumed
+        if (more) load_p(ncn, kk);          // refill the operand registers just consumed
       }
     }
     if (more) commit_w((it + 1) & 1);

@@ -101,48 +101,6 @@ __device__ __forceinline__ h8 load_act8(const void* base, size_t elem_off, bool 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Transposed staging of a weight tile.  Weights are row-major [K, N] with the contraction index K
-// as the slow axis, while an MFMA operand wants 8 consecutive contraction slots per lane, so a
-// tile is transposed in registers on its way into LDS: a thread loads a 4 (k) x 8 (n) block with
-// four 16-byte loads and emits, for each of the 8 columns, the 4 k-values as one 8-byte LDS store.
-// ---------------------------------------------------------------------------------------------
-template <int WT>
-__device__ __forceinline__ void load_w4x8(const void* W, size_t ldw, int k, int n, int K, int N, u4 raw[4]) {
-  const uint16_t* w = (const uint16_t*)W;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    u4 z = {0u, 0u, 0u, 0u};
-    raw[i] = z;
-    if (k + i < K && n < N) raw[i] = *(const u4*)(w + (size_t)(k + i) * ldw + n);
-  }
-}
-
-// out[j] = { W[k..k+3][n+j] } as 4 halves
-template <int WT>
-__device__ __forceinline__ void transpose_w4x8(const u4 raw[4], u2 out[8]) {
-#pragma unroll
-  for (int d = 0; d < 4; ++d) {
-    uint32_t r0 = raw[0][d], r1 = raw[1][d], r2 = raw[2][d], r3 = raw[3][d];
-    if constexpr (WT == DT_BF16) {
-      float l0 = __uint_as_float(r0 << 16), l1 = __uint_as_float(r1 << 16);
-      float l2 = __uint_as_float(r2 << 16), l3 = __uint_as_float(r3 << 16);
-      float g0 = __uint_as_float(r0 & 0xffff0000u), g1 = __uint_as_float(r1 & 0xffff0000u);
-      float g2 = __uint_as_float(r2 & 0xffff0000u), g3 = __uint_as_float(r3 & 0xffff0000u);
-      out[2 * d][0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(l0, l1));
-      out[2 * d][1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(l2, l3));
-      out[2 * d + 1][0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(g0, g1));
-      out[2 * d + 1][1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(g2, g3));
-    } else {
-      out[2 * d][0] = (r0 & 0xffffu) | (r1 << 16);
-      out[2 * d][1] = (r2 & 0xffffu) | (r3 << 16);
-      out[2 * d + 1][0] = (r0 >> 16) | (r1 & 0xffff0000u);
-      out[2 * d + 1][1] = (r2 >> 16) | (r3 & 0xffff0000u);
-    }
-  }
-}
-
-
-// ---------------------------------------------------------------------------------------------
 // Buffer addressing.  A tensor (or the part of it that starts at some scalar byte offset) is
 // described by a 128-bit resource held in scalar registers; an access is resource + one 32-bit
 // per-lane byte offset (+ immediate), and an access whose per-lane offset reaches the resource's
@@ -177,14 +135,6 @@ __device__ __forceinline__ f4v raw_to_f4(u2 raw) {
   return o;
 }
 
-// 4 (k) x 8 (n) weight block: rows start at voff + i * row_bytes.  K is a multiple of 4 and blocks
-// start at multiples of 4, so a block is in range as a whole or not at all: the range check of
-// row 0 (voff against the resource size) is applied to every row.
-__device__ __forceinline__ void buf_load_w4x8(rsrc_t r, int voff, int row_bytes, u4 raw[4]) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) raw[i] = __builtin_amdgcn_raw_buffer_load_b128(r, voff, i * row_bytes, 0);
-}
-
 // ---------------------------------------------------------------------------------------------
 // Fragment-major ("FM") layout of an fp16 activation A[T, K] that will be an MFMA operand.
 // Tokens are grouped in tiles of 32 and the contraction axis in chunks of 64; one (tile, chunk)
@@ -203,10 +153,38 @@ __device__ __forceinline__ int fm_voff(int t, int kchunks, int g) {
 constexpr int kFmChunkBytes = 4096;
 constexpr int kFmStepBytes = 1024;
 
-// LDS weight tiles are stored [n][k] with a row of kLdsK halves of payload plus 8 halves of padding,
-// so that 16 lanes reading 16 bytes from 16 consecutive rows hit distinct banks.
-constexpr int kChunkK = 64;             // contraction chunk staged per step
-constexpr int kLdsRow = kChunkK + 8;    // halves per LDS row
+// ---------------------------------------------------------------------------------------------
+// Weight tiles in LDS.  Weights are row-major [K, N] with the contraction index K as the slow axis,
+// while an MFMA operand wants 8 consecutive contraction slots per lane.  A tile is copied into LDS
+// as it lies in memory ([k][n], 16 bytes = 8 columns per lane, rows fully coalesced, bf16 widened to
+// fp16 on the way) and the transposition is done by the LDS itself on the way out: the gfx950
+// transposing read ds_read_b64_tr_b16 lets every 16 lanes fetch a 4 (k) x 16 (n) block such that
+// lane i receives column i's four k-values.  Two such reads make one operand register set.
+// Rows are padded by 32 bytes so that the four rows of a block fall into disjoint banks.
+// ---------------------------------------------------------------------------------------------
+typedef short s4v __attribute__((ext_vector_type(4)));
+constexpr int kChunkK = 64;                                   // contraction chunk staged per step
+__host__ __device__ constexpr int wtile_stride(int ncols) { return ncols + 16; }   // halves per LDS row
+
+// per-lane part of a transposing read's address (in halves): lane = 16 * group + i supplies row i / 4,
+// columns 4 * (i % 4) of its group's 4 x 16 block; groups 0..3 are (columns 0-15 | 16-31) x (g = 0 | 1)
+__device__ __forceinline__ int tr_lane_off(int lane, int stride) {
+  const int i = lane & 15;
+  return (i >> 2) * stride + 16 * ((lane >> 4) & 1) + 4 * (i & 3);
+}
+// operand registers of lane (column l % 32): k-rows of p0 then k-rows of p1 (4 each)
+__device__ __forceinline__ h8 tr_frag(const _Float16* p0, const _Float16* p1) {
+  const s4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s4v*)p0);
+  const s4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s4v*)p1);
+  typedef short s8v __attribute__((ext_vector_type(8)));
+  const s8v r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(h8, r);
+}
+// 8 stored weights (one 16-byte load) -> LDS as fp16
+template <int WT>
+__device__ __forceinline__ void stage_store16(_Float16* dst, u4 raw) {
+  *(u4*)dst = __builtin_bit_cast(u4, raw_to_h8<WT>(raw));
+}
 
 // Contraction-slot mapping inside one 64-wide chunk: MFMA step kk (0..3), lane group g (0..1),
 // slot s (0..7) stand for chunk offset 32*g + 8*kk + s.  An activation lane therefore reads 64

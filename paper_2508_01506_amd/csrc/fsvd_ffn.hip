@@ -10,8 +10,9 @@
 //            partner wavefront through LDS in MFMA operand order;
 //   phase B  Z^T[128*s + 64*wr.., tokens 64*wt..] += U_2[chunk, :]^T Y^T, one 128-rank sub-stage s at a
 //            time.
-// Every weight tile (128 contraction rows x 128 output columns) is transposed in registers on its
-// way into a double-buffered LDS tile; tile i+1 is fetched from global memory while tile i is used.
+// Every weight tile (128 contraction rows x 128 output columns) is copied as it lies in memory into a
+// double-buffered LDS tile and read back with the LDS's transposing read; tile i+1 is fetched from global
+// memory while tile i is used.
 // When r2 > 512 the slices are separate workgroups and phase A is recomputed per slice.
 #include "fsvd_common.h"
 #include "fsvd_kernels.h"
@@ -22,7 +23,7 @@ namespace {
 
 constexpr int kFfnBF = 128;                 // F chunk
 constexpr int kTile = 128;                  // weight tile edge
-constexpr int kTileRow = kTile + 8;         // halves per LDS tile row (16-lane conflict-free 16-byte reads)
+constexpr int kTileRow = wtile_stride(kTile);   // halves per LDS tile row
 constexpr int kMaxSlice = 512;
 
 // exact-GELU via the Abramowitz-Stegun 7.1.26 rational approximation of erf (|error| <= 1.5e-7),
@@ -62,42 +63,31 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
   const long long p_total = (long long)fm_bytes(T, r1);
   const long long v1_total = (long long)r1 * F * 2, u2_total = (long long)F * r2 * 2;
 
-  // ---- weight tile staging: each thread moves two 4 (k) x 8 (n) blocks
-  int sq[2], sng[2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int bid = tid + 256 * i;
-    sng[i] = (bid & 3) + 4 * ((bid >> 6) & 3);
-    sq[i] = ((bid >> 2) & 15) + 16 * (bid >> 8);
-  }
-  u4 w_raw[2][4];
+  // ---- weight tile staging: thread -> tile row s_r (+ 16 per pass), 8 columns from s_c; rows are copied as they
+  // lie in memory, the LDS transposes on the way out
+  const int s_r = tid >> 4, s_c = 8 * (tid & 15);
+  u4 w_raw[8];
   // kind 0: V_1 rows r of stage idx, columns f of chunk c.  kind 1: U_2 rows f of chunk c, columns s0 + 128*idx.
   auto issue_tile = [&](int kind, int c, int idx) {
     if (kind == 0) {
       const rsrc_t r = rsrc_at(a.V1, v1_total, ((long long)idx * kTile * F + c * kFfnBF) * 2);
+      const bool ok = c * kFfnBF + s_c < F;
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-        buf_load_w4x8(r, (c * kFfnBF + 8 * sng[i] < F) ? (4 * sq[i] * F + 8 * sng[i]) * 2 : kOobOffset, F * 2, w_raw[i]);
+      for (int p = 0; p < 8; ++p) w_raw[p] = buf_load16(r, ok ? ((s_r + 16 * p) * F + s_c) * 2 : kOobOffset);
     } else {
       const int n0 = s0 + idx * kTile;
       const rsrc_t r = rsrc_at(a.U2, u2_total, ((long long)c * kFfnBF * r2 + n0) * 2);
+      const bool ok = n0 + s_c < s_end;
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-        buf_load_w4x8(r, (n0 + 8 * sng[i] < s_end) ? (4 * sq[i] * r2 + 8 * sng[i]) * 2 : kOobOffset, r2 * 2, w_raw[i]);
+      for (int p = 0; p < 8; ++p) w_raw[p] = buf_load16(r, ok ? ((s_r + 16 * p) * r2 + s_c) * 2 : kOobOffset);
     }
   };
-  // kind 1 tiles store their 4-row groups in accumulator order (0-3, 8-11, 4-7, 12-15 of every 16)
-  auto commit_tile = [&](int kind, int p) {
+  auto commit_tile = [&](int pb) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      u2 t[8];
-      transpose_w4x8<WT>(w_raw[i], t);
-      int q = sq[i];
-      if (kind == 1) q = (q & ~3) | ((q & 1) << 1) | ((q >> 1) & 1);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) *(u2*)&wt_lds[p][(8 * sng[i] + j) * kTileRow + 4 * q] = t[j];
-    }
+    for (int p = 0; p < 8; ++p) stage_store16<WT>(&wt_lds[pb][(s_r + 16 * p) * kTileRow + s_c], w_raw[p]);
   };
+  const int trA = tr_lane_off(lane, kTileRow) + 32 * g * kTileRow;   // phase A: k rows 32 g + 8 kk + 0..7
+  const int trB = tr_lane_off(lane, kTileRow) + 4 * g * kTileRow;    // phase B: k rows 16 fs + 4 g + {0..3, 8..11}
 
   // ---- P1 operands of this wavefront's tokens (fragment-major: one contiguous 1 KiB load each)
   int voffP[2];
@@ -108,12 +98,11 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
     voffP[tt] = fm_voff(tok, pch, g);
   }
   h8 pfr[2][4];
-  auto load_p = [&](int half, int kk) {   // half: 64-wide piece of r1
-    const rsrc_t r = rsrc_at(a.P1, p_total, (long long)half * kFmChunkBytes);
-    const bool ok = half * 64 + 32 * g + 8 * kk < r1;
+  auto load_p = [&](int half, int kk) {   // half: 64-wide piece of r1 (the rank padding of an FM tensor holds zeros;
+                                          // a half beyond the tensor falls outside the resource)
+    const rsrc_t r = rsrc_at(a.P1, (half < pch) ? p_total : 0, (long long)half * kFmChunkBytes);
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt)
-      pfr[tt][kk] = __builtin_bit_cast(h8, buf_load16(r, (ok ? voffP[tt] : kOobOffset) + kk * kFmStepBytes));
+    for (int tt = 0; tt < 2; ++tt) pfr[tt][kk] = __builtin_bit_cast(h8, buf_load16(r, voffP[tt] + kk * kFmStepBytes));
   };
   const int nhalf = 2 * nA;
 
@@ -127,7 +116,7 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
   issue_tile(0, 0, 0);
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) load_p(0, kk);
-  commit_tile(0, 0);
+  commit_tile(0);
   __syncthreads();
 
   for (int c = 0; c < nchunks; ++c) {
@@ -148,8 +137,10 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
         for (int kk = 0; kk < 4; ++kk) {
           h8 wf[FT];
 #pragma unroll
-          for (int ft = 0; ft < FT; ++ft)
-            wf[ft] = *(const h8*)&wb[(ROWS * wr + 32 * ft + l32) * kTileRow + 64 * hh + 32 * g + 8 * kk];
+          for (int ft = 0; ft < FT; ++ft) {
+            const _Float16* q = wb + trA + (64 * hh + 8 * kk) * kTileRow + ROWS * wr + 32 * ft;
+            wf[ft] = tr_frag(q, q + 4 * kTileRow);
+          }
 #pragma unroll
           for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
@@ -181,7 +172,7 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
         else if (a.act == 1) publish([](float x) { return gelu_tanh_f(x); });
         else publish([](float x) { return fmaxf(x, 0.f); });
       }
-      commit_tile(lastA ? 1 : 0, parity ^ 1);
+      commit_tile(parity ^ 1);
       __syncthreads();
       parity ^= 1;
     }
@@ -202,14 +193,17 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
         for (int fs = 0; fs < 8; ++fs) {
           h8 wf[FT];
 #pragma unroll
-          for (int rt = 0; rt < FT; ++rt) wf[rt] = *(const h8*)&wb[(ROWS * wr + 32 * rt + l32) * kTileRow + 16 * fs + 8 * g];
+          for (int rt = 0; rt < FT; ++rt) {
+            const _Float16* q = wb + trB + 16 * fs * kTileRow + ROWS * wr + 32 * rt;
+            wf[rt] = tr_frag(q, q + 8 * kTileRow);
+          }
 #pragma unroll
           for (int rt = 0; rt < FT; ++rt)
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) z[s][rt][tt] = mfma32(wf[rt], gq[fs][tt], z[s][rt][tt]);   // rows ranks, cols tokens
         }
       }
-      if (more) commit_tile(lastB ? 0 : 1, parity ^ 1);
+      if (more) commit_tile(parity ^ 1);
       __syncthreads();
       parity ^= 1;
     }
@@ -228,7 +222,7 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
           const int r = s0 + s * kTile + ROWS * wr + 32 * rt + 8 * jj + 4 * g;
-          if (r < s_end) {
+          if (r < s0 + slice_w && r < zch * 64) {   // ranks r2 .. 64*zch-1 are written as zeros (FM padding)
             const size_t unit = ((size_t)((tok >> 5) * zch + (r >> 6)) * 4 + ((r >> 3) & 3)) * 64 + ((r >> 5) & 1) * 32 + (tok & 31);
             h4 o;
 #pragma unroll

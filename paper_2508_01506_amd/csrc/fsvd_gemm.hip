@@ -5,8 +5,8 @@
 // One workgroup = 4 wavefronts stacked along the rows: a 256 x BN output tile, each wavefront a
 // 64 x BN slab held as 32x32 MFMA accumulators.  Activation operands go from global memory straight
 // into registers (no other wavefront needs them); in the fragment-major layout that is one
-// contiguous 1 KiB load per operand.  Weight tiles are transposed in registers and double-buffered
-// in LDS, where all four wavefronts read them: 0.5 KiB of LDS reads per MFMA.
+// contiguous 1 KiB load per operand.  Weight tiles are copied row by row into a double-buffered LDS
+// tile and read back with the LDS's transposing read by all four wavefronts: 0.5 KiB per MFMA.
 // A fragment-major output is produced with the operand roles swapped (rows = output columns,
 // lanes = tokens), so that each lane owns 4 consecutive output columns of one token and a wavefront
 // writes contiguous 512-byte runs of the destination layout.
@@ -40,9 +40,12 @@ __device__ __forceinline__ h8 cvt_raw_act(const RawAct<AM>& r) {
 template <int AM, int WT, int BN, bool CFM>
 __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel(LinearArgs a, int tiles_m, int tiles_n) {
   constexpr int NT = BN / 32;            // 32-column MFMA tiles per wavefront
-  constexpr int STAGE_WAVES = BN / 32;   // wavefronts that stage the weight tile
   constexpr int ESZ = (AM == AM_ROW_F32) ? 4 : 2;
-  __shared__ __attribute__((aligned(16))) _Float16 lds[2][BN * kLdsRow];
+  constexpr int WS = wtile_stride(BN);   // halves per LDS tile row
+  constexpr int LPR = BN / 8;            // lanes per tile row while staging (16 bytes each)
+  constexpr int RPP = 256 / LPR;         // tile rows staged per pass
+  constexpr int NP = kChunkK / RPP;      // passes (loads per thread) per chunk
+  __shared__ __attribute__((aligned(16))) _Float16 lds[2][kChunkK * WS];
 
   const int tile = xcd_tile(blockIdx.x, tiles_m * tiles_n);
   const int tm = tile / tiles_n;
@@ -74,12 +77,11 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
       voffA[mt] = (r * a.lda + 32 * g) * ESZ;
     }
   }
-  // ---- weight staging: thread -> 4 (k) x 8 (n) block
-  const int s_ng = (lane & 3) + 4 * wave;
-  const int s_q = lane >> 2;
-  const bool stager = wave < STAGE_WAVES;
+  // ---- weight staging: thread -> row s_r (+ RPP per pass), 8 columns from s_c
+  const int s_r = threadIdx.x / LPR, s_c = 8 * (threadIdx.x % LPR);
   const long long w_total = (long long)K * G.ldw * 2;
-  const int voffW = (n0 + 8 * s_ng < G.N) ? (4 * s_q * G.ldw + 8 * s_ng) * 2 : kOobOffset;
+  const bool s_ok = n0 + s_c < G.N;
+  const int trA = tr_lane_off(lane, WS) + 32 * g * WS;   // transposing-read base of this lane (halves)
 
   f16v acc[2][NT];
 #pragma unroll
@@ -88,7 +90,7 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
     for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = zero16();
 
   RawAct<AM> rawA[2][2][4];   // [ping-pong][row tile][step]
-  u4 w_raw[4];
+  u4 w_raw[NP];
 
   auto load_a = [&](int c, RawAct<AM> (&dst)[2][4]) {
     const int kleft = K - c * kChunkK;
@@ -98,9 +100,12 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
+        if constexpr (AM == AM_FM) {
+          dst[mt][kk].v = buf_load16(r, voffA[mt] + kk * kFmStepBytes);   // the k padding of an FM tensor holds zeros
+          continue;
+        }
         const int v = (32 * g + 8 * kk < kleft) ? voffA[mt] : kOobOffset;
         if constexpr (AM == AM_FM) {
-          dst[mt][kk].v = buf_load16(r, v + kk * kFmStepBytes);
         } else if constexpr (AM == AM_ROW_F32) {
           dst[mt][kk].lo = buf_load16(r, v + kk * 32);
           dst[mt][kk].hi = buf_load16(r, v + kk * 32 + 16);
@@ -110,25 +115,24 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
       }
   };
   auto load_w = [&](int c) {
-    if (stager) {
-      const rsrc_t r = rsrc_at(G.W, w_total, ((long long)c * kChunkK * G.ldw + n0) * 2);
-      buf_load_w4x8(r, voffW, G.ldw * 2, w_raw);
-    }
+    const rsrc_t r = rsrc_at(G.W, w_total, ((long long)c * kChunkK * G.ldw + n0) * 2);
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+      w_raw[p] = buf_load16(r, s_ok ? ((s_r + p * RPP) * G.ldw + s_c) * 2 : kOobOffset);   // rows past K: out of range -> 0
   };
   auto store_w = [&](int buf) {
-    if (stager) {
-      u2 t[8];
-      transpose_w4x8<WT>(w_raw, t);
 #pragma unroll
-      for (int j = 0; j < 8; ++j) *(u2*)&lds[buf][(8 * s_ng + j) * kLdsRow + 4 * s_q] = t[j];
-    }
+    for (int p = 0; p < NP; ++p) stage_store16<WT>(&lds[buf][(s_r + p * RPP) * WS + s_c], w_raw[p]);
   };
   auto compute = [&](const RawAct<AM> (&ra)[2][4], const _Float16* wt) {
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       h8 bf[NT], af[2];
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) bf[nt] = *(const h8*)&wt[(32 * nt + l32) * kLdsRow + chunk_off(kk, g)];
+      for (int nt = 0; nt < NT; ++nt) {
+        const _Float16* q = wt + trA + 8 * kk * WS + 32 * nt;
+        bf[nt] = tr_frag(q, q + 4 * WS);
+      }
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt) af[mt] = cvt_raw_act<AM>(ra[mt][kk]);
 #pragma unroll
@@ -170,7 +174,7 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
         const int n = n0 + 32 * nt + 8 * jj + 4 * g;   // first of 4 columns
-        if (n >= G.N) continue;
+        if (n >= nch * 64) continue;                   // columns N .. 64*nch-1 are written as zeros (FM padding)
         const f4v bias = raw_to_f4<WT>(buf_load8(rB, n * 2));
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
