@@ -1,15 +1,17 @@
 // Streaming attention over rank-space inputs (Alg. 1): Q, K and V tiles are rebuilt on chip from
-// P_q, P_k, P_v [T, r] (fragment-major fp16) and the head's columns of V_q, V_k, V_v [r, D] (Alg. 1 Part I), scores and the
-// streaming softmax never leave registers (Part II), and only the context C [T, D] is written (fragment-major fp16).
+// P_q, P_k, P_v [T, r] (fragment-major fp16) and the head's columns of V_q, V_k, V_v [r, D] (Alg. 1 Part I),
+// scores and the streaming softmax never leave registers (Part II), and only the context C [T, D] is
+// written (fragment-major fp16).
 //
-// One workgroup (4 wavefronts) owns one (sequence, head, block of BQ = 128*QT queries).
+// One workgroup (8 wavefronts, two per SIMD so that one wavefront's softmax / waits overlap the other's
+// MFMAs) owns one (sequence, head, block of BQ = 256*QT queries).
 //   Q phase : every wavefront rebuilds Q^T [d_h, 32*QT] for its own queries, contraction over r_q
 //             in 64-wide chunks, pre-scaled by softmax_scale*log2(e), and keeps it as MFMA operands.
-//   KV loop : per step of 128 keys, wavefront w rebuilds 64 keys of K (w even) or V (w odd) — weight
+//   KV loop : per step of 128 keys, wavefront w rebuilds 32 keys of K (w even) or V (w odd) — weight
 //             chunks are copied into LDS (double-buffered), shared, and read back transposed; P operands
-//             come straight from global memory — adds the bias and publishes the fp16 tile in LDS in operand order.
-//             Then every wavefront computes S^T = K Q^T for its queries, masks, updates the running
-//             row maximum / sum and accumulates O^T += V^T P~^T.
+//             come straight from global memory — adds the bias and publishes the fp16 tile in LDS in
+//             operand order.  Then every wavefront computes S^T = K Q^T for its queries, masks, updates
+//             the running row maximum / sum and accumulates O^T += V^T P~^T.
 // All products are arranged "transposed" (keys or features along accumulator rows, queries along
 // lanes), so the accumulators of one product are, after rounding to fp16, exactly the operand
 // registers of the next one: no activation ever needs a transpose or an LDS round trip except the
@@ -21,8 +23,9 @@ namespace fsvd {
 
 namespace {
 
-constexpr int kAttnWaves = 4;
-constexpr int kBKV = 128;            // keys per step (two 64-key slabs, each rebuilt by a K and a V wavefront)
+constexpr int kAttnWaves = 8;
+constexpr int kAttnThreads = kAttnWaves * 64;
+constexpr int kBKV = 128;            // keys per step: four 32-key slabs, each rebuilt by a K and a V wavefront
 constexpr float kLog2e = 1.4426950408889634f;
 
 __device__ __forceinline__ h8 pack8(const f16v& x, int t, float add) {
@@ -33,14 +36,14 @@ __device__ __forceinline__ h8 pack8(const f16v& x, int t, float add) {
 }
 
 template <int DH, int QT, int WT>
-__global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int nqb) {
+__global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs a, int nqb) {
   constexpr int DT32 = DH / 32;             // 32-wide feature tiles
   constexpr int DST = DH / 16;              // 16-wide contraction steps over d_h
   constexpr int BQ = kAttnWaves * QT * 32;  // queries per workgroup
   constexpr int WS = wtile_stride(DH);      // halves per LDS row of a staged weight chunk [64 ranks][DH]
   constexpr int WBUF = kChunkK * WS;        // halves per staged weight chunk (one matrix)
   constexpr int LPR = DH / 8;               // lanes per chunk row while staging (16 bytes each)
-  constexpr int RPP = 256 / LPR;            // chunk rows staged per pass
+  constexpr int RPP = kAttnThreads / LPR;   // chunk rows staged per pass
   constexpr int NP = kChunkK / RPP;         // passes (loads per thread) per matrix chunk
 
   __shared__ __attribute__((aligned(16))) _Float16 wbuf[2][2][WBUF];   // [parity][K|V weights]
@@ -48,7 +51,8 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
   __shared__ __attribute__((aligned(16))) h8 vtile[kBKV / 32][DT32][2][64];
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+  const int lane = tid & 63, l32 = lane & 31, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it scalar
   const int BH = a.B * a.H;
   const int bh = blockIdx.x % BH;
   const int qb = nqb - 1 - blockIdx.x / BH;   // late query blocks (most keys under a causal mask) first
@@ -112,10 +116,12 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) load_p(0, kk);
     commit_w(0);
+    if (nc > 1) issue_w(1);
     __syncthreads();
     for (int c = 0; c < nc; ++c) {
       const bool more = c + 1 < nc;
-      if (more) issue_w(c + 1);
+      if (more) commit_w((c + 1) & 1);       // chunk c+1 arrived during the previous iteration
+      if (c + 2 < nc) issue_w(c + 2);        // chunk c+2 has this whole iteration to land
       const _Float16* wb = wbuf[c & 1][0];
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
@@ -131,7 +137,6 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
           for (int qt = 0; qt < QT; ++qt) acc[dt][qt] = mfma32(wf[dt], pfr[qt][kk], acc[dt][qt]);
         if (more) load_p(c + 1, kk);     // refill the operand registers just consumed
       }
-      if (more) commit_w((c + 1) & 1);
       __syncthreads();
     }
     // bias, softmax scale (log2 domain), round to fp16 operands
@@ -164,7 +169,7 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
     for (int dt = 0; dt < DT32; ++dt) o[dt][qt] = zero16();
   }
 
-  const int kvt = wave >> 1;        // which 64-key slab of the step this wavefront rebuilds
+  const int kvt = wave >> 1;        // which 32-key slab of the step this wavefront rebuilds
   const int which = wave & 1;       // 0: keys, 1: values
   const void* Psrc = which ? a.Pv : a.Pk;
   const int rr = which ? a.rv : a.rk;
@@ -189,25 +194,21 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
 #pragma unroll
       for (int p = 0; p < NP; ++p) stage_store16<WT>(&wbuf[pb][m][(s_r + p * RPP) * WS + s_c], w_raw[m][p]);
   };
-  h8 pfr[2][4];
-  int voffKV[2];
+  h8 pfr[4];
+  int voffKV;
   auto set_keys = [&](int step) {
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-      int key = step * kBKV + 64 * kvt + 32 * kt + l32;
-      key = key < M ? key : M - 1;
-      voffKV[kt] = fm_voff(tok0 + key, pch, g);
-    }
+    int key = step * kBKV + 32 * kvt + l32;
+    key = key < M ? key : M - 1;
+    voffKV = fm_voff(tok0 + key, pch, g);
   };
   auto load_p = [&](int c, int kk) {      // chunks past this matrix's rank fall outside the resource: 0
     const rsrc_t r = rsrc_at(Psrc, (c < pch) ? p_total : 0, (long long)c * kFmChunkBytes);
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) pfr[kt][kk] = __builtin_bit_cast(h8, buf_load16(r, voffKV[kt] + kk * kFmStepBytes));
+    pfr[kk] = __builtin_bit_cast(h8, buf_load16(r, voffKV + kk * kFmStepBytes));
   };
 
-  f16v acc[DT32][2];
+  f16v acc[DT32];
 #pragma unroll
-  for (int dt = 0; dt < DT32; ++dt) { acc[dt][0] = zero16(); acc[dt][1] = zero16(); }
+  for (int dt = 0; dt < DT32; ++dt) acc[dt] = zero16();
 
   if (total > 0) {
     issue_w(0);
@@ -215,6 +216,7 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) load_p(0, kk);
     commit_w(0);
+    if (total > 1) issue_w(nc > 1 ? 1 : 0);
   }
   __syncthreads();
 
@@ -223,33 +225,23 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
     const bool more = it + 1 < total;
     int nstep = step, ncn = c + 1;
     if (ncn == nc) { ncn = 0; nstep = step + 1; }
-    if (more) issue_w(ncn);
-    if (ncn == 0) set_keys(nstep);          // the refills below already belong to the next step
+    if (more) commit_w((it + 1) & 1);                    // chunk it+1 arrived during the previous iteration
+    if (it + 2 < total) issue_w(ncn + 1 == nc ? 0 : ncn + 1);   // chunk it+2 has this whole iteration to land
+    if (ncn == 0) set_keys(nstep);                       // the refills below already belong to the next step
     {
       const _Float16* wb = wbuf[it & 1][which];
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
-        h8 wf[DT32];
 #pragma unroll
         for (int dt = 0; dt < DT32; ++dt) {
           const _Float16* q = wb + trA + 8 * kk * WS + 32 * dt;
-          wf[dt] = tr_frag(q, q + 4 * WS);
-        }
-        if (which == 0) {
-#pragma unroll
-          for (int dt = 0; dt < DT32; ++dt)
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt) acc[dt][kt] = mfma32(wf[dt], pfr[kt][kk], acc[dt][kt]);   // K^T: rows d, cols keys
-        } else {
-#pragma unroll
-          for (int dt = 0; dt < DT32; ++dt)
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt) acc[dt][kt] = mfma32(pfr[kt][kk], wf[dt], acc[dt][kt]);   // V: rows keys, cols d
+          const h8 wf = tr_frag(q, q + 4 * WS);
+          if (which == 0) acc[dt] = mfma32(wf, pfr[kk], acc[dt]);   // K^T: rows d, cols keys
+          else acc[dt] = mfma32(pfr[kk], wf, acc[dt]);              // V: rows keys, cols d
         }
         if (more) load_p(ncn, kk);          // refill the operand registers just consumed
       }
     }
-    if (more) commit_w((it + 1) & 1);
     __syncthreads();
 
     if (c == nc - 1) {
@@ -261,27 +253,23 @@ __global__ void __launch_bounds__(256, 1) attn_core_kernel(AttnCoreArgs a, int n
 #pragma unroll
           for (int jj = 0; jj < 4; ++jj) bias[jj] = bias4(a.bk, 32 * dt + 8 * jj + 4 * g);
 #pragma unroll
-          for (int kt = 0; kt < 2; ++kt)
+          for (int t = 0; t < 2; ++t) {
+            h8 r;
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-              h8 r;
-#pragma unroll
-              for (int i = 0; i < 8; ++i) r[i] = (_Float16)(acc[dt][kt][8 * t + i] + bias[2 * t + (i >> 2)][i & 3]);
-              ktile[2 * kvt + kt][2 * dt + t][lane] = r;
-            }
+            for (int i = 0; i < 8; ++i) r[i] = (_Float16)(acc[dt][8 * t + i] + bias[2 * t + (i >> 2)][i & 3]);
+            ktile[kvt][2 * dt + t][lane] = r;
+          }
         }
       } else {
 #pragma unroll
         for (int dt = 0; dt < DT32; ++dt) {
           const float bias = a.bv ? load_param(a.bv, col0 + 32 * dt + l32, a.w_dt) : 0.f;
 #pragma unroll
-          for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-            for (int t = 0; t < 2; ++t) vtile[2 * kvt + kt][dt][t][lane] = pack8(acc[dt][kt], t, bias);
+          for (int t = 0; t < 2; ++t) vtile[kvt][dt][t][lane] = pack8(acc[dt], t, bias);
         }
       }
 #pragma unroll
-      for (int dt = 0; dt < DT32; ++dt) { acc[dt][0] = zero16(); acc[dt][1] = zero16(); }
+      for (int dt = 0; dt < DT32; ++dt) acc[dt] = zero16();
       __syncthreads();
 
       // ---- scores, streaming softmax, context for this wavefront's queries
@@ -390,7 +378,7 @@ template <int DH, int QT>
 hipError_t launch_qt(const AttnCoreArgs& a, hipStream_t s) {
   constexpr int BQ = kAttnWaves * QT * 32;
   const int nqb = (a.M + BQ - 1) / BQ;
-  const dim3 grid(a.B * a.H * nqb), block(256);
+  const dim3 grid(a.B * a.H * nqb), block(kAttnThreads);
   if (a.w_dt == DT_F16) hipLaunchKernelGGL((attn_core_kernel<DH, QT, DT_F16>), grid, block, 0, s, a, nqb);
   else hipLaunchKernelGGL((attn_core_kernel<DH, QT, DT_BF16>), grid, block, 0, s, a, nqb);
   return hipGetLastError();
@@ -400,15 +388,8 @@ hipError_t launch_qt(const AttnCoreArgs& a, hipStream_t s) {
 
 hipError_t launch_attn_core(const AttnCoreArgs& a, hipStream_t s) {
   const int dh = a.D / a.H;
-  if (dh == 64) {
-    if (a.M <= 128) return launch_qt<64, 1>(a, s);
-    if (a.M <= 256) return launch_qt<64, 2>(a, s);
-    return launch_qt<64, 4>(a, s);
-  }
-  if (dh == 128) {
-    if (a.M <= 128) return launch_qt<128, 1>(a, s);
-    return launch_qt<128, 2>(a, s);
-  }
+  if (dh == 64) return a.M <= 256 ? launch_qt<64, 1>(a, s) : launch_qt<64, 2>(a, s);
+  if (dh == 128) return launch_qt<128, 1>(a, s);
   return hipErrorInvalidValue;
 }
 

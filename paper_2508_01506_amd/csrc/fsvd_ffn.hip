@@ -49,7 +49,8 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
   __shared__ __attribute__((aligned(16))) h8 gtile[4][2][2][64];   // [f tile][t][token tile][lane]
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+  const int lane = tid & 63, l32 = lane & 31, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it in scalar registers
   const int slice = blockIdx.x % nslices;
   const int tb = blockIdx.x / nslices;
   const int t0 = tb * kFfnBT;

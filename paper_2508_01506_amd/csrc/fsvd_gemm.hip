@@ -58,7 +58,8 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
   }
   const LinearGroup G = a.g[gi];
   const int n0 = tn * BN;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
   const int l32 = lane & 31, g = lane >> 5;
   const int m0 = tm * 256 + wave * 64;
   const int K = a.K, T = a.T;
@@ -89,30 +90,27 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = zero16();
 
-  RawAct<AM> rawA[2][2][4];   // [ping-pong][row tile][step]
+  RawAct<AM> rawA[2][4];      // [row tile][step]; a slot is refilled right after its last use with the next chunk's data
   u4 w_raw[NP];
 
-  auto load_a = [&](int c, RawAct<AM> (&dst)[2][4]) {
+  auto load_a = [&](int c, int kk) {
     const int kleft = K - c * kChunkK;
     const rsrc_t r = (AM == AM_FM) ? rsrc_at(a.A, a_total, (long long)c * kFmChunkBytes)
                                    : rsrc_at(a.A, a_total, (long long)c * kChunkK * ESZ);
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        if constexpr (AM == AM_FM) {
-          dst[mt][kk].v = buf_load16(r, voffA[mt] + kk * kFmStepBytes);   // the k padding of an FM tensor holds zeros
-          continue;
-        }
+    for (int mt = 0; mt < 2; ++mt) {
+      if constexpr (AM == AM_FM) {
+        rawA[mt][kk].v = buf_load16(r, voffA[mt] + kk * kFmStepBytes);   // the k padding of an FM tensor holds zeros
+      } else {
         const int v = (32 * g + 8 * kk < kleft) ? voffA[mt] : kOobOffset;
-        if constexpr (AM == AM_FM) {
-        } else if constexpr (AM == AM_ROW_F32) {
-          dst[mt][kk].lo = buf_load16(r, v + kk * 32);
-          dst[mt][kk].hi = buf_load16(r, v + kk * 32 + 16);
+        if constexpr (AM == AM_ROW_F32) {
+          rawA[mt][kk].lo = buf_load16(r, v + kk * 32);
+          rawA[mt][kk].hi = buf_load16(r, v + kk * 32 + 16);
         } else {
-          dst[mt][kk].v = buf_load16(r, v + kk * 16);
+          rawA[mt][kk].v = buf_load16(r, v + kk * 16);
         }
       }
+    }
   };
   auto load_w = [&](int c) {
     const rsrc_t r = rsrc_at(G.W, w_total, ((long long)c * kChunkK * G.ldw + n0) * 2);
@@ -124,7 +122,18 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
 #pragma unroll
     for (int p = 0; p < NP; ++p) stage_store16<WT>(&lds[buf][(s_r + p * RPP) * WS + s_c], w_raw[p]);
   };
-  auto compute = [&](const RawAct<AM> (&ra)[2][4], const _Float16* wt) {
+  // prologue: chunk 0 in LDS and in the operand registers, chunk 1's weights in flight
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) load_a(0, kk);
+  load_w(0);
+  store_w(0);
+  if (kchunks > 1) load_w(1);
+  __syncthreads();
+  for (int c = 0; c < kchunks; ++c) {
+    const bool more1 = c + 1 < kchunks;
+    if (more1) store_w((c + 1) & 1);          // chunk c+1 arrived during the previous iteration
+    if (c + 2 < kchunks) load_w(c + 2);       // chunk c+2 has this whole iteration to land
+    const _Float16* wt = lds[c & 1];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       h8 bf[NT], af[2];
@@ -134,7 +143,7 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
         bf[nt] = tr_frag(q, q + 4 * WS);
       }
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) af[mt] = cvt_raw_act<AM>(ra[mt][kk]);
+      for (int mt = 0; mt < 2; ++mt) af[mt] = cvt_raw_act<AM>(rawA[mt][kk]);
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -142,24 +151,8 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
           if constexpr (CFM) acc[mt][nt] = mfma32(bf[nt], af[mt], acc[mt][nt]);   // rows n, cols tokens
           else acc[mt][nt] = mfma32(af[mt], bf[nt], acc[mt][nt]);                 // rows tokens, cols n
         }
+      if (more1) load_a(c + 1, kk);
     }
-  };
-
-  load_a(0, rawA[0]);
-  load_w(0);
-  store_w(0);
-  __syncthreads();
-  for (int c = 0; c < kchunks; c += 2) {
-    const bool more1 = c + 1 < kchunks;
-    if (more1) { load_a(c + 1, rawA[1]); load_w(c + 1); }
-    compute(rawA[0], lds[0]);
-    if (more1) store_w(1);
-    __syncthreads();
-    if (!more1) break;
-    const bool more2 = c + 2 < kchunks;
-    if (more2) { load_a(c + 2, rawA[0]); load_w(c + 2); }
-    compute(rawA[1], lds[1]);
-    if (more2) store_w(0);
     __syncthreads();
   }
 
