@@ -171,7 +171,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
 
   const int kvt = wave >> 1;        // which 32-key slab of the step this wavefront rebuilds
   const int which = wave & 1;       // 0: keys, 1: values
-  const void* Psrc = which ? a.Pv : a.Pk;
+  const char* const Psrc = which ? uniform_ptr(a.Pv) : uniform_ptr(a.Pk);
   const int rr = which ? a.rv : a.rk;
   const int pch = (rr + kChunkK - 1) / kChunkK;
   const long long p_total = (long long)fm_bytes(T, rr);

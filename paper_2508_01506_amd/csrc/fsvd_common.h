@@ -160,11 +160,12 @@ constexpr int kFmStepBytes = 1024;
 // fp16 on the way) and the transposition is done by the LDS itself on the way out: the gfx950
 // transposing read ds_read_b64_tr_b16 lets every 16 lanes fetch a 4 (k) x 16 (n) block such that
 // lane i receives column i's four k-values.  Two such reads make one operand register set.
-// Rows are padded by 32 bytes so that the four rows of a block fall into disjoint banks.
+// Rows are padded by 64 bytes so that the four 64-byte row segments touched by 32 lanes of a
+// transposing read fall into disjoint banks.
 // ---------------------------------------------------------------------------------------------
 typedef short s4v __attribute__((ext_vector_type(4)));
 constexpr int kChunkK = 64;                                   // contraction chunk staged per step
-__host__ __device__ constexpr int wtile_stride(int ncols) { return ncols + 16; }   // halves per LDS row
+__host__ __device__ constexpr int wtile_stride(int ncols) { return ncols + 32; }   // halves per LDS row
 
 // per-lane part of a transposing read's address (in halves): lane = 16 * group + i supplies row i / 4,
 // columns 4 * (i % 4) of its group's 4 x 16 block; groups 0..3 are (columns 0-15 | 16-31) x (g = 0 | 1)
@@ -196,6 +197,15 @@ __device__ __forceinline__ int chunk_off(int kk, int g) { return 32 * g + 8 * kk
 __device__ __forceinline__ int xcd_tile(int linear, int total) {
   if ((total & 7) != 0) return linear;
   return (linear & 7) * (total >> 3) + (linear >> 3);
+}
+
+// A kernel-argument pointer as an opaque wave-uniform value in scalar registers.  Selecting between two such
+// pointers with a run-time condition then stays a scalar select instead of a lookup in a stack table of arguments.
+__device__ __forceinline__ const char* uniform_ptr(const void* p) {
+  const unsigned long long u = (unsigned long long)p;
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)u);
+  const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(u >> 32));
+  return (const char*)(((unsigned long long)hi << 32) | lo);
 }
 
 __device__ __forceinline__ float wave_sum(float v) {

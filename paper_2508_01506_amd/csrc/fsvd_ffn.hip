@@ -60,30 +60,43 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
   const int nA = (r1 + kTile - 1) / kTile;
   const int nchunks = (F + kFfnBF - 1) / kFfnBF;
   const int per_chunk = nA + NS;                                // tiles per chunk: nA of V_1, then NS of U_2
-  const int ntiles = nchunks * per_chunk;
   const int pch = (r1 + 63) / 64, zch = (r2 + 63) / 64;
   const long long p_total = (long long)fm_bytes(T, r1);
   const long long v1_total = (long long)r1 * F * 2, u2_total = (long long)F * r2 * 2;
+  const char* const pV1 = uniform_ptr(a.V1);
+  const char* const pU2 = uniform_ptr(a.U2);
 
   // ---- weight tile stream.  Tile (c, j): j < nA -> V_1 rows 128 j.., columns f of chunk c;
   //                                        j >= nA -> U_2 rows f of chunk c, columns s0 + 128 (j - nA)..
   // Thread -> tile row s_r (+ 16 per pass), 8 columns from s_c; rows are copied as they lie in memory.
   const int s_r = tid >> 4, s_c = 8 * (tid & 15);
+  // The stream is software-pipelined at the granularity of one 16-row pass p (0..7): while tile i is being used,
+  // pass p of tile i+1 (requested one stage ago) is converted and stored to the other LDS buffer and pass p of
+  // tile i+2 is requested into the same registers, interleaved with the MFMAs of step p.
   u4 w_raw[8];
-  auto issue_tile = [&](int c, int j) {
+  const char* src_base = nullptr;   // source of the tile currently being requested (two ahead of the tile in use)
+  int src_left = 0;
+  unsigned src_v0 = 0, src_ld = 0;
+  auto tile_src = [&](int c, int j) {
     const bool isA = j < nA;
     const int ld = isA ? F : r2;
     const long long off = isA ? ((long long)j * kTile * F + c * kFfnBF) : ((long long)c * kFfnBF * r2 + s0 + (j - nA) * kTile);
     const int cols = isA ? (F - c * kFfnBF) : (s_end - s0 - (j - nA) * kTile);      // valid columns of this tile
-    const rsrc_t r = rsrc_at(isA ? a.V1 : a.U2, isA ? v1_total : u2_total, off * 2);
-    const unsigned v0 = (s_c < cols) ? (unsigned)(s_r * ld + s_c) * 2u : (unsigned)kOobOffset;
-#pragma unroll
-    for (int p = 0; p < 8; ++p) w_raw[p] = buf_load16(r, (int)(v0 + (unsigned)(32 * p) * (unsigned)ld));   // rows past the end: 0
+    // branch-free scalar arithmetic (a chain of selects over kernel arguments would be turned into a table in scratch)
+    const long long sel = isA ? 1 : 0, live = (c < nchunks) ? 1 : 0;
+    long long left = (u2_total + (v1_total - u2_total) * sel) * live - off * 2;       // past the last tile: nothing
+    left = left < 0 ? 0 : left;
+    const unsigned long long pb = (unsigned long long)pU2 + ((unsigned long long)pV1 - (unsigned long long)pU2) * (unsigned long long)sel;
+    src_base = (const char*)pb + (left > 0 ? off * 2 : 0);
+    src_left = (int)left;
+    src_v0 = (s_c < cols) ? (unsigned)(s_r * ld + s_c) * 2u : (unsigned)kOobOffset;
+    src_ld = (unsigned)ld;
   };
-  auto commit_tile = [&](int pb) {
-#pragma unroll
-    for (int p = 0; p < 8; ++p) stage_store16<WT>(&wt_lds[pb][(s_r + 16 * p) * kTileRow + s_c], w_raw[p]);
+  auto issue_pass = [&](int p) {      // rows past the end of the tensor: 0
+    const rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void*)src_base, 0, src_left, 0x00020000);
+    w_raw[p] = buf_load16(r, (int)(src_v0 + (unsigned)(32 * p) * src_ld));
   };
+  auto commit_pass = [&](int pb, int p) { stage_store16<WT>(&wt_lds[pb][(s_r + 16 * p) * kTileRow + s_c], w_raw[p]); };
   const int trA = tr_lane_off(lane, kTileRow) + 32 * g * kTileRow + 32 * wave;   // phase A: k rows 32 g + 8 kk + 0..7
   const int trB = tr_lane_off(lane, kTileRow) + 4 * g * kTileRow + 32 * wave;    // phase B: k rows 16 fs + 4 g + {0..3, 8..11}
 
@@ -109,26 +122,25 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
   y[0] = zero16(); y[1] = zero16();
   h8 gq[8][2];
 
-  // ---- one stage of phase A: y += V_1 tile^T (features 32*wave..) x P1^T
-  auto stage_a = [&](const _Float16* wb, int c, int ra) {
+  // ---- one stage of phase A: y += V_1 tile^T (features 32*wave..) x P1^T; step p also moves pass p of the stream
+  auto stage_a = [&](const _Float16* wb, int c, int ra, int pb_next) {
     const bool lastA = ra + 1 == nA;
-    h8 wf[2][4];
+    h8 wf = tr_frag(wb + trA, wb + trA + 4 * kTileRow);
 #pragma unroll
-    for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const _Float16* q = wb + trA + (64 * hh + 8 * kk) * kTileRow;
-        wf[hh][kk] = tr_frag(q, q + 4 * kTileRow);
-      }
-#pragma unroll
-    for (int hh = 0; hh < 2; ++hh) {
+    for (int st = 0; st < 8; ++st) {
+      const int hh = st >> 2, kk = st & 3;
       const int nh = (lastA ? 0 : 2 * (ra + 1)) + hh;   // same slot of the next stage (wrapping into the next chunk)
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) y[tt] = mfma32(wf[hh][kk], pfr[hh][tt][kk], y[tt]);   // rows f, cols tokens
-        load_p(nh, hh, kk);
+      h8 wf_next = wf;
+      if (st < 7) {                                     // operand of the next step, fetched before this step's MFMAs
+        const _Float16* q = wb + trA + (64 * ((st + 1) >> 2) + 8 * ((st + 1) & 3)) * kTileRow;
+        wf_next = tr_frag(q, q + 4 * kTileRow);
       }
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) y[tt] = mfma32(wf, pfr[hh][tt][kk], y[tt]);   // rows f, cols tokens
+      commit_pass(pb_next, st);
+      issue_pass(st);
+      load_p(nh, hh, kk);
+      wf = wf_next;
     }
     if (lastA) {
       // bias, phi, fp16, publish in operand order for phase B
@@ -154,17 +166,23 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
     }
   };
   // ---- one sub-stage of phase B: z[s] += U_2 tile^T (ranks 128 s + 32*wave..) x Y^T
-  auto stage_b = [&](const _Float16* wb, f16v (&zs)[2]) {
-    h8 wf[8];
+  auto stage_b = [&](const _Float16* wb, f16v (&zs)[2], bool active, int pb_next) {
+    h8 wf = tr_frag(wb + trB, wb + trB + 8 * kTileRow);
 #pragma unroll
     for (int fs = 0; fs < 8; ++fs) {
-      const _Float16* q = wb + trB + 16 * fs * kTileRow;
-      wf[fs] = tr_frag(q, q + 8 * kTileRow);
+      h8 wf_next = wf;
+      if (fs < 7) {
+        const _Float16* q = wb + trB + 16 * (fs + 1) * kTileRow;
+        wf_next = tr_frag(q, q + 8 * kTileRow);
+      }
+      if (active) {
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) zs[tt] = mfma32(wf, gq[fs][tt], zs[tt]);   // rows ranks, cols tokens
+      }
+      commit_pass(pb_next, fs);
+      issue_pass(fs);
+      wf = wf_next;
     }
-#pragma unroll
-    for (int fs = 0; fs < 8; ++fs)
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt) zs[tt] = mfma32(wf[fs], gq[fs][tt], zs[tt]);   // rows ranks, cols tokens
   };
 
   // ---- prologue: tile 0 into LDS, tile 1 in flight
@@ -172,24 +190,24 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
   for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) load_p(hh, hh, kk);
-  issue_tile(0, 0);
-  commit_tile(0);
-  if (ntiles > 1) issue_tile(per_chunk > 1 ? 0 : 1, per_chunk > 1 ? 1 : 0);
+  tile_src(0, 0);
+#pragma unroll
+  for (int p = 0; p < 8; ++p) issue_pass(p);
+  tile_src(0, 1);
+#pragma unroll
+  for (int p = 0; p < 8; ++p) { commit_pass(0, p); issue_pass(p); }
   __syncthreads();
 
   int it = 0;
-  auto pipeline_step = [&](int c, int j) {              // (c, j): the tile in use
-    if (it + 1 < ntiles) commit_tile((it + 1) & 1);     // tile it+1 arrived during the previous stage
-    if (it + 2 < ntiles) {                              // tile it+2 has this whole stage and the next commit to land
-      int c2 = c, j2 = j + 2;
-      if (j2 >= per_chunk) { j2 -= per_chunk; ++c2; }
-      issue_tile(c2, j2);
-    }
+  auto next2_src = [&](int c, int j) {                 // source of the tile two ahead of (c, j); past the end: nothing
+    int c2 = c, j2 = j + 2;
+    if (j2 >= per_chunk) { j2 -= per_chunk; ++c2; }
+    tile_src(c2, j2);
   };
   for (int c = 0; c < nchunks; ++c) {
     for (int ra = 0; ra < nA; ++ra) {
-      pipeline_step(c, ra);
-      stage_a(wt_lds[it & 1], c, ra);
+      next2_src(c, ra);
+      stage_a(wt_lds[it & 1], c, ra, (it + 1) & 1);
       __syncthreads();
       ++it;
     }
@@ -199,8 +217,8 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
       for (int tt = 0; tt < 2; ++tt) gq[fs][tt] = gtile[fs >> 1][fs & 1][tt][lane];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-      pipeline_step(c, nA + s);
-      if (s0 + s * kTile < s_end) stage_b(wt_lds[it & 1], z[s]);
+      next2_src(c, nA + s);
+      stage_b(wt_lds[it & 1], z[s], s0 + s * kTile < s_end, (it + 1) & 1);
       __syncthreads();
       ++it;
     }
@@ -235,7 +253,6 @@ hipError_t launch_ns(const FfnCoreArgs& a, int nslices, int slice_w, hipStream_t
   else hipLaunchKernelGGL((ffn_core_kernel<NS, DT_BF16>), grid, block, 0, s, a, nslices, slice_w);
   return hipGetLastError();
 }
-
 }  // namespace
 
 hipError_t launch_ffn_core(const FfnCoreArgs& a, hipStream_t s) {
