@@ -21,6 +21,13 @@ for p in (ROOT, os.path.join(ROOT, "tests")):
 
 PEAK_MFMA_TFLOPS = 2500.0   # MI355X dense fp16 / bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch of the roofline kernel from hardware counters (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors
+# a copy of known size gives; summary in profiles/hbm_traffic_cores_<workload>.md).  Counters cannot be read from inside
+# this process, so the figure is the one of the committed profile; workloads without one report null.
+MEASURED_TRAFFIC_BYTES = {
+    ("cfg5_llm_b1_m4096_causal", "ffn_core_kernel"): int((4431.1 * 2.0 + 16.0) * 2 ** 20),
+    ("cfg5_llm_b1_m4096_causal", "attn_core_kernel"): int((343.5 * 2.0 + 34.0) * 2 ** 20),
+}
 DEFAULT_WORKLOAD = "cfg5_llm_b1_m4096_causal"   # the largest configuration: the one the MFMA-peak target is stated on
 
 
@@ -47,6 +54,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-traffic", action="store_true",
+                    help="also launch a plain copy of known size (fsvd_pack_fm of a 512 MiB fp16 matrix: reads 512 MiB, "
+                         "writes 512 MiB) so that a hardware-counter run can scale its byte counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding or collectives exist); use --gpus 1",
@@ -93,32 +103,48 @@ def main():
 
     # ---- dominant kernels, timed alone with events on the launch stream, in the launch configuration
     # the layer uses (same shapes, same dispatch): the fused FFN core and the streaming attention core
-    def timed(fn, n):
-        for _ in range(3):
+    # Each timed launch is preceded by the other core's launch and by a 512 MiB fill, so that it starts, as inside
+    # the layer, with its weights in HBM and not in the 256 MiB last-level cache left warm by its own previous launch.
+    def timed(fn, other, n):
+        for _ in range(2):
+            other(); fn()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for e0, e1 in ev:
+            other()
+            e0.record()
             fn()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(n):
-            fn()
-        e1.record()
+            e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / n
+        return sum(e0.elapsed_time(e1) for e0, e1 in ev) / n
 
-    g = torch.Generator(device="cuda:0").manual_seed(1)
-    P1 = torch.randn((w.T, rf), generator=g, device="cuda:0", dtype=torch.float16)
-    Z = torch.empty((w.T, rf), device="cuda:0", dtype=torch.float16)
-    Pq, Pk, Pv = (torch.randn((w.T, ra), generator=g, device="cuda:0", dtype=torch.float16) for _ in range(3))
-    Cx = torch.empty((w.B, w.M, w.D), device="cuda:0", dtype=torch.float16)
+    # operands of the two cores exactly as the layer produces them: rank projections of X, fragment-major
+    X2 = dev["X"].reshape(w.T, w.D)
+    proj = lambda f: fb.fsvd_pack_fm(fb.fsvd_linear(X2, f.U, out_dtype=torch.float16))
+    P1, Pq, Pk, Pv = proj(dev["w1"]), proj(dev["q"]), proj(dev["k"]), proj(dev["v"])
+    Z = torch.empty(fb.fsvd_fm_bytes(w.T, rf), device="cuda:0", dtype=torch.uint8)
+    Cx = torch.empty(fb.fsvd_fm_bytes(w.T, w.D), device="cuda:0", dtype=torch.uint8)
     n_k = max(3, min(args.steps, 20))
-    ffn_ms = timed(lambda: fb.fsvd_ffn_core(d, P1, dev["w1"], dev["w2"], out=Z), n_k)
-    attn_ms = timed(lambda: fb.fsvd_attention_core(d, Pq, Pk, Pv, dev["q"], dev["k"], dev["v"], out=Cx), n_k)
+    flush = torch.empty(512 << 20, device="cuda:0", dtype=torch.uint8)
+    run_ffn = lambda: fb.fsvd_ffn_core(d, P1, dev["w1"], dev["w2"], out=Z)
+    run_attn = lambda: fb.fsvd_attention_core(d, Pq, Pk, Pv, dev["q"], dev["k"], dev["v"], out=Cx)
+    ffn_ms = timed(run_ffn, lambda: (run_attn(), flush.zero_()), n_k)
+    attn_ms = timed(run_attn, lambda: (run_ffn(), flush.zero_()), n_k)
+    del flush
+    if args.calibrate_traffic:
+        src = torch.zeros((65536, 4096), device="cuda:0", dtype=torch.float16)
+        dst = torch.empty(fb.fsvd_fm_bytes(65536, 4096), device="cuda:0", dtype=torch.uint8)
+        for _ in range(3):
+            fb.fsvd_pack_fm(src, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     if ffn_ms >= attn_ms:
         kname, kflops, kms = "ffn_core_kernel", fl["ffn_core"], ffn_ms
     else:
         kname, kflops, kms = "attn_core_kernel", fl["rebuild_qkv"] + fl["attn_core"], attn_ms
     achieved = kflops / (kms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": kname, "achieved": round(achieved, 2), "peak": PEAK_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_TFLOPS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, kname)),
                 "kernel_ms": round(kms, 4), "algorithmic_flops": kflops,
                 "other_kernel_ms": {"ffn_core_kernel": round(ffn_ms, 4), "attn_core_kernel": round(attn_ms, 4)}}
 
