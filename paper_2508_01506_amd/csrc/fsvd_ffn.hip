@@ -33,24 +33,27 @@ constexpr int kMaxSlice = 512;
 // written so that the negative tail does not cancel.
 __device__ __forceinline__ float gelu_erf_f(float x) {
   const float z = fabsf(x) * 0.70710678118654752f;
-  const float t = __frcp_rn(1.0f + 0.3275911f * z);
+  const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * z);
   const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
   const float tail = 0.5f * poly * __builtin_amdgcn_exp2f(-z * z * 1.4426950408889634f);   // 0.5 * erfc(|x|/sqrt2)
   return x >= 0.f ? x * (1.0f - tail) : x * tail;
 }
 __device__ __forceinline__ float gelu_tanh_f(float x) {
   const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-  return x * __frcp_rn(1.0f + __builtin_amdgcn_exp2f(-2.0f * u * 1.4426950408889634f));
+  return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-2.0f * u * 1.4426950408889634f));
 }
 
 template <int NS, int WT>
-__global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nslices, int slice_w) {
+__global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nslices, int slice_w) {
   __shared__ __attribute__((aligned(16))) _Float16 wt_lds[2][kTile * kTileRow];
+  __shared__ __attribute__((aligned(16))) h8 ptile[2][16][64];     // [buffer][(token tile * 2 + hh) * 4 + kk][lane]
   __shared__ __attribute__((aligned(16))) h8 gtile[4][2][2][64];   // [f tile][t][token tile][lane]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, l32 = lane & 31, g = lane >> 5;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it in scalar registers
+  const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it in scalar registers
+  const int wave = wave8 & 3;                                    // index inside the role
+  const bool loader = wave8 >= 4;
   const int slice = blockIdx.x % nslices;
   const int tb = blockIdx.x / nslices;
   const int t0 = tb * kFfnBT;
@@ -61,60 +64,104 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
   const int nchunks = (F + kFfnBF - 1) / kFfnBF;
   const int per_chunk = nA + NS;                                // tiles per chunk: nA of V_1, then NS of U_2
   const int pch = (r1 + 63) / 64, zch = (r2 + 63) / 64;
-  const long long p_total = (long long)fm_bytes(T, r1);
-  const long long v1_total = (long long)r1 * F * 2, u2_total = (long long)F * r2 * 2;
-  const char* const pV1 = uniform_ptr(a.V1);
-  const char* const pU2 = uniform_ptr(a.U2);
 
-  // ---- weight tile stream.  Tile (c, j): j < nA -> V_1 rows 128 j.., columns f of chunk c;
-  //                                        j >= nA -> U_2 rows f of chunk c, columns s0 + 128 (j - nA)..
-  // Thread -> tile row s_r (+ 16 per pass), 8 columns from s_c; rows are copied as they lie in memory.
-  const int s_r = tid >> 4, s_c = 8 * (tid & 15);
-  // The stream is software-pipelined at the granularity of one 16-row pass p (0..7): while tile i is being used,
-  // pass p of tile i+1 (requested one stage ago) is converted and stored to the other LDS buffer and pass p of
-  // tile i+2 is requested into the same registers, interleaved with the MFMAs of step p.
-  u4 w_raw[8];
-  const char* src_base = nullptr;   // source of the tile currently being requested (two ahead of the tile in use)
-  int src_left = 0;
-  unsigned src_v0 = 0, src_ld = 0;
-  auto tile_src = [&](int c, int j) {
-    const bool isA = j < nA;
-    const int ld = isA ? F : r2;
-    const long long off = isA ? ((long long)j * kTile * F + c * kFfnBF) : ((long long)c * kFfnBF * r2 + s0 + (j - nA) * kTile);
-    const int cols = isA ? (F - c * kFfnBF) : (s_end - s0 - (j - nA) * kTile);      // valid columns of this tile
-    // branch-free scalar arithmetic (a chain of selects over kernel arguments would be turned into a table in scratch)
-    const long long sel = isA ? 1 : 0, live = (c < nchunks) ? 1 : 0;
-    long long left = (u2_total + (v1_total - u2_total) * sel) * live - off * 2;       // past the last tile: nothing
-    left = left < 0 ? 0 : left;
-    const unsigned long long pb = (unsigned long long)pU2 + ((unsigned long long)pV1 - (unsigned long long)pU2) * (unsigned long long)sel;
-    src_base = (const char*)pb + (left > 0 ? off * 2 : 0);
-    src_left = (int)left;
-    src_v0 = (s_c < cols) ? (unsigned)(s_r * ld + s_c) * 2u : (unsigned)kOobOffset;
-    src_ld = (unsigned)ld;
-  };
-  auto issue_pass = [&](int p) {      // rows past the end of the tensor: 0
-    const rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void*)src_base, 0, src_left, 0x00020000);
-    w_raw[p] = buf_load16(r, (int)(src_v0 + (unsigned)(32 * p) * src_ld));
-  };
-  auto commit_pass = [&](int pb, int p) { stage_store16<WT>(&wt_lds[pb][(s_r + 16 * p) * kTileRow + s_c], w_raw[p]); };
+  if (loader) {
+    // =====================================================================================================
+    // Loader wavefronts: tile i+1 of the weight stream (requested one stage ago) is converted and written to
+    // the LDS buffer the compute wavefronts will read next, tile i+2 is requested from global memory; the
+    // P1 tiles of phase A travel the same way.
+    // Tile (c, j): j < nA -> V_1 rows 128 j.., columns f of chunk c; j >= nA -> U_2 rows f of chunk c,
+    // columns s0 + 128 (j - nA)..   Thread -> tile row s_r (+ 16 per pass), 8 columns from s_c.
+    // =====================================================================================================
+    const int lt = tid & 255;
+    const int s_r = lt >> 4, s_c = 8 * (lt & 15);
+    const long long p_total = (long long)fm_bytes(T, r1);
+    const long long v1_total = (long long)r1 * F * 2, u2_total = (long long)F * r2 * 2;
+    const char* const pV1 = uniform_ptr(a.V1);
+    const char* const pU2 = uniform_ptr(a.U2);
+    u4 w_raw[8], p_raw[4];
+    const char* src_base = nullptr;   // source of the tile currently being requested (two ahead of the tile in use)
+    int src_left = 0;
+    unsigned src_v0 = 0, src_ld = 0;
+    auto tile_src = [&](int c, int j) {
+      const bool isA = j < nA;
+      const int ld = isA ? F : r2;
+      const long long off = isA ? ((long long)j * kTile * F + c * kFfnBF) : ((long long)c * kFfnBF * r2 + s0 + (j - nA) * kTile);
+      const int cols = isA ? (F - c * kFfnBF) : (s_end - s0 - (j - nA) * kTile);      // valid columns of this tile
+      // branch-free scalar arithmetic (a chain of selects over kernel arguments would be turned into a table in scratch)
+      const long long sel = isA ? 1 : 0, live = (c < nchunks) ? 1 : 0;
+      long long left = (u2_total + (v1_total - u2_total) * sel) * live - off * 2;       // past the last tile: nothing
+      left = left < 0 ? 0 : left;
+      const unsigned long long pb = (unsigned long long)pU2 + ((unsigned long long)pV1 - (unsigned long long)pU2) * (unsigned long long)sel;
+      src_base = (const char*)pb + (left > 0 ? off * 2 : 0);
+      src_left = (int)left;
+      src_v0 = (s_c < cols) ? (unsigned)(s_r * ld + s_c) * 2u : (unsigned)kOobOffset;
+      src_ld = (unsigned)ld;
+    };
+    auto issue_pass = [&](int p) {      // rows past the end of the tensor: 0
+      const rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void*)src_base, 0, src_left, 0x00020000);
+      w_raw[p] = buf_load16(r, (int)(src_v0 + (unsigned)(32 * p) * src_ld));
+    };
+    auto commit_pass = [&](int pb, int p) { stage_store16<WT>(&wt_lds[pb][(s_r + 16 * p) * kTileRow + s_c], w_raw[p]); };
+    // P1 tile of phase-A stage ra: four 4 KiB fragment-major blocks (token tile tt, 64-wide piece 2 ra + hh), copied as they lie
+    const rsrc_t rP = __builtin_amdgcn_make_buffer_rsrc((void*)uniform_ptr(a.P1), 0, (int)p_total, 0x00020000);
+    auto issue_p = [&](int ra) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int piece = 2 * ra + (j & 1);
+        const int voff = (piece < pch) ? (((t0 >> 5) + (j >> 1)) * pch + piece) * kFmChunkBytes + lt * 16 : kOobOffset;
+        p_raw[j] = buf_load16(rP, voff);    // token tiles past the end of the buffer read 0
+      }
+    };
+    auto commit_p = [&](int pb) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) ((u4*)ptile[pb])[j * 256 + lt] = p_raw[j];
+    };
+
+    // prologue: tile 0 and the first P1 tile into LDS, tile 1 and the second P1 tile in flight
+    tile_src(0, 0);
+#pragma unroll
+    for (int p = 0; p < 8; ++p) issue_pass(p);
+    issue_p(0);
+    tile_src(0, 1);
+#pragma unroll
+    for (int p = 0; p < 8; ++p) { commit_pass(0, p); issue_pass(p); }
+    commit_p(0);
+    issue_p(1 % nA);
+    __syncthreads();
+
+    int it = 0, ac = 0;
+    auto next2_src = [&](int c, int j) {                 // source of the tile two ahead of (c, j); past the end: nothing
+      int c2 = c, j2 = j + 2;
+      if (j2 >= per_chunk) { j2 -= per_chunk; ++c2; }
+      tile_src(c2, j2);
+    };
+    for (int c = 0; c < nchunks; ++c) {
+      for (int ra = 0; ra < nA; ++ra) {
+        next2_src(c, ra);
+#pragma unroll
+        for (int p = 0; p < 8; ++p) { commit_pass((it + 1) & 1, p); issue_pass(p); }
+        commit_p((ac + 1) & 1);
+        issue_p((ra + 2) % nA);
+        __syncthreads();
+        ++it; ++ac;
+      }
+      for (int s = 0; s < NS; ++s) {
+        next2_src(c, nA + s);
+#pragma unroll
+        for (int p = 0; p < 8; ++p) { commit_pass((it + 1) & 1, p); issue_pass(p); }
+        __syncthreads();
+        ++it;
+      }
+    }
+    return;
+  }
+
+  // =======================================================================================================
+  // Compute wavefronts
+  // =======================================================================================================
   const int trA = tr_lane_off(lane, kTileRow) + 32 * g * kTileRow + 32 * wave;   // phase A: k rows 32 g + 8 kk + 0..7
   const int trB = tr_lane_off(lane, kTileRow) + 4 * g * kTileRow + 32 * wave;    // phase B: k rows 16 fs + 4 g + {0..3, 8..11}
-
-  // ---- P1 operands of the 64 tokens (fragment-major: one contiguous 1 KiB load each).  The registers hold one
-  // whole 128-wide stage; slot (hh, kk) is refilled right after its last use with the same slot of the next stage.
-  int voffP[2];
-#pragma unroll
-  for (int tt = 0; tt < 2; ++tt) {
-    int tok = t0 + 32 * tt + l32;
-    tok = tok < T ? tok : T - 1;
-    voffP[tt] = fm_voff(tok, pch, g);
-  }
-  h8 pfr[2][2][4];   // [hh][token tile][kk]
-  auto load_p = [&](int half, int hh, int kk) {   // half: 64-wide piece of r1; beyond the tensor -> outside the resource -> 0
-    const rsrc_t r = rsrc_at(a.P1, (half < pch) ? p_total : 0, (long long)half * kFmChunkBytes);
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt) pfr[hh][tt][kk] = __builtin_bit_cast(h8, buf_load16(r, voffP[tt] + kk * kFmStepBytes));
-  };
 
   f16v z[NS][2], y[2];
 #pragma unroll
@@ -122,25 +169,23 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
   y[0] = zero16(); y[1] = zero16();
   h8 gq[8][2];
 
-  // ---- one stage of phase A: y += V_1 tile^T (features 32*wave..) x P1^T; step p also moves pass p of the stream
-  auto stage_a = [&](const _Float16* wb, int c, int ra, int pb_next) {
-    const bool lastA = ra + 1 == nA;
+  // ---- one stage of phase A: y += V_1 tile^T (features 32*wave..) x P1^T, operands fetched from LDS one step ahead
+  auto stage_a = [&](const _Float16* wb, const h8 (*pb)[64], int c, bool lastA) {
     h8 wf = tr_frag(wb + trA, wb + trA + 4 * kTileRow);
+    h8 pf0 = pb[0][lane], pf1 = pb[8][lane];
 #pragma unroll
     for (int st = 0; st < 8; ++st) {
-      const int hh = st >> 2, kk = st & 3;
-      const int nh = (lastA ? 0 : 2 * (ra + 1)) + hh;   // same slot of the next stage (wrapping into the next chunk)
-      h8 wf_next = wf;
-      if (st < 7) {                                     // operand of the next step, fetched before this step's MFMAs
-        const _Float16* q = wb + trA + (64 * ((st + 1) >> 2) + 8 * ((st + 1) & 3)) * kTileRow;
+      h8 wf_next = wf, pn0 = pf0, pn1 = pf1;
+      if (st < 7) {
+        const int hh = (st + 1) >> 2, kk = (st + 1) & 3;
+        const _Float16* q = wb + trA + (64 * hh + 8 * kk) * kTileRow;
         wf_next = tr_frag(q, q + 4 * kTileRow);
+        pn0 = pb[hh * 4 + kk][lane];
+        pn1 = pb[8 + hh * 4 + kk][lane];
       }
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt) y[tt] = mfma32(wf, pfr[hh][tt][kk], y[tt]);   // rows f, cols tokens
-      commit_pass(pb_next, st);
-      issue_pass(st);
-      load_p(nh, hh, kk);
-      wf = wf_next;
+      y[0] = mfma32(wf, pf0, y[0]);   // rows f, cols tokens
+      y[1] = mfma32(wf, pf1, y[1]);
+      wf = wf_next; pf0 = pn0; pf1 = pn1;
     }
     if (lastA) {
       // bias, phi, fp16, publish in operand order for phase B
@@ -166,7 +211,7 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
     }
   };
   // ---- one sub-stage of phase B: z[s] += U_2 tile^T (ranks 128 s + 32*wave..) x Y^T
-  auto stage_b = [&](const _Float16* wb, f16v (&zs)[2], bool active, int pb_next) {
+  auto stage_b = [&](const _Float16* wb, f16v (&zs)[2], bool active) {
     h8 wf = tr_frag(wb + trB, wb + trB + 8 * kTileRow);
 #pragma unroll
     for (int fs = 0; fs < 8; ++fs) {
@@ -179,37 +224,17 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) zs[tt] = mfma32(wf, gq[fs][tt], zs[tt]);   // rows ranks, cols tokens
       }
-      commit_pass(pb_next, fs);
-      issue_pass(fs);
       wf = wf_next;
     }
   };
 
-  // ---- prologue: tile 0 into LDS, tile 1 in flight
-#pragma unroll
-  for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) load_p(hh, hh, kk);
-  tile_src(0, 0);
-#pragma unroll
-  for (int p = 0; p < 8; ++p) issue_pass(p);
-  tile_src(0, 1);
-#pragma unroll
-  for (int p = 0; p < 8; ++p) { commit_pass(0, p); issue_pass(p); }
-  __syncthreads();
-
-  int it = 0;
-  auto next2_src = [&](int c, int j) {                 // source of the tile two ahead of (c, j); past the end: nothing
-    int c2 = c, j2 = j + 2;
-    if (j2 >= per_chunk) { j2 -= per_chunk; ++c2; }
-    tile_src(c2, j2);
-  };
+  __syncthreads();   // prologue of the loader wavefronts
+  int it = 0, ac = 0;
   for (int c = 0; c < nchunks; ++c) {
     for (int ra = 0; ra < nA; ++ra) {
-      next2_src(c, ra);
-      stage_a(wt_lds[it & 1], c, ra, (it + 1) & 1);
+      stage_a(wt_lds[it & 1], ptile[ac & 1], c, ra + 1 == nA);
       __syncthreads();
-      ++it;
+      ++it; ++ac;
     }
 #pragma unroll
     for (int fs = 0; fs < 8; ++fs)
@@ -217,8 +242,7 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
       for (int tt = 0; tt < 2; ++tt) gq[fs][tt] = gtile[fs >> 1][fs & 1][tt][lane];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-      next2_src(c, nA + s);
-      stage_b(wt_lds[it & 1], z[s], s0 + s * kTile < s_end, (it + 1) & 1);
+      stage_b(wt_lds[it & 1], z[s], s0 + s * kTile < s_end);
       __syncthreads();
       ++it;
     }
@@ -248,7 +272,7 @@ __global__ void __launch_bounds__(256, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
 
 template <int NS>
 hipError_t launch_ns(const FfnCoreArgs& a, int nslices, int slice_w, hipStream_t s) {
-  const dim3 grid(((a.T + kFfnBT - 1) / kFfnBT) * nslices), block(256);
+  const dim3 grid(((a.T + kFfnBT - 1) / kFfnBT) * nslices), block(512);
   if (a.w_dt == DT_F16) hipLaunchKernelGGL((ffn_core_kernel<NS, DT_F16>), grid, block, 0, s, a, nslices, slice_w);
   else hipLaunchKernelGGL((ffn_core_kernel<NS, DT_BF16>), grid, block, 0, s, a, nslices, slice_w);
   return hipGetLastError();
