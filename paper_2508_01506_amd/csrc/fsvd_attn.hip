@@ -25,7 +25,6 @@ namespace {
 
 constexpr int kAttnWaves = 8;
 constexpr int kAttnThreads = kAttnWaves * 64;
-constexpr int kBKV = 128;            // keys per step: four 32-key slabs, each rebuilt by a K and a V wavefront
 constexpr float kLog2e = 1.4426950408889634f;
 
 __device__ __forceinline__ h8 pack8(const f16v& x, int t, float add) {
@@ -40,6 +39,13 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
   constexpr int DT32 = DH / 32;             // 32-wide feature tiles
   constexpr int DST = DH / 16;              // 16-wide contraction steps over d_h
   constexpr int BQ = kAttnWaves * QT * 32;  // queries per workgroup
+  // K/V rebuild: wavefront tile = KTW key tiles x DTW feature tiles of one matrix (operands reused KTW resp. DTW times);
+  // 2 matrices x (NKT / KTW) key groups x (DT32 / DTW) feature groups = 8 wavefronts
+  constexpr int KTW = (DH == 64 && QT == 1) ? 1 : 2;
+  constexpr int DTW = 2;
+  constexpr int NDG = DT32 / DTW;           // feature groups
+  constexpr int NKT = (kAttnWaves / 2 / NDG) * KTW;   // 32-key tiles per step
+  constexpr int BKV = 32 * NKT;             // keys per step
   constexpr int WS = wtile_stride(DH);      // halves per LDS row of a staged weight chunk [64 ranks][DH]
   constexpr int WBUF = kChunkK * WS;        // halves per staged weight chunk (one matrix)
   constexpr int LPR = DH / 8;               // lanes per chunk row while staging (16 bytes each)
@@ -47,8 +53,8 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
   constexpr int NP = kChunkK / RPP;         // passes (loads per thread) per matrix chunk
 
   __shared__ __attribute__((aligned(16))) _Float16 wbuf[2][2][WBUF];   // [parity][K|V weights]
-  __shared__ __attribute__((aligned(16))) h8 ktile[kBKV / 32][DST][64];
-  __shared__ __attribute__((aligned(16))) h8 vtile[kBKV / 32][DT32][2][64];
+  __shared__ __attribute__((aligned(16))) h8 ktile[NKT][DST][64];
+  __shared__ __attribute__((aligned(16))) h8 vtile[NKT][DT32][2][64];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, l32 = lane & 31, g = lane >> 5;
@@ -64,7 +70,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
   kv_len = kv_len < 1 ? 1 : (kv_len > M ? M : kv_len);
   int kv_end = kv_len;
   if (a.causal && q0 + BQ < kv_end) kv_end = q0 + BQ;
-  const int nsteps = (kv_end + kBKV - 1) / kBKV;
+  const int nsteps = (kv_end + BKV - 1) / BKV;
   const int tok0 = b * M;
   const int col0 = h * DH;                    // this head's columns in V_a, b_a and C
 
@@ -169,8 +175,9 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
     for (int dt = 0; dt < DT32; ++dt) o[dt][qt] = zero16();
   }
 
-  const int kvt = wave >> 1;        // which 32-key slab of the step this wavefront rebuilds
-  const int which = wave & 1;       // 0: keys, 1: values
+  const int which = wave & 1;                 // 0: keys, 1: values
+  const int kt0 = ((wave >> 1) / NDG) * KTW;  // first key tile of this wavefront
+  const int dt0 = ((wave >> 1) % NDG) * DTW;  // first feature tile of this wavefront
   const char* const Psrc = which ? uniform_ptr(a.Pv) : uniform_ptr(a.Pk);
   const int rr = which ? a.rv : a.rk;
   const int pch = (rr + kChunkK - 1) / kChunkK;
@@ -194,21 +201,27 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
 #pragma unroll
       for (int p = 0; p < NP; ++p) stage_store16<WT>(&wbuf[pb][m][(s_r + p * RPP) * WS + s_c], w_raw[m][p]);
   };
-  h8 pfr[4];
-  int voffKV;
+  h8 pfr[KTW][4];
+  int voffKV[KTW];
   auto set_keys = [&](int step) {
-    int key = step * kBKV + 32 * kvt + l32;
-    key = key < M ? key : M - 1;
-    voffKV = fm_voff(tok0 + key, pch, g);
+#pragma unroll
+    for (int i = 0; i < KTW; ++i) {
+      int key = step * BKV + 32 * (kt0 + i) + l32;
+      key = key < M ? key : M - 1;
+      voffKV[i] = fm_voff(tok0 + key, pch, g);
+    }
   };
   auto load_p = [&](int c, int kk) {      // chunks past this matrix's rank fall outside the resource: 0
     const rsrc_t r = rsrc_at(Psrc, (c < pch) ? p_total : 0, (long long)c * kFmChunkBytes);
-    pfr[kk] = __builtin_bit_cast(h8, buf_load16(r, voffKV + kk * kFmStepBytes));
+#pragma unroll
+    for (int i = 0; i < KTW; ++i) pfr[i][kk] = __builtin_bit_cast(h8, buf_load16(r, voffKV[i] + kk * kFmStepBytes));
   };
 
-  f16v acc[DT32];
+  f16v acc[KTW][DTW];
 #pragma unroll
-  for (int dt = 0; dt < DT32; ++dt) acc[dt] = zero16();
+  for (int i = 0; i < KTW; ++i)
+#pragma unroll
+    for (int j = 0; j < DTW; ++j) acc[i][j] = zero16();
 
   if (total > 0) {
     issue_w(0);
@@ -229,54 +242,66 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
     if (it + 2 < total) issue_w(ncn + 1 == nc ? 0 : ncn + 1);   // chunk it+2 has this whole iteration to land
     if (ncn == 0) set_keys(nstep);                       // the refills below already belong to the next step
     {
-      const _Float16* wb = wbuf[it & 1][which];
+      const _Float16* wb = wbuf[it & 1][which] + trA + 32 * dt0;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
+        h8 wf[DTW];
 #pragma unroll
-        for (int dt = 0; dt < DT32; ++dt) {
-          const _Float16* q = wb + trA + 8 * kk * WS + 32 * dt;
-          const h8 wf = tr_frag(q, q + 4 * WS);
-          if (which == 0) acc[dt] = mfma32(wf, pfr[kk], acc[dt]);   // K^T: rows d, cols keys
-          else acc[dt] = mfma32(pfr[kk], wf, acc[dt]);              // V: rows keys, cols d
+        for (int j = 0; j < DTW; ++j) {
+          const _Float16* q = wb + 8 * kk * WS + 32 * j;
+          wf[j] = tr_frag(q, q + 4 * WS);
         }
+#pragma unroll
+        for (int i = 0; i < KTW; ++i)
+#pragma unroll
+          for (int j = 0; j < DTW; ++j) {
+            if (which == 0) acc[i][j] = mfma32(wf[j], pfr[i][kk], acc[i][j]);   // K^T: rows d, cols keys
+            else acc[i][j] = mfma32(pfr[i][kk], wf[j], acc[i][j]);              // V: rows keys, cols d
+          }
         if (more) load_p(ncn, kk);          // refill the operand registers just consumed
       }
     }
     __syncthreads();
 
     if (c == nc - 1) {
-      // ---- publish the rebuilt tile (bias added, fp16, operand order)
+      // ---- publish the rebuilt tiles (bias added, fp16, operand order)
       if (which == 0) {
 #pragma unroll
-        for (int dt = 0; dt < DT32; ++dt) {
+        for (int j = 0; j < DTW; ++j) {
           f4v bias[4];
 #pragma unroll
-          for (int jj = 0; jj < 4; ++jj) bias[jj] = bias4(a.bk, 32 * dt + 8 * jj + 4 * g);
+          for (int jj = 0; jj < 4; ++jj) bias[jj] = bias4(a.bk, 32 * (dt0 + j) + 8 * jj + 4 * g);
 #pragma unroll
-          for (int t = 0; t < 2; ++t) {
-            h8 r;
+          for (int i = 0; i < KTW; ++i)
 #pragma unroll
-            for (int i = 0; i < 8; ++i) r[i] = (_Float16)(acc[dt][8 * t + i] + bias[2 * t + (i >> 2)][i & 3]);
-            ktile[kvt][2 * dt + t][lane] = r;
-          }
+            for (int t = 0; t < 2; ++t) {
+              h8 r;
+#pragma unroll
+              for (int e = 0; e < 8; ++e) r[e] = (_Float16)(acc[i][j][8 * t + e] + bias[2 * t + (e >> 2)][e & 3]);
+              ktile[kt0 + i][2 * (dt0 + j) + t][lane] = r;
+            }
         }
       } else {
 #pragma unroll
-        for (int dt = 0; dt < DT32; ++dt) {
-          const float bias = a.bv ? load_param(a.bv, col0 + 32 * dt + l32, a.w_dt) : 0.f;
+        for (int j = 0; j < DTW; ++j) {
+          const float bias = a.bv ? load_param(a.bv, col0 + 32 * (dt0 + j) + l32, a.w_dt) : 0.f;
 #pragma unroll
-          for (int t = 0; t < 2; ++t) vtile[kvt][dt][t][lane] = pack8(acc[dt], t, bias);
+          for (int i = 0; i < KTW; ++i)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) vtile[kt0 + i][dt0 + j][t][lane] = pack8(acc[i][j], t, bias);
         }
       }
 #pragma unroll
-      for (int dt = 0; dt < DT32; ++dt) acc[dt] = zero16();
+      for (int i = 0; i < KTW; ++i)
+#pragma unroll
+        for (int j = 0; j < DTW; ++j) acc[i][j] = zero16();
       __syncthreads();
 
       // ---- scores, streaming softmax, context for this wavefront's queries
       const int qlast = qw + 32 * QT - 1;
 #pragma unroll 1
-      for (int ks = 0; ks < kBKV / 32; ++ks) {
-        const int key0 = step * kBKV + 32 * ks;
+      for (int ks = 0; ks < NKT; ++ks) {
+        const int key0 = step * BKV + 32 * ks;
         if (key0 >= kv_end) break;
         if (a.causal && key0 > qlast) break;
         f16v s[QT];
