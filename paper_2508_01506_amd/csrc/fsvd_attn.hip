@@ -54,7 +54,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
 
   __shared__ __attribute__((aligned(16))) _Float16 wbuf[2][2][WBUF];   // [parity][K|V weights]
   __shared__ __attribute__((aligned(16))) h8 ktile[NKT][DST][64];
-  __shared__ __attribute__((aligned(16))) h8 vtile[NKT][DT32][2][64];
+  __shared__ __attribute__((aligned(16))) _Float16 vtile[BKV * WS];   // V [key][d] row-major, read back transposed
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, l32 = lane & 31, g = lane >> 5;
@@ -77,6 +77,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
   // ---- weight staging: thread -> chunk row s_r (+ RPP per pass), 8 head columns from s_c
   const int s_r = tid / LPR, s_c = 8 * (tid % LPR);
   const int trA = tr_lane_off(lane, WS) + 32 * g * WS;   // transposing-read base of this lane (halves)
+  const int trV = tr_lane_off(lane, WS) + 4 * g * WS;    // same for the V tile: keys 16 t + 4 g + {0..3, 8..11}
   // 4 consecutive bias entries of this head, as floats
   auto bias4 = [&](const void* bp, int d) -> f4v {
     const rsrc_t r = rsrc_at(bp, bp ? (long long)D * 2 : 0, 0);
@@ -179,6 +180,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
   const int kt0 = ((wave >> 1) / NDG) * KTW;  // first key tile of this wavefront
   const int dt0 = ((wave >> 1) % NDG) * DTW;  // first feature tile of this wavefront
   const char* const Psrc = which ? uniform_ptr(a.Pv) : uniform_ptr(a.Pk);
+  const char* const bsel = which ? uniform_ptr(a.bv) : uniform_ptr(a.bk);
   const int rr = which ? a.rv : a.rk;
   const int pch = (rr + kChunkK - 1) / kChunkK;
   const long long p_total = (long long)fm_bytes(T, rr);
@@ -242,6 +244,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
     if (it + 2 < total) issue_w(ncn + 1 == nc ? 0 : ncn + 1);   // chunk it+2 has this whole iteration to land
     if (ncn == 0) set_keys(nstep);                       // the refills below already belong to the next step
     {
+      // both roles compute (weights^T) x (P^T): rows = features, columns = keys, so the loop has no role-dependent code
       const _Float16* wb = wbuf[it & 1][which] + trA + 32 * dt0;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
@@ -254,25 +257,23 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
 #pragma unroll
         for (int i = 0; i < KTW; ++i)
 #pragma unroll
-          for (int j = 0; j < DTW; ++j) {
-            if (which == 0) acc[i][j] = mfma32(wf[j], pfr[i][kk], acc[i][j]);   // K^T: rows d, cols keys
-            else acc[i][j] = mfma32(pfr[i][kk], wf[j], acc[i][j]);              // V: rows keys, cols d
-          }
+          for (int j = 0; j < DTW; ++j) acc[i][j] = mfma32(wf[j], pfr[i][kk], acc[i][j]);   // rows d, cols keys
         if (more) load_p(ncn, kk);          // refill the operand registers just consumed
       }
     }
     __syncthreads();
 
     if (c == nc - 1) {
-      // ---- publish the rebuilt tiles (bias added, fp16, operand order)
-      if (which == 0) {
+      // ---- publish the rebuilt tiles (bias added, fp16): K^T in operand order; V as rows of [key][d], which the
+      // transposing LDS read turns into the V^T operand of the context product
 #pragma unroll
-        for (int j = 0; j < DTW; ++j) {
-          f4v bias[4];
+      for (int j = 0; j < DTW; ++j) {
+        f4v bias[4];
 #pragma unroll
-          for (int jj = 0; jj < 4; ++jj) bias[jj] = bias4(a.bk, 32 * (dt0 + j) + 8 * jj + 4 * g);
+        for (int jj = 0; jj < 4; ++jj) bias[jj] = bias4(bsel, 32 * (dt0 + j) + 8 * jj + 4 * g);
 #pragma unroll
-          for (int i = 0; i < KTW; ++i)
+        for (int i = 0; i < KTW; ++i) {
+          if (which == 0) {
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
               h8 r;
@@ -280,15 +281,15 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
               for (int e = 0; e < 8; ++e) r[e] = (_Float16)(acc[i][j][8 * t + e] + bias[2 * t + (e >> 2)][e & 3]);
               ktile[kt0 + i][2 * (dt0 + j) + t][lane] = r;
             }
-        }
-      } else {
+          } else {
 #pragma unroll
-        for (int j = 0; j < DTW; ++j) {
-          const float bias = a.bv ? load_param(a.bv, col0 + 32 * (dt0 + j) + l32, a.w_dt) : 0.f;
+            for (int jj = 0; jj < 4; ++jj) {
+              h4 r;
 #pragma unroll
-          for (int i = 0; i < KTW; ++i)
-#pragma unroll
-            for (int t = 0; t < 2; ++t) vtile[kt0 + i][dt0 + j][t][lane] = pack8(acc[i][j], t, bias);
+              for (int e = 0; e < 4; ++e) r[e] = (_Float16)(acc[i][j][4 * jj + e] + bias[jj][e]);
+              *(h4*)&vtile[(32 * (kt0 + i) + l32) * WS + 32 * (dt0 + j) + 8 * jj + 4 * g] = r;
+            }
+          }
         }
       }
 #pragma unroll
@@ -361,7 +362,8 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
         for (int dt = 0; dt < DT32; ++dt)
 #pragma unroll
           for (int t = 0; t < 2; ++t) {
-            const h8 vf = vtile[ks][dt][t][lane];
+            const _Float16* vq = vtile + (32 * ks + 16 * t) * WS + trV + 32 * dt;
+            const h8 vf = tr_frag(vq, vq + 8 * WS);
 #pragma unroll
             for (int qt = 0; qt < QT; ++qt) o[dt][qt] = mfma32(vf, pf[qt][t], o[dt][qt]);   // O^T: rows d, cols queries
           }
