@@ -41,8 +41,8 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
   constexpr int BQ = kAttnWaves * QT * 32;  // queries per workgroup
   // K/V rebuild: wavefront tile = KTW key tiles x DTW feature tiles of one matrix (operands reused KTW resp. DTW times);
   // 2 matrices x (NKT / KTW) key groups x (DT32 / DTW) feature groups = 8 wavefronts
-  constexpr int KTW = (DH == 64 && QT == 1) ? 1 : 2;
-  constexpr int DTW = 2;
+  constexpr int KTW = (DH == 64 && QT == 1) ? 1 : (DH == 128 ? 1 : 2);
+  constexpr int DTW = DH == 128 ? 4 : 2;    // d_h = 128: all four feature tiles, so that no two wavefronts load the same P operands
   constexpr int NDG = DT32 / DTW;           // feature groups
   constexpr int NKT = (kAttnWaves / 2 / NDG) * KTW;   // 32-key tiles per step
   constexpr int BKV = 32 * NKT;             // keys per step
@@ -240,25 +240,51 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
     const bool more = it + 1 < total;
     int nstep = step, ncn = c + 1;
     if (ncn == nc) { ncn = 0; nstep = step + 1; }
-    if (more) commit_w((it + 1) & 1);                    // chunk it+1 arrived during the previous iteration
-    if (it + 2 < total) issue_w(ncn + 1 == nc ? 0 : ncn + 1);   // chunk it+2 has this whole iteration to land
     if (ncn == 0) set_keys(nstep);                       // the refills below already belong to the next step
     {
+      // Chunk it+1 (requested during the previous iteration) is converted and written to the other LDS buffer and
+      // chunk it+2 is requested, one staging pass per MFMA step, so that the LDS writes and the global requests of
+      // the eight wavefronts spread over the iteration instead of bursting after the barrier.  Past the last chunk
+      // the resources have size 0: the loads return zeros and nothing branches.
+      const int c2 = ncn + 1 == nc ? 0 : ncn + 1;
+      const rsrc_t rw0 = rsrc_at(a.Vk, (it + 2 < total) ? (long long)a.rk * D * 2 : 0, ((long long)c2 * kChunkK * D + col0) * 2);
+      const rsrc_t rw1 = rsrc_at(a.Vv, (it + 2 < total) ? (long long)a.rv * D * 2 : 0, ((long long)c2 * kChunkK * D + col0) * 2);
+      const rsrc_t rp = rsrc_at(Psrc, (more && ncn < pch) ? p_total : 0, (long long)ncn * kFmChunkBytes);
+      _Float16* const wnext = wbuf[(it + 1) & 1][0];
       // both roles compute (weights^T) x (P^T): rows = features, columns = keys, so the loop has no role-dependent code
       const _Float16* wb = wbuf[it & 1][which] + trA + 32 * dt0;
+      // The 4 DTW weight fragments of the chunk pass through a rolling window of kWin registers sets: fragment
+      // f + kWin is requested from LDS right after fragment f has been consumed, kWin MFMA groups ahead of its use.
+      constexpr int NF = 4 * DTW, kWin = 4;
+      auto read_w = [&](int f) {
+        const _Float16* q = wb + 8 * (f / DTW) * WS + 32 * (f % DTW);
+        return tr_frag(q, q + 4 * WS);
+      };
+      h8 win[kWin];
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        h8 wf[DTW];
+      for (int f = 0; f < kWin; ++f) win[f] = read_w(f);
 #pragma unroll
-        for (int j = 0; j < DTW; ++j) {
-          const _Float16* q = wb + 8 * kk * WS + 32 * j;
-          wf[j] = tr_frag(q, q + 4 * WS);
+      for (int f = 0; f < NF; ++f) {
+        const int kk = f / DTW, j = f % DTW;
+#pragma unroll
+        for (int i = 0; i < KTW; ++i) acc[i][j] = mfma32(win[f % kWin], pfr[i][kk], acc[i][j]);   // rows d, cols keys
+        if (f + kWin < NF) win[f % kWin] = read_w(f + kWin);
+        if (j == DTW - 1) {
+          // refill the operand registers just consumed
+#pragma unroll
+          for (int i = 0; i < KTW; ++i) pfr[i][kk] = __builtin_bit_cast(h8, buf_load16(rp, voffKV[i] + kk * kFmStepBytes));
+          if ((kk * 2 * NP) % 4 == 0) {   // staging pass q of 2 NP, spread evenly over the four steps
+            constexpr int kPassesPerStep = (2 * NP + 3) / 4;
+#pragma unroll
+            for (int u = 0; u < kPassesPerStep; ++u) {
+              const int q = kk * 2 * NP / 4 + u;
+              const int m = q / NP, pp = q % NP;
+              stage_store16<WT>(wnext + m * WBUF + (s_r + pp * RPP) * WS + s_c, w_raw[m][pp]);
+              w_raw[m][pp] = buf_load16(m ? rw1 : rw0, ((s_r + pp * RPP) * D + s_c) * 2);   // rows past the rank: 0
+            }
+          }
         }
-#pragma unroll
-        for (int i = 0; i < KTW; ++i)
-#pragma unroll
-          for (int j = 0; j < DTW; ++j) acc[i][j] = mfma32(wf[j], pfr[i][kk], acc[i][j]);   // rows d, cols keys
-        if (more) load_p(ncn, kk);          // refill the operand registers just consumed
+        __builtin_amdgcn_sched_barrier(0);   // keep the window rolling in this order
       }
     }
     __syncthreads();
