@@ -54,8 +54,11 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
   const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it in scalar registers
   const int wave = wave8 & 3;                                    // index inside the role
   const bool loader = wave8 >= 4;
-  const int slice = blockIdx.x % nslices;
-  const int tb = blockIdx.x / nslices;
+  // The slices of one token tile re-read the same P1 block once per chunk of F: keep them (and neighbouring token
+  // tiles) on one XCD so that those re-reads hit its L2 instead of each XCD's L2 cycling through all of P1.
+  const int wg = xcd_tile(blockIdx.x, gridDim.x);
+  const int slice = wg % nslices;
+  const int tb = wg / nslices;
   const int t0 = tb * kFfnBT;
   const int s0 = slice * slice_w;                               // first output rank of this slice
   const int r1 = a.r1, F = a.F, r2 = a.r2, T = a.T;
