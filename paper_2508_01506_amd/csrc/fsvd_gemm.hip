@@ -188,16 +188,21 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
       if (col >= G.N) continue;
       const float bias = G.bias ? load_param(G.bias, col, a.w_dt) : 0.f;
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+      for (int mt = 0; mt < 2; ++mt) {
+        // all residual values of the tile are requested before the first store: the output may alias the residual
+        // (in-place update of the residual stream), so a load placed after a store would have to wait for it
+        float res[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int row = m0 + 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
-          if (row < T) {
-            float x = acc[mt][nt][v] + bias;
-            if (a.R) x += load_param(a.R, (size_t)row * a.ldr + col, a.r_dt);
-            store_out(G.C, (size_t)row * G.ldc + col, x, a.c_dt);
-          }
+          res[v] = (a.R && row < T) ? load_param(a.R, (size_t)row * a.ldr + col, a.r_dt) : 0.f;
         }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
+          if (row < T) store_out(G.C, (size_t)row * G.ldc + col, acc[mt][nt][v] + bias + res[v], a.c_dt);
+        }
+      }
     }
   }
 }
