@@ -78,6 +78,35 @@ __device__ __forceinline__ void store_out(void* p, size_t i, float v, int dt) {
   else ((uint16_t*)p)[i] = float_to_bf16_bits(v);
 }
 
+// 4 consecutive elements (index a multiple of 4, base 16-byte aligned) of a typed array
+__device__ __forceinline__ f4v load4(const void* p, size_t i, int dt) {
+  if (dt == DT_F32) return *(const f4v*)((const float*)p + i);
+  const u2 raw = *(const u2*)((const uint16_t*)p + i);
+  f4v o;
+  if (dt == DT_F16) {
+    const h4 h = __builtin_bit_cast(h4, raw);
+    o[0] = (float)h[0]; o[1] = (float)h[1]; o[2] = (float)h[2]; o[3] = (float)h[3];
+  } else {
+    o[0] = __uint_as_float(raw[0] << 16); o[1] = __uint_as_float(raw[0] & 0xffff0000u);
+    o[2] = __uint_as_float(raw[1] << 16); o[3] = __uint_as_float(raw[1] & 0xffff0000u);
+  }
+  return o;
+}
+__device__ __forceinline__ void store4(void* p, size_t i, f4v x, int dt) {
+  if (dt == DT_F32) {
+    *(f4v*)((float*)p + i) = x;
+  } else if (dt == DT_F16) {
+    h4 h;
+    h[0] = (_Float16)x[0]; h[1] = (_Float16)x[1]; h[2] = (_Float16)x[2]; h[3] = (_Float16)x[3];
+    *(h4*)((_Float16*)p + i) = h;
+  } else {
+    u2 raw;
+    raw[0] = (uint32_t)float_to_bf16_bits(x[0]) | ((uint32_t)float_to_bf16_bits(x[1]) << 16);
+    raw[1] = (uint32_t)float_to_bf16_bits(x[2]) | ((uint32_t)float_to_bf16_bits(x[3]) << 16);
+    *(u2*)((uint16_t*)p + i) = raw;
+  }
+}
+
 // 8 consecutive elements of a row-major activation (row pointer already applied) as an MFMA fragment.
 // AT: storage type of the activation.  `ok` false yields zeros (ragged contraction tails).
 template <int AT>

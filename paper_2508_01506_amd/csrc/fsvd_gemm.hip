@@ -148,8 +148,7 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-          if constexpr (CFM) acc[mt][nt] = mfma32(bf[nt], af[mt], acc[mt][nt]);   // rows n, cols tokens
-          else acc[mt][nt] = mfma32(af[mt], bf[nt], acc[mt][nt]);                 // rows tokens, cols n
+          acc[mt][nt] = mfma32(bf[nt], af[mt], acc[mt][nt]);   // rows n, cols tokens
         }
       if (more1) load_a(c + 1, kk);
     }
@@ -182,25 +181,33 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
         }
       }
   } else {
+    // row-major output: lane = token, registers = 4 consecutive output columns -> one 16-byte (fp32) or 8-byte store
+    const rsrc_t rB = rsrc_at(G.bias, G.bias ? (long long)G.N * 2 : 0, 0);
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      const int col = n0 + 32 * nt + l32;
-      if (col >= G.N) continue;
-      const float bias = G.bias ? load_param(G.bias, col, a.w_dt) : 0.f;
+      f4v bias[4];
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) bias[jj] = raw_to_f4<WT>(buf_load8(rB, (n0 + 32 * nt + 8 * jj + 4 * g) * 2));   // past N: 0
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt) {
+        const int tok = m0 + 32 * mt + l32;
         // all residual values of the tile are requested before the first store: the output may alias the residual
         // (in-place update of the residual stream), so a load placed after a store would have to wait for it
-        float res[16];
+        f4v res[4];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = m0 + 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
-          res[v] = (a.R && row < T) ? load_param(a.R, (size_t)row * a.ldr + col, a.r_dt) : 0.f;
+        for (int jj = 0; jj < 4; ++jj) {
+          const int n = n0 + 32 * nt + 8 * jj + 4 * g;
+          res[jj] = (a.R && tok < T && n < G.N) ? load4(a.R, (size_t)tok * a.ldr + n, a.r_dt) : f4v{0.f, 0.f, 0.f, 0.f};
         }
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = m0 + 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
-          if (row < T) store_out(G.C, (size_t)row * G.ldc + col, acc[mt][nt][v] + bias + res[v], a.c_dt);
+        for (int jj = 0; jj < 4; ++jj) {
+          const int n = n0 + 32 * nt + 8 * jj + 4 * g;
+          if (tok < T && n < G.N) {
+            f4v x;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[i] = acc[mt][nt][4 * jj + i] + bias[jj][i] + res[jj][i];
+            store4(G.C, (size_t)tok * G.ldc + n, x, a.c_dt);
+          }
         }
       }
     }
