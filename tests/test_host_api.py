@@ -4,6 +4,8 @@ import ctypes as C
 import os
 import re
 
+import numpy as np
+
 import pytest
 import torch
 
@@ -130,3 +132,22 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(fb, "LIB_PATH", "/nonexistent/libfsvd.so")
     with pytest.raises(FileNotFoundError):
         fb.lib()
+
+
+def test_gelu_tail_polynomial_of_the_kernel_is_erf_accurate():
+    """The FFN kernel evaluates erf-GELU as max(x,0) - |x| 2^p(min(|x|,6)); its coefficients, read from the source,
+    must reproduce 0.5 x (1 + erf(x / sqrt 2)) (scipy) to 1e-6 when evaluated in float32 as the kernel does."""
+    import re
+    from scipy.special import erf
+    src = open(os.path.join(ROOT, "paper_2508_01506_amd", "csrc", "fsvd_ffn.hip")).read()
+    body = re.search(r"kGeluTail\[7\]\s*=\s*\{([^}]*)\}", src).group(1)
+    c = [np.float32(v.strip().rstrip("f")) for v in body.split(",")]
+    assert len(c) == 7
+    x = np.linspace(-12.0, 12.0, 240001).astype(np.float32)
+    t = np.minimum(np.abs(x), np.float32(6.0))
+    p = np.full_like(t, c[6])
+    for k in range(5, -1, -1):
+        p = p * t + c[k]
+    got = np.maximum(x, np.float32(0)) - np.abs(x) * np.exp2(p).astype(np.float32)
+    ref = 0.5 * x.astype(np.float64) * (1.0 + erf(x.astype(np.float64) / np.sqrt(2.0)))
+    assert np.abs(got.astype(np.float64) - ref).max() < 1e-6
