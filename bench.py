@@ -125,7 +125,8 @@ def main():
     Cx = torch.empty(fb.fsvd_fm_bytes(w.T, w.D), device="cuda:0", dtype=torch.uint8)
     n_k = max(3, min(args.steps, 20))
     flush = torch.empty(512 << 20, device="cuda:0", dtype=torch.uint8)
-    run_ffn = lambda: fb.fsvd_ffn_core(d, P1, dev["w1"], dev["w2"], out=Z)
+    core_ws = torch.empty(max(1, fb.fsvd_ffn_core_workspace(d, rf, rf)), device="cuda:0", dtype=torch.uint8)
+    run_ffn = lambda: fb.fsvd_ffn_core(d, P1, dev["w1"], dev["w2"], out=Z, workspace=core_ws)
     run_attn = lambda: fb.fsvd_attention_core(d, Pq, Pk, Pv, dev["q"], dev["k"], dev["v"], out=Cx)
     ffn_ms = timed(run_ffn, lambda: (run_attn(), flush.zero_()), n_k)
     attn_ms = timed(run_attn, lambda: (run_ffn(), flush.zero_()), n_k)

@@ -181,9 +181,13 @@ fsvd_status fsvd_attention_core(const fsvd_desc *desc, const void *Pq, const voi
                                 void *context, void *hip_stream);
 
 /* The on-chip loops of Alg. 2: P1 [B*M, w1->rank] (FM), V / bias of w1 and U of w2 -> Z [B*M, w2->rank]
- * (FM) with Z = phi(P1 V_1 + b_1) U_2. */
+ * (FM) with Z = phi(P1 V_1 + b_1) U_2.  When few tokens or large ranks would leave compute units idle the sum over
+ * D_ff is split across workgroups and their fp32 partial sums are added in a fixed order by a second launch; the
+ * partial sums live in `workspace` (256-byte aligned device memory of at least fsvd_ffn_core_workspace() bytes, which
+ * is 0 when no split is used and never more than B*M*F bytes; NULL is accepted when it is 0). */
+size_t fsvd_ffn_core_workspace(const fsvd_desc *desc, int32_t r_1, int32_t r_2);
 fsvd_status fsvd_ffn_core(const fsvd_desc *desc, const void *P1, const fsvd_factor *w1, const fsvd_factor *w2,
-                          void *Z, void *hip_stream);
+                          void *Z, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Y[T, D] = gamma (X - mean) / sqrt(var + eps) + beta per row; X in x_dtype, gamma / beta in p_dtype,
  * Y in y_dtype (any of F16, BF16, F32).  D <= 8192, D % 8 == 0. */

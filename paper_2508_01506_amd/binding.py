@@ -28,7 +28,7 @@ _TORCH2FSVD = {torch.float16: FSVD_F16, torch.bfloat16: FSVD_BF16, torch.float32
 
 EXPORTS = ["fsvd_attention_workspace", "fsvd_ffn_workspace", "fsvd_layer_workspace", "fsvd_attention_check",
            "fsvd_ffn_check", "fsvd_attention", "fsvd_ffn", "fsvd_layer", "fsvd_linear", "fsvd_attention_core",
-           "fsvd_ffn_core", "fsvd_layernorm", "fsvd_status_string", "fsvd_version", "fsvd_fm_bytes", "fsvd_pack_fm",
+           "fsvd_ffn_core", "fsvd_ffn_core_workspace", "fsvd_layernorm", "fsvd_status_string", "fsvd_version", "fsvd_fm_bytes", "fsvd_pack_fm",
            "fsvd_unpack_fm"]
 
 
@@ -82,8 +82,10 @@ def lib():
         L.fsvd_linear.argtypes = [i32, i32, i32, P, C.c_int, P, P, C.c_int, P, C.c_int, P, C.c_int, P]
         L.fsvd_attention_core.restype = C.c_int
         L.fsvd_attention_core.argtypes = [D, P, P, P, F, F, F, P, P]
+        L.fsvd_ffn_core_workspace.restype = sz
+        L.fsvd_ffn_core_workspace.argtypes = [D, i32, i32]
         L.fsvd_ffn_core.restype = C.c_int
-        L.fsvd_ffn_core.argtypes = [D, P, F, F, P, P]
+        L.fsvd_ffn_core.argtypes = [D, P, F, F, P, P, sz, P]
         L.fsvd_layernorm.restype = C.c_int
         L.fsvd_layernorm.argtypes = [i32, i32, P, C.c_int, P, P, C.c_int, C.c_float, P, C.c_int, P]
         L.fsvd_fm_bytes.restype = sz
@@ -247,13 +249,20 @@ def fsvd_attention_core(desc, Pq, Pk, Pv, q: Factor, k: Factor, v: Factor, out=N
     return out
 
 
-def fsvd_ffn_core(desc, P1, w1: Factor, w2: Factor, out=None):
+def fsvd_ffn_core_workspace(desc, r1, r2) -> int:
+    return lib().fsvd_ffn_core_workspace(C.byref(desc), r1, r2)
+
+
+def fsvd_ffn_core(desc, P1, w1: Factor, w2: Factor, out=None, workspace=None):
     """P1 and the returned Z are fragment-major buffers."""
     if out is None:
         out = torch.empty(fsvd_fm_bytes(desc.B * desc.M, w2.rank), dtype=torch.uint8, device=P1.device)
+    need = fsvd_ffn_core_workspace(desc, w1.rank, w2.rank)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=P1.device)
     f1, f2 = w1.c(), w2.c()
-    _check(lib().fsvd_ffn_core(C.byref(desc), _ptr(P1), C.byref(f1), C.byref(f2), _ptr(out), _stream()),
-           "fsvd_ffn_core")
+    _check(lib().fsvd_ffn_core(C.byref(desc), _ptr(P1), C.byref(f1), C.byref(f2), _ptr(out), _ptr(workspace),
+                               0 if workspace is None else workspace.numel(), _stream()), "fsvd_ffn_core")
     return out
 
 

@@ -89,12 +89,13 @@ AttnPlan plan_attn(size_t T, size_t D, size_t rq, size_t rk, size_t rv, size_t r
   pl.total = smax(p_end, pl.to + align_up(fm_bytes(T, ro)));
   return pl;
 }
-struct FfnPlan { size_t p1, z, total; };
-FfnPlan plan_ffn(size_t T, size_t r1, size_t r2) {
+struct FfnPlan { size_t p1, z, part, total; };   // P1 | Z | fp32 partial sums of Z (only when the core splits F)
+FfnPlan plan_ffn(size_t T, size_t r1, size_t r2, size_t F) {
   FfnPlan pl;
   pl.p1 = 0;
   pl.z = align_up(fm_bytes(T, r1));
-  pl.total = pl.z + align_up(fm_bytes(T, r2));
+  pl.part = pl.z + align_up(fm_bytes(T, r2));
+  pl.total = pl.part + align_up(ffn_core_plan((int)T, (int)r1, (int)r2, (int)F).partial_bytes);
   return pl;
 }
 
@@ -154,7 +155,7 @@ fsvd_status run_ffn(const fsvd_desc* d, const void* A_in, int a_layout, int a_dt
                     const fsvd_factor* w2, const void* residual, int r_dt, void* out, int c_dt, char* scratch,
                     hipStream_t s) {
   const int T = d->B * d->M, D = d->D;
-  const FfnPlan pl = plan_ffn(T, w1->rank, w2->rank);
+  const FfnPlan pl = plan_ffn(T, w1->rank, w2->rank, d->F);
   char* P1 = scratch + pl.p1;
   char* Z = scratch + pl.z;
 
@@ -166,7 +167,7 @@ fsvd_status run_ffn(const fsvd_desc* d, const void* A_in, int a_layout, int a_dt
 
   FfnCoreArgs fa{};
   fa.P1 = P1; fa.r1 = w1->rank; fa.V1 = w1->V; fa.b1 = w1->bias; fa.U2 = w2->U; fa.r2 = w2->rank;
-  fa.w_dt = d->io_dtype; fa.T = T; fa.F = d->F; fa.act = d->act; fa.Z = Z;
+  fa.w_dt = d->io_dtype; fa.T = T; fa.F = d->F; fa.act = d->act; fa.Z = Z; fa.Zpart = (float*)(scratch + pl.part);
   FSVD_HIP(launch_ffn_core(fa, s));
 
   LinearArgs h7{};
@@ -187,7 +188,7 @@ LayerPlan plan_layer(const fsvd_desc* d, size_t rq, size_t rk, size_t rv, size_t
   pl.c = d->norm == FSVD_NORM_NONE ? 0 : align_up(T * D * 4);
   pl.rank = pl.c + align_up(fm_bytes(T, D));
   const AttnPlan ap = plan_attn(T, D, rq, rk, rv, ro);
-  pl.total = pl.rank + smax(ap.total - ap.p, plan_ffn(T, r1, r2).total);
+  pl.total = pl.rank + smax(ap.total - ap.p, plan_ffn(T, r1, r2, d->F).total);
   return pl;
 }
 
@@ -216,7 +217,7 @@ size_t fsvd_attention_workspace(const fsvd_desc* d, int32_t rq, int32_t rk, int3
 size_t fsvd_ffn_workspace(const fsvd_desc* d, int32_t r1, int32_t r2) {
   if (check_desc(d, true) != FSVD_OK) return 0;
   if (check_rank(r1) || check_rank(r2)) return 0;
-  return plan_ffn((size_t)d->B * d->M, r1, r2).total;
+  return plan_ffn((size_t)d->B * d->M, r1, r2, d->F).total;
 }
 size_t fsvd_layer_workspace(const fsvd_desc* d, int32_t rq, int32_t rk, int32_t rv, int32_t ro, int32_t r1, int32_t r2) {
   if (check_desc(d, true) != FSVD_OK) return 0;
@@ -249,7 +250,7 @@ fsvd_status fsvd_ffn(const fsvd_desc* d, const void* X, const fsvd_factor* w1, c
                      void* ws, size_t ws_bytes, void* stream) {
   FSVD_TRY(check_ffn(d, w1, w2, true));
   if (!X || !out) return FSVD_ERR_INVALID_ARG;
-  FSVD_TRY(check_ws(ws, ws_bytes, plan_ffn((size_t)d->B * d->M, w1->rank, w2->rank).total));
+  FSVD_TRY(check_ws(ws, ws_bytes, plan_ffn((size_t)d->B * d->M, w1->rank, w2->rank, d->F).total));
   return run_ffn(d, X, LAYOUT_ROW, d->io_dtype, w1, w2, nullptr, 0, out, d->out_dtype, (char*)ws, (hipStream_t)stream);
 }
 
@@ -354,16 +355,24 @@ fsvd_status fsvd_attention_core(const fsvd_desc* d, const void* Pq, const void* 
   return FSVD_OK;
 }
 
+size_t fsvd_ffn_core_workspace(const fsvd_desc* d, int32_t r1, int32_t r2) {
+  if (check_desc(d, true) != FSVD_OK) return 0;
+  if (check_rank(r1) || check_rank(r2)) return 0;
+  return align_up(ffn_core_plan(d->B * d->M, r1, r2, d->F).partial_bytes);
+}
+
 fsvd_status fsvd_ffn_core(const fsvd_desc* d, const void* P1, const fsvd_factor* w1, const fsvd_factor* w2, void* Z,
-                          void* stream) {
+                          void* ws, size_t ws_bytes, void* stream) {
   FSVD_TRY(check_desc(d, true));
   FSVD_TRY(check_factor(w1, d->D, d->F, false, true));
   FSVD_TRY(check_factor(w2, d->F, d->D, true, false));
   if (!P1 || !Z) return FSVD_ERR_INVALID_ARG;
+  const size_t need = fsvd_ffn_core_workspace(d, w1->rank, w2->rank);
+  if (need) FSVD_TRY(check_ws(ws, ws_bytes, need));
   FfnCoreArgs fa{};
   fa.P1 = P1; fa.r1 = w1->rank; fa.V1 = w1->V; fa.b1 = w1->bias; fa.U2 = w2->U;
   fa.r2 = w2->rank; fa.w_dt = d->io_dtype; fa.T = d->B * d->M; fa.F = d->F; fa.act = d->act;
-  fa.Z = Z;
+  fa.Z = Z; fa.Zpart = need ? (float*)ws : nullptr;
   FSVD_HIP(launch_ffn_core(fa, (hipStream_t)stream));
   return FSVD_OK;
 }

@@ -27,7 +27,6 @@ constexpr int kFfnBT = 64;                  // tokens per workgroup
 constexpr int kFfnBF = 128;                 // F chunk
 constexpr int kTile = 128;                  // weight tile edge
 constexpr int kTileRow = wtile_stride(kTile);   // halves per LDS tile row
-constexpr int kMaxSlice = 512;
 
 // Exact (erf) GELU as  max(x, 0) - |x| * Q(|x|),  Q(t) = 0.5 erfc(t / sqrt 2)  the upper Gaussian tail, with
 // log2 Q(t) replaced on [0, 6] by a degree-6 polynomial (weighted least-squares fit on Chebyshev nodes, weight t Q(t)):
@@ -47,8 +46,45 @@ __device__ __forceinline__ float gelu_tanh_f(float x) {
   return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-2.0f * u * 1.4426950408889634f));
 }
 
-template <int NS, int WT>
-__global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nslices, int slice_w) {
+// One output tile of a wavefront's accumulators: ranks [rbase + 128 s + 32 wave ..) of tokens t0.. -> either the final
+// fragment-major fp16 Z (4 consecutive ranks per 8-byte store) or, when F is split across workgroups, this
+// workgroup's fp32 partial sums, laid out [split][rank / 4][token][4] so that a wavefront writes 512-byte runs.
+template <int N>
+__device__ __forceinline__ void write_z(const f16v (&z)[N][2], const FfnCoreArgs& a, int fsplit, int fs, int t0, int rbase,
+                                        int rlimit, int wave, int l32, int g) {
+  const int T = a.T, zch = (a.r2 + 63) / 64;
+#pragma unroll
+  for (int tt = 0; tt < 2; ++tt) {
+    const int tok = t0 + 32 * tt + l32;
+    if (tok >= T) continue;
+#pragma unroll
+    for (int s = 0; s < N; ++s)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int r = rbase + s * kTile + 32 * wave + 8 * jj + 4 * g;
+        if (r < rlimit && r < zch * 64) {   // ranks r2 .. 64*zch-1 are written as zeros (FM padding)
+          if (fsplit == 1) {
+            const size_t unit = ((size_t)((tok >> 5) * zch + (r >> 6)) * 4 + ((r >> 3) & 3)) * 64 + ((r >> 5) & 1) * 32 + (tok & 31);
+            h4 o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = (_Float16)z[s][tt][4 * jj + i];
+            *(h4*)((_Float16*)a.Z + unit * 8 + 4 * ((r >> 2) & 1)) = o;
+          } else {
+            f4v o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = z[s][tt][4 * jj + i];
+            *(f4v*)(a.Zpart + (((size_t)fs * (zch * 16) + (r >> 2)) * T + tok) * 4) = o;
+          }
+        }
+      }
+  }
+}
+
+// NS: 128-rank sub-tiles accumulated by the compute wavefronts, NS2: further sub-tiles accumulated by the loader
+// wavefronts (their registers are otherwise idle), so that one workgroup covers up to 1024 output ranks with a single
+// pass of phase A.
+template <int NS, int NS2, int WT>
+__global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nslices, int slice_w, int fsplit) {
   __shared__ __attribute__((aligned(16))) _Float16 wt_lds[2][kTile * kTileRow];
   __shared__ __attribute__((aligned(16))) h8 ptile[2][16][64];     // [buffer][(token tile * 2 + hh) * 4 + kk][lane]
   __shared__ __attribute__((aligned(16))) h8 gtile[4][2][2][64];   // [f tile][t][token tile][lane]
@@ -62,14 +98,19 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
   // tiles) on one XCD so that those re-reads hit its L2 instead of each XCD's L2 cycling through all of P1.
   const int wg = xcd_tile(blockIdx.x, gridDim.x);
   const int slice = wg % nslices;
-  const int tb = wg / nslices;
+  const int ntile = (a.T + kFfnBT - 1) / kFfnBT;
+  const int tb = (wg / nslices) % ntile;
+  const int fs = wg / (nslices * ntile);                        // which part of F this workgroup sums over
   const int t0 = tb * kFfnBT;
   const int s0 = slice * slice_w;                               // first output rank of this slice
   const int r1 = a.r1, F = a.F, r2 = a.r2, T = a.T;
   const int s_end = (s0 + slice_w < r2) ? s0 + slice_w : r2;
   const int nA = (r1 + kTile - 1) / kTile;
-  const int nchunks = (F + kFfnBF - 1) / kFfnBF;
-  const int per_chunk = nA + NS;                                // tiles per chunk: nA of V_1, then NS of U_2
+  const int nchunks_all = (F + kFfnBF - 1) / kFfnBF;
+  const int cps = (nchunks_all + fsplit - 1) / fsplit;
+  const int c_begin = fs * cps;
+  const int nchunks = (c_begin + cps < nchunks_all) ? c_begin + cps : nchunks_all;   // this workgroup: chunks c_begin .. nchunks-1
+  const int per_chunk = nA + NS + NS2;                          // tiles per chunk: nA of V_1, then NS + NS2 of U_2
   const int pch = (r1 + 63) / 64, zch = (r2 + 63) / 64;
 
   if (loader) {
@@ -126,11 +167,11 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
     };
 
     // prologue: tile 0 and the first P1 tile into LDS, tile 1 and the second P1 tile in flight
-    tile_src(0, 0);
+    tile_src(c_begin, 0);
 #pragma unroll
     for (int p = 0; p < 8; ++p) issue_pass(p);
     issue_p(0);
-    tile_src(0, 1);
+    tile_src(c_begin + (per_chunk > 1 ? 0 : 1), per_chunk > 1 ? 1 : 0);
 #pragma unroll
     for (int p = 0; p < 8; ++p) { commit_pass(0, p); issue_pass(p); }
     commit_p(0);
@@ -143,7 +184,11 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
       if (j2 >= per_chunk) { j2 -= per_chunk; ++c2; }
       tile_src(c2, j2);
     };
-    for (int c = 0; c < nchunks; ++c) {
+    const int trB = tr_lane_off(lane, kTileRow) + 4 * g * kTileRow + 32 * wave;    // as in the compute wavefronts
+    f16v z2[NS2 > 0 ? NS2 : 1][2];
+#pragma unroll
+    for (int s = 0; s < (NS2 > 0 ? NS2 : 1); ++s) { z2[s][0] = zero16(); z2[s][1] = zero16(); }
+    for (int c = c_begin; c < nchunks; ++c) {
       for (int ra = 0; ra < nA; ++ra) {
         next2_src(c, ra);
 #pragma unroll
@@ -160,7 +205,38 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
         __syncthreads();
         ++it;
       }
+      if constexpr (NS2 > 0) {
+        // sub-tiles NS .. NS+NS2-1: the MFMAs of step fs run between the staging passes of the stream
+#pragma unroll
+        for (int s = 0; s < NS2; ++s) {
+          next2_src(c, nA + NS + s);
+          const _Float16* wb = wt_lds[it & 1];
+          const bool active = s0 + (NS + s) * kTile < s_end;
+          h8 wf = tr_frag(wb + trB, wb + trB + 8 * kTileRow);
+          h8 g0 = gtile[0][0][0][lane], g1 = gtile[0][0][1][lane];
+#pragma unroll
+          for (int f = 0; f < 8; ++f) {
+            h8 wf_next = wf, n0 = g0, n1 = g1;
+            if (f < 7) {
+              const _Float16* q = wb + trB + 16 * (f + 1) * kTileRow;
+              wf_next = tr_frag(q, q + 8 * kTileRow);
+              n0 = gtile[(f + 1) >> 1][(f + 1) & 1][0][lane];
+              n1 = gtile[(f + 1) >> 1][(f + 1) & 1][1][lane];
+            }
+            if (active) {
+              z2[s][0] = mfma32(wf, g0, z2[s][0]);
+              z2[s][1] = mfma32(wf, g1, z2[s][1]);
+            }
+            commit_pass((it + 1) & 1, f);
+            issue_pass(f);
+            wf = wf_next; g0 = n0; g1 = n1;
+          }
+          __syncthreads();
+          ++it;
+        }
+      }
     }
+    if constexpr (NS2 > 0) write_z(z2, a, fsplit, fs, t0, s0 + NS * kTile, s0 + slice_w, wave, l32, g);
     return;
   }
 
@@ -237,7 +313,7 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
 
   __syncthreads();   // prologue of the loader wavefronts
   int it = 0, ac = 0;
-  for (int c = 0; c < nchunks; ++c) {
+  for (int c = c_begin; c < nchunks; ++c) {
     for (int ra = 0; ra < nA; ++ra) {
       stage_a(wt_lds[it & 1], ptile[ac & 1], c, ra + 1 == nA);
       __syncthreads();
@@ -253,50 +329,103 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
       __syncthreads();
       ++it;
     }
+#pragma unroll
+    for (int s = 0; s < NS2; ++s) {   // the loader wavefronts' sub-tiles
+      __syncthreads();
+      ++it;
+    }
   }
 
-  // ---- write Z fragment-major (fp16), 4 consecutive ranks per 8-byte store
-  _Float16* Z = (_Float16*)a.Z;
-#pragma unroll
-  for (int tt = 0; tt < 2; ++tt) {
-    const int tok = t0 + 32 * tt + l32;
-    if (tok >= T) continue;
-#pragma unroll
-    for (int s = 0; s < NS; ++s)
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const int r = s0 + s * kTile + 32 * wave + 8 * jj + 4 * g;
-        if (r < s0 + slice_w && r < zch * 64) {   // ranks r2 .. 64*zch-1 are written as zeros (FM padding)
-          const size_t unit = ((size_t)((tok >> 5) * zch + (r >> 6)) * 4 + ((r >> 3) & 3)) * 64 + ((r >> 5) & 1) * 32 + (tok & 31);
-          h4 o;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) o[i] = (_Float16)z[s][tt][4 * jj + i];
-          *(h4*)(Z + unit * 8 + 4 * ((r >> 2) & 1)) = o;
-        }
-      }
-  }
+  write_z(z, a, fsplit, fs, t0, s0, s0 + slice_w, wave, l32, g);
 }
 
-template <int NS>
-hipError_t launch_ns(const FfnCoreArgs& a, int nslices, int slice_w, hipStream_t s) {
-  const dim3 grid(((a.T + kFfnBT - 1) / kFfnBT) * nslices), block(512);
-  if (a.w_dt == DT_F16) hipLaunchKernelGGL((ffn_core_kernel<NS, DT_F16>), grid, block, 0, s, a, nslices, slice_w);
-  else hipLaunchKernelGGL((ffn_core_kernel<NS, DT_BF16>), grid, block, 0, s, a, nslices, slice_w);
+// Sum of the fp32 partial results over the splits of F -> fragment-major fp16 Z.  One thread per 16-byte FM unit
+// (8 ranks of one token); the partial layout [split][rank / 4][token][4] makes the reads of a wavefront contiguous.
+__global__ void __launch_bounds__(256) ffn_reduce_kernel(const float* __restrict__ part, int fsplit, int T, int r2, _Float16* Z,
+                                                         size_t units) {
+  const size_t u = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (u >= units) return;
+  const int zch = (r2 + 63) / 64;
+  const int lane = u & 63, kk = (u >> 6) & 3;
+  const size_t blk = u >> 8;
+  const int c = blk % zch, tile = blk / zch;
+  const int tok = tile * 32 + (lane & 31), k = 64 * c + 32 * (lane >> 5) + 8 * kk;
+  if (tok >= T) return;
+  f4v lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+  for (int f = 0; f < fsplit; ++f) {   // fixed order: the result does not depend on scheduling
+    const float* p = part + (((size_t)f * (zch * 16) + (k >> 2)) * T + tok) * 4;
+    const f4v a0 = *(const f4v*)p, a1 = *(const f4v*)(p + (size_t)T * 4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { lo[i] += a0[i]; hi[i] += a1[i]; }
+  }
+  h8 o;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { o[i] = (_Float16)lo[i]; o[4 + i] = (_Float16)hi[i]; }
+  *(h8*)(Z + u * 8) = o;
+}
+
+template <int NS, int NS2>
+hipError_t launch_ns(const FfnCoreArgs& a, const FfnCorePlan& pl, hipStream_t s) {
+  const dim3 grid(((a.T + kFfnBT - 1) / kFfnBT) * pl.nslices * pl.fsplit), block(512);
+  if (a.w_dt == DT_F16) hipLaunchKernelGGL((ffn_core_kernel<NS, NS2, DT_F16>), grid, block, 0, s, a, pl.nslices, pl.slice_w, pl.fsplit);
+  else hipLaunchKernelGGL((ffn_core_kernel<NS, NS2, DT_BF16>), grid, block, 0, s, a, pl.nslices, pl.slice_w, pl.fsplit);
   return hipGetLastError();
 }
 }  // namespace
 
-hipError_t launch_ffn_core(const FfnCoreArgs& a, hipStream_t s) {
-  const int nslices = (a.r2 + kMaxSlice - 1) / kMaxSlice;
-  int slice_w = (a.r2 + nslices - 1) / nslices;
-  slice_w = (slice_w + 63) / 64 * 64;
-  switch ((slice_w + kTile - 1) / kTile) {
-    case 1: return launch_ns<1>(a, nslices, slice_w, s);
-    case 2: return launch_ns<2>(a, nslices, slice_w, s);
-    case 3: return launch_ns<3>(a, nslices, slice_w, s);
-    case 4: return launch_ns<4>(a, nslices, slice_w, s);
+// Launch shape: W sub-tiles of 128 ranks per workgroup (up to 4 on the compute wavefronts, up to 4 more on the loader
+// wavefronts), the slices of r2 that follow from W, and the number of parts F is split into.  Splitting F needs fp32
+// partial sums in the workspace; they may take at most T * F bytes (half of what the hidden activation itself would).
+// The choice minimises (rounds of workgroups over the 256 compute units) x (weight tiles and GELU passes per workgroup).
+FfnCorePlan ffn_core_plan(int T, int r1, int r2, int F) {
+  const int tiles = (T + kFfnBT - 1) / kFfnBT;
+  const int nsub = (r2 + kTile - 1) / kTile, nA = (r1 + kTile - 1) / kTile, nchunks = (F + kFfnBF - 1) / kFfnBF;
+  const size_t zpad = (size_t)((r2 + 63) / 64) * 64;
+  FfnCorePlan best{};
+  double best_cost = 0.0;
+  for (int W = 1; W <= 8; ++W) {
+    const int nsl = (nsub + W - 1) / W;
+    int slice_w = (r2 + nsl - 1) / nsl;
+    slice_w = (slice_w + 63) / 64 * 64;
+    const int w_eff = (slice_w + kTile - 1) / kTile;
+    if (w_eff != W) continue;                               // the same shape is reached with a smaller W
+    for (int fsplit = 1; fsplit <= nchunks; fsplit *= 2) {
+      const size_t part = fsplit > 1 ? (size_t)fsplit * zpad * T * 4 : 0;
+      if (part > (size_t)T * F) break;
+      const long wgs = (long)tiles * nsl * fsplit;
+      const double rounds = (double)((wgs + 255) / 256);
+      const int on_loader = W > 4 ? W - 4 : 0;
+      const double per_chunk = 1.2 * nA + (W - on_loader) + 1.25 * on_loader + 1.5;
+      const double cost = rounds * ((nchunks + fsplit - 1) / fsplit) * per_chunk + 2.0 * (fsplit > 1);
+      if (best.nslices == 0 || cost < best_cost - 1e-9) {
+        best_cost = cost;
+        best.nslices = nsl; best.slice_w = slice_w; best.ns = W - on_loader; best.ns2 = on_loader; best.fsplit = fsplit;
+        best.partial_bytes = part;
+      }
+    }
   }
-  return hipErrorInvalidValue;
+  return best;
+}
+
+hipError_t launch_ffn_core(const FfnCoreArgs& a, hipStream_t s) {
+  const FfnCorePlan pl = ffn_core_plan(a.T, a.r1, a.r2, a.F);
+  if (pl.fsplit > 1 && !a.Zpart) return hipErrorInvalidValue;
+  hipError_t e = hipErrorInvalidValue;
+  switch (pl.ns * 8 + pl.ns2) {
+    case 1 * 8 + 0: e = launch_ns<1, 0>(a, pl, s); break;
+    case 2 * 8 + 0: e = launch_ns<2, 0>(a, pl, s); break;
+    case 3 * 8 + 0: e = launch_ns<3, 0>(a, pl, s); break;
+    case 4 * 8 + 0: e = launch_ns<4, 0>(a, pl, s); break;
+    case 4 * 8 + 1: e = launch_ns<4, 1>(a, pl, s); break;
+    case 4 * 8 + 2: e = launch_ns<4, 2>(a, pl, s); break;
+    case 4 * 8 + 3: e = launch_ns<4, 3>(a, pl, s); break;
+    case 4 * 8 + 4: e = launch_ns<4, 4>(a, pl, s); break;
+  }
+  if (e != hipSuccess || pl.fsplit == 1) return e;
+  const size_t units = fm_bytes(a.T, a.r2) / 16;
+  hipLaunchKernelGGL(ffn_reduce_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s, a.Zpart, pl.fsplit, a.T, a.r2,
+                     (_Float16*)a.Z, units);
+  return hipGetLastError();
 }
 
 }  // namespace fsvd

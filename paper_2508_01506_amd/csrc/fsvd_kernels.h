@@ -63,8 +63,12 @@ struct FfnCoreArgs {
   int w_dt;
   int T, F;
   int act;
-  void* Z;
+  void* Z;           // [T, r2] fragment-major fp16
+  float* Zpart;      // fp32 partial sums, FfnCorePlan::partial_bytes (needed when the plan splits F)
 };
+// launch shape of the FFN core for a problem size (host-side, no device needed)
+struct FfnCorePlan { int nslices, slice_w, ns, ns2, fsplit; size_t partial_bytes; };
+FfnCorePlan ffn_core_plan(int T, int r1, int r2, int F);
 hipError_t launch_ffn_core(const FfnCoreArgs& a, hipStream_t s);
 
 // ---- LayerNorm over the last axis of a row-major [T, D]; writes a row-major copy and/or an FM copy

@@ -154,6 +154,37 @@ def test_ffn_core_from_rank_space_input(fb, name, act):
     assert rel_err(got, ref) < 2.5e-3      # fp16 hidden activation + fp16 Z
 
 
+@pytest.mark.parametrize("r2,dt", [(1024, "fp16"), (1024, "bf16"), (896, "fp16"), (640, "bf16")])
+def test_ffn_core_wide_rank_slices_and_split_over_f(fb, r2, dt):
+    """Shapes for which the core lets one workgroup cover more than 512 output ranks (the extra accumulators live in
+    the loader wavefronts) and splits the sum over D_ff across workgroups (fp32 partial sums + a second launch):
+    sampled rows of Z against the plain definition, ragged token count, tanh-free exact GELU."""
+    T, D, F, r1 = 8192 - 37, 128, 8192, 256
+    rng = np.random.default_rng(77 + r2)
+    tdt = torch.float16 if dt == "fp16" else torch.bfloat16
+    rnd = lambda a: W.round_to_storage(a.astype(np.float32), dt).astype(np.float64)
+    V1 = rnd(rng.standard_normal((r1, F)) / np.sqrt(r1))
+    b1 = rnd(0.02 * rng.standard_normal(F))
+    U2 = rnd(rng.standard_normal((F, r2)) / np.sqrt(F))
+    P1 = rng.standard_normal((T, r1)).astype(np.float16)
+    up = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float32)).to(device=DEV, dtype=tdt).contiguous()
+    # U of w1 and V of w2 are not read by the core: any tensors of the right shape do
+    w1 = fb.Factor(up(np.zeros((D, r1))), up(V1), up(b1))
+    w2 = fb.Factor(up(U2), up(np.zeros((r2, D))), None)
+    d = fb.make_desc(1, T, D, 2, F, tdt)
+    assert fb.fsvd_ffn_core_workspace(d, r1, r2) > 0          # this shape does split F
+    Zfm = fb.fsvd_ffn_core(d, fb.fsvd_pack_fm(torch.from_numpy(P1).to(DEV)), w1, w2)
+    got = fb.fsvd_unpack_fm(Zfm, T, r2, torch.float32).cpu().numpy()
+    rows = np.unique(np.concatenate([np.arange(0, 70), np.arange(T - 70, T), rng.integers(0, T, 200)]))
+    hidden = O.activation(P1[rows].astype(np.float64) @ V1 + b1, "gelu_erf")
+    ref = hidden @ U2
+    assert np.isfinite(got).all()
+    assert rel_err(got[rows], ref) < 2.5e-3
+    again = fb.fsvd_unpack_fm(fb.fsvd_ffn_core(d, fb.fsvd_pack_fm(torch.from_numpy(P1).to(DEV)), w1, w2), T, r2,
+                              torch.float32).cpu().numpy()
+    assert np.array_equal(got, again)                          # partial sums are added in a fixed order
+
+
 # ------------------------------------------------------------------ entry points, small shapes, every element
 SMALL = ["tiny_h2_d64", "tiny_pad", "tiny_causal_d128", "small_multi_qblock", "small_causal_d64"]
 

@@ -49,7 +49,11 @@ def test_workspace_sizes_follow_the_documented_plan():
         assert fb.fsvd_fm_bytes(T, ra) == fm(T, ra)
         attn_rank = max(3 * up(fm(T, ra)), up(fm(T, ra)))                # P_q | P_k | P_v, later T_o in the same bytes
         attn = up(fm(T, D)) + attn_rank                                  # context (first the packed X) + rank scratch
-        ffn = 2 * up(fm(T, rf))                                          # P1 + Z
+        part = fb.fsvd_ffn_core_workspace(d, rf, rf)                     # fp32 partial sums of Z when the core splits F
+        assert part % 256 == 0 and part <= up(T * w.F)                   # never more than half the hidden activation
+        zpad = (rf + 63) // 64 * 64
+        assert part == 0 or part % up(zpad * T * 4) == 0 or part == up(part)   # a whole number of [r2, T] fp32 slabs
+        ffn = 2 * up(fm(T, rf)) + part                                   # P1 + Z (+ partial sums)
         assert fb.fsvd_attention_workspace(d, ra, ra, ra, ra) == attn
         assert fb.fsvd_ffn_workspace(d, rf, rf) == ffn
         stream = 0 if w.norm == "none" else up(T * D * 4)                # fp32 residual stream
@@ -59,8 +63,8 @@ def test_workspace_sizes_follow_the_documented_plan():
         # that path also materialises Q, K, V [T, D] next to P and the hidden [T, F] next to P1 and Z
         assert attn < attn + 3 * T * D * 2 and ffn < ffn + T * w.F * 2
         unfused = stream + T * D * 2 + max(3 * T * ra * 2 + 3 * T * D * 2, 2 * T * rf * 2 + T * w.F * 2)
-        if T >= 1024:     # padding of tiny shapes aside, the fused workspace is strictly smaller
-            assert layer < unfused
+        if T >= 256 and T % 32 == 0:     # padding of tiny shapes aside, the fused workspace is strictly smaller
+            assert layer < unfused, (w.name, layer, unfused)
 
 
 def test_workspace_query_rejects_bad_configurations():
