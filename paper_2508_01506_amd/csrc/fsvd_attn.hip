@@ -33,6 +33,12 @@ __device__ __forceinline__ h8 pack8(const f16v& x, int t, float add) {
   for (int i = 0; i < 8; ++i) r[i] = (_Float16)(x[8 * t + i] + add);
   return r;
 }
+__device__ __forceinline__ h8 pack8(const f16v& x, int t) {   // no "+ 0.f": that is not a no-op and would cost an add per element
+  h8 r;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r[i] = (_Float16)x[8 * t + i];
+  return r;
+}
 
 template <int DH, int QT, int WT>
 __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs a, int nqb) {
@@ -352,37 +358,46 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
             }
           }
         }
+        // Lazy running maximum (log2 domain): the reference maximum of a row is raised, and O and l rescaled, only when
+        // the slab's maximum exceeds it by more than 8; until then the probabilities are at most 2^8, which fp16
+        // holds with full relative precision.  The softmax does not depend on the reference, so nothing changes
+        // but the number of rescalings (one per row for most inputs instead of one per slab).
         h8 pf[QT][2];
-        float alpha[QT];
-        bool rescale = false;
+        float mx[QT];
+        bool raise = false;
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
-          float mx = s[qt][0];
+          float m = s[qt][0];
 #pragma unroll
-          for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[qt][v]);
-          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-          const float m_new = fmaxf(m_run[qt], mx);
-          alpha[qt] = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
-          m_run[qt] = m_new;
+          for (int v = 1; v < 16; ++v) m = fmaxf(m, s[qt][v]);
+          mx[qt] = fmaxf(m, __shfl_xor(m, 32, 64));
+          raise = raise || (mx[qt] > m_run[qt] + 8.0f);
+        }
+        if (__any(raise)) {
+#pragma unroll
+          for (int qt = 0; qt < QT; ++qt) {
+            const float m_new = fmaxf(m_run[qt], mx[qt]);
+            const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
+            m_run[qt] = m_new;
+            l_run[qt] *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < DT32; ++dt)
+#pragma unroll
+              for (int v = 0; v < 16; ++v) o[dt][qt][v] *= alpha;
+          }
+        }
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
           float sum = 0.f;
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
-            const float p = __builtin_amdgcn_exp2f(s[qt][v] - m_new);
+            const float p = __builtin_amdgcn_exp2f(s[qt][v] - m_run[qt]);
             s[qt][v] = p;
             sum += p;
           }
-          l_run[qt] = l_run[qt] * alpha[qt] + sum;
-          rescale = rescale || (alpha[qt] != 1.0f);
-          pf[qt][0] = pack8(s[qt], 0, 0.f);
-          pf[qt][1] = pack8(s[qt], 1, 0.f);
-        }
-        if (__any(rescale)) {
-#pragma unroll
-          for (int dt = 0; dt < DT32; ++dt)
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-              for (int v = 0; v < 16; ++v) o[dt][qt][v] *= alpha[qt];
+          l_run[qt] += sum;
+          pf[qt][0] = pack8(s[qt], 0);
+          pf[qt][1] = pack8(s[qt], 1);
         }
 #pragma unroll
         for (int dt = 0; dt < DT32; ++dt)
