@@ -176,21 +176,24 @@ def main():
             threads = len(os.sched_getaffinity(0))
         n_rows = w.M if w.M <= 4096 else 1024
         rows = np.arange(w.M - n_rows, w.M)
-        done, dt, err, seqs = 0, 0.0, 0.0, []
-        for b in range(w.B - 1, -1, -1):        # whole sequences until about 10 s of CPU work are spent
-            t0 = time.perf_counter()
-            ref = oracle_rows(inp, b, rows, "layer")
-            dt += time.perf_counter() - t0
-            got = out[b, w.M - n_rows:].cpu().numpy()
-            err = max(err, float(np.abs(got - ref).max() / np.sqrt(np.mean(ref ** 2))))
-            done += n_rows
-            seqs.append(b)
-            if dt > 10.0:
-                break
+        done, dt, err, seqs, passes = 0, 0.0, 0.0, [], 0
+        while dt < 10.0:                        # whole sequences (again from the last one) until about 10 s of CPU work
+            for b in range(w.B - 1, -1, -1):
+                t0 = time.perf_counter()
+                ref = oracle_rows(inp, b, rows, "layer")
+                dt += time.perf_counter() - t0
+                got = out[b, w.M - n_rows:].cpu().numpy()
+                err = max(err, float(np.abs(got - ref).max() / np.sqrt(np.mean(ref ** 2))))
+                done += n_rows
+                if passes == 0:
+                    seqs.append(b)
+                if dt > 10.0:
+                    break
+            passes += 1
         result["cpu_baseline"] = {"value": round(done / dt, 1), "unit": "tokens/s", "cores": int(threads),
                                   "kind": "oracle",
                                   "sample": f"last {n_rows} query rows (keys/values of the whole sequence) of "
-                                            f"{len(seqs)} sequence(s) {seqs[-1]}..{seqs[0]}, fp64 numpy, {dt:.1f} s"}
+                                            f"{len(seqs)} sequence(s) {seqs[-1]}..{seqs[0]}, {done // n_rows} oracle evaluation(s), fp64 numpy, {dt:.1f} s"}
         result["max_err_over_rms_vs_oracle_sample"] = float(f"{err:.3e}")
     print(json.dumps(result))
 
