@@ -167,7 +167,7 @@ fsvd_status run_ffn(const fsvd_desc* d, const void* A_in, int a_layout, int a_dt
 
   FfnCoreArgs fa{};
   fa.P1 = P1; fa.r1 = w1->rank; fa.V1 = w1->V; fa.b1 = w1->bias; fa.U2 = w2->U; fa.r2 = w2->rank;
-  fa.w_dt = d->io_dtype; fa.T = T; fa.F = d->F; fa.act = d->act; fa.Z = Z; fa.Zpart = scratch + pl.part;
+  fa.w_dt = d->io_dtype; fa.T = T; fa.F = d->F; fa.act = d->act; fa.Z = Z; fa.Zpart = (float*)(scratch + pl.part);
   FSVD_HIP(launch_ffn_core(fa, s));
 
   LinearArgs h7{};
@@ -372,7 +372,7 @@ fsvd_status fsvd_ffn_core(const fsvd_desc* d, const void* P1, const fsvd_factor*
   FfnCoreArgs fa{};
   fa.P1 = P1; fa.r1 = w1->rank; fa.V1 = w1->V; fa.b1 = w1->bias; fa.U2 = w2->U;
   fa.r2 = w2->rank; fa.w_dt = d->io_dtype; fa.T = d->B * d->M; fa.F = d->F; fa.act = d->act;
-  fa.Z = Z; fa.Zpart = need ? ws : nullptr;
+  fa.Z = Z; fa.Zpart = need ? (float*)ws : nullptr;
   FSVD_HIP(launch_ffn_core(fa, (hipStream_t)stream));
   return FSVD_OK;
 }

@@ -70,18 +70,10 @@ __device__ __forceinline__ void write_z(const f16v (&z)[N][2], const FfnCoreArgs
             for (int i = 0; i < 4; ++i) o[i] = (_Float16)z[s][tt][4 * jj + i];
             *(h4*)((_Float16*)a.Z + unit * 8 + 4 * ((r >> 2) & 1)) = o;
           } else {
-            const size_t idx = (((size_t)fs * (zch * 16) + (r >> 2)) * T + tok) * 4;
-            if (a.part_f16) {
-              h4 o;
+            f4v o;
 #pragma unroll
-              for (int i = 0; i < 4; ++i) o[i] = (_Float16)z[s][tt][4 * jj + i];
-              *(h4*)((_Float16*)a.Zpart + idx) = o;
-            } else {
-              f4v o;
-#pragma unroll
-              for (int i = 0; i < 4; ++i) o[i] = z[s][tt][4 * jj + i];
-              *(f4v*)((float*)a.Zpart + idx) = o;
-            }
+            for (int i = 0; i < 4; ++i) o[i] = z[s][tt][4 * jj + i];
+            *(f4v*)(a.Zpart + (((size_t)fs * (zch * 16) + (r >> 2)) * T + tok) * 4) = o;
           }
         }
       }
@@ -347,11 +339,10 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
   write_z(z, a, fsplit, fs, t0, s0, s0 + slice_w, wave, l32, g);
 }
 
-// Sum of the partial results (fp32, or fp16 when only that fits the memory bound) over the splits of F, in fp32 ->
-// fragment-major fp16 Z.  One thread per 16-byte FM unit
+// Sum of the fp32 partial results over the splits of F -> fragment-major fp16 Z.  One thread per 16-byte FM unit
 // (8 ranks of one token); the partial layout [split][rank / 4][token][4] makes the reads of a wavefront contiguous.
-__global__ void __launch_bounds__(256) ffn_reduce_kernel(const void* __restrict__ part, int part_f16, int fsplit, int T, int r2,
-                                                         _Float16* Z, size_t units) {
+__global__ void __launch_bounds__(256) ffn_reduce_kernel(const float* __restrict__ part, int fsplit, int T, int r2, _Float16* Z,
+                                                         size_t units) {
   const size_t u = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (u >= units) return;
   const int zch = (r2 + 63) / 64;
@@ -362,16 +353,8 @@ __global__ void __launch_bounds__(256) ffn_reduce_kernel(const void* __restrict_
   if (tok >= T) return;
   f4v lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
   for (int f = 0; f < fsplit; ++f) {   // fixed order: the result does not depend on scheduling
-    const size_t idx = (((size_t)f * (zch * 16) + (k >> 2)) * T + tok) * 4;
-    f4v a0, a1;
-    if (part_f16) {
-      const h4 b0 = *(const h4*)((const _Float16*)part + idx), b1 = *(const h4*)((const _Float16*)part + idx + (size_t)T * 4);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) { a0[i] = (float)b0[i]; a1[i] = (float)b1[i]; }
-    } else {
-      a0 = *(const f4v*)((const float*)part + idx);
-      a1 = *(const f4v*)((const float*)part + idx + (size_t)T * 4);
-    }
+    const float* p = part + (((size_t)f * (zch * 16) + (k >> 2)) * T + tok) * 4;
+    const f4v a0 = *(const f4v*)p, a1 = *(const f4v*)(p + (size_t)T * 4);
 #pragma unroll
     for (int i = 0; i < 4; ++i) { lo[i] += a0[i]; hi[i] += a1[i]; }
   }
@@ -391,9 +374,8 @@ hipError_t launch_ns(const FfnCoreArgs& a, const FfnCorePlan& pl, hipStream_t s)
 }  // namespace
 
 // Launch shape: W sub-tiles of 128 ranks per workgroup (up to 4 on the compute wavefronts, up to 4 more on the loader
-// wavefronts), the slices of r2 that follow from W, and the number of parts F is split into.  Splitting F needs partial
-// sums in the workspace; they may take at most T * F bytes (half of what the hidden activation itself would) and are
-// kept in fp32 when that fits, else in fp16 (each partial sum then carries one more fp16 rounding).
+// wavefronts), the slices of r2 that follow from W, and the number of parts F is split into.  Splitting F needs fp32
+// partial sums in the workspace; they may take at most T * F bytes (half of what the hidden activation itself would).
 // The choice minimises (rounds of workgroups over the 256 compute units) x (weight tiles and GELU passes per workgroup).
 FfnCorePlan ffn_core_plan(int T, int r1, int r2, int F) {
   const int tiles = (T + kFfnBT - 1) / kFfnBT;
@@ -408,9 +390,7 @@ FfnCorePlan ffn_core_plan(int T, int r1, int r2, int F) {
     const int w_eff = (slice_w + kTile - 1) / kTile;
     if (w_eff != W) continue;                               // the same shape is reached with a smaller W
     for (int fsplit = 1; fsplit <= nchunks; fsplit *= 2) {
-      size_t part = fsplit > 1 ? (size_t)fsplit * zpad * T * 4 : 0;
-      int part_f16 = 0;
-      if (part > (size_t)T * F) { part /= 2; part_f16 = 1; }
+      const size_t part = fsplit > 1 ? (size_t)fsplit * zpad * T * 4 : 0;
       if (part > (size_t)T * F) break;
       const long wgs = (long)tiles * nsl * fsplit;
       const double rounds = (double)((wgs + 255) / 256);
@@ -420,7 +400,7 @@ FfnCorePlan ffn_core_plan(int T, int r1, int r2, int F) {
       if (best.nslices == 0 || cost < best_cost - 1e-9) {
         best_cost = cost;
         best.nslices = nsl; best.slice_w = slice_w; best.ns = W - on_loader; best.ns2 = on_loader; best.fsplit = fsplit;
-        best.partial_bytes = part; best.part_f16 = part_f16;
+        best.partial_bytes = part;
       }
     }
   }
@@ -430,22 +410,20 @@ FfnCorePlan ffn_core_plan(int T, int r1, int r2, int F) {
 hipError_t launch_ffn_core(const FfnCoreArgs& a, hipStream_t s) {
   const FfnCorePlan pl = ffn_core_plan(a.T, a.r1, a.r2, a.F);
   if (pl.fsplit > 1 && !a.Zpart) return hipErrorInvalidValue;
-  FfnCoreArgs b = a;
-  b.part_f16 = pl.part_f16;
   hipError_t e = hipErrorInvalidValue;
   switch (pl.ns * 8 + pl.ns2) {
-    case 1 * 8 + 0: e = launch_ns<1, 0>(b, pl, s); break;
-    case 2 * 8 + 0: e = launch_ns<2, 0>(b, pl, s); break;
-    case 3 * 8 + 0: e = launch_ns<3, 0>(b, pl, s); break;
-    case 4 * 8 + 0: e = launch_ns<4, 0>(b, pl, s); break;
-    case 4 * 8 + 1: e = launch_ns<4, 1>(b, pl, s); break;
-    case 4 * 8 + 2: e = launch_ns<4, 2>(b, pl, s); break;
-    case 4 * 8 + 3: e = launch_ns<4, 3>(b, pl, s); break;
-    case 4 * 8 + 4: e = launch_ns<4, 4>(b, pl, s); break;
+    case 1 * 8 + 0: e = launch_ns<1, 0>(a, pl, s); break;
+    case 2 * 8 + 0: e = launch_ns<2, 0>(a, pl, s); break;
+    case 3 * 8 + 0: e = launch_ns<3, 0>(a, pl, s); break;
+    case 4 * 8 + 0: e = launch_ns<4, 0>(a, pl, s); break;
+    case 4 * 8 + 1: e = launch_ns<4, 1>(a, pl, s); break;
+    case 4 * 8 + 2: e = launch_ns<4, 2>(a, pl, s); break;
+    case 4 * 8 + 3: e = launch_ns<4, 3>(a, pl, s); break;
+    case 4 * 8 + 4: e = launch_ns<4, 4>(a, pl, s); break;
   }
   if (e != hipSuccess || pl.fsplit == 1) return e;
   const size_t units = fm_bytes(a.T, a.r2) / 16;
-  hipLaunchKernelGGL(ffn_reduce_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s, a.Zpart, pl.part_f16, pl.fsplit, a.T, a.r2,
+  hipLaunchKernelGGL(ffn_reduce_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s, a.Zpart, pl.fsplit, a.T, a.r2,
                      (_Float16*)a.Z, units);
   return hipGetLastError();
 }

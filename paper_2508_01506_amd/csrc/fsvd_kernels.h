@@ -64,11 +64,10 @@ struct FfnCoreArgs {
   int T, F;
   int act;
   void* Z;           // [T, r2] fragment-major fp16
-  void* Zpart;       // partial sums, FfnCorePlan::partial_bytes (needed when the plan splits F)
-  int part_f16;      // set by the launcher from the plan: partial sums in fp16 instead of fp32
+  float* Zpart;      // fp32 partial sums, FfnCorePlan::partial_bytes (needed when the plan splits F)
 };
 // launch shape of the FFN core for a problem size (host-side, no device needed)
-struct FfnCorePlan { int nslices, slice_w, ns, ns2, fsplit, part_f16; size_t partial_bytes; };
+struct FfnCorePlan { int nslices, slice_w, ns, ns2, fsplit; size_t partial_bytes; };
 FfnCorePlan ffn_core_plan(int T, int r1, int r2, int F);
 hipError_t launch_ffn_core(const FfnCoreArgs& a, hipStream_t s);
 
