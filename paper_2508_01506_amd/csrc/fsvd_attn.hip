@@ -7,11 +7,15 @@
 // MFMAs) owns one (sequence, head, block of BQ = 256*QT queries).
 //   Q phase : every wavefront rebuilds Q^T [d_h, 32*QT] for its own queries, contraction over r_q
 //             in 64-wide chunks, pre-scaled by softmax_scale*log2(e), and keeps it as MFMA operands.
-//   KV loop : per step of 128 keys, wavefront w rebuilds 32 keys of K (w even) or V (w odd) — weight
-//             chunks are copied into LDS (double-buffered), shared, and read back transposed; P operands
-//             come straight from global memory — adds the bias and publishes the fp16 tile in LDS in
-//             operand order.  Then every wavefront computes S^T = K Q^T for its queries, masks, updates
-//             the running row maximum / sum and accumulates O^T += V^T P~^T.
+//   KV loop : per step of BKV keys (128 for d_h = 128, 256 for long sequences with d_h = 64) the wavefronts
+//             rebuild the K and V tiles: half of them K, half V, each a tile of KTW x DTW 32x32 blocks of
+//             (V_a[:, head])^T P_a^T (features x keys) - one loop without role-dependent code.  Weight chunks
+//             [64 ranks, d_h] are copied into LDS (double-buffered, staging passes spread between the MFMA
+//             steps), shared, and read back transposed through a rolling window; P operands come straight from
+//             global memory (fragment-major).  K^T is published in LDS in operand order, V as rows [key][d]
+//             that the context product reads back with the transposing read.  Then every wavefront computes
+//             S^T = K Q^T for its queries, masks, updates the (lazily raised) row maximum and the row sum and
+//             accumulates O^T += V^T P~^T.
 // All products are arranged "transposed" (keys or features along accumulator rows, queries along
 // lanes), so the accumulators of one product are, after rounding to fp16, exactly the operand
 // registers of the next one: no activation ever needs a transpose or an LDS round trip except the

@@ -1,21 +1,25 @@
 // Fused FFN core (Alg. 2, the on-chip loops): Z[T, r2] = phi(P1[T, r1] V_1[r1, F] + b_1) U_2[F, r2].
 // The hidden activation phi(...) [T, F] exists only as 128-wide slabs in registers / LDS.
 //
-// One workgroup (4 wavefronts) owns 64 tokens and one slice of at most 512 output ranks; the
-// accumulator Z^T [slice, 64 tokens] stays in registers for the whole sweep over F.  Per 128-wide
-// chunk of F:
-//   phase A  Y^T[128 f, 64 tok] = V_1[:, chunk]^T P1^T, contraction over r1 in 128-wide stages;
-//            wavefront w computes features 32*w.. (P1 operands come straight from global memory in the
-//            fragment-major layout), adds b_1, applies phi, rounds to fp16 and publishes the result to
-//            the other wavefronts through LDS in MFMA operand order;
-//   phase B  Z^T[128*s + 32*w.., 64 tok] += U_2[chunk, :]^T Y^T, one 128-rank sub-stage s at a time.
-// The weight tiles of both phases form one stream: while tile i is being used, tile i+1 (fetched during
-// the previous stage) is converted and written to the other LDS buffer and tile i+2 is requested from
-// global memory, so every global load has a full stage to land.
-// Every weight tile (128 contraction rows x 128 output columns) is copied as it lies in memory into a
-// double-buffered LDS tile and read back with the LDS's transposing read; tile i+1 is fetched from global
-// memory while tile i is used.
-// When r2 > 512 the slices are separate workgroups and phase A is recomputed per slice.
+// One workgroup owns 64 tokens, one slice of at most 1024 output ranks and one part of F; its 8 wavefronts
+// have two roles.
+//   Compute wavefronts (4, one per SIMD) keep the accumulator Z^T [up to 512 ranks, 64 tokens] in registers for
+//   the whole sweep over F.  Per 128-wide chunk of F:
+//     phase A  Y^T[128 f, 64 tok] = V_1[:, chunk]^T P1^T, contraction over r1 in 128-wide stages; wavefront w
+//              computes features 32*w.., adds b_1, applies phi, rounds to fp16 and publishes the result to all
+//              wavefronts through LDS in MFMA operand order;
+//     phase B  Z^T[128*s + 32*w.., 64 tok] += U_2[chunk, :]^T Y^T, one 128-rank sub-tile s per stage.
+//   Loader wavefronts (4) run the same sequence of stages one tile ahead: every weight tile (128 contraction rows
+//   x 128 output columns) is copied as it lies in memory into a double-buffered LDS tile (bf16 widened to fp16 on
+//   the way) and read back by the compute wavefronts with the LDS's transposing read; while tile i is in use, tile
+//   i+1 (requested one stage earlier) is stored and tile i+2 is requested, pass by pass.  The P1 tiles of phase A
+//   (fragment-major, contiguous) travel the same way through a second double buffer.  One barrier per stage.
+//   When the slice is wider than 512 ranks the loaders' otherwise idle registers hold the accumulators of the
+//   remaining sub-tiles and they issue those sub-tiles' MFMAs between their staging passes, so one pass of phase A
+//   serves up to 1024 ranks.
+// Slices of r2 beyond that are separate workgroups (phase A is recomputed per slice).  When there are fewer
+// workgroups than compute units the sum over F is split across workgroups: each writes fp32 partial sums and a
+// second kernel adds them in a fixed order.  ffn_core_plan() picks the shape on the host.
 #include "fsvd_common.h"
 #include "fsvd_kernels.h"
 
