@@ -129,6 +129,16 @@ def test_compute_entry_points_validate_before_any_launch():
     assert L.fsvd_linear(0, 32, 16, 256, 0, 256, None, 0, None, 0, 256, 0, None) == INVALID
     assert L.fsvd_layernorm(4, 16384, 256, 0, 256, 256, 0, 1e-5, 256, 2, None) == UNSUPPORTED
     assert L.fsvd_layernorm(4, 64, None, 0, 256, 256, 0, 1e-5, 256, 2, None) == INVALID
+    # the FFN core splits D_ff for this small shape: it then needs its partial-sum workspace, and only then
+    w1r, w2r = fac(768, 384, 3072), fac(3072, 384, 768)
+    core_need = fb.fsvd_ffn_core_workspace(d, 384, 384)
+    assert core_need > 0 and core_need % 256 == 0
+    core = lambda ws, n: L.fsvd_ffn_core(C.byref(d), 256, C.byref(w1r), C.byref(w2r), 256, ws, n, None)
+    assert core(None, 0) == WORKSPACE
+    assert core(256, core_need - 256) == WORKSPACE
+    assert L.fsvd_ffn_core(C.byref(d), None, C.byref(w1r), C.byref(w2r), 256, 256, core_need, None) == INVALID
+    big = desc(B=32, M=512, D=1024, H=16, F=4096)                  # plenty of workgroups: no split, no workspace
+    assert fb.fsvd_ffn_core_workspace(big, 256, 256) == 0
 
 
 def test_missing_library_fails_loudly(monkeypatch):
