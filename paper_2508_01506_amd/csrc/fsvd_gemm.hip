@@ -93,10 +93,12 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
   RawAct<AM> rawA[2][4];      // [row tile][step]; a slot is refilled right after its last use with the next chunk's data
   u4 w_raw[NP];
 
-  auto load_a = [&](int c, int kk) {
+  // Operand and weight requests never branch: past the last chunk the resource has size 0 and the loads return zeros
+  // (a conditional request inside the MFMA loop would split it into basic blocks with conservative waits).
+  auto load_a = [&](int c, int kk, bool live) {
     const int kleft = K - c * kChunkK;
-    const rsrc_t r = (AM == AM_FM) ? rsrc_at(a.A, a_total, (long long)c * kFmChunkBytes)
-                                   : rsrc_at(a.A, a_total, (long long)c * kChunkK * ESZ);
+    const rsrc_t r = (AM == AM_FM) ? rsrc_at(a.A, live ? a_total : 0, (long long)c * kFmChunkBytes)
+                                   : rsrc_at(a.A, live ? a_total : 0, (long long)c * kChunkK * ESZ);
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
       if constexpr (AM == AM_FM) {
@@ -112,27 +114,27 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
       }
     }
   };
-  auto load_w = [&](int c) {
-    const rsrc_t r = rsrc_at(G.W, w_total, ((long long)c * kChunkK * G.ldw + n0) * 2);
-#pragma unroll
-    for (int p = 0; p < NP; ++p)
-      w_raw[p] = buf_load16(r, s_ok ? ((s_r + p * RPP) * G.ldw + s_c) * 2 : kOobOffset);   // rows past K: out of range -> 0
+  auto w_rsrc = [&](int c, bool live) { return rsrc_at(G.W, live ? w_total : 0, ((long long)c * kChunkK * G.ldw + n0) * 2); };
+  auto load_w_pass = [&](const rsrc_t& r, int p) {
+    w_raw[p] = buf_load16(r, s_ok ? ((s_r + p * RPP) * G.ldw + s_c) * 2 : kOobOffset);   // rows past K: out of range -> 0
   };
-  auto store_w = [&](int buf) {
-#pragma unroll
-    for (int p = 0; p < NP; ++p) stage_store16<WT>(&lds[buf][(s_r + p * RPP) * WS + s_c], w_raw[p]);
-  };
+  auto store_w_pass = [&](int buf, int p) { stage_store16<WT>(&lds[buf][(s_r + p * RPP) * WS + s_c], w_raw[p]); };
   // prologue: chunk 0 in LDS and in the operand registers, chunk 1's weights in flight
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) load_a(0, kk);
-  load_w(0);
-  store_w(0);
-  if (kchunks > 1) load_w(1);
+  for (int kk = 0; kk < 4; ++kk) load_a(0, kk, true);
+  {
+    const rsrc_t r0 = w_rsrc(0, true), r1 = w_rsrc(1, kchunks > 1);
+#pragma unroll
+    for (int p = 0; p < NP; ++p) load_w_pass(r0, p);
+#pragma unroll
+    for (int p = 0; p < NP; ++p) { store_w_pass(0, p); load_w_pass(r1, p); }
+  }
   __syncthreads();
   for (int c = 0; c < kchunks; ++c) {
+    // chunk c+1 (requested during the previous iteration) is stored to the other buffer and chunk c+2 is requested, one
+    // staging pass per MFMA step; the activation operands of a step are refilled with chunk c+1's right after their use
+    const rsrc_t rw2 = w_rsrc(c + 2, c + 2 < kchunks);
     const bool more1 = c + 1 < kchunks;
-    if (more1) store_w((c + 1) & 1);          // chunk c+1 arrived during the previous iteration
-    if (c + 2 < kchunks) load_w(c + 2);       // chunk c+2 has this whole iteration to land
     const _Float16* wt = lds[c & 1];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
@@ -147,10 +149,13 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          acc[mt][nt] = mfma32(bf[nt], af[mt], acc[mt][nt]);   // rows n, cols tokens
-        }
-      if (more1) load_a(c + 1, kk);
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = mfma32(bf[nt], af[mt], acc[mt][nt]);   // rows n, cols tokens
+      load_a(c + 1, kk, more1);
+      if ((kk * NP) % 4 == 0) {
+        const int p = kk * NP / 4;
+        store_w_pass((c + 1) & 1, p);
+        load_w_pass(rw2, p);
+      }
     }
     __syncthreads();
   }
