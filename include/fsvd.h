@@ -20,7 +20,10 @@
  *    device memory and keeps no state between calls; all scratch is carved
  *    from `workspace`, which must be 256-byte aligned and at least as large as
  *    the matching fsvd_*_workspace() value.  The transient activation memory
- *    of a call is therefore exactly `workspace_bytes`.
+ *    of a call is therefore exactly `workspace_bytes`.  Every other data
+ *    pointer must be 16-byte aligned (FSVD_ERR_INVALID_ARG otherwise).
+ *    Calls on one stream may share a workspace; calls that overlap in time
+ *    need workspaces of their own.
  *  - Layouts.  Row-major, contiguous.  X and out are [B, M, D]; U is
  *    [in, rank]; V is [rank, out]; bias is [out] (or NULL for no bias).  Head h
  *    of an attention projection owns output columns [h*d_h, (h+1)*d_h) of V,

@@ -13,6 +13,8 @@ inline size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
 inline bool dtype_ok16(int d) { return d == FSVD_F16 || d == FSVD_BF16; }
 inline bool dtype_ok(int d) { return d == FSVD_F16 || d == FSVD_BF16 || d == FSVD_F32; }
 inline size_t smax(size_t a, size_t b) { return a > b ? a : b; }
+// every tensor is read and written with 16-byte vector accesses
+inline bool mis16(const void* p) { return p && ((uintptr_t)p & 15) != 0; }
 
 fsvd_status check_desc(const fsvd_desc* d, bool need_ffn) {
   if (!d) return FSVD_ERR_INVALID_ARG;
@@ -48,6 +50,7 @@ fsvd_status check_factor(const fsvd_factor* f, int in_dim, int out_dim, bool nee
   if ((long long)f->rank * widest >= (1LL << 29)) return FSVD_ERR_UNSUPPORTED;   // each factor < 1 GiB
   if (need_u && !f->U) return FSVD_ERR_INVALID_ARG;
   if (need_v && !f->V) return FSVD_ERR_INVALID_ARG;
+  if (mis16(f->U) || mis16(f->V) || mis16(f->bias)) return FSVD_ERR_INVALID_ARG;
   return FSVD_OK;
 }
 
@@ -236,7 +239,7 @@ fsvd_status fsvd_ffn_check(const fsvd_desc* d, const fsvd_factor* w1, const fsvd
 fsvd_status fsvd_attention(const fsvd_desc* d, const void* X, const fsvd_factor* q, const fsvd_factor* k,
                            const fsvd_factor* v, const fsvd_factor* o, void* out, void* ws, size_t ws_bytes, void* stream) {
   FSVD_TRY(check_attn(d, q, k, v, o, true));
-  if (!X || !out) return FSVD_ERR_INVALID_ARG;
+  if (!X || !out || mis16(X) || mis16(out)) return FSVD_ERR_INVALID_ARG;
   const int T = d->B * d->M;
   const AttnPlan pl = plan_attn(T, d->D, q->rank, k->rank, v->rank, o->rank);
   FSVD_TRY(check_ws(ws, ws_bytes, pl.total));
@@ -249,7 +252,7 @@ fsvd_status fsvd_attention(const fsvd_desc* d, const void* X, const fsvd_factor*
 fsvd_status fsvd_ffn(const fsvd_desc* d, const void* X, const fsvd_factor* w1, const fsvd_factor* w2, void* out,
                      void* ws, size_t ws_bytes, void* stream) {
   FSVD_TRY(check_ffn(d, w1, w2, true));
-  if (!X || !out) return FSVD_ERR_INVALID_ARG;
+  if (!X || !out || mis16(X) || mis16(out)) return FSVD_ERR_INVALID_ARG;
   FSVD_TRY(check_ws(ws, ws_bytes, plan_ffn((size_t)d->B * d->M, w1->rank, w2->rank, d->F).total));
   return run_ffn(d, X, LAYOUT_ROW, d->io_dtype, w1, w2, nullptr, 0, out, d->out_dtype, (char*)ws, (hipStream_t)stream);
 }
@@ -260,8 +263,9 @@ fsvd_status fsvd_layer(const fsvd_desc* d, const void* X, const fsvd_factor* q, 
                        void* ws, size_t ws_bytes, void* stream) {
   FSVD_TRY(check_attn(d, q, k, v, o, true));
   FSVD_TRY(check_ffn(d, w1, w2, true));
-  if (!X || !out) return FSVD_ERR_INVALID_ARG;
+  if (!X || !out || mis16(X) || mis16(out)) return FSVD_ERR_INVALID_ARG;
   if (d->norm != FSVD_NORM_NONE && (!g1 || !b1 || !g2 || !b2)) return FSVD_ERR_INVALID_ARG;
+  if (mis16(g1) || mis16(b1) || mis16(g2) || mis16(b2)) return FSVD_ERR_INVALID_ARG;
   const LayerPlan pl = plan_layer(d, q->rank, k->rank, v->rank, o->rank, w1->rank, w2->rank);
   FSVD_TRY(check_ws(ws, ws_bytes, pl.total));
   hipStream_t s = (hipStream_t)stream;
@@ -307,6 +311,7 @@ fsvd_status fsvd_linear(int32_t T, int32_t K, int32_t N, const void* A, fsvd_dty
                         const void* bias, fsvd_dtype w_dtype, const void* residual, fsvd_dtype r_dtype, void* C,
                         fsvd_dtype c_dtype, void* stream) {
   if (T <= 0 || K <= 0 || N <= 0 || !A || !W || !C) return FSVD_ERR_INVALID_ARG;
+  if (mis16(A) || mis16(W) || mis16(C) || mis16(bias) || mis16(residual)) return FSVD_ERR_INVALID_ARG;
   if (!dtype_ok(a_dtype) || !dtype_ok16(w_dtype) || !dtype_ok(c_dtype) || (residual && !dtype_ok(r_dtype))) return FSVD_ERR_INVALID_ARG;
   if (K % 16 != 0 || N % 16 != 0) return FSVD_ERR_UNSUPPORTED;
   if ((long long)T * (K > N ? K : N) >= (1LL << 29)) return FSVD_ERR_UNSUPPORTED;
@@ -324,14 +329,14 @@ size_t fsvd_fm_bytes(int32_t T, int32_t K) {
 }
 
 fsvd_status fsvd_pack_fm(int32_t T, int32_t K, const void* src, fsvd_dtype src_dtype, void* dst_fm, void* stream) {
-  if (T <= 0 || K <= 0 || !src || !dst_fm || !dtype_ok(src_dtype)) return FSVD_ERR_INVALID_ARG;
+  if (T <= 0 || K <= 0 || !src || !dst_fm || !dtype_ok(src_dtype) || mis16(src) || mis16(dst_fm)) return FSVD_ERR_INVALID_ARG;
   if (K % 8 != 0 || fm_bytes(T, K) >= (1ULL << 31)) return FSVD_ERR_UNSUPPORTED;
   FSVD_HIP(launch_pack_fm(src, src_dtype, T, K, dst_fm, (hipStream_t)stream));
   return FSVD_OK;
 }
 
 fsvd_status fsvd_unpack_fm(int32_t T, int32_t K, const void* src_fm, void* dst, fsvd_dtype dst_dtype, void* stream) {
-  if (T <= 0 || K <= 0 || !src_fm || !dst || !dtype_ok(dst_dtype)) return FSVD_ERR_INVALID_ARG;
+  if (T <= 0 || K <= 0 || !src_fm || !dst || !dtype_ok(dst_dtype) || mis16(src_fm) || mis16(dst)) return FSVD_ERR_INVALID_ARG;
   if (K % 8 != 0 || fm_bytes(T, K) >= (1ULL << 31)) return FSVD_ERR_UNSUPPORTED;
   FSVD_HIP(launch_unpack_fm(src_fm, T, K, dst, dst_dtype, (hipStream_t)stream));
   return FSVD_OK;
@@ -343,7 +348,7 @@ fsvd_status fsvd_attention_core(const fsvd_desc* d, const void* Pq, const void* 
   FSVD_TRY(check_factor(q, d->D, d->D, false, true));
   FSVD_TRY(check_factor(k, d->D, d->D, false, true));
   FSVD_TRY(check_factor(v, d->D, d->D, false, true));
-  if (!Pq || !Pk || !Pv || !context) return FSVD_ERR_INVALID_ARG;
+  if (!Pq || !Pk || !Pv || !context || mis16(Pq) || mis16(Pk) || mis16(Pv) || mis16(context)) return FSVD_ERR_INVALID_ARG;
   AttnCoreArgs ca{};
   ca.Pq = Pq; ca.Pk = Pk; ca.Pv = Pv;
   ca.rq = q->rank; ca.rk = k->rank; ca.rv = v->rank;
@@ -366,7 +371,7 @@ fsvd_status fsvd_ffn_core(const fsvd_desc* d, const void* P1, const fsvd_factor*
   FSVD_TRY(check_desc(d, true));
   FSVD_TRY(check_factor(w1, d->D, d->F, false, true));
   FSVD_TRY(check_factor(w2, d->F, d->D, true, false));
-  if (!P1 || !Z) return FSVD_ERR_INVALID_ARG;
+  if (!P1 || !Z || mis16(P1) || mis16(Z)) return FSVD_ERR_INVALID_ARG;
   const size_t need = fsvd_ffn_core_workspace(d, w1->rank, w2->rank);
   if (need) FSVD_TRY(check_ws(ws, ws_bytes, need));
   FfnCoreArgs fa{};
@@ -380,6 +385,7 @@ fsvd_status fsvd_ffn_core(const fsvd_desc* d, const void* P1, const fsvd_factor*
 fsvd_status fsvd_layernorm(int32_t T, int32_t D, const void* X, fsvd_dtype x_dtype, const void* gamma, const void* beta,
                            fsvd_dtype p_dtype, float eps, void* Y, fsvd_dtype y_dtype, void* stream) {
   if (T <= 0 || D <= 0 || !X || !gamma || !beta || !Y) return FSVD_ERR_INVALID_ARG;
+  if (mis16(X) || mis16(gamma) || mis16(beta) || mis16(Y)) return FSVD_ERR_INVALID_ARG;
   if (!dtype_ok(x_dtype) || !dtype_ok(p_dtype) || !dtype_ok(y_dtype) || !(eps >= 0.f)) return FSVD_ERR_INVALID_ARG;
   if (D > 8192 || D % 8 != 0) return FSVD_ERR_UNSUPPORTED;
   if ((long long)T * D >= (1LL << 31)) return FSVD_ERR_UNSUPPORTED;

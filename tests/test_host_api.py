@@ -77,7 +77,7 @@ def test_workspace_query_rejects_bad_configurations():
     assert fb.fsvd_attention_workspace(desc(), 64, 64, 64, 64) > 0
 
 
-def fac(i, r, o, U=1, V=1):
+def fac(i, r, o, U=256, V=256):
     return fb.fsvd_factor(U, V, 0, i, r, o)
 
 
@@ -117,6 +117,9 @@ def test_compute_entry_points_validate_before_any_launch():
     assert call(256, 256, None, need) == WORKSPACE
     assert call(256, 256, 256, need - 1) == WORKSPACE
     assert call(256, 256, 257, need) == WORKSPACE               # not 256-byte aligned
+    assert call(264, 256, 256, need) == INVALID                 # X not 16-byte aligned
+    assert call(256, 260, 256, need) == INVALID                 # out not 16-byte aligned
+    assert L.fsvd_attention(C.byref(d), 256, C.byref(fac(768, 64, 768, V=8)), C.byref(q), C.byref(q), C.byref(q), 256, 256, need, None) == INVALID
     nullU = fac(768, 64, 768, U=0)
     assert L.fsvd_attention(C.byref(d), 256, C.byref(nullU), C.byref(q), C.byref(q), C.byref(q), 256, 256, need, None) == INVALID
     w1, w2 = fac(768, 64, 3072), fac(3072, 64, 768)
