@@ -102,28 +102,36 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
     for (int dt = 0; dt < DT32; ++dt)
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt) acc[dt][qt] = zero16();
-    const int rq = a.rq;
-    const int nc = (rq + kChunkK - 1) / kChunkK;
-    const long long p_total = (long long)fm_bytes(T, rq);
-    const long long w_total = (long long)rq * D * 2;
+    // rank window of this head in V_q / P_q: all of [0, r_q) for whole-matrix factors, [h r_q, (h+1) r_q) of the
+    // concatenated ranks for per-head factors; chunks are 64 ranks of the concatenated axis
+    const int lo = a.per_head ? h * a.rq : 0, hi = lo + a.rq;
+    const int c0 = lo / kChunkK, nc = (hi - 1) / kChunkK - c0 + 1;
+    const int ld = a.per_head ? DH : D, wcol0 = a.per_head ? 0 : col0;
+    const int rtot = a.per_head ? a.H * a.rq : a.rq;
+    const int pchq = (rtot + kChunkK - 1) / kChunkK;
+    const long long p_total = (long long)fm_bytes(T, rtot);
+    const long long w_total = (long long)rtot * ld * 2;
     int voffP[QT];
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
       int q = qw + 32 * qt + l32;
       q = q < M ? q : M - 1;
-      voffP[qt] = fm_voff(tok0 + q, nc, g);
+      voffP[qt] = fm_voff(tok0 + q, pchq, g);
     }
     u4 w_raw[NP];
     h8 pfr[QT][4];
     auto load_p = [&](int c, int kk) {   // the rank padding of an FM tensor holds zeros: no tail handling
-      const rsrc_t r = rsrc_at(a.Pq, p_total, (long long)c * kFmChunkBytes);
+      const rsrc_t r = rsrc_at(a.Pq, p_total, (long long)(c0 + c) * kFmChunkBytes);
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt) pfr[qt][kk] = __builtin_bit_cast(h8, buf_load16(r, voffP[qt] + kk * kFmStepBytes));
     };
     auto issue_w = [&](int c) {
-      const rsrc_t r = rsrc_at(a.Vq, w_total, ((long long)c * kChunkK * D + col0) * 2);
+      const rsrc_t r = rsrc_at(a.Vq, w_total, ((long long)(c0 + c) * kChunkK * ld + wcol0) * 2);
 #pragma unroll
-      for (int p = 0; p < NP; ++p) w_raw[p] = buf_load16(r, ((s_r + p * RPP) * D + s_c) * 2);   // rows past r_q: 0
+      for (int p = 0; p < NP; ++p) {
+        const int rho = (c0 + c) * kChunkK + s_r + p * RPP;          // ranks outside the window contribute nothing
+        w_raw[p] = buf_load16(r, (rho >= lo && rho < hi) ? ((s_r + p * RPP) * ld + s_c) * 2 : kOobOffset);
+      }
     };
     auto commit_w = [&](int pb) {
 #pragma unroll
@@ -191,20 +199,38 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
   const int dt0 = ((wave >> 1) % NDG) * DTW;  // first feature tile of this wavefront
   const char* const Psrc = which ? uniform_ptr(a.Pv) : uniform_ptr(a.Pk);
   const char* const bsel = which ? uniform_ptr(a.bv) : uniform_ptr(a.bk);
-  const int rr = which ? a.rv : a.rk;
-  const int pch = (rr + kChunkK - 1) / kChunkK;
-  const long long p_total = (long long)fm_bytes(T, rr);
-  const int rmax = a.rk > a.rv ? a.rk : a.rv;
-  const int nc = (rmax + kChunkK - 1) / kChunkK;
+  // rank windows of this head in (V_k, P_k) and (V_v, P_v), as in the Q phase
+  const int lo_k = a.per_head ? h * a.rk : 0, hi_k = lo_k + a.rk;
+  const int lo_v = a.per_head ? h * a.rv : 0, hi_v = lo_v + a.rv;
+  const int c0_k = lo_k / kChunkK, nch_k = (hi_k - 1) / kChunkK - c0_k + 1;
+  const int c0_v = lo_v / kChunkK, nch_v = (hi_v - 1) / kChunkK - c0_v + 1;
+  const int ld = a.per_head ? DH : D, wcol0 = a.per_head ? 0 : col0;
+  const int rtot_k = a.per_head ? a.H * a.rk : a.rk, rtot_v = a.per_head ? a.H * a.rv : a.rv;
+  const long long wt_k = (long long)rtot_k * ld * 2, wt_v = (long long)rtot_v * ld * 2;
+  // the P operands of this wavefront's role
+  const int rtot_p = which ? rtot_v : rtot_k;
+  const int pch = (rtot_p + kChunkK - 1) / kChunkK;
+  const int c0_p = which ? c0_v : c0_k, nch_p = which ? nch_v : nch_k;
+  const long long p_total = (long long)fm_bytes(T, rtot_p);
+  const int nc = nch_k > nch_v ? nch_k : nch_v;
   const int total = nsteps * nc;
+  // per-lane staging offsets of the two weight matrices for relative chunk c (rows outside the window: nothing)
+  auto w_voff = [&](int m, int c, int pp) {
+    const int rho = ((m ? c0_v : c0_k) + c) * kChunkK + s_r + pp * RPP;
+    const bool ok = m ? (rho >= lo_v && rho < hi_v) : (rho >= lo_k && rho < hi_k);
+    return ok ? ((s_r + pp * RPP) * ld + s_c) * 2 : kOobOffset;
+  };
+  auto w_rsrc = [&](int m, int c, bool live) {
+    return rsrc_at(m ? a.Vv : a.Vk, live ? (m ? wt_v : wt_k) : 0, ((long long)((m ? c0_v : c0_k) + c) * kChunkK * ld + wcol0) * 2);
+  };
 
   u4 w_raw[2][NP];
   auto issue_w = [&](int c) {
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
-      const rsrc_t r = rsrc_at(m ? a.Vv : a.Vk, (long long)(m ? a.rv : a.rk) * D * 2, ((long long)c * kChunkK * D + col0) * 2);
+      const rsrc_t r = w_rsrc(m, c, true);
 #pragma unroll
-      for (int p = 0; p < NP; ++p) w_raw[m][p] = buf_load16(r, ((s_r + p * RPP) * D + s_c) * 2);   // rows past the rank: 0
+      for (int p = 0; p < NP; ++p) w_raw[m][p] = buf_load16(r, w_voff(m, c, p));
     }
   };
   auto commit_w = [&](int pb) {
@@ -224,7 +250,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
     }
   };
   auto load_p = [&](int c, int kk) {      // chunks past this matrix's rank fall outside the resource: 0
-    const rsrc_t r = rsrc_at(Psrc, (c < pch) ? p_total : 0, (long long)c * kFmChunkBytes);
+    const rsrc_t r = rsrc_at(Psrc, (c < nch_p) ? p_total : 0, (long long)(c0_p + c) * kFmChunkBytes);
 #pragma unroll
     for (int i = 0; i < KTW; ++i) pfr[i][kk] = __builtin_bit_cast(h8, buf_load16(r, voffKV[i] + kk * kFmStepBytes));
   };
@@ -257,9 +283,9 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
       // the eight wavefronts spread over the iteration instead of bursting after the barrier.  Past the last chunk
       // the resources have size 0: the loads return zeros and nothing branches.
       const int c2 = ncn + 1 == nc ? 0 : ncn + 1;
-      const rsrc_t rw0 = rsrc_at(a.Vk, (it + 2 < total) ? (long long)a.rk * D * 2 : 0, ((long long)c2 * kChunkK * D + col0) * 2);
-      const rsrc_t rw1 = rsrc_at(a.Vv, (it + 2 < total) ? (long long)a.rv * D * 2 : 0, ((long long)c2 * kChunkK * D + col0) * 2);
-      const rsrc_t rp = rsrc_at(Psrc, (more && ncn < pch) ? p_total : 0, (long long)ncn * kFmChunkBytes);
+      const rsrc_t rw0 = w_rsrc(0, c2, it + 2 < total);
+      const rsrc_t rw1 = w_rsrc(1, c2, it + 2 < total);
+      const rsrc_t rp = rsrc_at(Psrc, (more && ncn < nch_p) ? p_total : 0, (long long)(c0_p + ncn) * kFmChunkBytes);
       _Float16* const wnext = wbuf[(it + 1) & 1][0];
       // both roles compute (weights^T) x (P^T): rows = features, columns = keys, so the loop has no role-dependent code
       const _Float16* wb = wbuf[it & 1][which] + trA + 32 * dt0;
@@ -290,7 +316,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
               const int q = kk * 2 * NP / 4 + u;
               const int m = q / NP, pp = q % NP;
               stage_store16<WT>(wnext + m * WBUF + (s_r + pp * RPP) * WS + s_c, w_raw[m][pp]);
-              w_raw[m][pp] = buf_load16(m ? rw1 : rw0, ((s_r + pp * RPP) * D + s_c) * 2);   // rows past the rank: 0
+              w_raw[m][pp] = buf_load16(m ? rw1 : rw0, w_voff(m, c2, pp));
             }
           }
         }

@@ -40,9 +40,10 @@ hipError_t launch_linear(const LinearArgs& a, hipStream_t s);
 
 // ---- streaming attention core (Alg. 1 Part II): FM P_q, P_k, P_v -> FM context C [T, D]
 struct AttnCoreArgs {
-  const void* Pq; const void* Pk; const void* Pv;   // FM [B*M, r_x]
+  const void* Pq; const void* Pk; const void* Pv;   // FM [B*M, r_x] (per-head factors: [B*M, H * r_x], head h = columns h r_x ..)
   int rq, rk, rv;
-  const void* Vq; const void* Vk; const void* Vv;   // [r_x, D] stored in w_dt
+  int per_head;            // 0: whole-matrix factors, V_x [r_x, D]; 1: per-head factors, V_x [H, r_x, d_h]
+  const void* Vq; const void* Vk; const void* Vv;   // stored in w_dt
   const void* bq; const void* bk; const void* bv;   // [D] in w_dt or nullptr
   int w_dt;
   int B, M, D, H;
