@@ -123,6 +123,22 @@ fsvd_status fsvd_attention(const fsvd_desc *desc, const void *X, const fsvd_fact
                            size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The same attention block with PER-HEAD factors of q, k and v, the setting Alg. 1 is written in (V_a in
+ * R^{r x d_h} per head; appendix on multi-head low-rank activations): head h of projection a has its own pair
+ * U_a^(h) [D, r_a], V_a^(h) [r_a, d_h].  For q, k, v the fsvd_factor members then mean: `rank` = r_a of ONE head;
+ * U = [U^(1) | ... | U^(H)], row-major [D, H * rank]; V = the H matrices V^(h) one after another, [H, rank, d_h];
+ * bias [D] as before (head h owns entries h*d_h ..); in_dim = out_dim = D.  o stays a whole-matrix factor.
+ * The rank-space activations P_a are [B*M, H * rank]; a head's K and V tiles are rebuilt from its own block of
+ * r_a ranks, so the on-chip rebuild costs 2 * r_a * d_h FLOPs per key and tile instead of 2 * r * d_h with a
+ * whole-matrix rank r.  Ranks are multiples of 16 (r_a <= d_h is the intended range, larger values work).
+ * Same conventions, limits and errors as fsvd_attention; additionally H * rank * D < 2^29.
+ */
+size_t fsvd_attention_heads_workspace(const fsvd_desc *desc, int32_t r_q, int32_t r_k, int32_t r_v, int32_t r_o);
+fsvd_status fsvd_attention_heads(const fsvd_desc *desc, const void *X, const fsvd_factor *q, const fsvd_factor *k,
+                                 const fsvd_factor *v, const fsvd_factor *o, void *out, void *workspace,
+                                 size_t workspace_bytes, void *hip_stream);
+
+/*
  * Feed-forward block, FlashSVDFFN V1 (Alg. 2; section "FlashSVDFFN V1"):
  *   P = X U_1                                            (rank space, workspace)
  *   per row block, streaming over F: Y = phi(P V_1[:, chunk] + b_1[chunk]) on chip,

@@ -151,6 +151,42 @@ def attention(X, q, k, v, o, H, causal=False, key_len=None, scale=None):
 # Z = Y U_o in rank space, O = Z V_o + b_o)
 # ---------------------------------------------------------------------------
 
+def attention_per_head(X, q, k, v, o, H, causal=False, key_len=None, scale=None):
+    """Attention block with per-head factors (the paper's own setting for attention: each head h has its rank-r pair
+    U_a^(h) [D, r], V_a^(h) [r, d_h]; Sec. FlashSVDAttention / Alg. 1 with V_a in r x d_h): q, k, v hold
+    U [D, H r] (head h = columns h r ..), V [H, r, d_h] and b [D]; o is a whole-matrix factor.
+
+    Written as the plain definition: per head Q_h = (X U_h) V_h + b_h and likewise K_h, V_h; scores, masking and
+    softmax per query row; heads concatenated; factored output projection."""
+    X = _f64(X)
+    B, M, D = X.shape
+    d_h = D // H
+    sc = (1.0 / np.sqrt(d_h)) if scale is None else float(scale)
+    out = np.empty((B, M, D), dtype=F64)
+
+    def project(x, fac, h):
+        r = fac["V"].shape[1]
+        y = (x @ _f64(fac["U"])[:, h * r:(h + 1) * r]) @ _f64(fac["V"])[h]
+        if fac.get("b") is not None:
+            y = y + _f64(fac["b"])[h * d_h:(h + 1) * d_h]
+        return y
+
+    for b in range(B):
+        ctx = np.empty((M, D), dtype=F64)
+        n_keys = M if key_len is None else int(key_len[b])
+        for h in range(H):
+            Qh, Kh, Vh = project(X[b], q, h), project(X[b], k, h), project(X[b], v, h)
+            S = (Qh @ Kh.T) * sc
+            allowed = np.zeros((M, M), dtype=bool)
+            allowed[:, :n_keys] = True
+            if causal:
+                allowed &= np.tril(np.ones((M, M), dtype=bool))
+            S = np.where(allowed, S, -np.inf)
+            ctx[:, h * d_h:(h + 1) * d_h] = softmax_rows(S) @ Vh
+        out[b] = factored_linear(ctx, o)
+    return out
+
+
 def ffn(X, w1, w2, act="gelu_erf"):
     hidden = activation(factored_linear(X, w1), act)
     return factored_linear(hidden, w2)

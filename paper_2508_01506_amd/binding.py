@@ -27,7 +27,8 @@ STATUS = {0: "FSVD_OK", 1: "FSVD_ERR_INVALID_ARG", 2: "FSVD_ERR_UNSUPPORTED", 3:
 _TORCH2FSVD = {torch.float16: FSVD_F16, torch.bfloat16: FSVD_BF16, torch.float32: FSVD_F32}
 
 EXPORTS = ["fsvd_attention_workspace", "fsvd_ffn_workspace", "fsvd_layer_workspace", "fsvd_attention_check",
-           "fsvd_ffn_check", "fsvd_attention", "fsvd_ffn", "fsvd_layer", "fsvd_linear", "fsvd_attention_core",
+           "fsvd_ffn_check", "fsvd_attention", "fsvd_attention_heads", "fsvd_attention_heads_workspace", "fsvd_ffn",
+           "fsvd_layer", "fsvd_linear", "fsvd_attention_core",
            "fsvd_ffn_core", "fsvd_ffn_core_workspace", "fsvd_layernorm", "fsvd_status_string", "fsvd_version", "fsvd_fm_bytes", "fsvd_pack_fm",
            "fsvd_unpack_fm"]
 
@@ -74,6 +75,10 @@ def lib():
         L.fsvd_ffn_check.argtypes = [D, F, F]
         L.fsvd_attention.restype = C.c_int
         L.fsvd_attention.argtypes = [D, P, F, F, F, F, P, P, sz, P]
+        L.fsvd_attention_heads_workspace.restype = sz
+        L.fsvd_attention_heads_workspace.argtypes = [D, i32, i32, i32, i32]
+        L.fsvd_attention_heads.restype = C.c_int
+        L.fsvd_attention_heads.argtypes = [D, P, F, F, F, F, P, P, sz, P]
         L.fsvd_ffn.restype = C.c_int
         L.fsvd_ffn.argtypes = [D, P, F, F, P, P, sz, P]
         L.fsvd_layer.restype = C.c_int
@@ -124,6 +129,23 @@ class Factor:
         return self.U.shape[1]
 
 
+@dataclass
+class HeadFactor(Factor):
+    """Per-head factors of one attention projection: U [D, H r], V [H, r, d_h], b [D] or None."""
+
+    def c(self) -> fsvd_factor:
+        for t in (self.U, self.V, self.b):
+            assert t is None or (t.is_contiguous() and t.is_cuda)
+        H, r, d_h = self.V.shape
+        assert self.U.shape[1] == H * r
+        return fsvd_factor(self.U.data_ptr(), self.V.data_ptr(), 0 if self.b is None else self.b.data_ptr(),
+                           self.U.shape[0], r, H * d_h)
+
+    @property
+    def rank(self) -> int:
+        return self.V.shape[1]
+
+
 def _ptr(t: Optional[torch.Tensor]) -> int:
     if t is None:
         return 0
@@ -164,6 +186,22 @@ def _out_dtype(desc: fsvd_desc):
 
 def fsvd_attention_workspace(desc, r_q, r_k, r_v, r_o) -> int:
     return lib().fsvd_attention_workspace(C.byref(desc), r_q, r_k, r_v, r_o)
+
+
+def fsvd_attention_heads_workspace(desc, r_q, r_k, r_v, r_o) -> int:
+    return lib().fsvd_attention_heads_workspace(C.byref(desc), r_q, r_k, r_v, r_o)
+
+
+def fsvd_attention_heads(desc, X, q: HeadFactor, k: HeadFactor, v: HeadFactor, o: Factor, out=None, workspace=None):
+    """Attention block with per-head factors of q, k, v (o: whole-matrix factor)."""
+    if out is None:
+        out = torch.empty(X.shape, dtype=_out_dtype(desc), device=X.device)
+    if workspace is None:
+        workspace = _workspace(fsvd_attention_heads_workspace(desc, q.rank, k.rank, v.rank, o.rank), X.device)
+    fq, fk, fv, fo = q.c(), k.c(), v.c(), o.c()
+    _check(lib().fsvd_attention_heads(C.byref(desc), _ptr(X), C.byref(fq), C.byref(fk), C.byref(fv), C.byref(fo),
+                                      _ptr(out), _ptr(workspace), workspace.numel(), _stream()), "fsvd_attention_heads")
+    return out
 
 
 def fsvd_ffn_workspace(desc, r_1, r_2) -> int:
@@ -287,7 +325,8 @@ def to_device(inp: dict, device="cuda:0"):
     up = lambda a: torch.from_numpy(a).to(device=device, dtype=dt).contiguous()
     dev = {"X": up(inp["X"])}
     for n in ("q", "k", "v", "o", "w1", "w2"):
-        dev[n] = Factor(up(inp[n]["U"]), up(inp[n]["V"]), up(inp[n]["b"]))
+        cls = HeadFactor if (w.r_head > 0 and n in "qkv") else Factor
+        dev[n] = cls(up(inp[n]["U"]), up(inp[n]["V"]), up(inp[n]["b"]))
     for n in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta"):
         dev[n] = up(inp[n])
     dev["key_len"] = None if inp["key_len"] is None else torch.from_numpy(inp["key_len"]).to(device)

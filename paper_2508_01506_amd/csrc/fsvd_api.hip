@@ -66,6 +66,17 @@ fsvd_status check_attn(const fsvd_desc* d, const fsvd_factor* q, const fsvd_fact
   FSVD_TRY(check_factor(o, d->D, d->D, ptrs, ptrs));
   return FSVD_OK;
 }
+// per-head factors of q, k, v: in_dim = out_dim = D, `rank` is the rank of ONE head
+fsvd_status check_attn_heads(const fsvd_desc* d, const fsvd_factor* q, const fsvd_factor* k, const fsvd_factor* v,
+                             const fsvd_factor* o, bool ptrs) {
+  FSVD_TRY(check_desc(d, false));
+  for (const fsvd_factor* f : {q, k, v}) {
+    FSVD_TRY(check_factor(f, d->D, d->D, ptrs, ptrs));
+    if ((long long)f->rank * d->H * d->D >= (1LL << 29)) return FSVD_ERR_UNSUPPORTED;
+  }
+  FSVD_TRY(check_factor(o, d->D, d->D, ptrs, ptrs));
+  return FSVD_OK;
+}
 fsvd_status check_ffn(const fsvd_desc* d, const fsvd_factor* w1, const fsvd_factor* w2, bool ptrs) {
   FSVD_TRY(check_desc(d, true));
   FSVD_TRY(check_factor(w1, d->D, d->F, ptrs, ptrs));
@@ -111,9 +122,13 @@ float resolve_scale(const fsvd_desc* d) {
 // The last GEMM writes `out` row-major in c_dt (+ residual) or, when out_fm is set, fragment-major fp16.
 fsvd_status run_attention(const fsvd_desc* d, const void* x_fm, const fsvd_factor* q, const fsvd_factor* k,
                           const fsvd_factor* v, const fsvd_factor* o, const void* residual, int r_dt, void* out,
-                          int c_dt, bool out_fm, char* c_buf, char* rank_buf, hipStream_t s) {
+                          int c_dt, bool out_fm, char* c_buf, char* rank_buf, hipStream_t s, bool per_head = false) {
   const int T = d->B * d->M, D = d->D;
-  const AttnPlan pl = plan_attn(T, D, q->rank, k->rank, v->rank, o->rank);
+  // per-head factors: U [D, H r] is one projection matrix with H r columns, head h's rank-space activations are
+  // columns h r .. of P; V [H, r, d_h] is read per head by the attention core
+  const int hq = per_head ? d->H * q->rank : q->rank, hk = per_head ? d->H * k->rank : k->rank,
+            hv = per_head ? d->H * v->rank : v->rank;
+  const AttnPlan pl = plan_attn(T, D, hq, hk, hv, o->rank);
   char* Pq = rank_buf;
   char* Pk = rank_buf + (pl.pk - pl.p);
   char* Pv = rank_buf + (pl.pv - pl.p);
@@ -122,14 +137,14 @@ fsvd_status run_attention(const fsvd_desc* d, const void* x_fm, const fsvd_facto
   LinearArgs h1{};
   h1.A = x_fm; h1.a_layout = LAYOUT_FM; h1.lda = D; h1.a_dt = DT_F16; h1.T = T; h1.K = D; h1.w_dt = d->io_dtype;
   h1.c_layout = LAYOUT_FM; h1.c_dt = DT_F16; h1.R = nullptr; h1.ngroups = 3;
-  h1.g[0] = {q->U, nullptr, Pq, q->rank, q->rank, 0};
-  h1.g[1] = {k->U, nullptr, Pk, k->rank, k->rank, 0};
-  h1.g[2] = {v->U, nullptr, Pv, v->rank, v->rank, 0};
+  h1.g[0] = {q->U, nullptr, Pq, hq, hq, 0};
+  h1.g[1] = {k->U, nullptr, Pk, hk, hk, 0};
+  h1.g[2] = {v->U, nullptr, Pv, hv, hv, 0};
   FSVD_HIP(launch_linear(h1, s));
 
   AttnCoreArgs ca{};
   ca.Pq = Pq; ca.Pk = Pk; ca.Pv = Pv;
-  ca.rq = q->rank; ca.rk = k->rank; ca.rv = v->rank;
+  ca.rq = q->rank; ca.rk = k->rank; ca.rv = v->rank; ca.per_head = per_head ? 1 : 0;
   ca.Vq = q->V; ca.Vk = k->V; ca.Vv = v->V;
   ca.bq = q->bias; ca.bk = k->bias; ca.bv = v->bias;
   ca.w_dt = d->io_dtype;
@@ -249,6 +264,26 @@ fsvd_status fsvd_attention(const fsvd_desc* d, const void* X, const fsvd_factor*
   return run_attention(d, w + pl.c, q, k, v, o, nullptr, 0, out, d->out_dtype, false, w + pl.c, w + pl.p, s);
 }
 
+size_t fsvd_attention_heads_workspace(const fsvd_desc* d, int32_t rq, int32_t rk, int32_t rv, int32_t ro) {
+  if (check_desc(d, false) != FSVD_OK) return 0;
+  if (check_rank(rq) || check_rank(rk) || check_rank(rv) || check_rank(ro)) return 0;
+  return plan_attn((size_t)d->B * d->M, d->D, (size_t)d->H * rq, (size_t)d->H * rk, (size_t)d->H * rv, ro).total;
+}
+
+fsvd_status fsvd_attention_heads(const fsvd_desc* d, const void* X, const fsvd_factor* q, const fsvd_factor* k,
+                                 const fsvd_factor* v, const fsvd_factor* o, void* out, void* ws, size_t ws_bytes,
+                                 void* stream) {
+  FSVD_TRY(check_attn_heads(d, q, k, v, o, true));
+  if (!X || !out || mis16(X) || mis16(out)) return FSVD_ERR_INVALID_ARG;
+  const int T = d->B * d->M;
+  const AttnPlan pl = plan_attn(T, d->D, (size_t)d->H * q->rank, (size_t)d->H * k->rank, (size_t)d->H * v->rank, o->rank);
+  FSVD_TRY(check_ws(ws, ws_bytes, pl.total));
+  hipStream_t s = (hipStream_t)stream;
+  char* w = (char*)ws;
+  FSVD_HIP(launch_pack_fm(X, d->io_dtype, T, d->D, w + pl.c, s));
+  return run_attention(d, w + pl.c, q, k, v, o, nullptr, 0, out, d->out_dtype, false, w + pl.c, w + pl.p, s, true);
+}
+
 fsvd_status fsvd_ffn(const fsvd_desc* d, const void* X, const fsvd_factor* w1, const fsvd_factor* w2, void* out,
                      void* ws, size_t ws_bytes, void* stream) {
   FSVD_TRY(check_ffn(d, w1, w2, true));
@@ -351,7 +386,7 @@ fsvd_status fsvd_attention_core(const fsvd_desc* d, const void* Pq, const void* 
   if (!Pq || !Pk || !Pv || !context || mis16(Pq) || mis16(Pk) || mis16(Pv) || mis16(context)) return FSVD_ERR_INVALID_ARG;
   AttnCoreArgs ca{};
   ca.Pq = Pq; ca.Pk = Pk; ca.Pv = Pv;
-  ca.rq = q->rank; ca.rk = k->rank; ca.rv = v->rank;
+  ca.rq = q->rank; ca.rk = k->rank; ca.rv = v->rank; ca.per_head = 0;
   ca.Vq = q->V; ca.Vk = k->V; ca.Vv = v->V; ca.bq = q->bias; ca.bk = k->bias; ca.bv = v->bias;
   ca.w_dt = d->io_dtype; ca.B = d->B; ca.M = d->M; ca.D = d->D; ca.H = d->H;
   ca.causal = d->causal; ca.key_len = d->key_len; ca.scale = resolve_scale(d);

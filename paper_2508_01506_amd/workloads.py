@@ -43,6 +43,8 @@ class Workload:
     norm: str = "post_ln"       # "post_ln" | "pre_ln" | "none"
     factors: str = "gaussian"   # "gaussian" | "spectrum" | "spectrum_unit"
     min_len: int = 0            # padding mask: key_len ~ integers U[min_len, M]
+    r_head: int = 0             # > 0: q, k, v are factored per head with this rank (U [D, H r], V [H, r, d_h]);
+                                # the output projection keeps a whole-matrix factorisation of rank r_attn
     seed: int = 1506
     ln_eps: float = 1e-5
 
@@ -94,6 +96,19 @@ _register(_wl(7, 3, name="small_multi_qblock", B=2, M=1100, D=192, H=3, F=768, r
               r_ffn=208, dtype="fp16", mask="padding", min_len=300))
 _register(_wl(7, 4, name="small_causal_d64", B=1, M=700, D=256, H=4, F=1024, r_attn=112,
               r_ffn=272, dtype="bf16", mask="causal", norm="none"))
+
+
+# Per-head factorisation of q, k, v (the paper's attention setting: one rank-r pair per head, r <= d_h), the encoder
+# shapes of its attention-kernel sweep: batch 16 or 64, sequence 128..1024, per-head ranks 64, 32, 16.
+for _i, (_b, _m, _r) in enumerate(((16, 512, 32), (16, 512, 64), (16, 512, 16), (64, 128, 32), (16, 1024, 48))):
+    _register(_wl(8, _i, name=f"ph_bert_base_b{_b}_m{_m}_r{_r}", B=_b, M=_m, D=768, H=12, F=3072, r_attn=192,
+                  r_ffn=384, dtype="fp16", mask="padding", min_len=_m // 2, r_head=_r))
+_register(_wl(9, name="ph_tiny_r16", B=2, M=150, D=128, H=2, F=256, r_attn=48, r_ffn=64, dtype="fp16",
+              mask="padding", min_len=1, r_head=16))
+_register(_wl(9, 1, name="ph_tiny_r48_causal", B=2, M=300, D=192, H=3, F=384, r_attn=64, r_ffn=64, dtype="bf16",
+              mask="causal", r_head=48))
+_register(_wl(9, 2, name="ph_tiny_d128_r32", B=1, M=270, D=256, H=2, F=512, r_attn=80, r_ffn=64, dtype="bf16",
+              r_head=32))
 
 
 def get_workload(name: str, **overrides) -> Workload:
@@ -203,8 +218,20 @@ def make_inputs(w: Workload) -> dict:
         out[name + "_gamma"] = round_to_storage(1.0 + 0.02 * rng.standard_normal(w.D), st)
         out[name + "_beta"] = round_to_storage(0.02 * rng.standard_normal(w.D), st)
 
+    def head_factor(name: str):
+        # per head: U_h ~ N(0, 1/D) [D, r], V_h ~ N(0, 1/r) [r, d_h]; stored as U [D, H r] (head h = columns h r ..)
+        # and V [H, r, d_h]
+        r = w.r_head
+        u = rng.standard_normal((w.D, w.H * r)) / np.sqrt(w.D)
+        v = rng.standard_normal((w.H, r, w.d_h)) / np.sqrt(r)
+        b = 0.02 * rng.standard_normal(w.D)
+        out[name] = {"U": round_to_storage(u, st), "V": round_to_storage(v, st), "b": round_to_storage(b, st)}
+
     for a in ("q", "k", "v", "o"):
-        factor(a, w.D, w.D, w.r_attn)
+        if w.r_head > 0 and a != "o":
+            head_factor(a)
+        else:
+            factor(a, w.D, w.D, w.r_attn)
     ln("ln1")
     factor("w1", w.D, w.F, w.r_ffn)
     factor("w2", w.F, w.D, w.r_ffn)

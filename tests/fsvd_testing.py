@@ -23,7 +23,8 @@ def oracle_call(inp, part="layer"):
     w = inp["workload"]
     a = (inp["q"], inp["k"], inp["v"], inp["o"])
     if part == "attention":
-        return O.attention(inp["X"], *a, w.H, inp["causal"], inp["key_len"])
+        fn = O.attention_per_head if w.r_head > 0 else O.attention
+        return fn(inp["X"], *a, w.H, inp["causal"], inp["key_len"])
     if part == "ffn":
         return O.ffn(inp["X"], inp["w1"], inp["w2"])
     return O.layer(inp["X"], *a, (inp["ln1_gamma"], inp["ln1_beta"]), inp["w1"], inp["w2"],
@@ -45,7 +46,8 @@ def gpu_call(dev, part="layer"):
     from paper_2508_01506_amd import binding as fb
     d = dev["desc"]
     if part == "attention":
-        return fb.fsvd_attention(d, dev["X"], dev["q"], dev["k"], dev["v"], dev["o"])
+        fn = fb.fsvd_attention_heads if isinstance(dev["q"], fb.HeadFactor) else fb.fsvd_attention
+        return fn(d, dev["X"], dev["q"], dev["k"], dev["v"], dev["o"])
     if part == "ffn":
         return fb.fsvd_ffn(d, dev["X"], dev["w1"], dev["w2"])
     return fb.fsvd_layer(d, dev["X"], dev["q"], dev["k"], dev["v"], dev["o"], dev["ln1_gamma"], dev["ln1_beta"],

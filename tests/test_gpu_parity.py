@@ -185,6 +185,54 @@ def test_ffn_core_wide_rank_slices_and_split_over_f(fb, r2, dt):
     assert np.array_equal(got, again)                          # partial sums are added in a fixed order
 
 
+# ------------------------------------------------------------------ per-head factors of q, k, v
+def attn_block_tol(w, ref):
+    """Tolerance of an attention block called alone: the derived relative bound for RMS(ref) >= 0.2, and for outputs
+    of smaller scale (short unmasked sequences with low per-head ranks average the values down) the same absolute
+    fp16 hand-off noise, 1e-3 at the maximum, expressed relative to RMS(ref)."""
+    return max(tol_for(w, "attention"), 1.0e-3 / float(np.sqrt(np.mean(np.asarray(ref, dtype=np.float64) ** 2))))
+
+
+@pytest.mark.parametrize("name", ["ph_tiny_r16", "ph_tiny_r48_causal", "ph_tiny_d128_r32"])
+def test_attention_with_per_head_factors_small(fb, name):
+    """Every element of the attention block with per-head factors (ranks 16, 48 - which straddles the 64-rank
+    chunks - and 32 with 128-wide heads) against the per-head oracle."""
+    w, inp, dev = workload(name, fb)
+    got = gpu_call(dev, "attention").cpu().numpy()
+    assert np.isfinite(got).all()
+    ref = oracle_call(inp, "attention")
+    assert rel_err(got, ref) < attn_block_tol(w, ref)
+
+
+@pytest.mark.parametrize("name", ["ph_bert_base_b16_m512_r32", "ph_bert_base_b16_m512_r64", "ph_bert_base_b16_m512_r16",
+                                  "ph_bert_base_b64_m128_r32", "ph_bert_base_b16_m1024_r48"])
+def test_attention_with_per_head_factors_encoder_shapes(fb, name):
+    """The encoder shapes of the paper's attention-kernel sweep, whole sequences against the per-head oracle."""
+    w, inp, dev = workload(name, fb)
+    got = gpu_call(dev, "attention").cpu().numpy()
+    assert np.isfinite(got).all()
+    for b in (0, w.B // 2, w.B - 1):
+        one = dict(inp, X=inp["X"][b:b + 1], key_len=None if inp["key_len"] is None else inp["key_len"][b:b + 1])
+        ref = oracle_call(one, "attention")
+        assert rel_err(got[b:b + 1], ref) < attn_block_tol(w, ref)
+
+
+def test_per_head_factors_agree_with_block_diagonal_whole_matrix_factors(fb):
+    """The same projections written as whole-matrix factors (V block diagonal) go through fsvd_attention: both entry
+    points must agree to rounding (they differ only in how many zero ranks the rebuild multiplies)."""
+    w, inp, dev = workload("ph_tiny_r16", fb)
+    got = gpu_call(dev, "attention").cpu().numpy()
+    H, r, d_h = inp["q"]["V"].shape
+    def whole(f):
+        V = np.zeros((H * r, w.D), dtype=np.float32)
+        for h in range(H):
+            V[h * r:(h + 1) * r, h * d_h:(h + 1) * d_h] = f["V"][h]
+        up = lambda a: torch.from_numpy(a).to(device=DEV, dtype=dev["X"].dtype).contiguous()
+        return fb.Factor(up(f["U"]), up(V), up(f["b"]))
+    same = fb.fsvd_attention(dev["desc"], dev["X"], whole(inp["q"]), whole(inp["k"]), whole(inp["v"]), dev["o"]).cpu().numpy()
+    assert rel_err(got, same) < 1e-3
+
+
 # ------------------------------------------------------------------ entry points, small shapes, every element
 SMALL = ["tiny_h2_d64", "tiny_pad", "tiny_causal_d128", "small_multi_qblock", "small_causal_d64"]
 

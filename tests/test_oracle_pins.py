@@ -231,6 +231,49 @@ def test_attention_invariants():
     assert np.abs(ca[..., 4:8] - cb[..., 4:8]).max() > 1e-3
 
 
+@pytest.mark.parametrize("mask", ["none", "causal", "padding", "both"])
+def test_per_head_attention_equals_torch_dense_attention(mask):
+    """Per-head factors multiply out to dense per-head projections W_a = [U_1 V_1 | ... | U_H V_H]: the per-head oracle
+    must equal a dense attention block written with torch's library routines (linear, scaled_dot_product_attention)."""
+    rng = np.random.default_rng(31)
+    B, M, D, H, r, ro = 2, 9, 24, 3, 4, 6
+    d_h = D // H
+    X = rng.standard_normal((B, M, D))
+    hf = lambda: {"U": rng.standard_normal((D, H * r)) / np.sqrt(D), "V": rng.standard_normal((H, r, d_h)) / np.sqrt(r),
+                  "b": 0.1 * rng.standard_normal(D)}
+    q, k, v = hf(), hf(), hf()
+    o = {"U": rng.standard_normal((D, ro)) / np.sqrt(D), "V": rng.standard_normal((ro, D)) / np.sqrt(ro),
+         "b": 0.1 * rng.standard_normal(D)}
+    causal = mask in ("causal", "both")
+    key_len = np.array([5, 9]) if mask in ("padding", "both") else None
+    dense = lambda f: np.concatenate([f["U"][:, h * r:(h + 1) * r] @ f["V"][h] for h in range(H)], axis=1)
+    Ws = {"q": dense(q), "k": dense(k), "v": dense(v), "o": o["U"] @ o["V"],
+          "w1": np.zeros((D, D)), "w2": np.zeros((D, D))}
+    bs = {"q": q["b"], "k": k["b"], "v": v["b"], "o": o["b"], "w1": np.zeros(D), "w2": np.zeros(D)}
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    Xt = t(X)
+    qq, kk, vv = (TF.linear(Xt, t(Ws[n]).T, t(bs[n])).view(B, M, H, d_h).transpose(1, 2) for n in "qkv")
+    m = torch.ones(B, 1, M, M, dtype=torch.bool)
+    if causal:
+        m &= torch.tril(torch.ones(M, M, dtype=torch.bool))
+    if key_len is not None:
+        m &= (torch.arange(M)[None, :] < torch.as_tensor(key_len)[:, None])[:, None, None, :]
+    c = TF.scaled_dot_product_attention(qq, kk, vv, attn_mask=m)
+    ref = TF.linear(c.transpose(1, 2).reshape(B, M, D), t(Ws["o"]).T, t(bs["o"])).numpy()
+    got = O.attention_per_head(X, q, k, v, o, H, causal=causal, key_len=key_len)
+    assert np.abs(got - ref).max() < 1e-10
+    # and the block-diagonal whole-matrix factors of the same projections give the same block
+    def whole(f):
+        V = np.zeros((H * r, D))
+        for h in range(H):
+            V[h * r:(h + 1) * r, h * d_h:(h + 1) * d_h] = f["V"][h]
+        return {"U": f["U"], "V": V, "b": f["b"]}
+    same = O.attention(X, whole(q), whole(k), whole(v), o, H, causal=causal, key_len=key_len)
+    assert np.abs(got - same).max() < 1e-12
+    # parameter count of this layout against the paper's per-head formula
+    assert sum(f["U"].size + f["V"].size for f in (q, k, v)) == 3 * H * r * (D + d_h)
+
+
 def test_softmax_rows():
     rng = np.random.default_rng(1)
     s = rng.standard_normal((5, 9)) * 4
