@@ -198,6 +198,10 @@ fsvd_status fsvd_unpack_fm(int32_t T, int32_t K, const void *src_fm, void *dst, 
 fsvd_status fsvd_attention_core(const fsvd_desc *desc, const void *Pq, const void *Pk, const void *Pv,
                                 const fsvd_factor *q, const fsvd_factor *k, const fsvd_factor *v,
                                 void *context, void *hip_stream);
+/* The same with per-head factors (see fsvd_attention_heads): Pq, Pk, Pv are [B*M, H * rank] (FM). */
+fsvd_status fsvd_attention_heads_core(const fsvd_desc *desc, const void *Pq, const void *Pk, const void *Pv,
+                                      const fsvd_factor *q, const fsvd_factor *k, const fsvd_factor *v,
+                                      void *context, void *hip_stream);
 
 /* The on-chip loops of Alg. 2: P1 [B*M, w1->rank] (FM), V / bias of w1 and U of w2 -> Z [B*M, w2->rank]
  * (FM) with Z = phi(P1 V_1 + b_1) U_2.  When few tokens or large ranks would leave compute units idle the sum over

@@ -28,7 +28,7 @@ _TORCH2FSVD = {torch.float16: FSVD_F16, torch.bfloat16: FSVD_BF16, torch.float32
 
 EXPORTS = ["fsvd_attention_workspace", "fsvd_ffn_workspace", "fsvd_layer_workspace", "fsvd_attention_check",
            "fsvd_ffn_check", "fsvd_attention", "fsvd_attention_heads", "fsvd_attention_heads_workspace", "fsvd_ffn",
-           "fsvd_layer", "fsvd_linear", "fsvd_attention_core",
+           "fsvd_layer", "fsvd_linear", "fsvd_attention_core", "fsvd_attention_heads_core",
            "fsvd_ffn_core", "fsvd_ffn_core_workspace", "fsvd_layernorm", "fsvd_status_string", "fsvd_version", "fsvd_fm_bytes", "fsvd_pack_fm",
            "fsvd_unpack_fm"]
 
@@ -87,6 +87,8 @@ def lib():
         L.fsvd_linear.argtypes = [i32, i32, i32, P, C.c_int, P, P, C.c_int, P, C.c_int, P, C.c_int, P]
         L.fsvd_attention_core.restype = C.c_int
         L.fsvd_attention_core.argtypes = [D, P, P, P, F, F, F, P, P]
+        L.fsvd_attention_heads_core.restype = C.c_int
+        L.fsvd_attention_heads_core.argtypes = [D, P, P, P, F, F, F, P, P]
         L.fsvd_ffn_core_workspace.restype = sz
         L.fsvd_ffn_core_workspace.argtypes = [D, i32, i32]
         L.fsvd_ffn_core.restype = C.c_int
@@ -282,8 +284,9 @@ def fsvd_attention_core(desc, Pq, Pk, Pv, q: Factor, k: Factor, v: Factor, out=N
     if out is None:
         out = torch.empty(fsvd_fm_bytes(desc.B * desc.M, desc.D), dtype=torch.uint8, device=Pq.device)
     fq, fk, fv = q.c(), k.c(), v.c()
-    _check(lib().fsvd_attention_core(C.byref(desc), _ptr(Pq), _ptr(Pk), _ptr(Pv), C.byref(fq), C.byref(fk),
-                                     C.byref(fv), _ptr(out), _stream()), "fsvd_attention_core")
+    fn = lib().fsvd_attention_heads_core if isinstance(q, HeadFactor) else lib().fsvd_attention_core
+    _check(fn(C.byref(desc), _ptr(Pq), _ptr(Pk), _ptr(Pv), C.byref(fq), C.byref(fk), C.byref(fv), _ptr(out), _stream()),
+           "fsvd_attention_core")
     return out
 
 

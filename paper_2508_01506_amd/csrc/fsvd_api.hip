@@ -377,8 +377,9 @@ fsvd_status fsvd_unpack_fm(int32_t T, int32_t K, const void* src_fm, void* dst, 
   return FSVD_OK;
 }
 
-fsvd_status fsvd_attention_core(const fsvd_desc* d, const void* Pq, const void* Pk, const void* Pv, const fsvd_factor* q,
-                                const fsvd_factor* k, const fsvd_factor* v, void* context, void* stream) {
+namespace {
+fsvd_status attention_core_impl(const fsvd_desc* d, const void* Pq, const void* Pk, const void* Pv, const fsvd_factor* q,
+                                const fsvd_factor* k, const fsvd_factor* v, void* context, void* stream, bool per_head) {
   FSVD_TRY(check_desc(d, false));
   FSVD_TRY(check_factor(q, d->D, d->D, false, true));
   FSVD_TRY(check_factor(k, d->D, d->D, false, true));
@@ -386,13 +387,24 @@ fsvd_status fsvd_attention_core(const fsvd_desc* d, const void* Pq, const void* 
   if (!Pq || !Pk || !Pv || !context || mis16(Pq) || mis16(Pk) || mis16(Pv) || mis16(context)) return FSVD_ERR_INVALID_ARG;
   AttnCoreArgs ca{};
   ca.Pq = Pq; ca.Pk = Pk; ca.Pv = Pv;
-  ca.rq = q->rank; ca.rk = k->rank; ca.rv = v->rank; ca.per_head = 0;
+  ca.rq = q->rank; ca.rk = k->rank; ca.rv = v->rank; ca.per_head = per_head ? 1 : 0;
   ca.Vq = q->V; ca.Vk = k->V; ca.Vv = v->V; ca.bq = q->bias; ca.bk = k->bias; ca.bv = v->bias;
   ca.w_dt = d->io_dtype; ca.B = d->B; ca.M = d->M; ca.D = d->D; ca.H = d->H;
   ca.causal = d->causal; ca.key_len = d->key_len; ca.scale = resolve_scale(d);
   ca.C = context;
   FSVD_HIP(launch_attn_core(ca, (hipStream_t)stream));
   return FSVD_OK;
+}
+}  // namespace
+
+fsvd_status fsvd_attention_core(const fsvd_desc* d, const void* Pq, const void* Pk, const void* Pv, const fsvd_factor* q,
+                                const fsvd_factor* k, const fsvd_factor* v, void* context, void* stream) {
+  return attention_core_impl(d, Pq, Pk, Pv, q, k, v, context, stream, false);
+}
+fsvd_status fsvd_attention_heads_core(const fsvd_desc* d, const void* Pq, const void* Pk, const void* Pv,
+                                      const fsvd_factor* q, const fsvd_factor* k, const fsvd_factor* v, void* context,
+                                      void* stream) {
+  return attention_core_impl(d, Pq, Pk, Pv, q, k, v, context, stream, true);
 }
 
 size_t fsvd_ffn_core_workspace(const fsvd_desc* d, int32_t r1, int32_t r2) {

@@ -144,6 +144,31 @@ def test_compute_entry_points_validate_before_any_launch():
     assert fb.fsvd_ffn_core_workspace(big, 256, 256) == 0
 
 
+def test_per_head_attention_entry_point_contract():
+    """Workspace of the per-head entry point = packed X / context + P_q | P_k | P_v with H * rank columns each; the same
+    validation as the whole-matrix entry point."""
+    L = fb.lib()
+    up = lambda n: (n + 255) // 256 * 256
+    fm = lambda T, K: ((T + 31) // 32) * ((K + 63) // 64) * 4096
+    for name in ("ph_bert_base_b16_m512_r32", "ph_bert_base_b16_m1024_r48", "ph_tiny_r16"):
+        w = W.get_workload(name)
+        d = fb.make_desc(w.B, w.M, w.D, w.H, w.F, torch.float16)
+        need = fb.fsvd_attention_heads_workspace(d, w.r_head, w.r_head, w.r_head, w.r_attn)
+        assert need == up(fm(w.T, w.D)) + max(3 * up(fm(w.T, w.H * w.r_head)), up(fm(w.T, w.r_attn)))
+        # strictly below the same block with Q, K, V materialised beside P
+        if w.T >= 1024:
+            assert need < w.T * w.D * 2 + 3 * w.T * w.H * w.r_head * 2 + 3 * w.T * w.D * 2
+    d = desc()
+    q, o = fac(768, 32, 768), fac(768, 192, 768)
+    need = fb.fsvd_attention_heads_workspace(d, 32, 32, 32, 192)
+    call = lambda X, out, ws, n, qq=q: L.fsvd_attention_heads(C.byref(d), X, C.byref(qq), C.byref(q), C.byref(q), C.byref(o), out, ws, n, None)
+    assert call(None, 256, 256, need) == INVALID
+    assert call(256, 256, 256, need - 256) == WORKSPACE
+    assert call(256, 256, 256, need, fac(768, 24, 768)) == UNSUPPORTED          # rank % 16
+    assert call(256, 256, 256, need, fac(768, 32, 512)) == INVALID              # out_dim must be D
+    assert fb.fsvd_attention_heads_workspace(desc(H=7), 32, 32, 32, 64) == 0
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(fb, "_lib", None)
     monkeypatch.setattr(fb, "LIB_PATH", "/nonexistent/libfsvd.so")
