@@ -34,14 +34,10 @@ DEFAULT_WORKLOAD = "cfg5_llm_b1_m4096_causal"   # the largest configuration: the
 def useful_flops(w, mean_pairs):
     """Algorithmic FLOPs of one layer, every tile built once (no recompute counted)."""
     T, D, F, ra, rf = w.T, w.D, w.F, w.r_attn, w.r_ffn
-    if w.r_head > 0:     # per-head factors of q, k, v: the attention block alone
-        f = {"rank_proj_qkv": 6.0 * T * D * w.H * w.r_head, "rebuild_qkv": 6.0 * T * w.r_head * D,
-             "attn_core": 4.0 * D * mean_pairs, "out_proj": 4.0 * T * D * ra}
-        f["total"] = sum(f.values())
-        return f
     f = {
-        "rank_proj_qkv": 6.0 * T * D * ra,
-        "rebuild_qkv": 6.0 * T * ra * D,
+        # per-head factors of q, k, v: H r columns per projection, each head rebuilt from its own r ranks
+        "rank_proj_qkv": 6.0 * T * D * (w.H * w.r_head if w.r_head > 0 else ra),
+        "rebuild_qkv": 6.0 * T * (w.r_head if w.r_head > 0 else ra) * D,
         "attn_core": 4.0 * D * mean_pairs,
         "out_proj": 4.0 * T * D * ra,
         "ffn_in": 2.0 * T * D * rf,
@@ -79,19 +75,17 @@ def main():
     dev = fb.to_device(inp, "cuda:0")
     d = dev["desc"]
     ra, rf = w.r_attn, w.r_ffn
-    per_head = w.r_head > 0       # per-head workloads time the attention block (the row they widen into) alone
+    per_head = w.r_head > 0       # per-head factors of q, k, v: the layer goes through fsvd_layer_heads
     rh = w.r_head
-    ws_bytes = (fb.fsvd_attention_heads_workspace(d, rh, rh, rh, ra) if per_head
+    ws_bytes = (fb.fsvd_layer_heads_workspace(d, rh, rh, rh, ra, rf, rf) if per_head
                 else fb.fsvd_layer_workspace(d, ra, ra, ra, ra, rf, rf))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
     out = torch.empty((w.B, w.M, w.D), dtype=torch.float32, device="cuda:0")
 
     def step():
-        if per_head:
-            fb.fsvd_attention_heads(d, dev["X"], dev["q"], dev["k"], dev["v"], dev["o"], out=out, workspace=ws)
-        else:
-            fb.fsvd_layer(d, dev["X"], dev["q"], dev["k"], dev["v"], dev["o"], dev["ln1_gamma"], dev["ln1_beta"],
-                          dev["w1"], dev["w2"], dev["ln2_gamma"], dev["ln2_beta"], out=out, workspace=ws)
+        layer = fb.fsvd_layer_heads if per_head else fb.fsvd_layer
+        layer(d, dev["X"], dev["q"], dev["k"], dev["v"], dev["o"], dev["ln1_gamma"], dev["ln1_beta"],
+              dev["w1"], dev["w2"], dev["ln2_gamma"], dev["ln2_beta"], out=out, workspace=ws)
 
     for _ in range(args.warmup):
         step()
@@ -139,12 +133,8 @@ def main():
     core_ws = torch.empty(max(1, fb.fsvd_ffn_core_workspace(d, rf, rf)), device="cuda:0", dtype=torch.uint8)
     run_ffn = lambda: fb.fsvd_ffn_core(d, P1, dev["w1"], dev["w2"], out=Z, workspace=core_ws)
     run_attn = lambda: fb.fsvd_attention_core(d, Pq, Pk, Pv, dev["q"], dev["k"], dev["v"], out=Cx)
-    if per_head:          # the FFN is not part of the timed block
-        ffn_ms = 0.0
-        attn_ms = timed(run_attn, lambda: flush.zero_(), n_k)
-    else:
-        ffn_ms = timed(run_ffn, lambda: (run_attn(), flush.zero_()), n_k)
-        attn_ms = timed(run_attn, lambda: (run_ffn(), flush.zero_()), n_k)
+    ffn_ms = timed(run_ffn, lambda: (run_attn(), flush.zero_()), n_k)
+    attn_ms = timed(run_attn, lambda: (run_ffn(), flush.zero_()), n_k)
     del flush
     if args.calibrate_traffic:
         src = torch.zeros((65536, 4096), device="cuda:0", dtype=torch.float16)
@@ -153,9 +143,7 @@ def main():
             fb.fsvd_pack_fm(src, out=dst)
         torch.cuda.synchronize()
         del src, dst
-    if per_head:
-        kname, kflops, kms = "attn_core_kernel", fl["rebuild_qkv"] + fl["attn_core"], attn_ms
-    elif ffn_ms >= attn_ms:
+    if ffn_ms >= attn_ms:
         kname, kflops, kms = "ffn_core_kernel", fl["ffn_core"], ffn_ms
     else:
         kname, kflops, kms = "attn_core_kernel", fl["rebuild_qkv"] + fl["attn_core"], attn_ms
@@ -170,8 +158,8 @@ def main():
     T, D, F = w.T, w.D, w.F
     stream_bytes = T * D * (2 if w.norm == "none" else 4)
     unfused = stream_bytes + T * D * 2 + max(T * 3 * ra * 2 + 3 * T * D * 2, 2 * T * rf * 2 + T * F * 2)
-    if per_head:      # attention block alone: packed X / context, P_q|P_k|P_v (and, unfused, Q, K, V beside them)
-        unfused = T * D * 2 + T * 3 * w.H * rh * 2 + 3 * T * D * 2
+    if per_head:      # P_q | P_k | P_v have H r columns each
+        unfused = stream_bytes + T * D * 2 + max(T * 3 * w.H * rh * 2 + 3 * T * D * 2, 2 * T * rf * 2 + T * F * 2)
     result = {
         "metric": "fused low-rank layer tokens/s + peak transient activation MB; % MFMA peak",
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -179,7 +167,7 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "M": w.M, "D": w.D, "H": w.H, "F": w.F, "r_attn": ra, "r_ffn": rf,
                    "storage": w.dtype, "mask": w.mask, "norm": w.norm,
-                   **({"r_head": rh, "block": "attention (per-head factors)"} if per_head else {})},
+                   **({"r_head": rh, "qkv_factors": "per head"} if per_head else {})},
         "useful_tflops": round(fl["total"] / (ms * 1e-3) / 1e12, 2),
         "mfma_peak_frac": round(fl["total"] / (ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS, 4),
         "transient_mb": round(ws_bytes / 2 ** 20, 2), "unfused_transient_mb": round(unfused / 2 ** 20, 2),
@@ -201,7 +189,7 @@ def main():
             for b in range(w.B - 1, -1, -1):
                 t0 = time.perf_counter()
                 ref = (oracle_call(dict(inp, X=inp["X"][b:b + 1], key_len=None if inp["key_len"] is None
-                                    else inp["key_len"][b:b + 1]), "attention")[0, rows] if per_head
+                                    else inp["key_len"][b:b + 1]), "layer")[0, rows] if per_head
                    else oracle_rows(inp, b, rows, "layer"))
                 dt += time.perf_counter() - t0
                 got = out[b, w.M - n_rows:].cpu().numpy()

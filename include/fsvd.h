@@ -163,6 +163,14 @@ fsvd_status fsvd_layer(const fsvd_desc *desc, const void *X, const fsvd_factor *
                        const fsvd_factor *w1, const fsvd_factor *w2, const void *ln2_gamma, const void *ln2_beta,
                        void *out, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The same layer with per-head factors of q, k and v (see fsvd_attention_heads); o, w1, w2 as in fsvd_layer. */
+size_t fsvd_layer_heads_workspace(const fsvd_desc *desc, int32_t r_q, int32_t r_k, int32_t r_v, int32_t r_o,
+                                  int32_t r_1, int32_t r_2);
+fsvd_status fsvd_layer_heads(const fsvd_desc *desc, const void *X, const fsvd_factor *q, const fsvd_factor *k,
+                             const fsvd_factor *v, const fsvd_factor *o, const void *ln1_gamma, const void *ln1_beta,
+                             const fsvd_factor *w1, const fsvd_factor *w2, const void *ln2_gamma, const void *ln2_beta,
+                             void *out, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 
 /* ------------------------------------------------------------------------------------------
  * Building blocks.  The three entry points above are sequences of these steps; they are exported

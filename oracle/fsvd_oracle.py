@@ -198,17 +198,18 @@ def ffn(X, w1, w2, act="gelu_erf"):
 # ---------------------------------------------------------------------------
 
 def layer(X, q, k, v, o, ln1, w1, w2, ln2, H, norm="post_ln", causal=False, key_len=None,
-          scale=None, act="gelu_erf", eps=1e-5):
-    """ln1/ln2 are (gamma, beta) pairs (ignored when norm == "none")."""
+          scale=None, act="gelu_erf", eps=1e-5, per_head=False):
+    """ln1/ln2 are (gamma, beta) pairs (ignored when norm == "none"); per_head: q, k, v hold per-head factors."""
     X = _f64(X)
+    attn = attention_per_head if per_head else attention
     if norm == "post_ln":
-        y1 = layer_norm(X + attention(X, q, k, v, o, H, causal, key_len, scale), *ln1, eps)
+        y1 = layer_norm(X + attn(X, q, k, v, o, H, causal, key_len, scale), *ln1, eps)
         return layer_norm(y1 + ffn(y1, w1, w2, act), *ln2, eps)
     if norm == "pre_ln":
-        x1 = X + attention(layer_norm(X, *ln1, eps), q, k, v, o, H, causal, key_len, scale)
+        x1 = X + attn(layer_norm(X, *ln1, eps), q, k, v, o, H, causal, key_len, scale)
         return x1 + ffn(layer_norm(x1, *ln2, eps), w1, w2, act)
     if norm == "none":
-        return ffn(attention(X, q, k, v, o, H, causal, key_len, scale), w1, w2, act)
+        return ffn(attn(X, q, k, v, o, H, causal, key_len, scale), w1, w2, act)
     raise ValueError(norm)
 
 

@@ -28,7 +28,7 @@ _TORCH2FSVD = {torch.float16: FSVD_F16, torch.bfloat16: FSVD_BF16, torch.float32
 
 EXPORTS = ["fsvd_attention_workspace", "fsvd_ffn_workspace", "fsvd_layer_workspace", "fsvd_attention_check",
            "fsvd_ffn_check", "fsvd_attention", "fsvd_attention_heads", "fsvd_attention_heads_workspace", "fsvd_ffn",
-           "fsvd_layer", "fsvd_linear", "fsvd_attention_core", "fsvd_attention_heads_core",
+           "fsvd_layer", "fsvd_layer_heads", "fsvd_layer_heads_workspace", "fsvd_linear", "fsvd_attention_core", "fsvd_attention_heads_core",
            "fsvd_ffn_core", "fsvd_ffn_core_workspace", "fsvd_layernorm", "fsvd_status_string", "fsvd_version", "fsvd_fm_bytes", "fsvd_pack_fm",
            "fsvd_unpack_fm"]
 
@@ -83,6 +83,10 @@ def lib():
         L.fsvd_ffn.argtypes = [D, P, F, F, P, P, sz, P]
         L.fsvd_layer.restype = C.c_int
         L.fsvd_layer.argtypes = [D, P, F, F, F, F, P, P, F, F, P, P, P, P, sz, P]
+        L.fsvd_layer_heads_workspace.restype = sz
+        L.fsvd_layer_heads_workspace.argtypes = [D, i32, i32, i32, i32, i32, i32]
+        L.fsvd_layer_heads.restype = C.c_int
+        L.fsvd_layer_heads.argtypes = [D, P, F, F, F, F, P, P, F, F, P, P, P, P, sz, P]
         L.fsvd_linear.restype = C.c_int
         L.fsvd_linear.argtypes = [i32, i32, i32, P, C.c_int, P, P, C.c_int, P, C.c_int, P, C.c_int, P]
         L.fsvd_attention_core.restype = C.c_int
@@ -245,6 +249,24 @@ def fsvd_layer(desc, X, q, k, v, o, ln1_gamma, ln1_beta, w1, w2, ln2_gamma, ln2_
     _check(lib().fsvd_layer(C.byref(desc), _ptr(X), C.byref(fq), C.byref(fk), C.byref(fv), C.byref(fo),
                             _ptr(ln1_gamma), _ptr(ln1_beta), C.byref(f1), C.byref(f2), _ptr(ln2_gamma),
                             _ptr(ln2_beta), _ptr(out), _ptr(workspace), workspace.numel(), _stream()), "fsvd_layer")
+    return out
+
+
+def fsvd_layer_heads_workspace(desc, r_q, r_k, r_v, r_o, r_1, r_2) -> int:
+    return lib().fsvd_layer_heads_workspace(C.byref(desc), r_q, r_k, r_v, r_o, r_1, r_2)
+
+
+def fsvd_layer_heads(desc, X, q, k, v, o, ln1_gamma, ln1_beta, w1, w2, ln2_gamma, ln2_beta, out=None, workspace=None):
+    """One layer with per-head factors of q, k, v (HeadFactor); o, w1, w2 whole-matrix factors."""
+    if out is None:
+        out = torch.empty(X.shape, dtype=_out_dtype(desc), device=X.device)
+    if workspace is None:
+        workspace = _workspace(fsvd_layer_heads_workspace(desc, q.rank, k.rank, v.rank, o.rank, w1.rank, w2.rank), X.device)
+    fq, fk, fv, fo, f1, f2 = q.c(), k.c(), v.c(), o.c(), w1.c(), w2.c()
+    _check(lib().fsvd_layer_heads(C.byref(desc), _ptr(X), C.byref(fq), C.byref(fk), C.byref(fv), C.byref(fo),
+                                  _ptr(ln1_gamma), _ptr(ln1_beta), C.byref(f1), C.byref(f2), _ptr(ln2_gamma),
+                                  _ptr(ln2_beta), _ptr(out), _ptr(workspace), workspace.numel(), _stream()),
+           "fsvd_layer_heads")
     return out
 
 

@@ -292,16 +292,20 @@ fsvd_status fsvd_ffn(const fsvd_desc* d, const void* X, const fsvd_factor* w1, c
   return run_ffn(d, X, LAYOUT_ROW, d->io_dtype, w1, w2, nullptr, 0, out, d->out_dtype, (char*)ws, (hipStream_t)stream);
 }
 
-fsvd_status fsvd_layer(const fsvd_desc* d, const void* X, const fsvd_factor* q, const fsvd_factor* k,
+}  // extern "C"
+
+namespace {
+fsvd_status layer_impl(const fsvd_desc* d, const void* X, const fsvd_factor* q, const fsvd_factor* k,
                        const fsvd_factor* v, const fsvd_factor* o, const void* g1, const void* b1,
                        const fsvd_factor* w1, const fsvd_factor* w2, const void* g2, const void* b2, void* out,
-                       void* ws, size_t ws_bytes, void* stream) {
-  FSVD_TRY(check_attn(d, q, k, v, o, true));
+                       void* ws, size_t ws_bytes, void* stream, bool per_head) {
+  FSVD_TRY(per_head ? check_attn_heads(d, q, k, v, o, true) : check_attn(d, q, k, v, o, true));
   FSVD_TRY(check_ffn(d, w1, w2, true));
   if (!X || !out || mis16(X) || mis16(out)) return FSVD_ERR_INVALID_ARG;
   if (d->norm != FSVD_NORM_NONE && (!g1 || !b1 || !g2 || !b2)) return FSVD_ERR_INVALID_ARG;
   if (mis16(g1) || mis16(b1) || mis16(g2) || mis16(b2)) return FSVD_ERR_INVALID_ARG;
-  const LayerPlan pl = plan_layer(d, q->rank, k->rank, v->rank, o->rank, w1->rank, w2->rank);
+  const size_t hm = per_head ? (size_t)d->H : 1;     // per-head factors: H * rank columns of P per projection
+  const LayerPlan pl = plan_layer(d, hm * q->rank, hm * k->rank, hm * v->rank, o->rank, w1->rank, w2->rank);
   FSVD_TRY(check_ws(ws, ws_bytes, pl.total));
   hipStream_t s = (hipStream_t)stream;
   char* w = (char*)ws;
@@ -322,23 +326,47 @@ fsvd_status fsvd_layer(const fsvd_desc* d, const void* X, const fsvd_factor* q, 
   if (d->norm == FSVD_NORM_POST_LN) {
     // S1 = X + Attn(X) (fp32 stream) -> Y1 = LN1(S1) in place + FM copy -> S2 = Y1 + FFN(Y1) in place -> out = LN2(S2)
     FSVD_HIP(launch_pack_fm(X, io, T, D, c_buf, s));
-    FSVD_TRY(run_attention(d, c_buf, q, k, v, o, X, io, stream_buf, DT_F32, false, c_buf, rank_buf, s));
+    FSVD_TRY(run_attention(d, c_buf, q, k, v, o, X, io, stream_buf, DT_F32, false, c_buf, rank_buf, s, per_head));
     FSVD_TRY(ln(stream_buf, DT_F32, g1, b1, stream_buf, DT_F32, c_buf));
     FSVD_TRY(run_ffn(d, c_buf, LAYOUT_FM, DT_F16, w1, w2, stream_buf, DT_F32, stream_buf, DT_F32, rank_buf, s));
     FSVD_TRY(ln(stream_buf, DT_F32, g2, b2, out, d->out_dtype, nullptr));
   } else if (d->norm == FSVD_NORM_PRE_LN) {
     // N1 = LN1(X) (FM) -> X1 = X + Attn(N1) (fp32 stream) -> N2 = LN2(X1) (FM) -> out = X1 + FFN(N2)
     FSVD_TRY(ln(X, io, g1, b1, nullptr, 0, c_buf));
-    FSVD_TRY(run_attention(d, c_buf, q, k, v, o, X, io, stream_buf, DT_F32, false, c_buf, rank_buf, s));
+    FSVD_TRY(run_attention(d, c_buf, q, k, v, o, X, io, stream_buf, DT_F32, false, c_buf, rank_buf, s, per_head));
     FSVD_TRY(ln(stream_buf, DT_F32, g2, b2, nullptr, 0, c_buf));
     FSVD_TRY(run_ffn(d, c_buf, LAYOUT_FM, DT_F16, w1, w2, stream_buf, DT_F32, out, d->out_dtype, rank_buf, s));
   } else {
     // out = FFN(Attn(X)): the attention output goes straight into the FM buffer that feeds the FFN
     FSVD_HIP(launch_pack_fm(X, io, T, D, c_buf, s));
-    FSVD_TRY(run_attention(d, c_buf, q, k, v, o, nullptr, 0, c_buf, DT_F16, true, c_buf, rank_buf, s));
+    FSVD_TRY(run_attention(d, c_buf, q, k, v, o, nullptr, 0, c_buf, DT_F16, true, c_buf, rank_buf, s, per_head));
     FSVD_TRY(run_ffn(d, c_buf, LAYOUT_FM, DT_F16, w1, w2, nullptr, 0, out, d->out_dtype, rank_buf, s));
   }
   return FSVD_OK;
+}
+}  // namespace
+
+extern "C" {
+
+fsvd_status fsvd_layer(const fsvd_desc* d, const void* X, const fsvd_factor* q, const fsvd_factor* k,
+                       const fsvd_factor* v, const fsvd_factor* o, const void* g1, const void* b1,
+                       const fsvd_factor* w1, const fsvd_factor* w2, const void* g2, const void* b2, void* out,
+                       void* ws, size_t ws_bytes, void* stream) {
+  return layer_impl(d, X, q, k, v, o, g1, b1, w1, w2, g2, b2, out, ws, ws_bytes, stream, false);
+}
+
+size_t fsvd_layer_heads_workspace(const fsvd_desc* d, int32_t rq, int32_t rk, int32_t rv, int32_t ro, int32_t r1, int32_t r2) {
+  if (check_desc(d, true) != FSVD_OK) return 0;
+  if (check_rank(rq) || check_rank(rk) || check_rank(rv) || check_rank(ro) || check_rank(r1) || check_rank(r2)) return 0;
+  const size_t H = d->H;
+  return plan_layer(d, H * rq, H * rk, H * rv, ro, r1, r2).total;
+}
+
+fsvd_status fsvd_layer_heads(const fsvd_desc* d, const void* X, const fsvd_factor* q, const fsvd_factor* k,
+                             const fsvd_factor* v, const fsvd_factor* o, const void* g1, const void* b1,
+                             const fsvd_factor* w1, const fsvd_factor* w2, const void* g2, const void* b2, void* out,
+                             void* ws, size_t ws_bytes, void* stream) {
+  return layer_impl(d, X, q, k, v, o, g1, b1, w1, w2, g2, b2, out, ws, ws_bytes, stream, true);
 }
 
 // ------------------------------------------------------------------ building blocks

@@ -29,7 +29,7 @@ def oracle_call(inp, part="layer"):
         return O.ffn(inp["X"], inp["w1"], inp["w2"])
     return O.layer(inp["X"], *a, (inp["ln1_gamma"], inp["ln1_beta"]), inp["w1"], inp["w2"],
                    (inp["ln2_gamma"], inp["ln2_beta"]), w.H, norm=w.norm, causal=inp["causal"],
-                   key_len=inp["key_len"], eps=w.ln_eps)
+                   key_len=inp["key_len"], eps=w.ln_eps, per_head=w.r_head > 0)
 
 
 def oracle_rows(inp, b, rows, part="layer"):
@@ -50,8 +50,9 @@ def gpu_call(dev, part="layer"):
         return fn(d, dev["X"], dev["q"], dev["k"], dev["v"], dev["o"])
     if part == "ffn":
         return fb.fsvd_ffn(d, dev["X"], dev["w1"], dev["w2"])
-    return fb.fsvd_layer(d, dev["X"], dev["q"], dev["k"], dev["v"], dev["o"], dev["ln1_gamma"], dev["ln1_beta"],
-                         dev["w1"], dev["w2"], dev["ln2_gamma"], dev["ln2_beta"])
+    fn = fb.fsvd_layer_heads if isinstance(dev["q"], fb.HeadFactor) else fb.fsvd_layer
+    return fn(d, dev["X"], dev["q"], dev["k"], dev["v"], dev["o"], dev["ln1_gamma"], dev["ln1_beta"],
+              dev["w1"], dev["w2"], dev["ln2_gamma"], dev["ln2_beta"])
 
 
 def sample_rows(w: W.Workload, n_rows: int, seed: int = 0):

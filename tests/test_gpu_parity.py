@@ -217,6 +217,24 @@ def test_attention_with_per_head_factors_encoder_shapes(fb, name):
         assert rel_err(got[b:b + 1], ref) < attn_block_tol(w, ref)
 
 
+@pytest.mark.parametrize("norm", ["post_ln", "pre_ln"])
+@pytest.mark.parametrize("name", ["ph_tiny_r16", "ph_tiny_r48_causal", "ph_tiny_d128_r32"])
+def test_layer_with_per_head_attention_meets_the_gate(fb, name, norm):
+    w = W.get_workload(name, norm=norm)
+    inp = W.make_inputs(w)
+    dev = fb.to_device(inp, DEV)
+    assert rel_err(gpu_call(dev, "layer").cpu().numpy(), oracle_call(inp, "layer")) < TOL_LAYER
+
+
+@pytest.mark.parametrize("name", ["ph_bert_base_b16_m512_r32", "ph_bert_base_b16_m1024_r48"])
+def test_layer_with_per_head_attention_encoder_shapes(fb, name):
+    w, inp, dev = workload(name, fb)
+    got = gpu_call(dev, "layer").cpu().numpy()
+    for b in (0, w.B - 1):
+        one = dict(inp, X=inp["X"][b:b + 1], key_len=None if inp["key_len"] is None else inp["key_len"][b:b + 1])
+        assert rel_err(got[b:b + 1], oracle_call(one, "layer")) < TOL_LAYER
+
+
 def test_per_head_factors_agree_with_block_diagonal_whole_matrix_factors(fb):
     """The same projections written as whole-matrix factors (V block diagonal) go through fsvd_attention: both entry
     points must agree to rounding (they differ only in how many zero ranks the rebuild multiplies)."""
