@@ -67,8 +67,14 @@ typedef enum { FSVD_F16 = 0, FSVD_BF16 = 1, FSVD_F32 = 2 } fsvd_dtype;
 typedef enum { FSVD_ACT_GELU_ERF = 0, FSVD_ACT_GELU_TANH = 1, FSVD_ACT_RELU = 2 } fsvd_act;
 typedef enum { FSVD_NORM_NONE = 0, FSVD_NORM_POST_LN = 1, FSVD_NORM_PRE_LN = 2 } fsvd_norm;
 
+/* How a factor matrix is stored.  ROW_MAJOR: as described under "Layouts", in io_dtype.  TILED: prepacked once by
+ * fsvd_pack_tiled (at model load) into fp16 tile images that the kernels copy into on-chip memory byte for byte;
+ * see fsvd_pack_tiled for the format and for which matrices may be given this way. */
+typedef enum { FSVD_ROW_MAJOR = 0, FSVD_TILED = 1 } fsvd_layout;
+
 /* One factored projection W ~= U V (+ bias).  U [in_dim, rank], V [rank, out_dim],
- * bias [out_dim] or NULL; device pointers in the descriptor's io_dtype. */
+ * bias [out_dim] or NULL; device pointers in the descriptor's io_dtype (bias always; U and V unless
+ * their layout member says FSVD_TILED).  A zero-initialised u_layout / v_layout means row-major. */
 typedef struct {
   const void *U;
   const void *V;
@@ -76,6 +82,8 @@ typedef struct {
   int32_t in_dim;
   int32_t rank;
   int32_t out_dim;
+  int32_t u_layout;   /* fsvd_layout of U */
+  int32_t v_layout;   /* fsvd_layout of V */
 } fsvd_factor;
 
 /* Problem descriptor (host memory). */
@@ -200,6 +208,23 @@ fsvd_status fsvd_linear(int32_t T, int32_t K, int32_t N, const void *A, fsvd_dty
 size_t fsvd_fm_bytes(int32_t T, int32_t K);
 fsvd_status fsvd_pack_fm(int32_t T, int32_t K, const void *src, fsvd_dtype src_dtype, void *dst_fm, void *hip_stream);
 fsvd_status fsvd_unpack_fm(int32_t T, int32_t K, const void *src_fm, void *dst, fsvd_dtype dst_dtype, void *hip_stream);
+
+/*
+ * Prepacked weights ("tile images").  The fused kernels stream their weight operands (the V factors that rebuild
+ * full-width tiles, Alg. 1 Part I and Alg. 2's inner loops) through on-chip memory in tiles of 128 x 128.  A matrix
+ * W [rows, cols] that is constant across calls can be converted once into the exact byte image of those tiles:
+ * fp16 (bf16 sources are widened, the same conversion the kernels apply on the fly), zero-padded to whole tiles,
+ * tile (i, j) = rows 128 i .., cols 128 j .. stored at (i * ceil(cols / 128) + j) * 32768 bytes; inside a tile,
+ * element (k, n) is the half at  k * 128 + (((n / 32) ^ (k % 4)) * 32) + n % 32.  The kernels then move a tile with
+ * loads that write on-chip memory directly, which removes the conversion and staging work from the loop.
+ * fsvd_tiled_bytes gives the buffer size (0 if rows or cols is not positive, cols % 8 != 0, or the image would
+ * reach 2 GiB); fsvd_pack_tiled converts a contiguous row-major [rows, cols] matrix (F16 or BF16).  Results are
+ * identical to the row-major path.  Matrices accepted as FSVD_TILED: V of w1 and U of w2 (both or neither) in
+ * fsvd_ffn, fsvd_layer, fsvd_layer_heads and fsvd_ffn_core; FSVD_ERR_UNSUPPORTED anywhere else.
+ */
+size_t fsvd_tiled_bytes(int32_t rows, int32_t cols);
+fsvd_status fsvd_pack_tiled(int32_t rows, int32_t cols, const void *src, fsvd_dtype src_dtype, void *dst,
+                            void *hip_stream);
 
 /* Alg. 1 Part II on rank-space inputs: Pq [B*M, q->rank], Pk, Pv (FM) and the V / bias members of
  * q, k, v (their U members are ignored) -> context [B*M, D] (FM, heads concatenated). */

@@ -30,7 +30,7 @@ EXPORTS = ["fsvd_attention_workspace", "fsvd_ffn_workspace", "fsvd_layer_workspa
            "fsvd_ffn_check", "fsvd_attention", "fsvd_attention_heads", "fsvd_attention_heads_workspace", "fsvd_ffn",
            "fsvd_layer", "fsvd_layer_heads", "fsvd_layer_heads_workspace", "fsvd_linear", "fsvd_attention_core", "fsvd_attention_heads_core",
            "fsvd_ffn_core", "fsvd_ffn_core_workspace", "fsvd_layernorm", "fsvd_status_string", "fsvd_version", "fsvd_fm_bytes", "fsvd_pack_fm",
-           "fsvd_unpack_fm"]
+           "fsvd_unpack_fm", "fsvd_tiled_bytes", "fsvd_pack_tiled"]
 
 
 class FsvdError(RuntimeError):
@@ -41,7 +41,8 @@ class FsvdError(RuntimeError):
 
 class fsvd_factor(C.Structure):
     _fields_ = [("U", C.c_void_p), ("V", C.c_void_p), ("bias", C.c_void_p),
-                ("in_dim", C.c_int32), ("rank", C.c_int32), ("out_dim", C.c_int32)]
+                ("in_dim", C.c_int32), ("rank", C.c_int32), ("out_dim", C.c_int32),
+                ("u_layout", C.c_int32), ("v_layout", C.c_int32)]
 
 
 class fsvd_desc(C.Structure):
@@ -105,6 +106,10 @@ def lib():
         L.fsvd_pack_fm.argtypes = [i32, i32, P, C.c_int, P, P]
         L.fsvd_unpack_fm.restype = C.c_int
         L.fsvd_unpack_fm.argtypes = [i32, i32, P, P, C.c_int, P]
+        L.fsvd_tiled_bytes.restype = sz
+        L.fsvd_tiled_bytes.argtypes = [i32, i32]
+        L.fsvd_pack_tiled.restype = C.c_int
+        L.fsvd_pack_tiled.argtypes = [i32, i32, P, C.c_int, P, P]
         L.fsvd_status_string.restype = C.c_char_p
         L.fsvd_status_string.argtypes = [C.c_int]
         L.fsvd_version.restype = i32
@@ -119,16 +124,29 @@ def lib():
 
 @dataclass
 class Factor:
-    """Device tensors of one factored projection (U [in, r], V [r, out], b [out] or None)."""
+    """Device tensors of one factored projection (U [in, r], V [r, out], b [out] or None).
+
+    U_tiled / V_tiled: optional tile images of U / V made by fsvd_pack_tiled (uint8 buffers); when present they are
+    what the library is handed, with the matching layout member set to FSVD_TILED."""
     U: torch.Tensor
     V: torch.Tensor
     b: Optional[torch.Tensor] = None
+    U_tiled: Optional[torch.Tensor] = None
+    V_tiled: Optional[torch.Tensor] = None
 
     def c(self) -> fsvd_factor:
-        for t in (self.U, self.V, self.b):
+        for t in (self.U, self.V, self.b, self.U_tiled, self.V_tiled):
             assert t is None or (t.is_contiguous() and t.is_cuda)
-        return fsvd_factor(self.U.data_ptr(), self.V.data_ptr(), 0 if self.b is None else self.b.data_ptr(),
-                           self.U.shape[0], self.U.shape[1], self.V.shape[1])
+        u = self.U if self.U_tiled is None else self.U_tiled
+        v = self.V if self.V_tiled is None else self.V_tiled
+        return fsvd_factor(u.data_ptr(), v.data_ptr(), 0 if self.b is None else self.b.data_ptr(),
+                           self.U.shape[0], self.U.shape[1], self.V.shape[1],
+                           int(self.U_tiled is not None), int(self.V_tiled is not None))
+
+    def with_tiled(self, u: bool = False, v: bool = False) -> "Factor":
+        """A copy of this factor whose U and / or V are additionally held as tile images."""
+        return Factor(self.U, self.V, self.b, fsvd_pack_tiled(self.U) if u else self.U_tiled,
+                      fsvd_pack_tiled(self.V) if v else self.V_tiled)
 
     @property
     def rank(self) -> int:
@@ -145,7 +163,7 @@ class HeadFactor(Factor):
         H, r, d_h = self.V.shape
         assert self.U.shape[1] == H * r
         return fsvd_factor(self.U.data_ptr(), self.V.data_ptr(), 0 if self.b is None else self.b.data_ptr(),
-                           self.U.shape[0], r, H * d_h)
+                           self.U.shape[0], r, H * d_h, 0, 0)
 
     @property
     def rank(self) -> int:
@@ -294,6 +312,19 @@ def fsvd_pack_fm(src, out=None):
     return out
 
 
+def fsvd_tiled_bytes(rows: int, cols: int) -> int:
+    return lib().fsvd_tiled_bytes(rows, cols)
+
+
+def fsvd_pack_tiled(src, out=None):
+    """Row-major weight matrix [rows, cols] (fp16 / bf16) -> fp16 tile images (uint8 tensor)."""
+    rows, cols = src.shape
+    if out is None:
+        out = torch.empty(fsvd_tiled_bytes(rows, cols), dtype=torch.uint8, device=src.device)
+    _check(lib().fsvd_pack_tiled(rows, cols, _ptr(src), _TORCH2FSVD[src.dtype], _ptr(out), _stream()), "fsvd_pack_tiled")
+    return out
+
+
 def fsvd_unpack_fm(src_fm, T, K, out_dtype=torch.float16, out=None):
     if out is None:
         out = torch.empty((T, K), dtype=out_dtype, device=src_fm.device)
@@ -343,8 +374,13 @@ def fsvd_layernorm(X, gamma, beta, eps, out_dtype=torch.float32, out=None):
 # workload plumbing: numpy inputs (already rounded to the storage type) -> device tensors
 # ---------------------------------------------------------------------------------------------
 
-def to_device(inp: dict, device="cuda:0"):
-    """Upload the arrays of workloads.make_inputs() in the workload's storage type."""
+# which matrices of which projection the library accepts as tile images: name -> (U, V)
+TILED_OK = {"w1": (False, True), "w2": (True, False)}
+
+
+def to_device(inp: dict, device="cuda:0", tiled: bool = False):
+    """Upload the arrays of workloads.make_inputs() in the workload's storage type.  tiled: additionally prepack
+    every matrix the library accepts in that form (fsvd_pack_tiled) and hand the library the tile images."""
     w = inp["workload"]
     dt = torch.float16 if w.dtype == "fp16" else torch.bfloat16
     up = lambda a: torch.from_numpy(a).to(device=device, dtype=dt).contiguous()
@@ -352,6 +388,8 @@ def to_device(inp: dict, device="cuda:0"):
     for n in ("q", "k", "v", "o", "w1", "w2"):
         cls = HeadFactor if (w.r_head > 0 and n in "qkv") else Factor
         dev[n] = cls(up(inp[n]["U"]), up(inp[n]["V"]), up(inp[n]["b"]))
+        if tiled and cls is Factor and n in TILED_OK:
+            dev[n] = dev[n].with_tiled(*TILED_OK[n])
     for n in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta"):
         dev[n] = up(inp[n])
     dev["key_len"] = None if inp["key_len"] is None else torch.from_numpy(inp["key_len"]).to(device)

@@ -41,8 +41,13 @@ fsvd_status check_rank(int r) {
 }
 
 // pointers are only required when a computation is about to run (need_ptrs)
-fsvd_status check_factor(const fsvd_factor* f, int in_dim, int out_dim, bool need_u, bool need_v) {
+// tiled_ok: bit 0 = U may be given as tile images, bit 1 = V may be
+fsvd_status check_factor(const fsvd_factor* f, int in_dim, int out_dim, bool need_u, bool need_v, int tiled_ok = 0) {
   if (!f) return FSVD_ERR_INVALID_ARG;
+  for (const int l : {f->u_layout, f->v_layout})
+    if (l != FSVD_ROW_MAJOR && l != FSVD_TILED) return FSVD_ERR_INVALID_ARG;
+  if (f->u_layout == FSVD_TILED && !(tiled_ok & 1)) return FSVD_ERR_UNSUPPORTED;
+  if (f->v_layout == FSVD_TILED && !(tiled_ok & 2)) return FSVD_ERR_UNSUPPORTED;
   if (f->in_dim != in_dim || f->out_dim != out_dim) return FSVD_ERR_INVALID_ARG;
   fsvd_status s = check_rank(f->rank);
   if (s != FSVD_OK) return s;
@@ -79,8 +84,9 @@ fsvd_status check_attn_heads(const fsvd_desc* d, const fsvd_factor* q, const fsv
 }
 fsvd_status check_ffn(const fsvd_desc* d, const fsvd_factor* w1, const fsvd_factor* w2, bool ptrs) {
   FSVD_TRY(check_desc(d, true));
-  FSVD_TRY(check_factor(w1, d->D, d->F, ptrs, ptrs));
-  FSVD_TRY(check_factor(w2, d->F, d->D, ptrs, ptrs));
+  FSVD_TRY(check_factor(w1, d->D, d->F, ptrs, ptrs, 2));
+  FSVD_TRY(check_factor(w2, d->F, d->D, ptrs, ptrs, 1));
+  if (w1->v_layout != w2->u_layout) return FSVD_ERR_UNSUPPORTED;   // the fused core reads both streams the same way
   return FSVD_OK;
 }
 fsvd_status check_ws(const void* ws, size_t have, size_t need) {
@@ -185,7 +191,8 @@ fsvd_status run_ffn(const fsvd_desc* d, const void* A_in, int a_layout, int a_dt
 
   FfnCoreArgs fa{};
   fa.P1 = P1; fa.r1 = w1->rank; fa.V1 = w1->V; fa.b1 = w1->bias; fa.U2 = w2->U; fa.r2 = w2->rank;
-  fa.w_dt = d->io_dtype; fa.T = T; fa.F = d->F; fa.act = d->act; fa.Z = Z; fa.Zpart = (float*)(scratch + pl.part);
+  fa.w_dt = d->io_dtype; fa.tiled = w1->v_layout == FSVD_TILED; fa.T = T; fa.F = d->F; fa.act = d->act; fa.Z = Z;
+  fa.Zpart = (float*)(scratch + pl.part);
   FSVD_HIP(launch_ffn_core(fa, s));
 
   LinearArgs h7{};
@@ -398,6 +405,18 @@ fsvd_status fsvd_pack_fm(int32_t T, int32_t K, const void* src, fsvd_dtype src_d
   return FSVD_OK;
 }
 
+size_t fsvd_tiled_bytes(int32_t rows, int32_t cols) {
+  if (rows <= 0 || cols <= 0 || cols % 8 != 0) return 0;
+  const size_t n = tiled_bytes(rows, cols);
+  return n < ((size_t)1 << 31) ? n : 0;
+}
+fsvd_status fsvd_pack_tiled(int32_t rows, int32_t cols, const void* src, fsvd_dtype src_dtype, void* dst, void* stream) {
+  if (rows <= 0 || cols <= 0 || !src || !dst || !dtype_ok16(src_dtype) || mis16(src) || mis16(dst)) return FSVD_ERR_INVALID_ARG;
+  if (!fsvd_tiled_bytes(rows, cols)) return FSVD_ERR_UNSUPPORTED;
+  FSVD_HIP(launch_pack_tiled(src, src_dtype, rows, cols, dst, (hipStream_t)stream));
+  return FSVD_OK;
+}
+
 fsvd_status fsvd_unpack_fm(int32_t T, int32_t K, const void* src_fm, void* dst, fsvd_dtype dst_dtype, void* stream) {
   if (T <= 0 || K <= 0 || !src_fm || !dst || !dtype_ok(dst_dtype) || mis16(src_fm) || mis16(dst)) return FSVD_ERR_INVALID_ARG;
   if (K % 8 != 0 || fm_bytes(T, K) >= (1ULL << 31)) return FSVD_ERR_UNSUPPORTED;
@@ -444,15 +463,16 @@ size_t fsvd_ffn_core_workspace(const fsvd_desc* d, int32_t r1, int32_t r2) {
 fsvd_status fsvd_ffn_core(const fsvd_desc* d, const void* P1, const fsvd_factor* w1, const fsvd_factor* w2, void* Z,
                           void* ws, size_t ws_bytes, void* stream) {
   FSVD_TRY(check_desc(d, true));
-  FSVD_TRY(check_factor(w1, d->D, d->F, false, true));
-  FSVD_TRY(check_factor(w2, d->F, d->D, true, false));
+  FSVD_TRY(check_factor(w1, d->D, d->F, false, true, 2));
+  FSVD_TRY(check_factor(w2, d->F, d->D, true, false, 1));
+  if (w1->v_layout != w2->u_layout) return FSVD_ERR_UNSUPPORTED;
   if (!P1 || !Z || mis16(P1) || mis16(Z)) return FSVD_ERR_INVALID_ARG;
   const size_t need = fsvd_ffn_core_workspace(d, w1->rank, w2->rank);
   if (need) FSVD_TRY(check_ws(ws, ws_bytes, need));
   FfnCoreArgs fa{};
   fa.P1 = P1; fa.r1 = w1->rank; fa.V1 = w1->V; fa.b1 = w1->bias; fa.U2 = w2->U;
-  fa.r2 = w2->rank; fa.w_dt = d->io_dtype; fa.T = d->B * d->M; fa.F = d->F; fa.act = d->act;
-  fa.Z = Z; fa.Zpart = need ? (float*)ws : nullptr;
+  fa.r2 = w2->rank; fa.w_dt = d->io_dtype; fa.tiled = w1->v_layout == FSVD_TILED; fa.T = d->B * d->M; fa.F = d->F;
+  fa.act = d->act; fa.Z = Z; fa.Zpart = need ? (float*)ws : nullptr;
   FSVD_HIP(launch_ffn_core(fa, (hipStream_t)stream));
   return FSVD_OK;
 }

@@ -216,6 +216,54 @@ __device__ __forceinline__ void stage_store16(_Float16* dst, u4 raw) {
   *(u4*)dst = __builtin_bit_cast(u4, raw_to_h8<WT>(raw));
 }
 
+// ---------------------------------------------------------------------------------------------
+// Prepacked weights ("tile images").  A weight matrix [K, N] that is packed once, when the model is loaded, is
+// stored as fp16 tiles of 128 (k) x 128 (n), zero-padded to whole tiles, tile (kt, nt) at
+// (kt * ceil(N / 128) + nt) * 32 KiB.  A tile is stored exactly as it will lie in LDS, so a kernel moves it with
+// loads that write LDS directly (no registers, no conversion).  Inside a tile, row k holds its 256 bytes with the
+// four 64-byte segments permuted: element (k, n) sits at half  k * 128 + (((n / 32) ^ (k % 4)) * 32) + n % 32.
+// The permutation does for unpadded rows what the 64-byte padding does for staged tiles: the four rows touched by
+// 32 lanes of a transposing read fall into disjoint banks.
+// ---------------------------------------------------------------------------------------------
+constexpr int kWtTiled = 3;                                   // "weight type" of kernels reading tile images
+constexpr int kTileImageBytes = 128 * 128 * 2;
+__host__ __device__ __forceinline__ size_t tiled_bytes(size_t K, size_t N) {
+  return ((K + 127) / 128) * ((N + 127) / 128) * (size_t)kTileImageBytes;
+}
+// per-lane part of a transposing read's address (in halves) inside a tile image, for the 32 columns 32 * seg ..;
+// row offsets added to it must be multiples of 4
+__device__ __forceinline__ int tr_lane_off_swz(int lane, int seg) {
+  const int i = lane & 15;
+  return (i >> 2) * 128 + ((seg ^ (i >> 2)) << 5) + 16 * ((lane >> 4) & 1) + 4 * (i & 3);
+}
+// One wavefront-wide 16-byte-per-lane load that writes LDS directly: lane l's 16 bytes at (resource base + soff +
+// voff_l) go to LDS byte address lds_addr + 16 l (lds_addr wave-uniform).  Issued as inline assembly so that the
+// compiler's wait-count bookkeeping does not see it: the compiler would otherwise wait for ALL such loads before any
+// LDS read and before every barrier, which defeats requesting tiles ahead.  The caller orders these loads against
+// their consumers with lds_dma_wait_barrier<N>() (they complete in issue order and are counted by vmcnt).
+__device__ __forceinline__ u4 lds_dma_rsrc(const void* base, unsigned bytes) {
+  const unsigned long long b = (unsigned long long)base;
+  u4 r;
+  r[0] = (unsigned)b; r[1] = (unsigned)(b >> 32) & 0xffffu; r[2] = bytes; r[3] = 0x00020000u;
+  return r;
+}
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"   // m0 is reserved; naming it documents that the statement overwrites it
+__device__ __forceinline__ void lds_dma16(u4 rsrc, unsigned lds_addr, int voff, int soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+// wait until at most N of this wavefront's vector-memory operations are outstanding and all its LDS operations are
+// done, then the workgroup barrier
+template <int N>
+__device__ __forceinline__ void lds_dma_wait_barrier() {
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" :: "n"(N) : "memory");
+}
+__device__ __forceinline__ unsigned lds_addr_of(const void* p) {
+  return (unsigned)(size_t)(__attribute__((address_space(3))) const void*)p;
+}
+
 // Contraction-slot mapping inside one 64-wide chunk: MFMA step kk (0..3), lane group g (0..1),
 // slot s (0..7) stand for chunk offset 32*g + 8*kk + s.  An activation lane therefore reads 64
 // contiguous bytes of its row over the four steps of a chunk.

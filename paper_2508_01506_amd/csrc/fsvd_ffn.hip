@@ -87,11 +87,17 @@ __device__ __forceinline__ void write_z(const f16v (&z)[N][2], const FfnCoreArgs
 // NS: 128-rank sub-tiles accumulated by the compute wavefronts, NS2: further sub-tiles accumulated by the loader
 // wavefronts (their registers are otherwise idle), so that one workgroup covers up to 1024 output ranks with a single
 // pass of phase A.
+// WT: DT_F16 / DT_BF16 = row-major weights of that type, staged through registers into padded LDS rows (two buffers);
+// kWtTiled = weights prepacked as fp16 tile images (see fsvd_common.h), copied by the loaders straight from memory into
+// LDS without passing through registers (three buffers, requests two tiles ahead).
 template <int NS, int NS2, int WT>
 __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nslices, int slice_w, int fsplit) {
-  __shared__ __attribute__((aligned(16))) _Float16 wt_lds[2][kTile * kTileRow];
-  __shared__ __attribute__((aligned(16))) h8 ptile[2][16][64];     // [buffer][(token tile * 2 + hh) * 4 + kk][lane]
-  __shared__ __attribute__((aligned(16))) h8 gtile[4][2][2][64];   // [f tile][t][token tile][lane]
+  constexpr bool PK = (WT == kWtTiled);
+  constexpr int NB = PK ? 3 : 2;                           // LDS buffers per stream
+  constexpr int kRow = PK ? kTile : kTileRow;              // halves per LDS tile row
+  __shared__ __attribute__((aligned(1024))) _Float16 wt_lds[NB][kTile * kRow];
+  __shared__ __attribute__((aligned(1024))) h8 ptile[NB][16][64];    // [buffer][(token tile * 2 + hh) * 4 + kk][lane]
+  __shared__ __attribute__((aligned(16))) h8 gtile[4][2][2][64];     // [f tile][t][token tile][lane]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, l32 = lane & 31, g = lane >> 5;
@@ -117,11 +123,120 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
   const int per_chunk = nA + NS + NS2;                          // tiles per chunk: nA of V_1, then NS + NS2 of U_2
   const int pch = (r1 + 63) / 64, zch = (r2 + 63) / 64;
 
+  // LDS buffers rotate: the tile in use sits in buffer `it % NB`
+  auto nxt = [](int b) { return b + 1 == NB ? 0 : b + 1; };
+  // per-lane part of the transposing reads of a weight tile (columns 32 * wave ..)
+  const int trl = PK ? tr_lane_off_swz(lane, wave) : tr_lane_off(lane, kRow) + 32 * wave;
+  const int trA = trl + 32 * g * kRow;   // phase A: k rows 32 g + 8 kk + 0..7
+  const int trB = trl + 4 * g * kRow;    // phase B: k rows 16 fs + 4 g + {0..3, 8..11}
+
   if (loader) {
+    // sub-tiles NS .. NS+NS2-1 of phase B run on the loader wavefronts; `between(f)` is called after the MFMAs of step f
+    f16v z2[NS2 > 0 ? NS2 : 1][2];
+#pragma unroll
+    for (int s = 0; s < (NS2 > 0 ? NS2 : 1); ++s) { z2[s][0] = zero16(); z2[s][1] = zero16(); }
+    auto stage_b2 = [&](const _Float16* wb, f16v (&zs)[2], bool active, auto between) {
+      h8 wf = tr_frag(wb + trB, wb + trB + 8 * kRow);
+      h8 g0 = gtile[0][0][0][lane], g1 = gtile[0][0][1][lane];
+#pragma unroll
+      for (int f = 0; f < 8; ++f) {
+        h8 wf_next = wf, n0 = g0, n1 = g1;
+        if (f < 7) {
+          const _Float16* q = wb + trB + 16 * (f + 1) * kRow;
+          wf_next = tr_frag(q, q + 8 * kRow);
+          n0 = gtile[(f + 1) >> 1][(f + 1) & 1][0][lane];
+          n1 = gtile[(f + 1) >> 1][(f + 1) & 1][1][lane];
+        }
+        if (active) {
+          zs[0] = mfma32(wf, g0, zs[0]);
+          zs[1] = mfma32(wf, g1, zs[1]);
+        }
+        between(f);
+        wf = wf_next; g0 = n0; g1 = n1;
+      }
+    };
+
+    if constexpr (PK) {
+      // =====================================================================================================
+      // Loader wavefronts, prepacked weights.  A tile image is 32 KiB that go to LDS byte for byte: wavefront w
+      // moves the 1 KiB pieces 4 p + w (p = 0..7) with loads that write LDS directly, so a tile costs 8
+      // instructions per wavefront and no registers.  Tile i+2 is requested while tile i is in use (three
+      // buffers); loads complete in order, so waiting until only the requests of this stage are outstanding
+      // means tile i+1 has landed.  The P1 tiles of phase A (16 KiB, fragment-major = LDS order) travel the same way.
+      // Nothing here depends on out-of-range reads: tile images are zero-padded to whole tiles, requests past the
+      // end of the stream re-read the last tile, and a rank piece past r1 re-reads the last valid piece (its
+      // weight rows are zero).
+      // =====================================================================================================
+      const int ntF = (F + kTile - 1) / kTile, ntR2 = (r2 + kTile - 1) / kTile;
+      const char* const pV1 = uniform_ptr(a.V1);
+      const char* const pU2 = uniform_ptr(a.U2);
+      const int voff = lane * 16;
+      const unsigned lds_w0 = lds_addr_of(&wt_lds[0][0]), lds_p0 = lds_addr_of(&ptile[0][0][0]);
+      auto request_tile = [&](int buf, int c, int j) {
+        c = c < nchunks ? c : nchunks - 1;
+        const bool isA = j < nA;
+        int nt2 = (s0 >> 7) + (j - nA);
+        nt2 = nt2 < ntR2 ? nt2 : ntR2 - 1;
+        const long long tile = isA ? ((long long)j * ntF + c) : ((long long)c * ntR2 + nt2);
+        const unsigned long long sel = isA ? 1 : 0;
+        const unsigned long long base = (unsigned long long)pU2 + ((unsigned long long)pV1 - (unsigned long long)pU2) * sel;
+        const u4 r = lds_dma_rsrc((const void*)(base + (unsigned long long)tile * kTileImageBytes), kTileImageBytes);
+        const unsigned dst = lds_w0 + buf * kTileImageBytes + wave * 1024;
+#pragma unroll
+        for (int p = 0; p < 8; ++p) lds_dma16(r, dst + p * 4096, voff, (4 * p + wave) * 1024);
+      };
+      const int ptiles = (T + 31) / 32;
+      const u4 rP = lds_dma_rsrc(uniform_ptr(a.P1), (unsigned)fm_bytes(T, r1));
+      auto request_p = [&](int buf, int ra) {
+        const unsigned dst = lds_p0 + buf * 16384 + wave * 1024;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          int piece = 2 * ra + (j & 1), tt = (t0 >> 5) + (j >> 1);
+          piece = piece < pch ? piece : pch - 1;
+          tt = tt < ptiles ? tt : ptiles - 1;
+          lds_dma16(rP, dst + j * 4096, voff, (tt * pch + piece) * kFmChunkBytes + wave * 1024);
+        }
+      };
+      auto request2 = [&](int buf, int c, int j) {          // tile two ahead of (c, j)
+        int c2 = c, j2 = j + 2;
+        if (j2 >= per_chunk) { j2 -= per_chunk; ++c2; }
+        request_tile(buf, c2, j2);
+      };
+      // prologue: tiles 0 and 1 and the P1 tiles of the first two stages
+      request_tile(0, c_begin, 0);
+      request_p(0, 0);
+      request_tile(1, c_begin, 1);                          // per_chunk >= 2
+      request_p(1, 1 % nA);
+      lds_dma_wait_barrier<12>();                           // tile 0 and its P1 tile are in LDS
+      int wb = 0, pb = 0;                                   // buffers of the tile / P1 tile in use
+      for (int c = c_begin; c < nchunks; ++c) {
+        for (int ra = 0; ra < nA; ++ra) {
+          request2(nxt(nxt(wb)), c, ra);
+          request_p(nxt(nxt(pb)), (ra + 2) % nA);
+          lds_dma_wait_barrier<12>();                       // everything requested before this stage has landed
+          wb = nxt(wb); pb = nxt(pb);
+        }
+        for (int s = 0; s < NS; ++s) {
+          request2(nxt(nxt(wb)), c, nA + s);
+          lds_dma_wait_barrier<8>();
+          wb = nxt(wb);
+        }
+        if constexpr (NS2 > 0) {
+#pragma unroll
+          for (int s = 0; s < NS2; ++s) {
+            request2(nxt(nxt(wb)), c, nA + NS + s);
+            stage_b2(wt_lds[wb], z2[s], s0 + (NS + s) * kTile < s_end, [](int) {});
+            lds_dma_wait_barrier<8>();
+            wb = nxt(wb);
+          }
+        }
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // nothing may still be writing LDS when the workgroup ends
+    } else {
     // =====================================================================================================
-    // Loader wavefronts: tile i+1 of the weight stream (requested one stage ago) is converted and written to
-    // the LDS buffer the compute wavefronts will read next, tile i+2 is requested from global memory; the
-    // P1 tiles of phase A travel the same way.
+    // Loader wavefronts, row-major weights: tile i+1 of the weight stream (requested one stage ago) is converted
+    // and written to the LDS buffer the compute wavefronts will read next, tile i+2 is requested from global
+    // memory; the P1 tiles of phase A travel the same way.
     // Tile (c, j): j < nA -> V_1 rows 128 j.., columns f of chunk c; j >= nA -> U_2 rows f of chunk c,
     // columns s0 + 128 (j - nA)..   Thread -> tile row s_r (+ 16 per pass), 8 columns from s_c.
     // =====================================================================================================
@@ -154,7 +269,7 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
       const rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void*)src_base, 0, src_left, 0x00020000);
       w_raw[p] = buf_load16(r, (int)(src_v0 + (unsigned)(32 * p) * src_ld));
     };
-    auto commit_pass = [&](int pb, int p) { stage_store16<WT>(&wt_lds[pb][(s_r + 16 * p) * kTileRow + s_c], w_raw[p]); };
+    auto commit_pass = [&](int pb, int p) { stage_store16<WT>(&wt_lds[pb][(s_r + 16 * p) * kRow + s_c], w_raw[p]); };
     // P1 tile of phase-A stage ra: four 4 KiB fragment-major blocks (token tile tt, 64-wide piece 2 ra + hh), copied as they lie
     const rsrc_t rP = __builtin_amdgcn_make_buffer_rsrc((void*)uniform_ptr(a.P1), 0, (int)p_total, 0x00020000);
     auto issue_p = [&](int ra) {
@@ -188,10 +303,6 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
       if (j2 >= per_chunk) { j2 -= per_chunk; ++c2; }
       tile_src(c2, j2);
     };
-    const int trB = tr_lane_off(lane, kTileRow) + 4 * g * kTileRow + 32 * wave;    // as in the compute wavefronts
-    f16v z2[NS2 > 0 ? NS2 : 1][2];
-#pragma unroll
-    for (int s = 0; s < (NS2 > 0 ? NS2 : 1); ++s) { z2[s][0] = zero16(); z2[s][1] = zero16(); }
     for (int c = c_begin; c < nchunks; ++c) {
       for (int ra = 0; ra < nA; ++ra) {
         next2_src(c, ra);
@@ -210,35 +321,19 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
         ++it;
       }
       if constexpr (NS2 > 0) {
-        // sub-tiles NS .. NS+NS2-1: the MFMAs of step fs run between the staging passes of the stream
+        // sub-tiles NS .. NS+NS2-1: the MFMAs of step f run between the staging passes of the stream
 #pragma unroll
         for (int s = 0; s < NS2; ++s) {
           next2_src(c, nA + NS + s);
-          const _Float16* wb = wt_lds[it & 1];
-          const bool active = s0 + (NS + s) * kTile < s_end;
-          h8 wf = tr_frag(wb + trB, wb + trB + 8 * kTileRow);
-          h8 g0 = gtile[0][0][0][lane], g1 = gtile[0][0][1][lane];
-#pragma unroll
-          for (int f = 0; f < 8; ++f) {
-            h8 wf_next = wf, n0 = g0, n1 = g1;
-            if (f < 7) {
-              const _Float16* q = wb + trB + 16 * (f + 1) * kTileRow;
-              wf_next = tr_frag(q, q + 8 * kTileRow);
-              n0 = gtile[(f + 1) >> 1][(f + 1) & 1][0][lane];
-              n1 = gtile[(f + 1) >> 1][(f + 1) & 1][1][lane];
-            }
-            if (active) {
-              z2[s][0] = mfma32(wf, g0, z2[s][0]);
-              z2[s][1] = mfma32(wf, g1, z2[s][1]);
-            }
+          stage_b2(wt_lds[it & 1], z2[s], s0 + (NS + s) * kTile < s_end, [&](int f) {
             commit_pass((it + 1) & 1, f);
             issue_pass(f);
-            wf = wf_next; g0 = n0; g1 = n1;
-          }
+          });
           __syncthreads();
           ++it;
         }
       }
+    }
     }
     if constexpr (NS2 > 0) write_z(z2, a, fsplit, fs, t0, s0 + NS * kTile, s0 + slice_w, wave, l32, g);
     return;
@@ -247,9 +342,6 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
   // =======================================================================================================
   // Compute wavefronts
   // =======================================================================================================
-  const int trA = tr_lane_off(lane, kTileRow) + 32 * g * kTileRow + 32 * wave;   // phase A: k rows 32 g + 8 kk + 0..7
-  const int trB = tr_lane_off(lane, kTileRow) + 4 * g * kTileRow + 32 * wave;    // phase B: k rows 16 fs + 4 g + {0..3, 8..11}
-
   f16v z[NS][2], y[2];
 #pragma unroll
   for (int s = 0; s < NS; ++s) { z[s][0] = zero16(); z[s][1] = zero16(); }
@@ -258,15 +350,15 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
 
   // ---- one stage of phase A: y += V_1 tile^T (features 32*wave..) x P1^T, operands fetched from LDS one step ahead
   auto stage_a = [&](const _Float16* wb, const h8 (*pb)[64], int c, bool lastA) {
-    h8 wf = tr_frag(wb + trA, wb + trA + 4 * kTileRow);
+    h8 wf = tr_frag(wb + trA, wb + trA + 4 * kRow);
     h8 pf0 = pb[0][lane], pf1 = pb[8][lane];
 #pragma unroll
     for (int st = 0; st < 8; ++st) {
       h8 wf_next = wf, pn0 = pf0, pn1 = pf1;
       if (st < 7) {
         const int hh = (st + 1) >> 2, kk = (st + 1) & 3;
-        const _Float16* q = wb + trA + (64 * hh + 8 * kk) * kTileRow;
-        wf_next = tr_frag(q, q + 4 * kTileRow);
+        const _Float16* q = wb + trA + (64 * hh + 8 * kk) * kRow;
+        wf_next = tr_frag(q, q + 4 * kRow);
         pn0 = pb[hh * 4 + kk][lane];
         pn1 = pb[8 + hh * 4 + kk][lane];
       }
@@ -279,7 +371,11 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
       const rsrc_t rB = rsrc_at(a.b1, a.b1 ? (long long)F * 2 : 0, (long long)c * kFfnBF * 2);
       f4v bias[4];
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj) bias[jj] = raw_to_f4<WT>(buf_load8(rB, (32 * wave + 8 * jj + 4 * g) * 2));
+      for (int jj = 0; jj < 4; ++jj) {
+        const u2 raw = buf_load8(rB, (32 * wave + 8 * jj + 4 * g) * 2);
+        if constexpr (PK) bias[jj] = a.w_dt == DT_BF16 ? raw_to_f4<DT_BF16>(raw) : raw_to_f4<DT_F16>(raw);
+        else bias[jj] = raw_to_f4<WT>(raw);
+      }
       auto publish = [&](auto phi) {
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt)
@@ -299,13 +395,13 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
   };
   // ---- one sub-stage of phase B: z[s] += U_2 tile^T (ranks 128 s + 32*wave..) x Y^T
   auto stage_b = [&](const _Float16* wb, f16v (&zs)[2], bool active) {
-    h8 wf = tr_frag(wb + trB, wb + trB + 8 * kTileRow);
+    h8 wf = tr_frag(wb + trB, wb + trB + 8 * kRow);
 #pragma unroll
     for (int fs = 0; fs < 8; ++fs) {
       h8 wf_next = wf;
       if (fs < 7) {
-        const _Float16* q = wb + trB + 16 * (fs + 1) * kTileRow;
-        wf_next = tr_frag(q, q + 8 * kTileRow);
+        const _Float16* q = wb + trB + 16 * (fs + 1) * kRow;
+        wf_next = tr_frag(q, q + 8 * kRow);
       }
       if (active) {
 #pragma unroll
@@ -316,12 +412,12 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
   };
 
   __syncthreads();   // prologue of the loader wavefronts
-  int it = 0, ac = 0;
+  int wb = 0, pb = 0;   // buffers of the weight tile / P1 tile in use
   for (int c = c_begin; c < nchunks; ++c) {
     for (int ra = 0; ra < nA; ++ra) {
-      stage_a(wt_lds[it & 1], ptile[ac & 1], c, ra + 1 == nA);
+      stage_a(wt_lds[wb], ptile[pb], c, ra + 1 == nA);
       __syncthreads();
-      ++it; ++ac;
+      wb = nxt(wb); pb = nxt(pb);
     }
 #pragma unroll
     for (int fs = 0; fs < 8; ++fs)
@@ -329,14 +425,14 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
       for (int tt = 0; tt < 2; ++tt) gq[fs][tt] = gtile[fs >> 1][fs & 1][tt][lane];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-      stage_b(wt_lds[it & 1], z[s], s0 + s * kTile < s_end);
+      stage_b(wt_lds[wb], z[s], s0 + s * kTile < s_end);
       __syncthreads();
-      ++it;
+      wb = nxt(wb);
     }
 #pragma unroll
     for (int s = 0; s < NS2; ++s) {   // the loader wavefronts' sub-tiles
       __syncthreads();
-      ++it;
+      wb = nxt(wb);
     }
   }
 
@@ -371,7 +467,8 @@ __global__ void __launch_bounds__(256) ffn_reduce_kernel(const float* __restrict
 template <int NS, int NS2>
 hipError_t launch_ns(const FfnCoreArgs& a, const FfnCorePlan& pl, hipStream_t s) {
   const dim3 grid(((a.T + kFfnBT - 1) / kFfnBT) * pl.nslices * pl.fsplit), block(512);
-  if (a.w_dt == DT_F16) hipLaunchKernelGGL((ffn_core_kernel<NS, NS2, DT_F16>), grid, block, 0, s, a, pl.nslices, pl.slice_w, pl.fsplit);
+  if (a.tiled) hipLaunchKernelGGL((ffn_core_kernel<NS, NS2, kWtTiled>), grid, block, 0, s, a, pl.nslices, pl.slice_w, pl.fsplit);
+  else if (a.w_dt == DT_F16) hipLaunchKernelGGL((ffn_core_kernel<NS, NS2, DT_F16>), grid, block, 0, s, a, pl.nslices, pl.slice_w, pl.fsplit);
   else hipLaunchKernelGGL((ffn_core_kernel<NS, NS2, DT_BF16>), grid, block, 0, s, a, pl.nslices, pl.slice_w, pl.fsplit);
   return hipGetLastError();
 }
@@ -390,7 +487,7 @@ FfnCorePlan ffn_core_plan(int T, int r1, int r2, int F) {
   for (int W = 1; W <= 8; ++W) {
     const int nsl = (nsub + W - 1) / W;
     int slice_w = (r2 + nsl - 1) / nsl;
-    slice_w = (slice_w + 63) / 64 * 64;
+    slice_w = (slice_w + kTile - 1) / kTile * kTile;   // whole sub-tiles (tile images are addressed by tile)
     const int w_eff = (slice_w + kTile - 1) / kTile;
     if (w_eff != W) continue;                               // the same shape is reached with a smaller W
     for (int fsplit = 1; fsplit <= nchunks; fsplit *= 2) {

@@ -62,6 +62,7 @@ struct FfnCoreArgs {
   const void* U2;    // [F, r2] in w_dt
   int r2;
   int w_dt;
+  int tiled;         // non-zero: V1 and U2 are prepacked fp16 tile images (b1 stays in w_dt)
   int T, F;
   int act;
   void* Z;           // [T, r2] fragment-major fp16
@@ -82,6 +83,9 @@ struct LayerNormArgs {
   void* Yfm;                          // FM fp16 output or nullptr
 };
 hipError_t launch_layernorm(const LayerNormArgs& a, hipStream_t s);
+
+// ---- weight prepacking: row-major [K, N] (F16 / BF16) -> fp16 tile images (tiled_bytes(K, N) bytes)
+hipError_t launch_pack_tiled(const void* src, int src_dt, int K, int N, void* dst, hipStream_t s);
 
 // ---- layout conversion: row-major [T, K] (F16 / BF16 / F32) <-> FM fp16
 hipError_t launch_pack_fm(const void* src, int src_dt, int T, int K, void* dst_fm, hipStream_t s);

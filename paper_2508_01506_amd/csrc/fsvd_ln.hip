@@ -112,6 +112,20 @@ __global__ void __launch_bounds__(256) pack_fm_kernel(const void* src, int src_d
   if (t < T && k < K) load8(src, (size_t)t * K + k, src_dt, x);
   store8(dst, u * 8, DT_F16, x);
 }
+// one thread per 16 bytes of the tile images: destination unit d of a tile is row d / 16, stored segment (d / 4) % 4
+__global__ void __launch_bounds__(256) pack_tiled_kernel(const void* src, int src_dt, int K, int N, _Float16* dst, size_t units) {
+  const size_t u = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (u >= units) return;
+  const int ntn = (N + 127) / 128;
+  const size_t tile = u >> 11;
+  const int d = (int)(u & 2047);
+  const int row = d >> 4, seg = ((d >> 2) & 3) ^ (row & 3);
+  const int k = (int)(tile / ntn) * 128 + row, n = (int)(tile % ntn) * 128 + 32 * seg + 8 * (d & 3);
+  u4 raw = {0u, 0u, 0u, 0u};
+  if (k < K && n < N) raw = *(const u4*)((const uint16_t*)src + (size_t)k * N + n);
+  // the conversion the kernels apply when they stage row-major weights, so both layouts give the same bits
+  *(h8*)(dst + u * 8) = src_dt == DT_BF16 ? raw_to_h8<DT_BF16>(raw) : raw_to_h8<DT_F16>(raw);
+}
 __global__ void __launch_bounds__(256) unpack_fm_kernel(const _Float16* src, int T, int K, void* dst, int dst_dt, size_t groups) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;   // group of 8 features
   if (i >= groups) return;
@@ -140,6 +154,12 @@ hipError_t launch_pack_fm(const void* src, int src_dt, int T, int K, void* dst_f
   const size_t units = fm_bytes(T, K) / 16;
   hipLaunchKernelGGL(pack_fm_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s, src, src_dt, T, K,
                      (_Float16*)dst_fm, units);
+  return hipGetLastError();
+}
+hipError_t launch_pack_tiled(const void* src, int src_dt, int K, int N, void* dst, hipStream_t s) {
+  const size_t units = tiled_bytes(K, N) / 16;
+  hipLaunchKernelGGL(pack_tiled_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s, src, src_dt, K, N,
+                     (_Float16*)dst, units);
   return hipGetLastError();
 }
 hipError_t launch_unpack_fm(const void* src_fm, int T, int K, void* dst, int dst_dt, hipStream_t s) {

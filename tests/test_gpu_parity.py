@@ -44,13 +44,20 @@ DEV = "cuda:0"
 _cache = {}
 
 
-def workload(name, fb):
-    if name not in _cache:
-        _cache.clear()
-        w = W.get_workload(name)
-        inp = W.make_inputs(w)
-        _cache[name] = (w, inp, fb.to_device(inp, DEV))
-    return _cache[name]
+def workload(name, fb, weights="row"):
+    """weights: "row" = factors as row-major tensors, "tiled" = the prepacked tile images wherever the library takes them."""
+    key = (name, weights)
+    if key not in _cache:
+        if not any(k[0] == name for k in _cache):
+            _cache.clear()
+        inp = next((v[1] for k, v in _cache.items() if k[0] == name), None)
+        if inp is None:
+            inp = W.make_inputs(W.get_workload(name))
+        _cache[key] = (inp["workload"], inp, fb.to_device(inp, DEV, tiled=(weights == "tiled")))
+    return _cache[key]
+
+
+WEIGHTS = ["row", "tiled"]
 
 
 # ------------------------------------------------------------------ building blocks
@@ -140,6 +147,34 @@ def test_attention_core_from_rank_space_inputs(fb, name):
     assert rel_err(got, ref) < (2e-2 if inp["causal"] else 8e-3)
 
 
+def expected_tile_images(Wm):
+    """The documented byte image of a weight matrix (fp16 values), written from the format's definition."""
+    K, N = Wm.shape
+    kt, nt = (K + 127) // 128, (N + 127) // 128
+    pad = np.zeros((kt * 128, nt * 128), np.float16)
+    pad[:K, :N] = Wm
+    out = np.empty((kt, nt, 128, 128), np.float16)
+    for k in range(128):
+        for seg in range(4):
+            out[:, :, k, 32 * (seg ^ (k & 3)):32 * (seg ^ (k & 3)) + 32] = \
+                pad.reshape(kt, 128, nt, 128)[:, k, :, 32 * seg:32 * seg + 32]
+    return out.reshape(-1)
+
+
+@pytest.mark.parametrize("K,N,dt", [(256, 1024, "fp16"), (200, 336, "bf16"), (16, 16, "fp16"), (1040, 136, "bf16"), (128, 128, "fp16")])
+def test_pack_tiled_writes_the_documented_image(fb, K, N, dt):
+    """Byte work: the prepacked tile images are bit-exact (values inside fp16's normal range, where widening bf16
+    is exact; ragged edges are zero-padded to whole tiles)."""
+    rng = np.random.default_rng(K + N)
+    x = rng.standard_normal((K, N)).astype(np.float32)
+    Wm = W.round_to_storage(np.where(np.abs(x) < 1e-3, np.float32(1e-3), x), dt)
+    tdt = torch.float16 if dt == "fp16" else torch.bfloat16
+    src = torch.from_numpy(Wm).to(device=DEV, dtype=tdt).contiguous()
+    assert fb.fsvd_tiled_bytes(K, N) == ((K + 127) // 128) * ((N + 127) // 128) * 32768
+    img = fb.fsvd_pack_tiled(src).view(torch.float16).cpu().numpy()
+    assert np.array_equal(img.view(np.uint16), expected_tile_images(Wm.astype(np.float16)).view(np.uint16))
+
+
 @pytest.mark.parametrize("name,act", [("tiny_h2_d64", "gelu_erf"), ("tiny_pad", "gelu_tanh"), ("tiny_causal_d128", "relu"),
                                       ("small_causal_d64", "gelu_erf")])
 def test_ffn_core_from_rank_space_input(fb, name, act):
@@ -154,8 +189,9 @@ def test_ffn_core_from_rank_space_input(fb, name, act):
     assert rel_err(got, ref) < 2.5e-3      # fp16 hidden activation + fp16 Z
 
 
+@pytest.mark.parametrize("weights", WEIGHTS)
 @pytest.mark.parametrize("r2,dt", [(1024, "fp16"), (1024, "bf16"), (896, "fp16"), (640, "bf16")])
-def test_ffn_core_wide_rank_slices_and_split_over_f(fb, r2, dt):
+def test_ffn_core_wide_rank_slices_and_split_over_f(fb, r2, dt, weights):
     """Shapes for which the core lets one workgroup cover more than 512 output ranks (the extra accumulators live in
     the loader wavefronts) and splits the sum over D_ff across workgroups (fp32 partial sums + a second launch):
     sampled rows of Z against the plain definition, ragged token count, tanh-free exact GELU."""
@@ -171,6 +207,8 @@ def test_ffn_core_wide_rank_slices_and_split_over_f(fb, r2, dt):
     # U of w1 and V of w2 are not read by the core: any tensors of the right shape do
     w1 = fb.Factor(up(np.zeros((D, r1))), up(V1), up(b1))
     w2 = fb.Factor(up(U2), up(np.zeros((r2, D))), None)
+    if weights == "tiled":
+        w1, w2 = w1.with_tiled(v=True), w2.with_tiled(u=True)
     d = fb.make_desc(1, T, D, 2, F, tdt)
     assert fb.fsvd_ffn_core_workspace(d, r1, r2) > 0          # this shape does split F
     Zfm = fb.fsvd_ffn_core(d, fb.fsvd_pack_fm(torch.from_numpy(P1).to(DEV)), w1, w2)
@@ -255,10 +293,11 @@ def test_per_head_factors_agree_with_block_diagonal_whole_matrix_factors(fb):
 SMALL = ["tiny_h2_d64", "tiny_pad", "tiny_causal_d128", "small_multi_qblock", "small_causal_d64"]
 
 
+@pytest.mark.parametrize("weights", WEIGHTS)
 @pytest.mark.parametrize("part", ["attention", "ffn", "layer"])
 @pytest.mark.parametrize("name", SMALL)
-def test_entry_points_small(fb, name, part):
-    w, inp, dev = workload(name, fb)
+def test_entry_points_small(fb, name, part, weights):
+    w, inp, dev = workload(name, fb, weights)
     got = gpu_call(dev, part).cpu().numpy()
     assert np.isfinite(got).all()
     assert rel_err(got, oracle_call(inp, part)) < tol_for(w, part)
@@ -279,10 +318,12 @@ FULL = ["cfg1_bert_base_b2_m128", "cfg2_bert_base_b16_m512_pad", "cfg2u_bert_bas
         "cfg4_long_b4_m8192", "cfg5_llm_b1_m4096_causal"]
 
 
+@pytest.mark.parametrize("weights", WEIGHTS)
 @pytest.mark.parametrize("name", FULL)
-def test_full_size_sampled_rows(fb, name):
-    """At the benchmark sizes, in the launch configuration bench.py times, on rows the oracle computes one by one."""
-    w, inp, dev = workload(name, fb)
+def test_full_size_sampled_rows(fb, name, weights):
+    """At the benchmark sizes, in the launch configuration bench.py times (prepacked weights; and with row-major
+    weights), on rows the oracle computes one by one."""
+    w, inp, dev = workload(name, fb, weights)
     outs = {part: gpu_call(dev, part).cpu().numpy() for part in ("layer", "attention", "ffn")}
     for part, got in outs.items():
         assert np.isfinite(got).all()

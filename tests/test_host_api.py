@@ -144,6 +144,38 @@ def test_compute_entry_points_validate_before_any_launch():
     assert fb.fsvd_ffn_core_workspace(big, 256, 256) == 0
 
 
+def test_tiled_weight_layout_contract():
+    """Tile images: documented size, accepted only where the header says, both FFN streams alike, bad values rejected."""
+    L = fb.lib()
+    d = desc()
+    assert fb.fsvd_tiled_bytes(128, 128) == 32768
+    assert fb.fsvd_tiled_bytes(129, 136) == 4 * 32768
+    assert fb.fsvd_tiled_bytes(2048, 16384) == 16 * 128 * 32768
+    assert fb.fsvd_tiled_bytes(16, 12) == 0 and fb.fsvd_tiled_bytes(0, 16) == 0
+    assert fb.fsvd_tiled_bytes(1 << 15, 1 << 15) == 0                     # would reach 2 GiB
+    assert L.fsvd_pack_tiled(128, 128, None, 0, 256, None) == INVALID
+    assert L.fsvd_pack_tiled(128, 128, 256, 2, 256, None) == INVALID     # fp32 weights are not a storage type
+    assert L.fsvd_pack_tiled(128, 128, 264, 0, 256, None) == INVALID     # misaligned
+    assert L.fsvd_pack_tiled(128, 12, 256, 0, 256, None) == UNSUPPORTED
+
+    def lay(f, u=0, v=0):
+        g = fb.fsvd_factor(f.U, f.V, f.bias, f.in_dim, f.rank, f.out_dim, u, v)
+        return g
+    w1, w2 = fac(768, 64, 3072), fac(3072, 64, 768)
+    ffn = lambda a, b: L.fsvd_ffn_check(C.byref(d), C.byref(a), C.byref(b))
+    assert ffn(lay(w1, v=1), lay(w2, u=1)) == OK
+    assert ffn(lay(w1, v=1), w2) == UNSUPPORTED                           # both streams of the fused core or neither
+    assert ffn(w1, lay(w2, u=1)) == UNSUPPORTED
+    assert ffn(lay(w1, u=1, v=1), lay(w2, u=1)) == UNSUPPORTED            # U of w1 feeds a plain projection
+    assert ffn(lay(w1, v=1), lay(w2, u=1, v=1)) == UNSUPPORTED
+    assert ffn(lay(w1, v=2), lay(w2, u=2)) == INVALID                     # not a layout
+    assert ffn(lay(w1, v=-1), w2) == INVALID
+    q = fac(768, 64, 768)
+    att = lambda a: L.fsvd_attention_check(C.byref(d), C.byref(a), C.byref(q), C.byref(q), C.byref(q))
+    for u, v in [(1, 0), (0, 1)]:
+        assert att(lay(q, u, v)) == (OK if fb.TILED_OK.get("q", (False, False))[u == 0] else UNSUPPORTED)
+
+
 def test_per_head_attention_entry_point_contract():
     """Workspace of the per-head entry point = packed X / context + P_q | P_k | P_v with H * rank columns each; the same
     validation as the whole-matrix entry point."""
