@@ -4,7 +4,11 @@ A step is one pass of the whole hot path — rank projections, streaming attenti
 projection, residual + LayerNorm, fused FFN, residual (+ LayerNorm) — i.e. one fsvd_layer call on one
 batch of synthetic inputs that are already resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+Weights are constants of the model: by default the matrices the library accepts as prepacked tile images
+(fsvd_pack_tiled; a one-off conversion when a model is loaded, outside the timed region like the factorisation
+itself) are handed over in that form; `--weights row` times the same layer with every factor left row-major.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--weights tiled|row] [--no-cpu-baseline]
 """
 from __future__ import annotations
 
@@ -54,6 +58,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--weights", choices=["tiled", "row"], default="tiled")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-traffic", action="store_true",
                     help="also launch a plain copy of known size (fsvd_pack_fm of a 512 MiB fp16 matrix: reads 512 MiB, "
@@ -72,7 +77,7 @@ def main():
     fb.lib()   # fails loudly if the HIP library is missing
     w = W.get_workload(args.workload)
     inp = W.make_inputs(w)
-    dev = fb.to_device(inp, "cuda:0")
+    dev = fb.to_device(inp, "cuda:0", tiled=(args.weights == "tiled"))
     d = dev["desc"]
     ra, rf = w.r_attn, w.r_ffn
     per_head = w.r_head > 0       # per-head factors of q, k, v: the layer goes through fsvd_layer_heads
@@ -167,6 +172,9 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "M": w.M, "D": w.D, "H": w.H, "F": w.F, "r_attn": ra, "r_ffn": rf,
                    "storage": w.dtype, "mask": w.mask, "norm": w.norm,
+                   "weights": ("prepacked tile images where accepted (" + ", ".join(
+                       f"{n}.{'U' if u else ''}{'V' if v else ''}" for n, (u, v) in fb.TILED_OK.items()) + ")")
+                   if args.weights == "tiled" else "row-major",
                    **({"r_head": rh, "qkv_factors": "per head"} if per_head else {})},
         "useful_tflops": round(fl["total"] / (ms * 1e-3) / 1e12, 2),
         "mfma_peak_frac": round(fl["total"] / (ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS, 4),

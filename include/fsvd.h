@@ -195,6 +195,11 @@ fsvd_status fsvd_linear(int32_t T, int32_t K, int32_t N, const void *A, fsvd_dty
                         const void *bias, fsvd_dtype w_dtype, const void *residual, fsvd_dtype r_dtype,
                         void *C, fsvd_dtype c_dtype, void *hip_stream);
 
+/* fsvd_linear with W given as tile images of [K, N] (fsvd_pack_tiled); bias, if any, in bias_dtype (F16 or BF16). */
+fsvd_status fsvd_linear_tiled(int32_t T, int32_t K, int32_t N, const void *A, fsvd_dtype a_dtype, const void *W_tiled,
+                              const void *bias, fsvd_dtype bias_dtype, const void *residual, fsvd_dtype r_dtype,
+                              void *C, fsvd_dtype c_dtype, void *hip_stream);
+
 /*
  * Fragment-major ("FM") layout.  Inside the library every activation that feeds a matrix-core
  * contraction is fp16 in this layout, and the two kernels below take and return it.  For A [T, K]:
@@ -215,12 +220,15 @@ fsvd_status fsvd_unpack_fm(int32_t T, int32_t K, const void *src_fm, void *dst, 
  * W [rows, cols] that is constant across calls can be converted once into the exact byte image of those tiles:
  * fp16 (bf16 sources are widened, the same conversion the kernels apply on the fly), zero-padded to whole tiles,
  * tile (i, j) = rows 128 i .., cols 128 j .. stored at (i * ceil(cols / 128) + j) * 32768 bytes; inside a tile,
- * element (k, n) is the half at  k * 128 + (((n / 32) ^ (k % 4)) * 32) + n % 32.  The kernels then move a tile with
- * loads that write on-chip memory directly, which removes the conversion and staging work from the loop.
+ * element (k, n) is the half at  k * 128 + (((n / 32) ^ (k % 4)) * 32) + n % 32.
  * fsvd_tiled_bytes gives the buffer size (0 if rows or cols is not positive, cols % 8 != 0, or the image would
- * reach 2 GiB); fsvd_pack_tiled converts a contiguous row-major [rows, cols] matrix (F16 or BF16).  Results are
- * identical to the row-major path.  Matrices accepted as FSVD_TILED: V of w1 and U of w2 (both or neither) in
- * fsvd_ffn, fsvd_layer, fsvd_layer_heads and fsvd_ffn_core; FSVD_ERR_UNSUPPORTED anywhere else.
+ * reach 2 GiB); fsvd_pack_tiled converts a contiguous row-major [rows, cols] matrix (F16 or BF16).  With tile images
+ * the kernels do the same arithmetic as with row-major weights (outputs agree up to the last bit).  Matrices accepted as
+ * FSVD_TILED: U and V of every whole-matrix factor (q, k, v, o, w1, w2) and U of per-head factors; V of a per-head
+ * factor must be row-major.  Matrices that are read by one launch must be given alike, else FSVD_ERR_UNSUPPORTED:
+ * U of q, k, v; V of q, k, v; V of w1 and U of w2.  The FFN core copies tile images into on-chip memory with direct
+ * loads; the projections and the attention rebuild read them in place of the row-major matrix (no conversion,
+ * contiguous requests).
  */
 size_t fsvd_tiled_bytes(int32_t rows, int32_t cols);
 fsvd_status fsvd_pack_tiled(int32_t rows, int32_t cols, const void *src, fsvd_dtype src_dtype, void *dst,

@@ -30,7 +30,7 @@ EXPORTS = ["fsvd_attention_workspace", "fsvd_ffn_workspace", "fsvd_layer_workspa
            "fsvd_ffn_check", "fsvd_attention", "fsvd_attention_heads", "fsvd_attention_heads_workspace", "fsvd_ffn",
            "fsvd_layer", "fsvd_layer_heads", "fsvd_layer_heads_workspace", "fsvd_linear", "fsvd_attention_core", "fsvd_attention_heads_core",
            "fsvd_ffn_core", "fsvd_ffn_core_workspace", "fsvd_layernorm", "fsvd_status_string", "fsvd_version", "fsvd_fm_bytes", "fsvd_pack_fm",
-           "fsvd_unpack_fm", "fsvd_tiled_bytes", "fsvd_pack_tiled"]
+           "fsvd_unpack_fm", "fsvd_tiled_bytes", "fsvd_pack_tiled", "fsvd_linear_tiled"]
 
 
 class FsvdError(RuntimeError):
@@ -90,6 +90,8 @@ def lib():
         L.fsvd_layer_heads.argtypes = [D, P, F, F, F, F, P, P, F, F, P, P, P, P, sz, P]
         L.fsvd_linear.restype = C.c_int
         L.fsvd_linear.argtypes = [i32, i32, i32, P, C.c_int, P, P, C.c_int, P, C.c_int, P, C.c_int, P]
+        L.fsvd_linear_tiled.restype = C.c_int
+        L.fsvd_linear_tiled.argtypes = [i32, i32, i32, P, C.c_int, P, P, C.c_int, P, C.c_int, P, C.c_int, P]
         L.fsvd_attention_core.restype = C.c_int
         L.fsvd_attention_core.argtypes = [D, P, P, P, F, F, F, P, P]
         L.fsvd_attention_heads_core.restype = C.c_int
@@ -161,9 +163,14 @@ class HeadFactor(Factor):
         for t in (self.U, self.V, self.b):
             assert t is None or (t.is_contiguous() and t.is_cuda)
         H, r, d_h = self.V.shape
-        assert self.U.shape[1] == H * r
-        return fsvd_factor(self.U.data_ptr(), self.V.data_ptr(), 0 if self.b is None else self.b.data_ptr(),
-                           self.U.shape[0], r, H * d_h, 0, 0)
+        assert self.U.shape[1] == H * r and self.V_tiled is None
+        u = self.U if self.U_tiled is None else self.U_tiled
+        return fsvd_factor(u.data_ptr(), self.V.data_ptr(), 0 if self.b is None else self.b.data_ptr(),
+                           self.U.shape[0], r, H * d_h, int(self.U_tiled is not None), 0)
+
+    def with_tiled(self, u: bool = False, v: bool = False) -> "HeadFactor":
+        assert not v, "V of a per-head factor stays row-major"
+        return HeadFactor(self.U, self.V, self.b, fsvd_pack_tiled(self.U) if u else self.U_tiled, None)
 
     @property
     def rank(self) -> int:
@@ -299,6 +306,19 @@ def fsvd_linear(A, W, bias=None, residual=None, out_dtype=torch.float16, out=Non
     return out
 
 
+def fsvd_linear_tiled(A, W_tiled, N, bias=None, residual=None, out_dtype=torch.float16, out=None,
+                      bias_dtype=torch.float16):
+    """fsvd_linear with the weight given as tile images of [K, N] (fsvd_pack_tiled)."""
+    T, K = A.shape
+    if out is None:
+        out = torch.empty((T, N), dtype=out_dtype, device=A.device)
+    bdt = bias.dtype if bias is not None else bias_dtype
+    _check(lib().fsvd_linear_tiled(T, K, N, _ptr(A), _TORCH2FSVD[A.dtype], _ptr(W_tiled), _ptr(bias), _TORCH2FSVD[bdt],
+                                   _ptr(residual), 0 if residual is None else _TORCH2FSVD[residual.dtype], _ptr(out),
+                                   _TORCH2FSVD[out.dtype], _stream()), "fsvd_linear_tiled")
+    return out
+
+
 def fsvd_fm_bytes(T, K) -> int:
     return lib().fsvd_fm_bytes(T, K)
 
@@ -375,7 +395,8 @@ def fsvd_layernorm(X, gamma, beta, eps, out_dtype=torch.float32, out=None):
 # ---------------------------------------------------------------------------------------------
 
 # which matrices of which projection the library accepts as tile images: name -> (U, V)
-TILED_OK = {"w1": (False, True), "w2": (True, False)}
+TILED_OK = {n: (True, True) for n in ("q", "k", "v", "o", "w1", "w2")}
+TILED_OK_HEADS = {n: (True, False) for n in ("q", "k", "v")}          # per-head factors: V [H, r, d_h] stays row-major
 
 
 def to_device(inp: dict, device="cuda:0", tiled: bool = False):
@@ -388,8 +409,8 @@ def to_device(inp: dict, device="cuda:0", tiled: bool = False):
     for n in ("q", "k", "v", "o", "w1", "w2"):
         cls = HeadFactor if (w.r_head > 0 and n in "qkv") else Factor
         dev[n] = cls(up(inp[n]["U"]), up(inp[n]["V"]), up(inp[n]["b"]))
-        if tiled and cls is Factor and n in TILED_OK:
-            dev[n] = dev[n].with_tiled(*TILED_OK[n])
+        if tiled:
+            dev[n] = dev[n].with_tiled(*(TILED_OK_HEADS if cls is HeadFactor else TILED_OK)[n])
     for n in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta"):
         dev[n] = up(inp[n])
     dev["key_len"] = None if inp["key_len"] is None else torch.from_numpy(inp["key_len"]).to(device)

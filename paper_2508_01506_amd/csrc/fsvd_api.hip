@@ -65,10 +65,13 @@ fsvd_status check_factor(const fsvd_factor* f, int in_dim, int out_dim, bool nee
 fsvd_status check_attn(const fsvd_desc* d, const fsvd_factor* q, const fsvd_factor* k, const fsvd_factor* v,
                        const fsvd_factor* o, bool ptrs) {
   FSVD_TRY(check_desc(d, false));
-  FSVD_TRY(check_factor(q, d->D, d->D, ptrs, ptrs));
-  FSVD_TRY(check_factor(k, d->D, d->D, ptrs, ptrs));
-  FSVD_TRY(check_factor(v, d->D, d->D, ptrs, ptrs));
-  FSVD_TRY(check_factor(o, d->D, d->D, ptrs, ptrs));
+  FSVD_TRY(check_factor(q, d->D, d->D, ptrs, ptrs, 3));
+  FSVD_TRY(check_factor(k, d->D, d->D, ptrs, ptrs, 3));
+  FSVD_TRY(check_factor(v, d->D, d->D, ptrs, ptrs, 3));
+  FSVD_TRY(check_factor(o, d->D, d->D, ptrs, ptrs, 3));
+  // q, k and v share one projection launch and one rebuild launch: one weight path per launch
+  if (q->u_layout != k->u_layout || q->u_layout != v->u_layout) return FSVD_ERR_UNSUPPORTED;
+  if (q->v_layout != k->v_layout || q->v_layout != v->v_layout) return FSVD_ERR_UNSUPPORTED;
   return FSVD_OK;
 }
 // per-head factors of q, k, v: in_dim = out_dim = D, `rank` is the rank of ONE head
@@ -76,16 +79,17 @@ fsvd_status check_attn_heads(const fsvd_desc* d, const fsvd_factor* q, const fsv
                              const fsvd_factor* o, bool ptrs) {
   FSVD_TRY(check_desc(d, false));
   for (const fsvd_factor* f : {q, k, v}) {
-    FSVD_TRY(check_factor(f, d->D, d->D, ptrs, ptrs));
+    FSVD_TRY(check_factor(f, d->D, d->D, ptrs, ptrs, 1));      // U [D, H r] feeds a plain projection; V stays row-major
     if ((long long)f->rank * d->H * d->D >= (1LL << 29)) return FSVD_ERR_UNSUPPORTED;
   }
-  FSVD_TRY(check_factor(o, d->D, d->D, ptrs, ptrs));
+  if (q->u_layout != k->u_layout || q->u_layout != v->u_layout) return FSVD_ERR_UNSUPPORTED;
+  FSVD_TRY(check_factor(o, d->D, d->D, ptrs, ptrs, 3));
   return FSVD_OK;
 }
 fsvd_status check_ffn(const fsvd_desc* d, const fsvd_factor* w1, const fsvd_factor* w2, bool ptrs) {
   FSVD_TRY(check_desc(d, true));
-  FSVD_TRY(check_factor(w1, d->D, d->F, ptrs, ptrs, 2));
-  FSVD_TRY(check_factor(w2, d->F, d->D, ptrs, ptrs, 1));
+  FSVD_TRY(check_factor(w1, d->D, d->F, ptrs, ptrs, 3));
+  FSVD_TRY(check_factor(w2, d->F, d->D, ptrs, ptrs, 3));
   if (w1->v_layout != w2->u_layout) return FSVD_ERR_UNSUPPORTED;   // the fused core reads both streams the same way
   return FSVD_OK;
 }
@@ -142,6 +146,7 @@ fsvd_status run_attention(const fsvd_desc* d, const void* x_fm, const fsvd_facto
 
   LinearArgs h1{};
   h1.A = x_fm; h1.a_layout = LAYOUT_FM; h1.lda = D; h1.a_dt = DT_F16; h1.T = T; h1.K = D; h1.w_dt = d->io_dtype;
+  h1.w_tiled = q->u_layout == FSVD_TILED;
   h1.c_layout = LAYOUT_FM; h1.c_dt = DT_F16; h1.R = nullptr; h1.ngroups = 3;
   h1.g[0] = {q->U, nullptr, Pq, hq, hq, 0};
   h1.g[1] = {k->U, nullptr, Pk, hk, hk, 0};
@@ -153,7 +158,7 @@ fsvd_status run_attention(const fsvd_desc* d, const void* x_fm, const fsvd_facto
   ca.rq = q->rank; ca.rk = k->rank; ca.rv = v->rank; ca.per_head = per_head ? 1 : 0;
   ca.Vq = q->V; ca.Vk = k->V; ca.Vv = v->V;
   ca.bq = q->bias; ca.bk = k->bias; ca.bv = v->bias;
-  ca.w_dt = d->io_dtype;
+  ca.w_dt = d->io_dtype; ca.tiled = q->v_layout == FSVD_TILED;
   ca.B = d->B; ca.M = d->M; ca.D = D; ca.H = d->H;
   ca.causal = d->causal; ca.key_len = d->key_len; ca.scale = resolve_scale(d);
   ca.C = c_buf;
@@ -161,13 +166,14 @@ fsvd_status run_attention(const fsvd_desc* d, const void* x_fm, const fsvd_facto
 
   LinearArgs h3a{};
   h3a.A = c_buf; h3a.a_layout = LAYOUT_FM; h3a.lda = D; h3a.a_dt = DT_F16; h3a.T = T; h3a.K = D; h3a.w_dt = d->io_dtype;
+  h3a.w_tiled = o->u_layout == FSVD_TILED;
   h3a.c_layout = LAYOUT_FM; h3a.c_dt = DT_F16; h3a.ngroups = 1;
   h3a.g[0] = {o->U, nullptr, To, o->rank, o->rank, 0};
   FSVD_HIP(launch_linear(h3a, s));
 
   LinearArgs h3b{};
   h3b.A = To; h3b.a_layout = LAYOUT_FM; h3b.lda = o->rank; h3b.a_dt = DT_F16; h3b.T = T; h3b.K = o->rank;
-  h3b.w_dt = d->io_dtype; h3b.c_layout = out_fm ? LAYOUT_FM : LAYOUT_ROW; h3b.c_dt = c_dt;
+  h3b.w_dt = d->io_dtype; h3b.w_tiled = o->v_layout == FSVD_TILED; h3b.c_layout = out_fm ? LAYOUT_FM : LAYOUT_ROW; h3b.c_dt = c_dt;
   h3b.R = residual; h3b.ldr = D; h3b.r_dt = r_dt; h3b.ngroups = 1;
   h3b.g[0] = {o->V, o->bias, out, D, D, D};
   FSVD_HIP(launch_linear(h3b, s));
@@ -185,6 +191,7 @@ fsvd_status run_ffn(const fsvd_desc* d, const void* A_in, int a_layout, int a_dt
 
   LinearArgs h5{};
   h5.A = A_in; h5.a_layout = a_layout; h5.lda = D; h5.a_dt = a_dt; h5.T = T; h5.K = D; h5.w_dt = d->io_dtype;
+  h5.w_tiled = w1->u_layout == FSVD_TILED;
   h5.c_layout = LAYOUT_FM; h5.c_dt = DT_F16; h5.ngroups = 1;
   h5.g[0] = {w1->U, nullptr, P1, w1->rank, w1->rank, 0};
   FSVD_HIP(launch_linear(h5, s));
@@ -197,6 +204,7 @@ fsvd_status run_ffn(const fsvd_desc* d, const void* A_in, int a_layout, int a_dt
 
   LinearArgs h7{};
   h7.A = Z; h7.a_layout = LAYOUT_FM; h7.lda = w2->rank; h7.a_dt = DT_F16; h7.T = T; h7.K = w2->rank; h7.w_dt = d->io_dtype;
+  h7.w_tiled = w2->v_layout == FSVD_TILED;
   h7.c_layout = LAYOUT_ROW; h7.c_dt = c_dt; h7.R = residual; h7.ldr = D; h7.r_dt = r_dt; h7.ngroups = 1;
   h7.g[0] = {w2->V, w2->bias, out, D, D, D};
   FSVD_HIP(launch_linear(h7, s));
@@ -377,20 +385,33 @@ fsvd_status fsvd_layer_heads(const fsvd_desc* d, const void* X, const fsvd_facto
 }
 
 // ------------------------------------------------------------------ building blocks
-fsvd_status fsvd_linear(int32_t T, int32_t K, int32_t N, const void* A, fsvd_dtype a_dtype, const void* W,
+namespace {
+fsvd_status linear_impl(int32_t T, int32_t K, int32_t N, const void* A, fsvd_dtype a_dtype, const void* W,
                         const void* bias, fsvd_dtype w_dtype, const void* residual, fsvd_dtype r_dtype, void* C,
-                        fsvd_dtype c_dtype, void* stream) {
+                        fsvd_dtype c_dtype, void* stream, bool tiled) {
   if (T <= 0 || K <= 0 || N <= 0 || !A || !W || !C) return FSVD_ERR_INVALID_ARG;
   if (mis16(A) || mis16(W) || mis16(C) || mis16(bias) || mis16(residual)) return FSVD_ERR_INVALID_ARG;
   if (!dtype_ok(a_dtype) || !dtype_ok16(w_dtype) || !dtype_ok(c_dtype) || (residual && !dtype_ok(r_dtype))) return FSVD_ERR_INVALID_ARG;
   if (K % 16 != 0 || N % 16 != 0) return FSVD_ERR_UNSUPPORTED;
   if ((long long)T * (K > N ? K : N) >= (1LL << 29)) return FSVD_ERR_UNSUPPORTED;
   LinearArgs a{};
-  a.A = A; a.a_layout = LAYOUT_ROW; a.lda = K; a.a_dt = a_dtype; a.T = T; a.K = K; a.w_dt = w_dtype;
+  a.A = A; a.a_layout = LAYOUT_ROW; a.lda = K; a.a_dt = a_dtype; a.T = T; a.K = K; a.w_dt = w_dtype; a.w_tiled = tiled;
   a.c_layout = LAYOUT_ROW; a.c_dt = c_dtype; a.R = residual; a.ldr = N; a.r_dt = r_dtype; a.ngroups = 1;
   a.g[0] = {W, bias, C, N, N, N};
   FSVD_HIP(launch_linear(a, (hipStream_t)stream));
   return FSVD_OK;
+}
+}  // namespace
+
+fsvd_status fsvd_linear(int32_t T, int32_t K, int32_t N, const void* A, fsvd_dtype a_dtype, const void* W,
+                        const void* bias, fsvd_dtype w_dtype, const void* residual, fsvd_dtype r_dtype, void* C,
+                        fsvd_dtype c_dtype, void* stream) {
+  return linear_impl(T, K, N, A, a_dtype, W, bias, w_dtype, residual, r_dtype, C, c_dtype, stream, false);
+}
+fsvd_status fsvd_linear_tiled(int32_t T, int32_t K, int32_t N, const void* A, fsvd_dtype a_dtype, const void* W_tiled,
+                              const void* bias, fsvd_dtype bias_dtype, const void* residual, fsvd_dtype r_dtype, void* C,
+                              fsvd_dtype c_dtype, void* stream) {
+  return linear_impl(T, K, N, A, a_dtype, W_tiled, bias, bias_dtype, residual, r_dtype, C, c_dtype, stream, true);
 }
 
 size_t fsvd_fm_bytes(int32_t T, int32_t K) {
@@ -428,15 +449,17 @@ namespace {
 fsvd_status attention_core_impl(const fsvd_desc* d, const void* Pq, const void* Pk, const void* Pv, const fsvd_factor* q,
                                 const fsvd_factor* k, const fsvd_factor* v, void* context, void* stream, bool per_head) {
   FSVD_TRY(check_desc(d, false));
-  FSVD_TRY(check_factor(q, d->D, d->D, false, true));
-  FSVD_TRY(check_factor(k, d->D, d->D, false, true));
-  FSVD_TRY(check_factor(v, d->D, d->D, false, true));
+  const int tiled_ok = per_head ? 1 : 3;   // the U members are not read here: any layout value is accepted for them
+  FSVD_TRY(check_factor(q, d->D, d->D, false, true, tiled_ok));
+  FSVD_TRY(check_factor(k, d->D, d->D, false, true, tiled_ok));
+  FSVD_TRY(check_factor(v, d->D, d->D, false, true, tiled_ok));
+  if (q->v_layout != k->v_layout || q->v_layout != v->v_layout) return FSVD_ERR_UNSUPPORTED;
   if (!Pq || !Pk || !Pv || !context || mis16(Pq) || mis16(Pk) || mis16(Pv) || mis16(context)) return FSVD_ERR_INVALID_ARG;
   AttnCoreArgs ca{};
   ca.Pq = Pq; ca.Pk = Pk; ca.Pv = Pv;
   ca.rq = q->rank; ca.rk = k->rank; ca.rv = v->rank; ca.per_head = per_head ? 1 : 0;
   ca.Vq = q->V; ca.Vk = k->V; ca.Vv = v->V; ca.bq = q->bias; ca.bk = k->bias; ca.bv = v->bias;
-  ca.w_dt = d->io_dtype; ca.B = d->B; ca.M = d->M; ca.D = d->D; ca.H = d->H;
+  ca.w_dt = d->io_dtype; ca.tiled = q->v_layout == FSVD_TILED; ca.B = d->B; ca.M = d->M; ca.D = d->D; ca.H = d->H;
   ca.causal = d->causal; ca.key_len = d->key_len; ca.scale = resolve_scale(d);
   ca.C = context;
   FSVD_HIP(launch_attn_core(ca, (hipStream_t)stream));
@@ -463,8 +486,8 @@ size_t fsvd_ffn_core_workspace(const fsvd_desc* d, int32_t r1, int32_t r2) {
 fsvd_status fsvd_ffn_core(const fsvd_desc* d, const void* P1, const fsvd_factor* w1, const fsvd_factor* w2, void* Z,
                           void* ws, size_t ws_bytes, void* stream) {
   FSVD_TRY(check_desc(d, true));
-  FSVD_TRY(check_factor(w1, d->D, d->F, false, true, 2));
-  FSVD_TRY(check_factor(w2, d->F, d->D, true, false, 1));
+  FSVD_TRY(check_factor(w1, d->D, d->F, false, true, 3));   // U of w1 and V of w2 are not read here
+  FSVD_TRY(check_factor(w2, d->F, d->D, true, false, 3));
   if (w1->v_layout != w2->u_layout) return FSVD_ERR_UNSUPPORTED;
   if (!P1 || !Z || mis16(P1) || mis16(Z)) return FSVD_ERR_INVALID_ARG;
   const size_t need = fsvd_ffn_core_workspace(d, w1->rank, w2->rank);

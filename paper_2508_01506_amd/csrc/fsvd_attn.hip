@@ -88,10 +88,19 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
   const int s_r = tid / LPR, s_c = 8 * (tid % LPR);
   const int trA = tr_lane_off(lane, WS) + 32 * g * WS;   // transposing-read base of this lane (halves)
   const int trV = tr_lane_off(lane, WS) + 4 * g * WS;    // same for the V tile: keys 16 t + 4 g + {0..3, 8..11}
+  // Prepacked weights (tile images, whole-matrix factors only): byte offset of the 8 columns this thread stages of rank
+  // row rho.  The column part is fixed per thread (chunks start at multiples of 64 rows, so rho % 4 == s_r % 4).
+  constexpr int ST = WT == kWtTiled ? DT_F16 : WT;          // type of the values as they arrive for staging
+  const int tl_ntn = (D + 127) / 128;
+  const int tl_n = (col0 + s_c) & 127;
+  const int tl_col = ((col0 + s_c) >> 7) * kTileImageBytes + ((((tl_n >> 5) ^ (s_r & 3)) << 5) + (tl_n & 31)) * 2;
+  auto tiled_off = [&](int rho) { return (rho >> 7) * tl_ntn * kTileImageBytes + (rho & 127) * 256 + tl_col; };
   // 4 consecutive bias entries of this head, as floats
   auto bias4 = [&](const void* bp, int d) -> f4v {
     const rsrc_t r = rsrc_at(bp, bp ? (long long)D * 2 : 0, 0);
-    return raw_to_f4<WT>(buf_load8(r, (col0 + d) * 2));
+    const u2 raw = buf_load8(r, (col0 + d) * 2);
+    if constexpr (WT == kWtTiled) return a.w_dt == DT_BF16 ? raw_to_f4<DT_BF16>(raw) : raw_to_f4<DT_F16>(raw);
+    else return raw_to_f4<WT>(raw);
   };
 
   // =================================== Q phase ===================================
@@ -126,16 +135,18 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
       for (int qt = 0; qt < QT; ++qt) pfr[qt][kk] = __builtin_bit_cast(h8, buf_load16(r, voffP[qt] + kk * kFmStepBytes));
     };
     auto issue_w = [&](int c) {
-      const rsrc_t r = rsrc_at(a.Vq, w_total, ((long long)(c0 + c) * kChunkK * ld + wcol0) * 2);
+      const rsrc_t r = WT == kWtTiled ? rsrc_at(a.Vq, (long long)tiled_bytes(rtot, D), 0)
+                                      : rsrc_at(a.Vq, w_total, ((long long)(c0 + c) * kChunkK * ld + wcol0) * 2);
 #pragma unroll
       for (int p = 0; p < NP; ++p) {
         const int rho = (c0 + c) * kChunkK + s_r + p * RPP;          // ranks outside the window contribute nothing
-        w_raw[p] = buf_load16(r, (rho >= lo && rho < hi) ? ((s_r + p * RPP) * ld + s_c) * 2 : kOobOffset);
+        const int off = WT == kWtTiled ? tiled_off(rho) : ((s_r + p * RPP) * ld + s_c) * 2;
+        w_raw[p] = buf_load16(r, (rho >= lo && rho < hi) ? off : kOobOffset);
       }
     };
     auto commit_w = [&](int pb) {
 #pragma unroll
-      for (int p = 0; p < NP; ++p) stage_store16<WT>(&wbuf[pb][0][(s_r + p * RPP) * WS + s_c], w_raw[p]);
+      for (int p = 0; p < NP; ++p) stage_store16<ST>(&wbuf[pb][0][(s_r + p * RPP) * WS + s_c], w_raw[p]);
     };
     issue_w(0);
 #pragma unroll
@@ -218,10 +229,13 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
   auto w_voff = [&](int m, int c, int pp) {
     const int rho = ((m ? c0_v : c0_k) + c) * kChunkK + s_r + pp * RPP;
     const bool ok = m ? (rho >= lo_v && rho < hi_v) : (rho >= lo_k && rho < hi_k);
-    return ok ? ((s_r + pp * RPP) * ld + s_c) * 2 : kOobOffset;
+    const int off = WT == kWtTiled ? tiled_off(rho) : ((s_r + pp * RPP) * ld + s_c) * 2;
+    return ok ? off : kOobOffset;
   };
+  const long long ti_k = (long long)tiled_bytes(rtot_k, D), ti_v = (long long)tiled_bytes(rtot_v, D);
   auto w_rsrc = [&](int m, int c, bool live) {
-    return rsrc_at(m ? a.Vv : a.Vk, live ? (m ? wt_v : wt_k) : 0, ((long long)((m ? c0_v : c0_k) + c) * kChunkK * ld + wcol0) * 2);
+    if constexpr (WT == kWtTiled) return rsrc_at(m ? a.Vv : a.Vk, live ? (m ? ti_v : ti_k) : 0, 0);
+    else return rsrc_at(m ? a.Vv : a.Vk, live ? (m ? wt_v : wt_k) : 0, ((long long)((m ? c0_v : c0_k) + c) * kChunkK * ld + wcol0) * 2);
   };
 
   u4 w_raw[2][NP];
@@ -237,7 +251,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
 #pragma unroll
     for (int m = 0; m < 2; ++m)
 #pragma unroll
-      for (int p = 0; p < NP; ++p) stage_store16<WT>(&wbuf[pb][m][(s_r + p * RPP) * WS + s_c], w_raw[m][p]);
+      for (int p = 0; p < NP; ++p) stage_store16<ST>(&wbuf[pb][m][(s_r + p * RPP) * WS + s_c], w_raw[m][p]);
   };
   h8 pfr[KTW][4];
   int voffKV[KTW];
@@ -315,7 +329,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
             for (int u = 0; u < kPassesPerStep; ++u) {
               const int q = kk * 2 * NP / 4 + u;
               const int m = q / NP, pp = q % NP;
-              stage_store16<WT>(wnext + m * WBUF + (s_r + pp * RPP) * WS + s_c, w_raw[m][pp]);
+              stage_store16<ST>(wnext + m * WBUF + (s_r + pp * RPP) * WS + s_c, w_raw[m][pp]);
               w_raw[m][pp] = buf_load16(m ? rw1 : rw0, w_voff(m, c2, pp));
             }
           }
@@ -477,7 +491,8 @@ hipError_t launch_qt(const AttnCoreArgs& a, hipStream_t s) {
   constexpr int BQ = kAttnWaves * QT * 32;
   const int nqb = (a.M + BQ - 1) / BQ;
   const dim3 grid(a.B * a.H * nqb), block(kAttnThreads);
-  if (a.w_dt == DT_F16) hipLaunchKernelGGL((attn_core_kernel<DH, QT, DT_F16>), grid, block, 0, s, a, nqb);
+  if (a.tiled) hipLaunchKernelGGL((attn_core_kernel<DH, QT, kWtTiled>), grid, block, 0, s, a, nqb);
+  else if (a.w_dt == DT_F16) hipLaunchKernelGGL((attn_core_kernel<DH, QT, DT_F16>), grid, block, 0, s, a, nqb);
   else hipLaunchKernelGGL((attn_core_kernel<DH, QT, DT_BF16>), grid, block, 0, s, a, nqb);
   return hipGetLastError();
 }

@@ -80,8 +80,13 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
   }
   // ---- weight staging: thread -> row s_r (+ RPP per pass), 8 columns from s_c
   const int s_r = threadIdx.x / LPR, s_c = 8 * (threadIdx.x % LPR);
-  const long long w_total = (long long)K * G.ldw * 2;
+  const long long w_total = WT == kWtTiled ? (long long)tiled_bytes(K, G.N) : (long long)K * G.ldw * 2;
   const bool s_ok = n0 + s_c < G.N;
+  // prepacked weights (tile images): the column part of this thread's byte offset is fixed (chunks start at multiples
+  // of 64 rows and RPP is a multiple of 4, so row % 4 == s_r % 4)
+  constexpr int ST = WT == kWtTiled ? DT_F16 : WT;        // type of the values as they arrive for staging
+  const int tl_ntn = (G.N + 127) / 128, tl_n = (n0 + s_c) & 127;
+  const int tl_col = ((n0 + s_c) >> 7) * kTileImageBytes + ((((tl_n >> 5) ^ (s_r & 3)) << 5) + (tl_n & 31)) * 2;
   const int trA = tr_lane_off(lane, WS) + 32 * g * WS;   // transposing-read base of this lane (halves)
 
   f16v acc[2][NT];
@@ -114,11 +119,23 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
       }
     }
   };
-  auto w_rsrc = [&](int c, bool live) { return rsrc_at(G.W, live ? w_total : 0, ((long long)c * kChunkK * G.ldw + n0) * 2); };
-  auto load_w_pass = [&](const rsrc_t& r, int p) {
-    w_raw[p] = buf_load16(r, s_ok ? ((s_r + p * RPP) * G.ldw + s_c) * 2 : kOobOffset);   // rows past K: out of range -> 0
+  auto w_rsrc = [&](int c, bool live) {
+    if constexpr (WT == kWtTiled) {
+      const int kt = c >> 1;                              // chunk c = rows 64 (c % 2) .. of tile row c / 2 (zero-padded past K)
+      return rsrc_at(G.W, live ? w_total : 0, (long long)kt * tl_ntn * kTileImageBytes + (c & 1) * 64 * 256);
+    } else {
+      return rsrc_at(G.W, live ? w_total : 0, ((long long)c * kChunkK * G.ldw + n0) * 2);
+    }
   };
-  auto store_w_pass = [&](int buf, int p) { stage_store16<WT>(&lds[buf][(s_r + p * RPP) * WS + s_c], w_raw[p]); };
+  auto load_w_pass = [&](const rsrc_t& r, int p) {
+    const int off = WT == kWtTiled ? (s_r + p * RPP) * 256 + tl_col : ((s_r + p * RPP) * G.ldw + s_c) * 2;
+    w_raw[p] = buf_load16(r, s_ok ? off : kOobOffset);   // rows past K: out of range -> 0
+  };
+  auto store_w_pass = [&](int buf, int p) { stage_store16<ST>(&lds[buf][(s_r + p * RPP) * WS + s_c], w_raw[p]); };
+  auto bias_f4 = [&](u2 raw) -> f4v {
+    if constexpr (WT == kWtTiled) return a.w_dt == DT_BF16 ? raw_to_f4<DT_BF16>(raw) : raw_to_f4<DT_F16>(raw);
+    else return raw_to_f4<WT>(raw);
+  };
   // prologue: chunk 0 in LDS and in the operand registers, chunk 1's weights in flight
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) load_a(0, kk, true);
@@ -172,7 +189,7 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
       for (int jj = 0; jj < 4; ++jj) {
         const int n = n0 + 32 * nt + 8 * jj + 4 * g;   // first of 4 columns
         if (n >= nch * 64) continue;                   // columns N .. 64*nch-1 are written as zeros (FM padding)
-        const f4v bias = raw_to_f4<WT>(buf_load8(rB, n * 2));
+        const f4v bias = bias_f4(buf_load8(rB, n * 2));
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
           const int tok = m0 + 32 * mt + l32;
@@ -192,7 +209,7 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
     for (int nt = 0; nt < NT; ++nt) {
       f4v bias[4];
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj) bias[jj] = raw_to_f4<WT>(buf_load8(rB, (n0 + 32 * nt + 8 * jj + 4 * g) * 2));   // past N: 0
+      for (int jj = 0; jj < 4; ++jj) bias[jj] = bias_f4(buf_load8(rB, (n0 + 32 * nt + 8 * jj + 4 * g) * 2));   // past N: 0
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt) {
         const int tok = m0 + 32 * mt + l32;
@@ -250,6 +267,7 @@ hipError_t launch_a(const LinearArgs& a, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_linear(const LinearArgs& a, hipStream_t s) {
+  if (a.w_tiled) return launch_a<kWtTiled>(a, s);
   return a.w_dt == DT_F16 ? launch_a<DT_F16>(a, s) : launch_a<DT_BF16>(a, s);
 }
 

@@ -13,7 +13,7 @@ enum : int { LAYOUT_ROW = 0, LAYOUT_FM = 1 };
 
 // ---- C[T, N] = A[T, K] W[K, N] (+ bias[N]) (+ R[T, N]) for up to three weight matrices sharing A
 struct LinearGroup {
-  const void* W;     // [K, N] row-major, stored in w_dt
+  const void* W;     // [K, N] row-major, stored in w_dt; or its tile images (LinearArgs::w_tiled)
   const void* bias;  // [N] in w_dt, or nullptr
   void* C;           // ROW: [T, N] with row stride ldc; FM: fragment-major [T, N] (fp16)
   int N;
@@ -27,7 +27,8 @@ struct LinearArgs {
   int a_dt;
   int T;
   int K;
-  int w_dt;       // F16 or BF16
+  int w_dt;       // F16 or BF16 (bias; and W unless w_tiled)
+  int w_tiled;    // non-zero: every group's W is a prepacked fp16 tile image of [K, N] (ldw unused)
   int c_layout;   // LAYOUT_ROW or LAYOUT_FM
   int c_dt;       // ROW only: F16, BF16 or F32
   const void* R;  // ROW only: residual [T, N] row stride ldr, added in the epilogue, or nullptr
@@ -46,6 +47,7 @@ struct AttnCoreArgs {
   const void* Vq; const void* Vk; const void* Vv;   // stored in w_dt
   const void* bq; const void* bk; const void* bv;   // [D] in w_dt or nullptr
   int w_dt;
+  int tiled;               // non-zero: Vq, Vk, Vv are prepacked fp16 tile images of [r_x, D] (whole-matrix factors only)
   int B, M, D, H;
   int causal;
   const int32_t* key_len;  // device [B] or nullptr

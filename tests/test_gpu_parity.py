@@ -87,6 +87,22 @@ def test_linear(fb, T, K, N, adt, wdt, odt):
     assert rel_err(plain, ref_plain) < 5e-6
 
 
+@pytest.mark.parametrize("T,K,N,adt,wdt", [(300, 96, 80, torch.float16, torch.float16), (513, 768, 1152, torch.bfloat16, torch.bfloat16),
+                                           (64, 16, 16, torch.float32, torch.bfloat16), (1000, 1024, 200 * 16, torch.float32, torch.float16)])
+def test_linear_with_tile_image_weights_matches_row_major(fb, T, K, N, adt, wdt):
+    """The projections read prepacked weights in place of the row-major matrix: same values, same order of operations."""
+    g = torch.Generator(device=DEV).manual_seed(T + N)
+    A = torch.randn(T, K, generator=g, device=DEV).to(adt)
+    Wm = (torch.randn(K, N, generator=g, device=DEV) * K ** -0.5).to(wdt)
+    b = (0.1 * torch.randn(N, generator=g, device=DEV)).to(wdt)
+    R = torch.randn(T, N, generator=g, device=DEV)
+    want = fb.fsvd_linear(A, Wm, b, R, out_dtype=torch.float32)
+    got = fb.fsvd_linear_tiled(A, fb.fsvd_pack_tiled(Wm), N, b, R, out_dtype=torch.float32)
+    assert torch.equal(got, want)
+    ref = A.double() @ Wm.double() + b.double() + R.double()
+    assert rel_err(got.cpu().numpy(), ref.cpu().numpy()) < 2e-3
+
+
 @pytest.mark.parametrize("T,D,xdt,ydt", [(37, 768, torch.float32, torch.float32), (5, 64, torch.float16, torch.float16),
                                          (130, 4096, torch.bfloat16, torch.float32), (3, 1104, torch.float32, torch.bfloat16)])
 def test_layernorm(fb, T, D, xdt, ydt):
@@ -231,11 +247,12 @@ def attn_block_tol(w, ref):
     return max(tol_for(w, "attention"), 1.0e-3 / float(np.sqrt(np.mean(np.asarray(ref, dtype=np.float64) ** 2))))
 
 
+@pytest.mark.parametrize("weights", WEIGHTS)
 @pytest.mark.parametrize("name", ["ph_tiny_r16", "ph_tiny_r48_causal", "ph_tiny_d128_r32"])
-def test_attention_with_per_head_factors_small(fb, name):
+def test_attention_with_per_head_factors_small(fb, name, weights):
     """Every element of the attention block with per-head factors (ranks 16, 48 - which straddles the 64-rank
     chunks - and 32 with 128-wide heads) against the per-head oracle."""
-    w, inp, dev = workload(name, fb)
+    w, inp, dev = workload(name, fb, weights)
     got = gpu_call(dev, "attention").cpu().numpy()
     assert np.isfinite(got).all()
     ref = oracle_call(inp, "attention")
@@ -264,9 +281,10 @@ def test_layer_with_per_head_attention_meets_the_gate(fb, name, norm):
     assert rel_err(gpu_call(dev, "layer").cpu().numpy(), oracle_call(inp, "layer")) < TOL_LAYER
 
 
+@pytest.mark.parametrize("weights", WEIGHTS)
 @pytest.mark.parametrize("name", ["ph_bert_base_b16_m512_r32", "ph_bert_base_b16_m1024_r48"])
-def test_layer_with_per_head_attention_encoder_shapes(fb, name):
-    w, inp, dev = workload(name, fb)
+def test_layer_with_per_head_attention_encoder_shapes(fb, name, weights):
+    w, inp, dev = workload(name, fb, weights)
     got = gpu_call(dev, "layer").cpu().numpy()
     for b in (0, w.B - 1):
         one = dict(inp, X=inp["X"][b:b + 1], key_len=None if inp["key_len"] is None else inp["key_len"][b:b + 1])

@@ -159,21 +159,28 @@ def test_tiled_weight_layout_contract():
     assert L.fsvd_pack_tiled(128, 12, 256, 0, 256, None) == UNSUPPORTED
 
     def lay(f, u=0, v=0):
-        g = fb.fsvd_factor(f.U, f.V, f.bias, f.in_dim, f.rank, f.out_dim, u, v)
-        return g
+        return fb.fsvd_factor(f.U, f.V, f.bias, f.in_dim, f.rank, f.out_dim, u, v)
     w1, w2 = fac(768, 64, 3072), fac(3072, 64, 768)
     ffn = lambda a, b: L.fsvd_ffn_check(C.byref(d), C.byref(a), C.byref(b))
     assert ffn(lay(w1, v=1), lay(w2, u=1)) == OK
+    assert ffn(lay(w1, u=1, v=1), lay(w2, u=1, v=1)) == OK
+    assert ffn(lay(w1, u=1), lay(w2, v=1)) == OK                          # the two plain projections, each on its own
     assert ffn(lay(w1, v=1), w2) == UNSUPPORTED                           # both streams of the fused core or neither
     assert ffn(w1, lay(w2, u=1)) == UNSUPPORTED
-    assert ffn(lay(w1, u=1, v=1), lay(w2, u=1)) == UNSUPPORTED            # U of w1 feeds a plain projection
-    assert ffn(lay(w1, v=1), lay(w2, u=1, v=1)) == UNSUPPORTED
     assert ffn(lay(w1, v=2), lay(w2, u=2)) == INVALID                     # not a layout
     assert ffn(lay(w1, v=-1), w2) == INVALID
     q = fac(768, 64, 768)
-    att = lambda a: L.fsvd_attention_check(C.byref(d), C.byref(a), C.byref(q), C.byref(q), C.byref(q))
-    for u, v in [(1, 0), (0, 1)]:
-        assert att(lay(q, u, v)) == (OK if fb.TILED_OK.get("q", (False, False))[u == 0] else UNSUPPORTED)
+    att = lambda a, b, c, o: L.fsvd_attention_check(C.byref(d), C.byref(a), C.byref(b), C.byref(c), C.byref(o))
+    tv, tu = lay(q, v=1), lay(q, u=1)
+    assert att(tv, tv, tv, q) == OK                                       # the rebuild weights V_q, V_k, V_v: all three
+    assert att(tv, q, tv, q) == UNSUPPORTED                               # ... or none
+    assert att(tu, tu, tu, lay(q, u=1, v=1)) == OK                        # likewise the three rank projections
+    assert att(tu, tu, q, q) == UNSUPPORTED
+    assert att(q, q, q, lay(q, v=1)) == OK                                # the output projection's factors are free
+    heads = lambda a: L.fsvd_attention_heads(C.byref(d), 256, C.byref(a), C.byref(a), C.byref(a), C.byref(q), 256, 256, 1 << 40, None)
+    assert heads(lay(fac(768, 32, 768), v=1)) == UNSUPPORTED              # V of per-head factors stays row-major
+    assert L.fsvd_linear_tiled(16, 32, 16, 256, 0, 256, None, 0, None, 0, 264, 0, None) == INVALID   # C misaligned
+    assert L.fsvd_linear_tiled(16, 40, 16, 256, 0, 256, None, 0, None, 0, 256, 0, None) == UNSUPPORTED
 
 
 def test_per_head_attention_entry_point_contract():
