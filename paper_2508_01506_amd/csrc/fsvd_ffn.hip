@@ -222,10 +222,32 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
           wb = nxt(wb);
         }
         if constexpr (NS2 > 0) {
+          // these wavefronts stage nothing through registers, so the chunk's activation operands fit in them (as in
+          // the compute wavefronts): one LDS read of the weight fragment per step instead of three
+          h8 gq2[8][2];
+#pragma unroll
+          for (int f = 0; f < 8; ++f)
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) gq2[f][tt] = gtile[f >> 1][f & 1][tt][lane];
 #pragma unroll
           for (int s = 0; s < NS2; ++s) {
             request2(nxt(nxt(wb)), c, nA + NS + s);
-            stage_b2(wt_lds[wb], z2[s], s0 + (NS + s) * kTile < s_end, [](int) {});
+            const _Float16* w2 = wt_lds[wb];
+            const bool active = s0 + (NS + s) * kTile < s_end;
+            h8 wf = tr_frag(w2 + trB, w2 + trB + 8 * kRow);
+#pragma unroll
+            for (int f = 0; f < 8; ++f) {
+              h8 wf_next = wf;
+              if (f < 7) {
+                const _Float16* q = w2 + trB + 16 * (f + 1) * kRow;
+                wf_next = tr_frag(q, q + 8 * kRow);
+              }
+              if (active) {
+                z2[s][0] = mfma32(wf, gq2[f][0], z2[s][0]);
+                z2[s][1] = mfma32(wf, gq2[f][1], z2[s][1]);
+              }
+              wf = wf_next;
+            }
             lds_dma_wait_barrier<8>();
             wb = nxt(wb);
           }
