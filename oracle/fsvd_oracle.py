@@ -14,7 +14,8 @@ and by nothing on the product path.
 Parity pins (tests/test_oracle_pins.py): full-rank identity against a dense
 layer written with torch's library routines, the Eckart-Young closed form for
 truncation, brute-force attention with python loops on tiny shapes, softmax /
-GELU / LayerNorm closed forms, mask and bias invariants.  The whole layer at
+GELU / LayerNorm closed forms, mask and bias invariants; the decoding step
+against the last row of causal attention over the whole sequence.  The whole layer at
 benchmark sizes has no printed values in the paper to compare against: beyond
 those pins it is "parity unpinned".
 
@@ -144,6 +145,46 @@ def attention(X, q, k, v, o, H, causal=False, key_len=None, scale=None):
         C = attention_context_one_sequence(X[b], q, k, v, H, causal, kl, scale)
         out[b] = factored_linear(C, o)
     return out
+
+
+# ---------------------------------------------------------------------------
+# decoding with a rank-space KV cache  (appendix on decoder models, paragraphs
+# "Prefill" / "Decoding Phase": the cache holds the rank-space keys and values
+# P_k, P_v [B, t, r] instead of K, V [B, t, D]; step t attends one new query
+# against the cached rows and its own)
+# ---------------------------------------------------------------------------
+
+def decode_attention(x_new, Pk_cache, Pv_cache, lens, q, k, v, o, H, scale=None):
+    """One decoding step of the attention block.  x_new [B, D] is the new token of every sequence; Pk_cache [B, t_max, r_k]
+    and Pv_cache [B, t_max, r_v] hold the rank-space keys / values of the lens[b] earlier tokens of sequence b (rows
+    beyond lens[b] are ignored).  Returns (out [B, D], pk_new [B, r_k], pv_new [B, r_v]): the block's output for the
+    new token and the two rows that extend the cache.
+
+    Written as the plain definition, with nothing absorbed or reordered: the cached rows and the new row are turned back
+    into full-width keys and values K = P_k V_k + b_k, V = P_v V_v + b_v, the new query is Q = (x U_q) V_q + b_q, and per
+    head the new token attends to all lens[b] + 1 keys (itself included: the causal mask of the last row)."""
+    x_new = _f64(x_new)
+    B, D = x_new.shape[0], np.shape(q["V"])[1]
+    d_h = D // H
+    if scale is None or scale == 0:
+        scale = 1.0 / np.sqrt(d_h)
+    pq = rank_projection(x_new, q["U"])
+    pk_new = rank_projection(x_new, k["U"])
+    pv_new = rank_projection(x_new, v["U"])
+    out = np.empty((B, D), dtype=F64)
+    for b in range(B):
+        n = int(lens[b])
+        Pk = np.concatenate([_f64(Pk_cache[b, :n]), pk_new[b:b + 1]], axis=0)
+        Pv = np.concatenate([_f64(Pv_cache[b, :n]), pv_new[b:b + 1]], axis=0)
+        Qb = pq[b:b + 1] @ _f64(q["V"]) + (0.0 if q.get("b") is None else _f64(q["b"]))
+        Kb = Pk @ _f64(k["V"]) + (0.0 if k.get("b") is None else _f64(k["b"]))
+        Vb = Pv @ _f64(v["V"]) + (0.0 if v.get("b") is None else _f64(v["b"]))
+        C = np.empty((1, D), dtype=F64)
+        for h in range(H):
+            sl = slice(h * d_h, (h + 1) * d_h)
+            C[:, sl] = softmax_rows((Qb[:, sl] @ Kb[:, sl].T) * scale) @ Vb[:, sl]
+        out[b] = factored_linear(C, o)[0]
+    return out, pk_new, pv_new
 
 
 # ---------------------------------------------------------------------------

@@ -408,3 +408,57 @@ def test_spectrum_workload_matches_recipe():
     np.testing.assert_allclose(sv[:w.r_attn], s[:w.r_attn], rtol=2e-3)   # fp16 rounding of the factors
     assert sv[w.r_attn:].max() < 1e-3
     assert inp["key_len"].min() >= 1
+
+
+# ------------------------------------------------------------------ decoding step with a rank-space KV cache
+def _decode_setup(rng, B, t, D, H, r, bias=True):
+    fac = lambda: {"U": rng.standard_normal((D, r)) / np.sqrt(D), "V": rng.standard_normal((r, D)) / np.sqrt(r),
+                   "b": 0.3 * rng.standard_normal(D) if bias else None}
+    X = rng.standard_normal((B, t, D))
+    return X, fac(), fac(), fac(), fac()
+
+
+def test_decode_step_is_the_last_row_of_causal_attention_in_torch():
+    """Full-rank factors make the block a dense attention layer: the decoding step of token n against a cache of the n
+    earlier tokens must equal row n of torch's causal scaled-dot-product attention over the whole sequence."""
+    rng = np.random.default_rng(41)
+    B, t, D, H = 2, 9, 16, 2
+    Ws, bs, facs = {}, {}, {}
+    for n in "qkvo":
+        Ws[n], facs[n] = full_rank_factors(rng, D, D)
+        bs[n] = facs[n]["b"]
+    X = rng.standard_normal((B, t, D))
+    tt = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    heads = lambda n: TF.linear(tt(X), tt(Ws[n]).T, tt(bs[n])).view(B, t, H, D // H).transpose(1, 2)
+    c = TF.scaled_dot_product_attention(heads("q"), heads("k"), heads("v"), is_causal=True)
+    want = TF.linear(c.transpose(1, 2).reshape(B, t, D), tt(Ws["o"]).T, tt(bs["o"])).numpy()
+    Pk, Pv = X @ facs["k"]["U"], X @ facs["v"]["U"]
+    for n in (0, 3, t - 1):
+        got, pk_new, pv_new = O.decode_attention(X[:, n], Pk, Pv, [n] * B, facs["q"], facs["k"], facs["v"], facs["o"], H)
+        assert np.allclose(got, want[:, n], rtol=1e-9, atol=1e-10)
+        assert np.allclose(pk_new, Pk[:, n]) and np.allclose(pv_new, Pv[:, n])
+
+
+def test_decode_steps_rebuild_causal_attention_with_low_rank_factors_and_ragged_lengths():
+    """Token by token, feeding back the returned cache rows, the decoding steps give the rows of the (pinned) causal
+    attention block; cache rows past a sequence's length and a shift of b_k (a constant added to all of a query's scores)
+    change nothing; a shift of b_v moves the context by exactly that shift."""
+    rng = np.random.default_rng(42)
+    B, t, D, H, r = 3, 7, 24, 3, 5
+    X, q, k, v, o = _decode_setup(rng, B, t, D, H, r)
+    want = O.attention(X, q, k, v, o, H, causal=True)
+    Pk = np.full((B, t + 2, r), np.nan)      # unwritten rows must never be read
+    Pv = np.full((B, t + 2, r), np.nan)
+    for n in range(t):
+        got, pk_new, pv_new = O.decode_attention(X[:, n], Pk, Pv, [n] * B, q, k, v, o, H)
+        assert np.allclose(got, want[:, n], rtol=1e-9, atol=1e-10)
+        Pk[:, n], Pv[:, n] = pk_new, pv_new
+    lens = [2, 6, 0]                           # ragged: each sequence is at its own step
+    got, _, _ = O.decode_attention(X[np.arange(B), lens], Pk, Pv, lens, q, k, v, o, H)
+    assert np.allclose(got, want[np.arange(B), lens], rtol=1e-9, atol=1e-10)
+    k2 = dict(k, b=k["b"] + 0.7)
+    assert np.allclose(O.decode_attention(X[:, 4], Pk, Pv, [4] * B, q, k2, v, o, H)[0], want[:, 4], rtol=1e-9, atol=1e-10)
+    shift = rng.standard_normal(D)
+    v2 = dict(v, b=v["b"] + shift)
+    moved = O.decode_attention(X[:, 4], Pk, Pv, [4] * B, q, k, v2, o, H)[0]
+    assert np.allclose(moved - want[:, 4], (shift @ o["U"]) @ o["V"], rtol=1e-8, atol=1e-9)
