@@ -253,6 +253,50 @@ size_t fsvd_ffn_core_workspace(const fsvd_desc *desc, int32_t r_1, int32_t r_2);
 fsvd_status fsvd_ffn_core(const fsvd_desc *desc, const void *P1, const fsvd_factor *w1, const fsvd_factor *w2,
                           void *Z, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Decoding step against a rank-space KV cache (appendix on decoder models, "Prefill" / "Decoding Phase": the
+ * cache holds P_k = X U_k and P_v = X U_v, 2 t r scalars per sequence instead of 2 t D, and a step attends one new
+ * query to the cached rows).  Whole-matrix factors; desc->M is the cache capacity t_max (tokens per sequence),
+ * desc->causal, key_len, F, act and norm are ignored.  Limits: r_k % 64 == 0, r_v % 32 == 0, both <= 1024, H <= 32,
+ * V of k and v row-major; FSVD_ERR_UNSUPPORTED otherwise.
+ *
+ * The two caches are device buffers owned by the caller, in layouts private to the library (so that a cached block is
+ * a matrix-core operand as it lies in memory); fsvd_decode_kcache_bytes / fsvd_decode_vcache_bytes give their sizes
+ * (0 for invalid arguments).  A new cache must be ZERO-FILLED by the caller: positions never written are masked, but
+ * they must hold finite values.  Sequence b of a cache starts at b * (bytes / B).
+ *
+ * fsvd_decode_cache_write stores rows P_new [B, n_new, r] (fp16, row-major) at positions t_start[b] .. t_start[b] +
+ * n_new - 1 of sequence b (t_start: device int32[B]); which = 0 writes the K cache, 1 the V cache; rows that would fall
+ * at or beyond t_max are dropped.  It serves to load the result of a prefill; fsvd_decode_attention appends the new
+ * token's rows itself.
+ *
+ * fsvd_decode_attention, for every sequence b with t_len[b] cached tokens (device int32[B], 0 <= t_len[b] < t_max):
+ *   p_a = x_new[b] U_a for a in {q, k, v};  p_k, p_v are written to position t_len[b] of the caches;
+ *   per head h: scores_j = (p_q V_q + b_q)_h . (P_k[j] V_k + b_k)_h * softmax_scale for j = 0 .. t_len[b],
+ *   evaluated as P_k[j] . (V_k[:, h] q_h) (the b_k term is the same for every key and cancels in the softmax);
+ *   context_h = (sum_j a_j P_v[j]) V_v[:, h] + b_v[h];   out[b] = (context U_o) V_o + b_o.
+ * x_new [B, D] in io_dtype -> out [B, D] in out_dtype.  The caller advances t_len after the call.  K and V are never
+ * rebuilt; per sequence the step reads (t_len + 1) (r_k + r_v) 2 bytes of cache once for all heads.
+ * ------------------------------------------------------------------------------------------ */
+size_t fsvd_decode_kcache_bytes(int32_t B, int32_t t_max, int32_t r_k);
+size_t fsvd_decode_vcache_bytes(int32_t B, int32_t t_max, int32_t r_v);
+fsvd_status fsvd_decode_cache_write(int32_t B, int32_t t_max, int32_t r, int32_t n_new, const int32_t *t_start,
+                                    const void *P_new, int32_t which, void *cache, void *hip_stream);
+size_t fsvd_decode_attention_workspace(const fsvd_desc *desc, int32_t r_q, int32_t r_k, int32_t r_v, int32_t r_o);
+fsvd_status fsvd_decode_attention(const fsvd_desc *desc, const void *x_new, const fsvd_factor *q, const fsvd_factor *k,
+                                  const fsvd_factor *v, const fsvd_factor *o, void *kcache, void *vcache,
+                                  const int32_t *t_len, void *out, void *workspace, size_t workspace_bytes,
+                                  void *hip_stream);
+/* Building block: the pass over the cache alone.  W: the absorbed queries, per sequence the fragment-major layout of
+ * a [32, r_k] fp16 matrix whose row h < H is softmax_scale * log2(e) * V_k[:, head h] q_h (rows >= H are ignored);
+ * n_keys: device int32[B], the number of valid cached keys per sequence (1 .. t_max);
+ * u_out [B, H, r_v] fp32 = sum_j a_j P_v[j] per head.  The keys of a sequence are split over several workgroups whose
+ * partial results (fp16 sums, fp32 softmax statistics) pass through `workspace` and are merged in a fixed order. */
+size_t fsvd_decode_core_workspace(const fsvd_desc *desc, int32_t r_k, int32_t r_v);
+fsvd_status fsvd_decode_attention_core(const fsvd_desc *desc, int32_t r_k, int32_t r_v, const void *W,
+                                       const void *kcache, const void *vcache, const int32_t *n_keys, void *u_out,
+                                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Y[T, D] = gamma (X - mean) / sqrt(var + eps) + beta per row; X in x_dtype, gamma / beta in p_dtype,
  * Y in y_dtype (any of F16, BF16, F32).  D <= 8192, D % 8 == 0. */
 fsvd_status fsvd_layernorm(int32_t T, int32_t D, const void *X, fsvd_dtype x_dtype, const void *gamma,

@@ -30,7 +30,9 @@ EXPORTS = ["fsvd_attention_workspace", "fsvd_ffn_workspace", "fsvd_layer_workspa
            "fsvd_ffn_check", "fsvd_attention", "fsvd_attention_heads", "fsvd_attention_heads_workspace", "fsvd_ffn",
            "fsvd_layer", "fsvd_layer_heads", "fsvd_layer_heads_workspace", "fsvd_linear", "fsvd_attention_core", "fsvd_attention_heads_core",
            "fsvd_ffn_core", "fsvd_ffn_core_workspace", "fsvd_layernorm", "fsvd_status_string", "fsvd_version", "fsvd_fm_bytes", "fsvd_pack_fm",
-           "fsvd_unpack_fm", "fsvd_tiled_bytes", "fsvd_pack_tiled", "fsvd_linear_tiled"]
+           "fsvd_unpack_fm", "fsvd_tiled_bytes", "fsvd_pack_tiled", "fsvd_linear_tiled", "fsvd_decode_kcache_bytes",
+           "fsvd_decode_vcache_bytes", "fsvd_decode_cache_write", "fsvd_decode_attention_workspace", "fsvd_decode_attention",
+           "fsvd_decode_core_workspace", "fsvd_decode_attention_core"]
 
 
 class FsvdError(RuntimeError):
@@ -112,6 +114,20 @@ def lib():
         L.fsvd_tiled_bytes.argtypes = [i32, i32]
         L.fsvd_pack_tiled.restype = C.c_int
         L.fsvd_pack_tiled.argtypes = [i32, i32, P, C.c_int, P, P]
+        L.fsvd_decode_kcache_bytes.restype = sz
+        L.fsvd_decode_kcache_bytes.argtypes = [i32, i32, i32]
+        L.fsvd_decode_vcache_bytes.restype = sz
+        L.fsvd_decode_vcache_bytes.argtypes = [i32, i32, i32]
+        L.fsvd_decode_cache_write.restype = C.c_int
+        L.fsvd_decode_cache_write.argtypes = [i32, i32, i32, i32, P, P, i32, P, P]
+        L.fsvd_decode_attention_workspace.restype = sz
+        L.fsvd_decode_attention_workspace.argtypes = [D, i32, i32, i32, i32]
+        L.fsvd_decode_attention.restype = C.c_int
+        L.fsvd_decode_attention.argtypes = [D, P, F, F, F, F, P, P, P, P, P, sz, P]
+        L.fsvd_decode_core_workspace.restype = sz
+        L.fsvd_decode_core_workspace.argtypes = [D, i32, i32]
+        L.fsvd_decode_attention_core.restype = C.c_int
+        L.fsvd_decode_attention_core.argtypes = [D, i32, i32, P, P, P, P, P, P, sz, P]
         L.fsvd_status_string.restype = C.c_char_p
         L.fsvd_status_string.argtypes = [C.c_int]
         L.fsvd_version.restype = i32
@@ -397,6 +413,60 @@ def fsvd_layernorm(X, gamma, beta, eps, out_dtype=torch.float32, out=None):
 # which matrices of which projection the library accepts as tile images: name -> (U, V)
 TILED_OK = {n: (True, True) for n in ("q", "k", "v", "o", "w1", "w2")}
 TILED_OK_HEADS = {n: (True, False) for n in ("q", "k", "v")}          # per-head factors: V [H, r, d_h] stays row-major
+
+
+# ---------------------------------------------------------------------------------------------
+# decoding step against a rank-space KV cache
+# ---------------------------------------------------------------------------------------------
+
+def fsvd_decode_new_caches(B: int, t_max: int, r_k: int, r_v: int, device="cuda:0"):
+    """Zero-filled K and V caches (uint8 tensors) of the sizes the library asks for."""
+    nk, nv = lib().fsvd_decode_kcache_bytes(B, t_max, r_k), lib().fsvd_decode_vcache_bytes(B, t_max, r_v)
+    if not nk or not nv:
+        raise FsvdError(2, "fsvd_decode_*cache_bytes")
+    return (torch.zeros(nk, dtype=torch.uint8, device=device), torch.zeros(nv, dtype=torch.uint8, device=device))
+
+
+def fsvd_decode_cache_write(cache, which: int, t_max: int, P_new, t_start):
+    """P_new [B, n_new, r] fp16 -> positions t_start[b].. of the K (which = 0) or V (which = 1) cache."""
+    B, n_new, r = P_new.shape
+    assert P_new.dtype == torch.float16 and t_start.dtype == torch.int32
+    _check(lib().fsvd_decode_cache_write(B, t_max, r, n_new, _ptr(t_start), _ptr(P_new), which, _ptr(cache), _stream()),
+           "fsvd_decode_cache_write")
+
+
+def fsvd_decode_attention_workspace(desc, r_q, r_k, r_v, r_o) -> int:
+    return lib().fsvd_decode_attention_workspace(C.byref(desc), r_q, r_k, r_v, r_o)
+
+
+def fsvd_decode_attention(desc, x_new, q: Factor, k: Factor, v: Factor, o: Factor, kcache, vcache, t_len, out=None,
+                          workspace=None):
+    """One decoding step: x_new [B, D], t_len int32 [B] (tokens already cached) -> out [B, D]; appends to the caches."""
+    if out is None:
+        out = torch.empty((desc.B, desc.D), dtype=_out_dtype(desc), device=x_new.device)
+    if workspace is None:
+        workspace = _workspace(fsvd_decode_attention_workspace(desc, q.rank, k.rank, v.rank, o.rank), x_new.device)
+    fq, fk, fv, fo = q.c(), k.c(), v.c(), o.c()
+    _check(lib().fsvd_decode_attention(C.byref(desc), _ptr(x_new), C.byref(fq), C.byref(fk), C.byref(fv), C.byref(fo),
+                                       _ptr(kcache), _ptr(vcache), _ptr(t_len), _ptr(out), _ptr(workspace),
+                                       workspace.numel(), _stream()), "fsvd_decode_attention")
+    return out
+
+
+def fsvd_decode_core_workspace(desc, r_k, r_v) -> int:
+    return lib().fsvd_decode_core_workspace(C.byref(desc), r_k, r_v)
+
+
+def fsvd_decode_attention_core(desc, r_k, r_v, W, kcache, vcache, n_keys, out=None, workspace=None):
+    """The pass over the cache alone: absorbed queries W (fragment-major [32, r_k] per sequence) -> u [B, H, r_v] fp32."""
+    if out is None:
+        out = torch.empty((desc.B, desc.H, r_v), dtype=torch.float32, device=W.device)
+    if workspace is None:
+        workspace = _workspace(fsvd_decode_core_workspace(desc, r_k, r_v), W.device)
+    _check(lib().fsvd_decode_attention_core(C.byref(desc), r_k, r_v, _ptr(W), _ptr(kcache), _ptr(vcache), _ptr(n_keys),
+                                            _ptr(out), _ptr(workspace), workspace.numel(), _stream()),
+           "fsvd_decode_attention_core")
+    return out
 
 
 def to_device(inp: dict, device="cuda:0", tiled: bool = False):

@@ -500,6 +500,153 @@ fsvd_status fsvd_ffn_core(const fsvd_desc* d, const void* P1, const fsvd_factor*
   return FSVD_OK;
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// Decoding step against a rank-space KV cache
+// ------------------------------------------------------------------------------------------------------------
+namespace {
+int decode_nsplit(int B) {          // parts the keys of one sequence are split into: about one workgroup per compute unit
+  int n = 256 / (B > 0 ? B : 1);
+  return n < 1 ? 1 : (n > 32 ? 32 : n);
+}
+fsvd_status check_decode_shape(const fsvd_desc* d, int r_k, int r_v) {
+  if (!d || d->M <= 0) return FSVD_ERR_INVALID_ARG;
+  fsvd_desc one = *d;      // M is the cache capacity here, not a dimension of a [B, M, D] tensor: the tensors are [B, D]
+  one.M = 1;
+  FSVD_TRY(check_desc(&one, false));
+  if (r_k <= 0 || r_v <= 0) return FSVD_ERR_INVALID_ARG;
+  if (r_k % 64 != 0 || r_v % 32 != 0 || r_k > 1024 || r_v > 1024 || d->H > 32) return FSVD_ERR_UNSUPPORTED;
+  if (fm_bytes(d->M, r_k) >= ((size_t)1 << 31) || decode_vcache_seq_bytes(d->M, r_v) >= ((size_t)1 << 31)) return FSVD_ERR_UNSUPPORTED;
+  return FSVD_OK;
+}
+struct DecodeCorePlan { size_t stats, upart, total; int nsplit; };
+DecodeCorePlan plan_decode_core(int B, int r_v) {
+  DecodeCorePlan pl;
+  pl.nsplit = decode_nsplit(B);
+  pl.stats = 0;
+  pl.upart = align_up((size_t)B * pl.nsplit * 64 * 4);
+  pl.total = pl.upart + align_up((size_t)B * pl.nsplit * r_v * 32 * 2);
+  return pl;
+}
+struct DecodePlan { size_t pq, pk, pv, qf, w, nk, u, ctx, to, core, total; };
+DecodePlan plan_decode(const fsvd_desc* d, int rq, int rk, int rv, int ro) {
+  const size_t B = d->B, D = d->D;
+  DecodePlan pl;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t at = off; off += align_up(bytes); return at; };
+  pl.pq = take(B * rq * 2); pl.pk = take(B * rk * 2); pl.pv = take(B * rv * 2);
+  pl.qf = take(B * D * 2);
+  pl.w = take(B * (size_t)((rk + 63) / 64) * 4096);
+  pl.nk = take(B * 4);
+  pl.u = take(B * d->H * (size_t)rv * 4);
+  pl.ctx = take(B * D * 2);
+  pl.to = take(B * ro * 2);
+  pl.core = take(plan_decode_core(d->B, rv).total);
+  pl.total = off;
+  return pl;
+}
+fsvd_status run_decode_core(const fsvd_desc* d, int r_k, int r_v, const void* W, const void* kc, const void* vc,
+                            const int32_t* n_keys, float* u_out, char* ws, hipStream_t s) {
+  const DecodeCorePlan pl = plan_decode_core(d->B, r_v);
+  DecodeCoreArgs ca{};
+  ca.W = W; ca.kcache = kc; ca.vcache = vc; ca.n_keys = n_keys;
+  ca.B = d->B; ca.t_max = d->M; ca.r_k = r_k; ca.r_v = r_v; ca.nsplit = pl.nsplit;
+  ca.stats = (float*)(ws + pl.stats); ca.upart = (_Float16*)(ws + pl.upart);
+  FSVD_HIP(launch_decode_core(ca, s));
+  FSVD_HIP(launch_decode_merge(ca.stats, ca.upart, d->B, pl.nsplit, d->H, r_v, u_out, s));
+  return FSVD_OK;
+}
+}  // namespace
+
+size_t fsvd_decode_kcache_bytes(int32_t B, int32_t t_max, int32_t r_k) {
+  if (B <= 0 || t_max <= 0 || r_k <= 0 || r_k % 64 != 0) return 0;
+  return (size_t)B * fm_bytes(t_max, r_k);
+}
+size_t fsvd_decode_vcache_bytes(int32_t B, int32_t t_max, int32_t r_v) {
+  if (B <= 0 || t_max <= 0 || r_v <= 0 || r_v % 32 != 0) return 0;
+  return (size_t)B * decode_vcache_seq_bytes(t_max, r_v);
+}
+fsvd_status fsvd_decode_cache_write(int32_t B, int32_t t_max, int32_t r, int32_t n_new, const int32_t* t_start, const void* P_new,
+                                    int32_t which, void* cache, void* stream) {
+  if (B <= 0 || t_max <= 0 || r <= 0 || n_new <= 0 || !t_start || !P_new || !cache || (which != 0 && which != 1)) return FSVD_ERR_INVALID_ARG;
+  if (mis16(P_new) || mis16(cache)) return FSVD_ERR_INVALID_ARG;
+  if (r % (which == 0 ? 64 : 32) != 0) return FSVD_ERR_UNSUPPORTED;
+  if ((size_t)B * n_new * r >= ((size_t)1 << 31)) return FSVD_ERR_UNSUPPORTED;
+  FSVD_HIP(launch_decode_cache_write(P_new, t_start, B, t_max, r, n_new, which, cache, (hipStream_t)stream));
+  return FSVD_OK;
+}
+
+size_t fsvd_decode_core_workspace(const fsvd_desc* d, int32_t r_k, int32_t r_v) {
+  if (check_decode_shape(d, r_k, r_v) != FSVD_OK) return 0;
+  return plan_decode_core(d->B, r_v).total;
+}
+fsvd_status fsvd_decode_attention_core(const fsvd_desc* d, int32_t r_k, int32_t r_v, const void* W, const void* kcache,
+                                       const void* vcache, const int32_t* n_keys, void* u_out, void* ws, size_t ws_bytes,
+                                       void* stream) {
+  FSVD_TRY(check_decode_shape(d, r_k, r_v));
+  if (!W || !kcache || !vcache || !n_keys || !u_out) return FSVD_ERR_INVALID_ARG;
+  if (mis16(W) || mis16(kcache) || mis16(vcache) || mis16(u_out)) return FSVD_ERR_INVALID_ARG;
+  FSVD_TRY(check_ws(ws, ws_bytes, plan_decode_core(d->B, r_v).total));
+  return run_decode_core(d, r_k, r_v, W, kcache, vcache, n_keys, (float*)u_out, (char*)ws, (hipStream_t)stream);
+}
+
+size_t fsvd_decode_attention_workspace(const fsvd_desc* d, int32_t rq, int32_t rk, int32_t rv, int32_t ro) {
+  if (check_decode_shape(d, rk, rv) != FSVD_OK) return 0;
+  if (check_rank(rq) || check_rank(ro)) return 0;
+  return plan_decode(d, rq, rk, rv, ro).total;
+}
+fsvd_status fsvd_decode_attention(const fsvd_desc* d, const void* x_new, const fsvd_factor* q, const fsvd_factor* k,
+                                  const fsvd_factor* v, const fsvd_factor* o, void* kcache, void* vcache,
+                                  const int32_t* t_len, void* out, void* ws, size_t ws_bytes, void* stream) {
+  if (!d) return FSVD_ERR_INVALID_ARG;
+  {
+    fsvd_desc one = *d;
+    one.M = 1;
+    FSVD_TRY(check_attn(&one, q, k, v, o, true));
+  }
+  FSVD_TRY(check_decode_shape(d, k->rank, v->rank));
+  if (k->v_layout != FSVD_ROW_MAJOR || v->v_layout != FSVD_ROW_MAJOR) return FSVD_ERR_UNSUPPORTED;   // read row by row here
+  if (!x_new || !kcache || !vcache || !t_len || !out) return FSVD_ERR_INVALID_ARG;
+  if (mis16(x_new) || mis16(kcache) || mis16(vcache) || mis16(out)) return FSVD_ERR_INVALID_ARG;
+  const DecodePlan pl = plan_decode(d, q->rank, k->rank, v->rank, o->rank);
+  FSVD_TRY(check_ws(ws, ws_bytes, pl.total));
+  char* w = (char*)ws;
+  hipStream_t s = (hipStream_t)stream;
+  const int B = d->B, D = d->D;
+
+  LinearArgs p{};       // rank projections of the new tokens, row-major fp16
+  p.A = x_new; p.a_layout = LAYOUT_ROW; p.lda = D; p.a_dt = d->io_dtype; p.T = B; p.K = D; p.w_dt = d->io_dtype;
+  p.w_tiled = q->u_layout == FSVD_TILED; p.c_layout = LAYOUT_ROW; p.c_dt = DT_F16; p.ngroups = 3;
+  p.g[0] = {q->U, nullptr, w + pl.pq, q->rank, q->rank, q->rank};
+  p.g[1] = {k->U, nullptr, w + pl.pk, k->rank, k->rank, k->rank};
+  p.g[2] = {v->U, nullptr, w + pl.pv, v->rank, v->rank, v->rank};
+  FSVD_HIP(launch_linear(p, s));
+  FSVD_HIP(launch_decode_cache_write(w + pl.pk, t_len, B, d->M, k->rank, 1, 0, kcache, s));
+  FSVD_HIP(launch_decode_cache_write(w + pl.pv, t_len, B, d->M, v->rank, 1, 1, vcache, s));
+  FSVD_HIP(launch_decode_count(t_len, B, (int32_t*)(w + pl.nk), s));
+
+  LinearArgs qa{};      // the new queries at full width, fp16
+  qa.A = w + pl.pq; qa.a_layout = LAYOUT_ROW; qa.lda = q->rank; qa.a_dt = DT_F16; qa.T = B; qa.K = q->rank; qa.w_dt = d->io_dtype;
+  qa.w_tiled = q->v_layout == FSVD_TILED; qa.c_layout = LAYOUT_ROW; qa.c_dt = DT_F16; qa.ngroups = 1;
+  qa.g[0] = {q->V, q->bias, w + pl.qf, D, D, D};
+  FSVD_HIP(launch_linear(qa, s));
+  FSVD_HIP(launch_decode_absorb(w + pl.qf, k->V, d->io_dtype, B, D, d->H, k->rank, resolve_scale(d), w + pl.w, s));
+  FSVD_TRY(run_decode_core(d, k->rank, v->rank, w + pl.w, kcache, vcache, (const int32_t*)(w + pl.nk), (float*)(w + pl.u),
+                           w + pl.core, s));
+  FSVD_HIP(launch_decode_value((const float*)(w + pl.u), v->V, v->bias, d->io_dtype, B, D, d->H, v->rank, w + pl.ctx, s));
+
+  LinearArgs oa{};      // factored output projection
+  oa.A = w + pl.ctx; oa.a_layout = LAYOUT_ROW; oa.lda = D; oa.a_dt = DT_F16; oa.T = B; oa.K = D; oa.w_dt = d->io_dtype;
+  oa.w_tiled = o->u_layout == FSVD_TILED; oa.c_layout = LAYOUT_ROW; oa.c_dt = DT_F16; oa.ngroups = 1;
+  oa.g[0] = {o->U, nullptr, w + pl.to, o->rank, o->rank, o->rank};
+  FSVD_HIP(launch_linear(oa, s));
+  LinearArgs ob{};
+  ob.A = w + pl.to; ob.a_layout = LAYOUT_ROW; ob.lda = o->rank; ob.a_dt = DT_F16; ob.T = B; ob.K = o->rank; ob.w_dt = d->io_dtype;
+  ob.w_tiled = o->v_layout == FSVD_TILED; ob.c_layout = LAYOUT_ROW; ob.c_dt = d->out_dtype; ob.ngroups = 1;
+  ob.g[0] = {o->V, o->bias, out, D, D, D};
+  FSVD_HIP(launch_linear(ob, s));
+  return FSVD_OK;
+}
+
 fsvd_status fsvd_layernorm(int32_t T, int32_t D, const void* X, fsvd_dtype x_dtype, const void* gamma, const void* beta,
                            fsvd_dtype p_dtype, float eps, void* Y, fsvd_dtype y_dtype, void* stream) {
   if (T <= 0 || D <= 0 || !X || !gamma || !beta || !Y) return FSVD_ERR_INVALID_ARG;

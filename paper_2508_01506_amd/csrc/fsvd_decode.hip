@@ -1,0 +1,365 @@
+// Decoding step against a rank-space KV cache (appendix on decoder models, "Decoding Phase"): one new query per
+// sequence attends to the cached rank-space keys and values P_k [t, r_k], P_v [t, r_v] - K and V are never rebuilt.
+//
+// With q_h = (p_q V_q + b_q)[head h] the score of key j is  q_h . (P_k[j] V_k[:, h] + b_k[h]) =  P_k[j] . w_h + const,
+// w_h = V_k[:, h] q_h in R^{r_k} ("absorbed" query; the constant q_h . b_k is the same for every key of the row and
+// drops out of the softmax), and the context is  sum_j a_j (P_v[j] V_v[:, h] + b_v[h]) = u_h V_v[:, h] + b_v[h] with
+// u_h = sum_j a_j P_v[j] in R^{r_v} (the a_j sum to one).  So the step is two passes over the cache with H vectors on
+// each side: S = P_k W^T and U = A P_v, both small matrix products per sequence.  Per sequence and step the kernel
+// reads t (r_k + r_v) 2 bytes of cache once for all heads: it is bound by HBM, not by the matrix cores.
+//
+// Cache layouts (chosen so that a wavefront-wide 16-byte load of 64 consecutive units IS an MFMA operand):
+//   K cache, per sequence: the fragment-major layout (fsvd_common.h) of P_k [t_max, r_k].
+//   V cache, per sequence: P_v^T in operand order of the U product: for rank tile R = rank / 32 and key tile J = key / 32
+//     a 2 KiB block at (R * ceil(t_max / 32) + J) * 2048; inside, unit s * 64 + 32 g + (rank % 32) (16 bytes, s = 0..1,
+//     g = 0..1) holds the 8 keys 32 J + 16 s + 4 g + {0, 1, 2, 3, 8, 9, 10, 11} of that rank - the contraction-slot
+//     order in which the probabilities leave the score accumulators, so they feed the U product without any shuffle.
+// Positions that were never written must hold finite values (the caller zero-fills a new cache): masked keys get
+// probability exactly 0, and 0 times a non-finite value would not be 0.
+#include "fsvd_common.h"
+#include "fsvd_kernels.h"
+
+namespace fsvd {
+
+namespace {
+
+constexpr float kLog2eD = 1.4426950408889634f;
+
+// ---------------------------------------------------------------------------------------------------------------
+// Cache write: rows P_new [B, n_new, r] (fp16, row-major) -> positions t_start[b] .. of sequence b.  which = 0: K cache
+// (one thread per 16-byte unit), which = 1: V cache (one thread per element).  Rows that would fall past t_max are dropped.
+// ---------------------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) decode_cache_write_kernel(const _Float16* __restrict__ src, const int32_t* __restrict__ t_start,
+                                                                 int B, int t_max, int r, int n_new, int which, _Float16* cache,
+                                                                 size_t seq_halves, size_t total) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  if (which == 0) {
+    const int groups = r / 8;
+    const int rho = 8 * (int)(i % groups);
+    const size_t row = i / groups;
+    const int n = (int)(row % n_new), b = (int)(row / n_new);
+    const int t = t_start[b] + n;
+    if (t < 0 || t >= t_max) return;
+    const int kch = (r + 63) / 64, off = rho & 63;
+    const size_t unit = ((size_t)((t >> 5) * kch + (rho >> 6)) * 4 + ((off >> 3) & 3)) * 64 + (off >> 5) * 32 + (t & 31);
+    *(h8*)(cache + b * seq_halves + unit * 8) = *(const h8*)(src + row * r + rho);
+  } else {
+    const int rho = (int)(i % r);
+    const size_t row = i / r;
+    const int n = (int)(row % n_new), b = (int)(row / n_new);
+    const int t = t_start[b] + n;
+    if (t < 0 || t >= t_max) return;
+    const int ktiles = (t_max + 31) / 32, kq = t & 31, o = kq & 15;
+    const size_t unit = ((size_t)((rho >> 5) * ktiles + (t >> 5)) * 2 + (kq >> 4)) * 64 + ((o >> 2) & 1) * 32 + (rho & 31);
+    cache[b * seq_halves + unit * 8 + (o & 3) + 4 * (o >> 3)] = src[row * r + rho];
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// Absorbed queries: W[b, h, rho] = scale log2(e) * sum_d V_k[rho, h d_h + d] * q[b, h d_h + d], written as the
+// fragment-major layout of a [32 (heads, padded), r_k] matrix per sequence (columns of heads >= H are left untouched:
+// their scores are never used).  One workgroup per (64 ranks, head): V_k is read once for the whole batch.
+// ---------------------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) decode_absorb_kernel(const _Float16* __restrict__ q, const void* __restrict__ Vk, int w_dt,
+                                                            int B, int D, int H, int r_k, float qs, _Float16* W) {
+  __shared__ float qh[64][128];              // up to 64 sequences x d_h at a time
+  const int dh = D / H, c = blockIdx.x, h = blockIdx.y;
+  const int rl = threadIdx.x >> 2, part = threadIdx.x & 3, dq = dh / 4;
+  const int rho = 64 * c + rl;
+  float vk[32];
+#pragma unroll
+  for (int i = 0; i < 32; ++i) vk[i] = (i < dq && rho < r_k) ? load_param(Vk, (size_t)rho * D + h * dh + part * dq + i, w_dt) : 0.f;
+  const size_t w_seq = (size_t)((r_k + 63) / 64) * 2048;   // halves per sequence
+  const int off = rl, g = off >> 5, kk = (off >> 3) & 3;
+  for (int b0 = 0; b0 < B; b0 += 64) {
+    const int nb = B - b0 < 64 ? B - b0 : 64;
+    __syncthreads();
+    for (int i = threadIdx.x; i < nb * dh; i += 256) qh[i / dh][i % dh] = (float)q[(size_t)(b0 + i / dh) * D + h * dh + i % dh];
+    __syncthreads();
+    for (int b = 0; b < nb; ++b) {
+      float s = 0.f;
+#pragma unroll
+      for (int i = 0; i < 32; ++i)
+        if (i < dq) s = fmaf(vk[i], qh[b][part * dq + i], s);
+      s += __shfl_xor(s, 1, 64);
+      s += __shfl_xor(s, 2, 64);
+      if (part == 0 && rho < r_k)
+        W[(size_t)(b0 + b) * w_seq + (size_t)c * 2048 + (kk * 64 + 32 * g + h) * 8 + (off & 7)] = (_Float16)(s * qs);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// The pass over the cache.  One workgroup (8 wavefronts) = one sequence x one part of its keys, all heads at once.
+// Per tile of 32 keys:
+//   S^T [32 keys, 32 heads] = P_k tile x W^T: the contraction over r_k is split over the wavefronts (64-rank chunks
+//   w, w + 8, ..), the partial tiles are exchanged through LDS and every wavefront ends up with the whole tile;
+//   mask, streaming softmax per head (head = lane; statistics are per-lane scalars, as in the prefill kernel);
+//   U^T [r_v, 32 heads] += (P_v^T tile) x A^T: every wavefront owns the rank tiles w, w + 8, .. of U.
+// Operands of the next key tile are requested before the current tile is computed (16 KiB per wavefront in flight).
+// NCK: 64-rank chunks of r_k per wavefront (r_k <= 512 NCK); NVT: 32-rank tiles of r_v per wavefront (r_v <= 256 NVT).
+// Output per (sequence, part): the running maximum m and sum l per head, and U / l in fp16, [r_v][32 heads].
+// ---------------------------------------------------------------------------------------------------------------
+template <int NCK, int NVT>
+__global__ void __launch_bounds__(512, 1) decode_core_kernel(DecodeCoreArgs a) {
+  __shared__ __attribute__((aligned(16))) h8 wlds[NCK * 8 * 4][64];      // absorbed queries, fragment-major
+  __shared__ __attribute__((aligned(16))) f4v sx[2][8][4][64];           // partial score tiles [parity][wavefront][quad][lane]
+
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int b = blockIdx.x / a.nsplit, sp = blockIdx.x % a.nsplit;
+  const int kch = (a.r_k + 63) / 64, vtl = (a.r_v + 31) / 32, ktiles = (a.t_max + 31) / 32;
+  int n = a.n_keys[b];
+  n = n < 0 ? 0 : (n > a.t_max ? a.t_max : n);
+  const int ntiles = (n + 31) / 32;
+  const int tps = (ntiles + a.nsplit - 1) / a.nsplit;
+  const int j0 = sp * tps, j1 = (j0 + tps < ntiles) ? j0 + tps : ntiles;
+
+  float m_run = -1e30f, l_run = 0.f;
+  f16v u[NVT];
+#pragma unroll
+  for (int i = 0; i < NVT; ++i) u[i] = zero16();
+
+  if (j0 < j1) {
+    // absorbed queries of this sequence -> LDS (fragment-major bytes as they lie)
+    {
+      const u4* src = (const u4*)((const char*)a.W + (size_t)b * kch * 4096);
+      for (int i = tid; i < kch * 256; i += 512) ((u4*)wlds)[i] = src[i];
+    }
+    const long long k_total = (long long)fm_bytes(a.t_max, a.r_k);
+    const long long v_total = (long long)vtl * ktiles * 2048;
+    const char* kbase = (const char*)a.kcache + (size_t)b * k_total;
+    const char* vbase = (const char*)a.vcache + (size_t)b * v_total;
+    h8 kf[NCK][4], vf[NVT][2], kn[NCK][4], vn[NVT][2];
+    auto request = [&](int j, h8 (&kd)[NCK][4], h8 (&vd)[NVT][2]) {
+#pragma unroll
+      for (int i = 0; i < NCK; ++i) {
+        const int c = wave + 8 * i;                       // chunks past r_k: resource of size 0 -> zeros
+        const rsrc_t r = rsrc_at(kbase, c < kch ? k_total : 0, ((long long)j * kch + c) * kFmChunkBytes);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) kd[i][kk] = __builtin_bit_cast(h8, buf_load16(r, kk * kFmStepBytes + lane * 16));
+      }
+#pragma unroll
+      for (int i = 0; i < NVT; ++i) {
+        const int rt = wave + 8 * i;
+        const rsrc_t r = rsrc_at(vbase, rt < vtl ? v_total : 0, ((long long)rt * ktiles + j) * 2048);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) vd[i][s] = __builtin_bit_cast(h8, buf_load16(r, s * 1024 + lane * 16));
+      }
+    };
+    request(j0, kf, vf);
+    __syncthreads();
+    int par = 0;
+    for (int j = j0; j < j1; ++j) {
+      request(j + 1 < j1 ? j + 1 : j, kn, vn);            // the last tile is requested twice; nothing is read out of range
+      // ---- partial scores of this wavefront's rank chunks
+      f16v sp_ = zero16();
+#pragma unroll
+      for (int i = 0; i < NCK; ++i)
+        if (wave + 8 * i < kch) {                          // wave-uniform; LDS past the last chunk was never written
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) sp_ = mfma32(kf[i][kk], wlds[(wave + 8 * i) * 4 + kk][lane], sp_);   // rows keys, cols heads
+        }
+#pragma unroll
+      for (int qd = 0; qd < 4; ++qd) {
+        f4v t;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t[e] = sp_[4 * qd + e];
+        sx[par][wave][qd][lane] = t;
+      }
+      __syncthreads();
+      f16v s = zero16();
+#pragma unroll
+      for (int w2 = 0; w2 < 8; ++w2)                       // the same order in every wavefront: identical sums
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+          const f4v t = sx[par][w2][qd][lane];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) s[4 * qd + e] += t[e];
+        }
+      par ^= 1;
+      // ---- mask, streaming softmax (log2 domain; W carries scale * log2 e)
+      const int key0 = 32 * j;
+      if (key0 + 32 > n) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (key0 + 8 * (v >> 2) + 4 * g + (v & 3) >= n) s[v] = -INFINITY;
+      }
+      float mx = s[0];
+#pragma unroll
+      for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[v]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      if (__any(mx > m_run + 8.0f)) {                      // lazily raised reference maximum, as in the prefill kernel
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int i = 0; i < NVT; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) u[i][v] *= alpha;
+      }
+      float sum = 0.f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float p = __builtin_amdgcn_exp2f(s[v] - m_run);
+        s[v] = p;
+        sum += p;
+      }
+      l_run += sum;
+      h8 pf[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pf[t][e] = (_Float16)s[8 * t + e];
+      // ---- U^T += P_v^T tile x A^T for this wavefront's rank tiles
+#pragma unroll
+      for (int i = 0; i < NVT; ++i)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) u[i] = mfma32(vf[i][t], pf[t], u[i]);   // rows ranks, cols heads
+#pragma unroll
+      for (int i = 0; i < NCK; ++i)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) kf[i][kk] = kn[i][kk];
+#pragma unroll
+      for (int i = 0; i < NVT; ++i)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) vf[i][t] = vn[i][t];
+    }
+  }
+
+  // ---- partial results of this part
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const size_t slot = (size_t)b * a.nsplit + sp;
+  if (wave == 0 && g == 0) {
+    a.stats[slot * 64 + l32] = m_run;
+    a.stats[slot * 64 + 32 + l32] = l_tot;
+  }
+  if (j0 < j1) {
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    _Float16* up = a.upart + slot * (size_t)a.r_v * 32;
+#pragma unroll
+    for (int i = 0; i < NVT; ++i) {
+      const int rt = wave + 8 * i;
+      if (rt < vtl) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int rank = 32 * rt + 8 * (v >> 2) + 4 * g + (v & 3);
+          if (rank < a.r_v) up[(size_t)rank * 32 + l32] = (_Float16)(u[i][v] * inv);
+        }
+      }
+    }
+  }
+}
+
+// merge the parts of one (sequence, head): u[b, h, :] = sum_s wgt_s U_s / sum_s wgt_s, wgt_s = l_s 2^(m_s - max m)
+__global__ void __launch_bounds__(256) decode_merge_kernel(const float* __restrict__ stats, const _Float16* __restrict__ upart,
+                                                           int nsplit, int H, int r_v, float* u_out) {
+  const int h = blockIdx.x, b = blockIdx.y;
+  const size_t slot0 = (size_t)b * nsplit;
+  float M = -1e30f;
+  for (int s = 0; s < nsplit; ++s)
+    if (stats[(slot0 + s) * 64 + 32 + h] > 0.f) M = fmaxf(M, stats[(slot0 + s) * 64 + h]);
+  float tot = 0.f;
+  for (int s = 0; s < nsplit; ++s) {
+    const float l = stats[(slot0 + s) * 64 + 32 + h];
+    if (l > 0.f) tot += l * exp2f(stats[(slot0 + s) * 64 + h] - M);
+  }
+  const float inv = tot > 0.f ? 1.0f / tot : 0.f;
+  for (int rho = threadIdx.x; rho < r_v; rho += 256) {
+    float acc = 0.f;
+    for (int s = 0; s < nsplit; ++s) {                       // fixed order
+      const float l = stats[(slot0 + s) * 64 + 32 + h];
+      if (l > 0.f) acc += l * exp2f(stats[(slot0 + s) * 64 + h] - M) * (float)upart[((slot0 + s) * r_v + rho) * 32 + h];
+    }
+    u_out[((size_t)b * H + h) * r_v + rho] = acc * inv;
+  }
+}
+
+// context[b, h d_h + d] = sum_rho u[b, h, rho] V_v[rho, h d_h + d] + b_v[h d_h + d], fp16 row-major [B, D].
+// One workgroup per head: the head's columns of V_v are read once for the whole batch (16 sequences at a time).
+__global__ void __launch_bounds__(256) decode_value_kernel(const float* __restrict__ u, const void* __restrict__ Vv, const void* __restrict__ bv,
+                                                           int w_dt, int B, int D, int H, int r_v, _Float16* ctx) {
+  __shared__ float red[4][16][128];
+  const int dh = D / H, h = blockIdx.x;
+  const int groups = 256 / dh;                 // 2 (d_h = 128) or 4 (d_h = 64)
+  const int d = threadIdx.x % dh, grp = threadIdx.x / dh;
+  for (int b0 = 0; b0 < B; b0 += 16) {
+    const int nb = B - b0 < 16 ? B - b0 : 16;
+    float acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    for (int rho = grp; rho < r_v; rho += groups) {
+      const float w = load_param(Vv, (size_t)rho * D + h * dh + d, w_dt);
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if (i < nb) acc[i] = fmaf(u[((size_t)(b0 + i) * H + h) * r_v + rho], w, acc[i]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) red[grp][i][d] = acc[i];
+    __syncthreads();
+    if (grp == 0) {
+      const float bias = bv ? load_param(bv, (size_t)h * dh + d, w_dt) : 0.f;
+      for (int i = 0; i < nb; ++i) {
+        float s = bias;
+        for (int g2 = 0; g2 < groups; ++g2) s += red[g2][i][d];
+        ctx[(size_t)(b0 + i) * D + h * dh + d] = (_Float16)s;
+      }
+    }
+  }
+}
+
+// n_keys[b] = t_len[b] + 1 (the new token is part of its own context)
+__global__ void decode_count_kernel(const int32_t* t_len, int B, int32_t* n_keys) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < B) n_keys[i] = t_len[i] + 1;
+}
+
+}  // namespace
+
+hipError_t launch_decode_cache_write(const void* src, const int32_t* t_start, int B, int t_max, int r, int n_new, int which,
+                                     void* cache, hipStream_t s) {
+  const size_t seq_halves = (which == 0 ? fm_bytes(t_max, r) : decode_vcache_seq_bytes(t_max, r)) / 2;
+  const size_t total = which == 0 ? (size_t)B * n_new * (r / 8) : (size_t)B * n_new * r;
+  hipLaunchKernelGGL(decode_cache_write_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const _Float16*)src, t_start,
+                     B, t_max, r, n_new, which, (_Float16*)cache, seq_halves, total);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_absorb(const void* q, const void* Vk, int w_dt, int B, int D, int H, int r_k, float scale, void* W,
+                                hipStream_t s) {
+  hipLaunchKernelGGL(decode_absorb_kernel, dim3((r_k + 63) / 64, H), dim3(256), 0, s, (const _Float16*)q, Vk, w_dt, B, D, H, r_k,
+                     scale * kLog2eD, (_Float16*)W);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_core(const DecodeCoreArgs& a, hipStream_t s) {
+  const dim3 grid(a.B * a.nsplit), block(512);
+  const int nck = ((a.r_k + 63) / 64 + 7) / 8, nvt = ((a.r_v + 31) / 32 + 7) / 8;
+  if (nck > 2 || nvt > 4) return hipErrorInvalidValue;
+  if (nck <= 1 && nvt <= 1) hipLaunchKernelGGL((decode_core_kernel<1, 1>), grid, block, 0, s, a);
+  else if (nck <= 1 && nvt <= 2) hipLaunchKernelGGL((decode_core_kernel<1, 2>), grid, block, 0, s, a);
+  else if (nvt <= 2) hipLaunchKernelGGL((decode_core_kernel<2, 2>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((decode_core_kernel<2, 4>), grid, block, 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_merge(const float* stats, const void* upart, int B, int nsplit, int H, int r_v, float* u_out, hipStream_t s) {
+  hipLaunchKernelGGL(decode_merge_kernel, dim3(H, B), dim3(256), 0, s, stats, (const _Float16*)upart, nsplit, H, r_v, u_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_value(const float* u, const void* Vv, const void* bv, int w_dt, int B, int D, int H, int r_v, void* ctx,
+                               hipStream_t s) {
+  hipLaunchKernelGGL(decode_value_kernel, dim3(H), dim3(256), 0, s, u, Vv, bv, w_dt, B, D, H, r_v, (_Float16*)ctx);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_count(const int32_t* t_len, int B, int32_t* n_keys, hipStream_t s) {
+  hipLaunchKernelGGL(decode_count_kernel, dim3((B + 255) / 256), dim3(256), 0, s, t_len, B, n_keys);
+  return hipGetLastError();
+}
+
+}  // namespace fsvd

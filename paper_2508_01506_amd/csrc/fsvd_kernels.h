@@ -75,6 +75,27 @@ struct FfnCorePlan { int nslices, slice_w, ns, ns2, fsplit; size_t partial_bytes
 FfnCorePlan ffn_core_plan(int T, int r1, int r2, int F);
 hipError_t launch_ffn_core(const FfnCoreArgs& a, hipStream_t s);
 
+// ---- decoding step against a rank-space KV cache (layouts and kernels: fsvd_decode.hip)
+inline size_t decode_vcache_seq_bytes(size_t t_max, size_t r_v) { return ((r_v + 31) / 32) * ((t_max + 31) / 32) * 2048; }
+struct DecodeCoreArgs {
+  const void* W;          // absorbed queries, per sequence the fragment-major layout of [32, r_k] (fp16)
+  const void* kcache;     // per sequence: fragment-major P_k [t_max, r_k]
+  const void* vcache;     // per sequence: P_v^T in operand order (decode_vcache_seq_bytes)
+  const int32_t* n_keys;  // device [B]: valid keys of each sequence
+  int B, t_max, r_k, r_v, nsplit;
+  float* stats;           // [B][nsplit][64]: running maximum (32 heads) | sum (32 heads)
+  _Float16* upart;        // [B][nsplit][r_v][32 heads]: U / l
+};
+hipError_t launch_decode_cache_write(const void* src, const int32_t* t_start, int B, int t_max, int r, int n_new, int which,
+                                     void* cache, hipStream_t s);
+hipError_t launch_decode_absorb(const void* q, const void* Vk, int w_dt, int B, int D, int H, int r_k, float scale, void* W,
+                                hipStream_t s);
+hipError_t launch_decode_core(const DecodeCoreArgs& a, hipStream_t s);
+hipError_t launch_decode_merge(const float* stats, const void* upart, int B, int nsplit, int H, int r_v, float* u_out, hipStream_t s);
+hipError_t launch_decode_value(const float* u, const void* Vv, const void* bv, int w_dt, int B, int D, int H, int r_v, void* ctx,
+                               hipStream_t s);
+hipError_t launch_decode_count(const int32_t* t_len, int B, int32_t* n_keys, hipStream_t s);
+
 // ---- LayerNorm over the last axis of a row-major [T, D]; writes a row-major copy and/or an FM copy
 struct LayerNormArgs {
   const void* X; int x_dt;            // row-major, F16 / BF16 / F32

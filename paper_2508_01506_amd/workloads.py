@@ -24,7 +24,7 @@ from typing import Dict, Optional
 import numpy as np
 
 __all__ = ["Workload", "WORKLOADS", "get_workload", "make_inputs", "round_to_storage",
-           "to_storage_bits", "spectrum_factors"]
+           "to_storage_bits", "spectrum_factors", "DecodeWorkload", "DECODE_WORKLOADS", "make_decode_inputs"]
 
 
 @dataclass(frozen=True)
@@ -243,4 +243,58 @@ def make_inputs(w: Workload) -> dict:
     out["causal"] = (w.mask == "causal")
     if sigma:
         out["sigma"] = sigma
+    return out
+
+
+# ---------------------------------------------------------------------------
+# decoding step against a rank-space KV cache
+# ---------------------------------------------------------------------------
+
+@dataclass(frozen=True)
+class DecodeWorkload:
+    """One decoding step: B sequences, each with its own number of cached tokens in [len_min, len_max] (< t_max)."""
+    name: str
+    B: int
+    t_max: int
+    D: int
+    H: int
+    r: int            # rank of q, k, v and o
+    dtype: str        # storage of the new tokens and of the parameters
+    len_min: int
+    len_max: int
+    seed: int
+
+    @property
+    def d_h(self) -> int:
+        return self.D // self.H
+
+
+DECODE_WORKLOADS = {w.name: w for w in [
+    # the decoder shape of the largest prefill configuration (D 4096, 32 heads of 128, rank 1024), a batch of 16
+    # sequences with 4096-token caches that are between half full and full
+    DecodeWorkload("decode_llm_b16_t4096_r1024", 16, 4096, 4096, 32, 1024, "bf16", 2048, 4095, 7506),
+    DecodeWorkload("decode_llm_b64_t2048_r512", 64, 2048, 4096, 32, 512, "bf16", 1024, 2047, 7507),
+    DecodeWorkload("decode_base_b32_t1024_r256", 32, 1024, 768, 12, 256, "fp16", 1, 1023, 7508),
+    DecodeWorkload("decode_tiny_d64", 3, 80, 128, 2, 64, "fp16", 0, 79, 7509),
+    DecodeWorkload("decode_tiny_d128", 5, 300, 512, 4, 128, "bf16", 0, 299, 7510),
+]}
+
+
+def make_decode_inputs(w: DecodeWorkload) -> dict:
+    """Seeded inputs of one decoding step.  Draw order: x_new; (U, V, b) for q, k, v, o (Gaussian, variance 1/fan_in);
+    the cached rank-space keys and values (standard normal, the scale rank projections of unit-variance tokens have,
+    rounded to fp16 as the cache stores them; rows at and beyond a sequence's length are drawn too and must be
+    ignored); lens (the first and the last sequence get len_min and len_max)."""
+    rng = np.random.Generator(np.random.PCG64(w.seed))
+    st = w.dtype
+    out: dict = {"workload": w, "x_new": round_to_storage(rng.standard_normal((w.B, w.D)), st)}
+    for a in ("q", "k", "v", "o"):
+        u, v = _gaussian_factors(rng, w.D, w.D, w.r)
+        out[a] = {"U": round_to_storage(u, st), "V": round_to_storage(v, st),
+                  "b": round_to_storage(0.02 * rng.standard_normal(w.D), st)}
+    out["Pk"] = round_to_storage(rng.standard_normal((w.B, w.t_max, w.r), dtype=np.float32), "fp16")
+    out["Pv"] = round_to_storage(rng.standard_normal((w.B, w.t_max, w.r), dtype=np.float32), "fp16")
+    lens = rng.integers(w.len_min, w.len_max + 1, size=w.B).astype(np.int32)
+    lens[0], lens[-1] = w.len_min, w.len_max
+    out["lens"] = lens
     return out
