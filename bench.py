@@ -52,6 +52,103 @@ def useful_flops(w, mean_pairs):
     return f
 
 
+def bench_decode(args):
+    """One step = fsvd_decode_attention on a batch: every sequence's new token against its rank-space KV cache."""
+    import numpy as np
+    import torch
+    from paper_2508_01506_amd import binding as fb
+    from paper_2508_01506_amd import workloads as W
+
+    fb.lib()
+    w = W.DECODE_WORKLOADS[args.workload]
+    inp = W.make_decode_inputs(w)
+    dt = torch.float16 if w.dtype == "fp16" else torch.bfloat16
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device="cuda:0", dtype=dt).contiguous()
+    fac = {n: fb.Factor(up(inp[n]["U"]), up(inp[n]["V"]), up(inp[n]["b"])) for n in "qkvo"}
+    if args.weights == "tiled":        # V of k and v is read row by row by the decode kernels: it stays row-major
+        fac = {n: f.with_tiled(u=True, v=(n in "qo")) for n, f in fac.items()}
+    x_new = up(inp["x_new"])
+    d = fb.make_desc(w.B, w.t_max, w.D, w.H, 16, dt, torch.float32)
+    kc, vc = fb.fsvd_decode_new_caches(w.B, w.t_max, w.r, w.r)
+    zero = torch.zeros(w.B, dtype=torch.int32, device="cuda:0")
+    fb.fsvd_decode_cache_write(kc, 0, w.t_max, torch.from_numpy(inp["Pk"]).to("cuda:0", torch.float16), zero)
+    fb.fsvd_decode_cache_write(vc, 1, w.t_max, torch.from_numpy(inp["Pv"]).to("cuda:0", torch.float16), zero)
+    lens = torch.from_numpy(inp["lens"]).to("cuda:0")
+    ws_bytes = fb.fsvd_decode_attention_workspace(d, w.r, w.r, w.r, w.r)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
+    out = torch.empty((w.B, w.D), dtype=torch.float32, device="cuda:0")
+
+    def step():       # the same step every time (the lengths are not advanced): each call re-writes the same cache row
+        fb.fsvd_decode_attention(d, x_new, fac["q"], fac["k"], fac["v"], fac["o"], kc, vc, lens, out=out, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # ---- the pass over the cache alone (the HBM-bound kernel), per-launch event pairs, last-level cache flushed between
+    n_keys = (lens + 1).to(torch.int32)
+    Wabs = torch.randn(w.B * (w.r // 64) * 2048, device="cuda:0").mul_(0.05).to(torch.float16).view(torch.uint8)
+    u = torch.empty((w.B, w.H, w.r), dtype=torch.float32, device="cuda:0")
+    cws = torch.empty(fb.fsvd_decode_core_workspace(d, w.r, w.r), dtype=torch.uint8, device="cuda:0")
+    flush = torch.empty(512 << 20, device="cuda:0", dtype=torch.uint8)
+    core = lambda: fb.fsvd_decode_attention_core(d, w.r, w.r, Wabs, kc, vc, n_keys, out=u, workspace=cws)
+    n_k = max(3, min(args.steps, 20))
+    for _ in range(2):
+        flush.zero_(); core()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_k)]
+    for e0, e1 in ev:
+        flush.zero_()
+        e0.record(); core(); e1.record()
+    torch.cuda.synchronize()
+    core_ms = sum(e0.elapsed_time(e1) for e0, e1 in ev) / n_k
+    del flush
+    cache_bytes = int(2 * 2 * w.r * int((inp["lens"].astype(np.int64) + 1).sum()))      # keys + values, fp16, every valid row once
+    achieved = cache_bytes / (core_ms * 1e-3) / 1e9
+    result = {
+        "metric": "decoding-step attention block tokens/s against a rank-space KV cache; HBM fraction of the cache pass",
+        "value": round(w.B / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "t_max": w.t_max, "D": w.D, "H": w.H, "r": w.r, "storage": w.dtype,
+                   "cached_tokens": f"{int(inp['lens'].min())}..{int(inp['lens'].max())}, mean {float(inp['lens'].mean()):.0f}",
+                   "weights": "prepacked tile images for the projections" if args.weights == "tiled" else "row-major"},
+        "transient_mb": round(ws_bytes / 2 ** 20, 2),
+        "kv_cache_mb": round((kc.numel() + vc.numel()) / 2 ** 20, 1),
+        "full_width_kv_cache_mb": round(2 * w.B * w.t_max * w.D * 2 / 2 ** 20, 1),
+        "roofline": {"bound": "hbm", "kernel": "decode_core_kernel (+ merge of its parts)", "achieved": round(achieved, 1),
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None,
+                     "kernel_ms": round(core_ms, 4), "algorithmic_bytes": cache_bytes},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import fsvd_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            threads = len(os.sched_getaffinity(0))
+        got = out.cpu().numpy()
+        done, dtm, err = 0, 0.0, 0.0
+        for b in range(w.B - 1, -1, -1):
+            sl = slice(b, b + 1)
+            t0 = time.perf_counter()
+            ref, _, _ = O.decode_attention(inp["x_new"][sl], inp["Pk"][sl], inp["Pv"][sl], inp["lens"][sl], inp["q"], inp["k"],
+                                           inp["v"], inp["o"], w.H)
+            dtm += time.perf_counter() - t0
+            err = max(err, float(np.abs(got[sl] - ref).max() / np.sqrt(np.mean(ref ** 2))))
+            done += 1
+            if dtm > 10.0:
+                break
+        result["cpu_baseline"] = {"value": round(done / dtm, 2), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+                                  "sample": f"the decoding step of the last {done} sequence(s) of the batch, fp64 numpy, {dtm:.1f} s"}
+        result["max_err_over_rms_vs_oracle_sample"] = float(f"{err:.3e}")
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -68,6 +165,9 @@ def main():
         print("bench.py: this build runs on ONE GPU only (no sharding or collectives exist); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+
+    if args.workload.startswith("decode_"):
+        return bench_decode(args)
 
     import numpy as np
     import torch

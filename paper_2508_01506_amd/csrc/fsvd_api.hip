@@ -527,7 +527,8 @@ DecodeCorePlan plan_decode_core(int B, int r_v) {
   pl.total = pl.upart + align_up((size_t)B * pl.nsplit * r_v * 32 * 2);
   return pl;
 }
-struct DecodePlan { size_t pq, pk, pv, qf, w, nk, u, ctx, to, core, total; };
+constexpr int kDecodeKParts = 16;     // room for this many partial results of a projection whose contraction is split
+struct DecodePlan { size_t pq, pk, pv, qf, w, nk, u, ctx, to, core, part, part_bytes, total; };
 DecodePlan plan_decode(const fsvd_desc* d, int rq, int rk, int rv, int ro) {
   const size_t B = d->B, D = d->D;
   DecodePlan pl;
@@ -541,6 +542,9 @@ DecodePlan plan_decode(const fsvd_desc* d, int rq, int rk, int rv, int ro) {
   pl.ctx = take(B * D * 2);
   pl.to = take(B * ro * 2);
   pl.core = take(plan_decode_core(d->B, rv).total);
+  const size_t widest = smax(smax((size_t)rq + rk + rv, D), (size_t)ro);
+  pl.part_bytes = (size_t)kDecodeKParts * B * widest * 4;
+  pl.part = take(pl.part_bytes);
   pl.total = off;
   return pl;
 }
@@ -598,13 +602,12 @@ fsvd_status fsvd_decode_attention(const fsvd_desc* d, const void* x_new, const f
                                   const fsvd_factor* v, const fsvd_factor* o, void* kcache, void* vcache,
                                   const int32_t* t_len, void* out, void* ws, size_t ws_bytes, void* stream) {
   if (!d) return FSVD_ERR_INVALID_ARG;
-  {
-    fsvd_desc one = *d;
-    one.M = 1;
-    FSVD_TRY(check_attn(&one, q, k, v, o, true));
-  }
+  FSVD_TRY(check_factor(q, d->D, d->D, true, true, 3));
+  FSVD_TRY(check_factor(k, d->D, d->D, true, true, 1));     // V of k and v is read row by row by the kernels of this step
+  FSVD_TRY(check_factor(v, d->D, d->D, true, true, 1));
+  FSVD_TRY(check_factor(o, d->D, d->D, true, true, 3));
+  if (q->u_layout != k->u_layout || q->u_layout != v->u_layout) return FSVD_ERR_UNSUPPORTED;   // one projection launch
   FSVD_TRY(check_decode_shape(d, k->rank, v->rank));
-  if (k->v_layout != FSVD_ROW_MAJOR || v->v_layout != FSVD_ROW_MAJOR) return FSVD_ERR_UNSUPPORTED;   // read row by row here
   if (!x_new || !kcache || !vcache || !t_len || !out) return FSVD_ERR_INVALID_ARG;
   if (mis16(x_new) || mis16(kcache) || mis16(vcache) || mis16(out)) return FSVD_ERR_INVALID_ARG;
   const DecodePlan pl = plan_decode(d, q->rank, k->rank, v->rank, o->rank);
@@ -619,15 +622,15 @@ fsvd_status fsvd_decode_attention(const fsvd_desc* d, const void* x_new, const f
   p.g[0] = {q->U, nullptr, w + pl.pq, q->rank, q->rank, q->rank};
   p.g[1] = {k->U, nullptr, w + pl.pk, k->rank, k->rank, k->rank};
   p.g[2] = {v->U, nullptr, w + pl.pv, v->rank, v->rank, v->rank};
+  p.part = (float*)(w + pl.part); p.part_bytes = pl.part_bytes; p.ldp = q->rank + k->rank + v->rank;
   FSVD_HIP(launch_linear(p, s));
-  FSVD_HIP(launch_decode_cache_write(w + pl.pk, t_len, B, d->M, k->rank, 1, 0, kcache, s));
-  FSVD_HIP(launch_decode_cache_write(w + pl.pv, t_len, B, d->M, v->rank, 1, 1, vcache, s));
-  FSVD_HIP(launch_decode_count(t_len, B, (int32_t*)(w + pl.nk), s));
+  FSVD_HIP(launch_decode_append(w + pl.pk, w + pl.pv, t_len, B, d->M, k->rank, v->rank, kcache, vcache, (int32_t*)(w + pl.nk), s));
 
   LinearArgs qa{};      // the new queries at full width, fp16
   qa.A = w + pl.pq; qa.a_layout = LAYOUT_ROW; qa.lda = q->rank; qa.a_dt = DT_F16; qa.T = B; qa.K = q->rank; qa.w_dt = d->io_dtype;
   qa.w_tiled = q->v_layout == FSVD_TILED; qa.c_layout = LAYOUT_ROW; qa.c_dt = DT_F16; qa.ngroups = 1;
   qa.g[0] = {q->V, q->bias, w + pl.qf, D, D, D};
+  qa.part = (float*)(w + pl.part); qa.part_bytes = pl.part_bytes; qa.ldp = D;
   FSVD_HIP(launch_linear(qa, s));
   FSVD_HIP(launch_decode_absorb(w + pl.qf, k->V, d->io_dtype, B, D, d->H, k->rank, resolve_scale(d), w + pl.w, s));
   FSVD_TRY(run_decode_core(d, k->rank, v->rank, w + pl.w, kcache, vcache, (const int32_t*)(w + pl.nk), (float*)(w + pl.u),
@@ -638,11 +641,13 @@ fsvd_status fsvd_decode_attention(const fsvd_desc* d, const void* x_new, const f
   oa.A = w + pl.ctx; oa.a_layout = LAYOUT_ROW; oa.lda = D; oa.a_dt = DT_F16; oa.T = B; oa.K = D; oa.w_dt = d->io_dtype;
   oa.w_tiled = o->u_layout == FSVD_TILED; oa.c_layout = LAYOUT_ROW; oa.c_dt = DT_F16; oa.ngroups = 1;
   oa.g[0] = {o->U, nullptr, w + pl.to, o->rank, o->rank, o->rank};
+  oa.part = (float*)(w + pl.part); oa.part_bytes = pl.part_bytes; oa.ldp = o->rank;
   FSVD_HIP(launch_linear(oa, s));
   LinearArgs ob{};
   ob.A = w + pl.to; ob.a_layout = LAYOUT_ROW; ob.lda = o->rank; ob.a_dt = DT_F16; ob.T = B; ob.K = o->rank; ob.w_dt = d->io_dtype;
   ob.w_tiled = o->v_layout == FSVD_TILED; ob.c_layout = LAYOUT_ROW; ob.c_dt = d->out_dtype; ob.ngroups = 1;
   ob.g[0] = {o->V, o->bias, out, D, D, D};
+  ob.part = (float*)(w + pl.part); ob.part_bytes = pl.part_bytes; ob.ldp = D;
   FSVD_HIP(launch_linear(ob, s));
   return FSVD_OK;
 }

@@ -10,8 +10,8 @@
 //
 // Cache layouts (chosen so that a wavefront-wide 16-byte load of 64 consecutive units IS an MFMA operand):
 //   K cache, per sequence: the fragment-major layout (fsvd_common.h) of P_k [t_max, r_k].
-//   V cache, per sequence: P_v^T in operand order of the U product: for rank tile R = rank / 32 and key tile J = key / 32
-//     a 2 KiB block at (R * ceil(t_max / 32) + J) * 2048; inside, unit s * 64 + 32 g + (rank % 32) (16 bytes, s = 0..1,
+//   V cache, per sequence: P_v^T in operand order of the U product: for key tile J = key / 32 and rank tile R = rank / 32
+//     a 2 KiB block at (J * (r_v / 32) + R) * 2048 (all of a key tile's blocks are contiguous, like its K rows); inside, unit s * 64 + 32 g + (rank % 32) (16 bytes, s = 0..1,
 //     g = 0..1) holds the 8 keys 32 J + 16 s + 4 g + {0, 1, 2, 3, 8, 9, 10, 11} of that rank - the contraction-slot
 //     order in which the probabilities leave the score accumulators, so they feed the U product without any shuffle.
 // Positions that were never written must hold finite values (the caller zero-fills a new cache): masked keys get
@@ -50,8 +50,8 @@ __global__ void __launch_bounds__(256) decode_cache_write_kernel(const _Float16*
     const int n = (int)(row % n_new), b = (int)(row / n_new);
     const int t = t_start[b] + n;
     if (t < 0 || t >= t_max) return;
-    const int ktiles = (t_max + 31) / 32, kq = t & 31, o = kq & 15;
-    const size_t unit = ((size_t)((rho >> 5) * ktiles + (t >> 5)) * 2 + (kq >> 4)) * 64 + ((o >> 2) & 1) * 32 + (rho & 31);
+    const int vtl = (r + 31) / 32, kq = t & 31, o = kq & 15;
+    const size_t unit = ((size_t)((t >> 5) * vtl + (rho >> 5)) * 2 + (kq >> 4)) * 64 + ((o >> 2) & 1) * 32 + (rho & 31);
     cache[b * seq_halves + unit * 8 + (o & 3) + 4 * (o >> 3)] = src[row * r + rho];
   }
 }
@@ -122,11 +122,6 @@ __global__ void __launch_bounds__(512, 1) decode_core_kernel(DecodeCoreArgs a) {
   for (int i = 0; i < NVT; ++i) u[i] = zero16();
 
   if (j0 < j1) {
-    // absorbed queries of this sequence -> LDS (fragment-major bytes as they lie)
-    {
-      const u4* src = (const u4*)((const char*)a.W + (size_t)b * kch * 4096);
-      for (int i = tid; i < kch * 256; i += 512) ((u4*)wlds)[i] = src[i];
-    }
     const long long k_total = (long long)fm_bytes(a.t_max, a.r_k);
     const long long v_total = (long long)vtl * ktiles * 2048;
     const char* kbase = (const char*)a.kcache + (size_t)b * k_total;
@@ -143,12 +138,17 @@ __global__ void __launch_bounds__(512, 1) decode_core_kernel(DecodeCoreArgs a) {
 #pragma unroll
       for (int i = 0; i < NVT; ++i) {
         const int rt = wave + 8 * i;
-        const rsrc_t r = rsrc_at(vbase, rt < vtl ? v_total : 0, ((long long)rt * ktiles + j) * 2048);
+        const rsrc_t r = rsrc_at(vbase, rt < vtl ? v_total : 0, ((long long)j * vtl + rt) * 2048);
 #pragma unroll
         for (int s = 0; s < 2; ++s) vd[i][s] = __builtin_bit_cast(h8, buf_load16(r, s * 1024 + lane * 16));
       }
     };
     request(j0, kf, vf);
+    // absorbed queries of this sequence -> LDS (fragment-major bytes as they lie), while the first tile is in flight
+    {
+      const u4* src = (const u4*)((const char*)a.W + (size_t)b * kch * 4096);
+      for (int i = tid; i < kch * 256; i += 512) ((u4*)wlds)[i] = src[i];
+    }
     __syncthreads();
     int par = 0;
     for (int j = j0; j < j1; ++j) {
@@ -253,68 +253,124 @@ __global__ void __launch_bounds__(512, 1) decode_core_kernel(DecodeCoreArgs a) {
   }
 }
 
-// merge the parts of one (sequence, head): u[b, h, :] = sum_s wgt_s U_s / sum_s wgt_s, wgt_s = l_s 2^(m_s - max m)
+// merge the parts of one sequence: u[b, h, :] = sum_s wgt_s U_s / sum_s wgt_s, wgt_s = l_s 2^(m_s - max m).
+// One workgroup per (64 ranks, sequence): the partial sums are read as they were written (32 heads contiguous per rank),
+// transposed through LDS and written as runs of 64 ranks per head.
 __global__ void __launch_bounds__(256) decode_merge_kernel(const float* __restrict__ stats, const _Float16* __restrict__ upart,
                                                            int nsplit, int H, int r_v, float* u_out) {
-  const int h = blockIdx.x, b = blockIdx.y;
+  __shared__ float tile[32][65];
+  __shared__ float wgt[32][32];               // [part][head], normalised weights
+  __shared__ float st[32][64];                // the parts' statistics
+  const int r0 = 64 * blockIdx.x, b = blockIdx.y;
   const size_t slot0 = (size_t)b * nsplit;
-  float M = -1e30f;
-  for (int s = 0; s < nsplit; ++s)
-    if (stats[(slot0 + s) * 64 + 32 + h] > 0.f) M = fmaxf(M, stats[(slot0 + s) * 64 + h]);
-  float tot = 0.f;
-  for (int s = 0; s < nsplit; ++s) {
-    const float l = stats[(slot0 + s) * 64 + 32 + h];
-    if (l > 0.f) tot += l * exp2f(stats[(slot0 + s) * 64 + h] - M);
-  }
-  const float inv = tot > 0.f ? 1.0f / tot : 0.f;
-  for (int rho = threadIdx.x; rho < r_v; rho += 256) {
-    float acc = 0.f;
-    for (int s = 0; s < nsplit; ++s) {                       // fixed order
-      const float l = stats[(slot0 + s) * 64 + 32 + h];
-      if (l > 0.f) acc += l * exp2f(stats[(slot0 + s) * 64 + h] - M) * (float)upart[((slot0 + s) * r_v + rho) * 32 + h];
+  for (int i = threadIdx.x; i < nsplit * 64; i += 256) st[i >> 6][i & 63] = stats[slot0 * 64 + i];
+  __syncthreads();
+  if (threadIdx.x < 32) {
+    const int h = threadIdx.x;
+    float M = -1e30f;
+    for (int s = 0; s < nsplit; ++s)
+      if (st[s][32 + h] > 0.f) M = fmaxf(M, st[s][h]);
+    float tot = 0.f;
+    for (int s = 0; s < nsplit; ++s) {
+      const float l = st[s][32 + h];
+      const float w = l > 0.f ? l * exp2f(st[s][h] - M) : 0.f;
+      wgt[s][h] = w;
+      tot += w;
     }
-    u_out[((size_t)b * H + h) * r_v + rho] = acc * inv;
+    const float inv = tot > 0.f ? 1.0f / tot : 0.f;
+    for (int s = 0; s < nsplit; ++s) wgt[s][h] *= inv;
+  }
+  __syncthreads();
+  const int h = threadIdx.x & 31;
+  for (int k = 0; k < 8; ++k) {
+    const int rl = (threadIdx.x >> 5) + 8 * k, rho = r0 + rl;
+    float acc = 0.f;
+    if (rho < r_v) {
+      // fixed order.  Every part's slot is read (independent requests, all in flight together); a part without keys has
+      // weight 0 and whatever its slot holds is discarded by the select, not multiplied.
+#pragma unroll 8
+      for (int s = 0; s < nsplit; ++s) {
+        const float w = wgt[s][h];
+        const float x = (float)upart[((slot0 + s) * r_v + rho) * 32 + h];
+        acc += w > 0.f ? w * x : 0.f;
+      }
+    }
+    tile[h][rl] = acc;
+  }
+  __syncthreads();
+  const int rl = threadIdx.x & 63;
+  for (int k = 0; k < 8; ++k) {
+    const int hh = (threadIdx.x >> 6) + 4 * k;
+    if (hh < H && r0 + rl < r_v) u_out[((size_t)b * H + hh) * r_v + r0 + rl] = tile[hh][rl];
   }
 }
 
 // context[b, h d_h + d] = sum_rho u[b, h, rho] V_v[rho, h d_h + d] + b_v[h d_h + d], fp16 row-major [B, D].
-// One workgroup per head: the head's columns of V_v are read once for the whole batch (16 sequences at a time).
+// One workgroup per (head, 32 columns): its [r_v, 32] piece of V_v is brought into LDS with all requests in flight at
+// once, then, 16 sequences at a time, their u rows; thread (column, rank group) walks every eighth rank and the eight
+// groups are added through LDS.
 __global__ void __launch_bounds__(256) decode_value_kernel(const float* __restrict__ u, const void* __restrict__ Vv, const void* __restrict__ bv,
                                                            int w_dt, int B, int D, int H, int r_v, _Float16* ctx) {
-  __shared__ float red[4][16][128];
-  const int dh = D / H, h = blockIdx.x;
-  const int groups = 256 / dh;                 // 2 (d_h = 128) or 4 (d_h = 64)
-  const int d = threadIdx.x % dh, grp = threadIdx.x / dh;
+  __shared__ float ul[16][1024];
+  __shared__ __attribute__((aligned(16))) uint16_t vt[1024][32];
+  __shared__ float red[8][16][33];
+  const int dh = D / H, h = blockIdx.x, col0 = h * dh + 32 * blockIdx.y, c = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  for (int i = threadIdx.x; i < r_v * 4; i += 256)
+    *(u4*)&vt[i >> 2][8 * (i & 3)] = *(const u4*)((const uint16_t*)Vv + (size_t)(i >> 2) * D + col0 + 8 * (i & 3));
   for (int b0 = 0; b0 < B; b0 += 16) {
     const int nb = B - b0 < 16 ? B - b0 : 16;
+    __syncthreads();
+    for (int i = threadIdx.x; i < 16 * r_v; i += 256) {
+      const int bb = i / r_v, rho = i % r_v;
+      ul[bb][rho] = bb < nb ? u[((size_t)(b0 + bb) * H + h) * r_v + rho] : 0.f;
+    }
+    __syncthreads();
     float acc[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-    for (int rho = grp; rho < r_v; rho += groups) {
-      const float w = load_param(Vv, (size_t)rho * D + h * dh + d, w_dt);
+#pragma unroll 4
+    for (int rho = grp; rho < r_v; rho += 8) {
+      const uint16_t raw = vt[rho][c];
+      const float w = w_dt == DT_BF16 ? bf16_bits_to_float(raw) : (float)__builtin_bit_cast(_Float16, raw);
 #pragma unroll
-      for (int i = 0; i < 16; ++i)
-        if (i < nb) acc[i] = fmaf(u[((size_t)(b0 + i) * H + h) * r_v + rho], w, acc[i]);
+      for (int i = 0; i < 16; ++i) acc[i] = fmaf(ul[i][rho], w, acc[i]);
     }
-    __syncthreads();
 #pragma unroll
-    for (int i = 0; i < 16; ++i) red[grp][i][d] = acc[i];
+    for (int i = 0; i < 16; ++i) red[grp][i][c] = acc[i];
     __syncthreads();
-    if (grp == 0) {
-      const float bias = bv ? load_param(bv, (size_t)h * dh + d, w_dt) : 0.f;
-      for (int i = 0; i < nb; ++i) {
-        float s = bias;
-        for (int g2 = 0; g2 < groups; ++g2) s += red[g2][i][d];
-        ctx[(size_t)(b0 + i) * D + h * dh + d] = (_Float16)s;
-      }
+    for (int i = threadIdx.x; i < nb * 32; i += 256) {
+      const int bb = i >> 5, cc = i & 31;
+      float s = bv ? load_param(bv, (size_t)col0 + cc, w_dt) : 0.f;
+#pragma unroll
+      for (int g2 = 0; g2 < 8; ++g2) s += red[g2][bb][cc];
+      ctx[(size_t)(b0 + bb) * D + col0 + cc] = (_Float16)s;
     }
   }
 }
 
-// n_keys[b] = t_len[b] + 1 (the new token is part of its own context)
-__global__ void decode_count_kernel(const int32_t* t_len, int B, int32_t* n_keys) {
+// The step's own bookkeeping in one launch: the new token's rows pk [B, r_k], pv [B, r_v] go to position t_len[b] of the
+// two caches (same addressing as decode_cache_write_kernel) and n_keys[b] = t_len[b] + 1 (the new token is part of its
+// own context).  One thread per 16-byte unit of pk, then one per element of pv.
+__global__ void __launch_bounds__(256) decode_append_kernel(const _Float16* __restrict__ pk, const _Float16* __restrict__ pv,
+                                                            const int32_t* __restrict__ t_len, int B, int t_max, int r_k, int r_v,
+                                                            _Float16* kcache, _Float16* vcache, size_t k_seq_halves, size_t v_seq_halves,
+                                                            int32_t* n_keys) {
   const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i < B) n_keys[i] = t_len[i] + 1;
+  const int per_seq = r_k / 8 + r_v;
+  if (i >= B * per_seq) return;
+  const int b = i / per_seq, j = i % per_seq;
+  const int t = t_len[b];
+  if (j == 0) n_keys[b] = t + 1;
+  if (t < 0 || t >= t_max) return;
+  if (j < r_k / 8) {
+    const int rho = 8 * j, kch = (r_k + 63) / 64, off = rho & 63;
+    const size_t unit = ((size_t)((t >> 5) * kch + (rho >> 6)) * 4 + ((off >> 3) & 3)) * 64 + (off >> 5) * 32 + (t & 31);
+    *(h8*)(kcache + b * k_seq_halves + unit * 8) = *(const h8*)(pk + (size_t)b * r_k + rho);
+  } else {
+    const int rho = j - r_k / 8, vtl = (r_v + 31) / 32, kq = t & 31, o = kq & 15;
+    const size_t unit = ((size_t)((t >> 5) * vtl + (rho >> 5)) * 2 + (kq >> 4)) * 64 + ((o >> 2) & 1) * 32 + (rho & 31);
+    vcache[b * v_seq_halves + unit * 8 + (o & 3) + 4 * (o >> 3)] = pv[(size_t)b * r_v + rho];
+  }
 }
 
 }  // namespace
@@ -347,18 +403,22 @@ hipError_t launch_decode_core(const DecodeCoreArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_decode_merge(const float* stats, const void* upart, int B, int nsplit, int H, int r_v, float* u_out, hipStream_t s) {
-  hipLaunchKernelGGL(decode_merge_kernel, dim3(H, B), dim3(256), 0, s, stats, (const _Float16*)upart, nsplit, H, r_v, u_out);
+  hipLaunchKernelGGL(decode_merge_kernel, dim3((r_v + 63) / 64, B), dim3(256), 0, s, stats, (const _Float16*)upart, nsplit, H, r_v, u_out);
   return hipGetLastError();
 }
 
 hipError_t launch_decode_value(const float* u, const void* Vv, const void* bv, int w_dt, int B, int D, int H, int r_v, void* ctx,
                                hipStream_t s) {
-  hipLaunchKernelGGL(decode_value_kernel, dim3(H), dim3(256), 0, s, u, Vv, bv, w_dt, B, D, H, r_v, (_Float16*)ctx);
+  hipLaunchKernelGGL(decode_value_kernel, dim3(H, (D / H) / 32), dim3(256), 0, s, u, Vv, bv, w_dt, B, D, H, r_v, (_Float16*)ctx);
   return hipGetLastError();
 }
 
-hipError_t launch_decode_count(const int32_t* t_len, int B, int32_t* n_keys, hipStream_t s) {
-  hipLaunchKernelGGL(decode_count_kernel, dim3((B + 255) / 256), dim3(256), 0, s, t_len, B, n_keys);
+hipError_t launch_decode_append(const void* pk, const void* pv, const int32_t* t_len, int B, int t_max, int r_k, int r_v,
+                                void* kcache, void* vcache, int32_t* n_keys, hipStream_t s) {
+  const int total = B * (r_k / 8 + r_v);
+  hipLaunchKernelGGL(decode_append_kernel, dim3((total + 255) / 256), dim3(256), 0, s, (const _Float16*)pk, (const _Float16*)pv, t_len,
+                     B, t_max, r_k, r_v, (_Float16*)kcache, (_Float16*)vcache, fm_bytes(t_max, r_k) / 2,
+                     decode_vcache_seq_bytes(t_max, r_v) / 2, n_keys);
   return hipGetLastError();
 }
 

@@ -38,7 +38,7 @@ __device__ __forceinline__ h8 cvt_raw_act(const RawAct<AM>& r) {
 }
 
 template <int AM, int WT, int BN, bool CFM>
-__global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel(LinearArgs a, int tiles_m, int tiles_n) {
+__global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel(LinearArgs a, int tiles_m, int tiles_n, int ksplit) {
   constexpr int NT = BN / 32;            // 32-column MFMA tiles per wavefront
   constexpr int ESZ = (AM == AM_ROW_F32) ? 4 : 2;
   constexpr int WS = wtile_stride(BN);   // halves per LDS tile row
@@ -47,14 +47,19 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
   constexpr int NP = kChunkK / RPP;      // passes (loads per thread) per chunk
   __shared__ __attribute__((aligned(16))) _Float16 lds[2][kChunkK * WS];
 
-  const int tile = xcd_tile(blockIdx.x, tiles_m * tiles_n);
+  // Few rows and a long contraction (the projections of a decoding step): the contraction is split over `ksplit`
+  // workgroups per tile, which write fp32 partial sums that a second kernel adds in a fixed order.
+  const int ntile = tiles_m * tiles_n;
+  const int ks = blockIdx.x / ntile;
+  const int tile = xcd_tile(blockIdx.x % ntile, ntile);
   const int tm = tile / tiles_n;
   int tn = tile % tiles_n;
-  int gi = 0;
+  int gi = 0, goff = 0;                 // goff: first column of this group in the concatenation of all groups' outputs
   for (; gi < a.ngroups - 1; ++gi) {
     int t = (a.g[gi].N + BN - 1) / BN;
     if (tn < t) break;
     tn -= t;
+    goff += a.g[gi].N;
   }
   const LinearGroup G = a.g[gi];
   const int n0 = tn * BN;
@@ -64,6 +69,8 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
   const int m0 = tm * 256 + wave * 64;
   const int K = a.K, T = a.T;
   const int kchunks = (K + kChunkK - 1) / kChunkK;
+  const int cps = (kchunks + ksplit - 1) / ksplit;
+  const int cb = ks * cps, ce = (cb + cps < kchunks) ? cb + cps : kchunks;   // this workgroup's chunks of the contraction
 
   // ---- activation addressing: one 32-bit offset per 32-row tile
   const long long a_total = (AM == AM_FM) ? (long long)fm_bytes(T, K) : (long long)T * a.lda * ESZ;
@@ -138,21 +145,21 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
   };
   // prologue: chunk 0 in LDS and in the operand registers, chunk 1's weights in flight
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) load_a(0, kk, true);
+  for (int kk = 0; kk < 4; ++kk) load_a(cb, kk, cb < ce);
   {
-    const rsrc_t r0 = w_rsrc(0, true), r1 = w_rsrc(1, kchunks > 1);
+    const rsrc_t r0 = w_rsrc(cb, cb < ce), r1 = w_rsrc(cb + 1, cb + 1 < ce);
 #pragma unroll
     for (int p = 0; p < NP; ++p) load_w_pass(r0, p);
 #pragma unroll
     for (int p = 0; p < NP; ++p) { store_w_pass(0, p); load_w_pass(r1, p); }
   }
   __syncthreads();
-  for (int c = 0; c < kchunks; ++c) {
+  for (int c = cb; c < ce; ++c) {
     // chunk c+1 (requested during the previous iteration) is stored to the other buffer and chunk c+2 is requested, one
     // staging pass per MFMA step; the activation operands of a step are refilled with chunk c+1's right after their use
-    const rsrc_t rw2 = w_rsrc(c + 2, c + 2 < kchunks);
-    const bool more1 = c + 1 < kchunks;
-    const _Float16* wt = lds[c & 1];
+    const rsrc_t rw2 = w_rsrc(c + 2, c + 2 < ce);
+    const bool more1 = c + 1 < ce;
+    const _Float16* wt = lds[(c - cb) & 1];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       h8 bf[NT], af[2];
@@ -170,7 +177,7 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
       load_a(c + 1, kk, more1);
       if ((kk * NP) % 4 == 0) {
         const int p = kk * NP / 4;
-        store_w_pass((c + 1) & 1, p);
+        store_w_pass((c + 1 - cb) & 1, p);
         load_w_pass(rw2, p);
       }
     }
@@ -199,6 +206,24 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
 #pragma unroll
             for (int i = 0; i < 4; ++i) o[i] = (_Float16)(acc[mt][nt][4 * jj + i] + bias[i]);
             *(h4*)(C + unit * 8 + 4 * g) = o;
+          }
+        }
+      }
+  } else if (ksplit > 1) {
+    // partial sums [part of the contraction][token][all groups' columns], fp32; bias and residual are added by the reduction
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
+        const int tok = m0 + 32 * mt + l32;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const int n = n0 + 32 * nt + 8 * jj + 4 * g;
+          if (tok < T && n < G.N) {
+            f4v x;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[i] = acc[mt][nt][4 * jj + i];
+            *(f4v*)(a.part + ((size_t)ks * T + tok) * a.ldp + goff + n) = x;
           }
         }
       }
@@ -236,6 +261,34 @@ __global__ void __launch_bounds__(256, (AM == AM_ROW_F32) ? 1 : 2) linear_kernel
   }
 }
 
+// sum of the partial results over the parts of the contraction (fixed order) + bias + residual -> row-major output
+__global__ void __launch_bounds__(256) linear_reduce_kernel(LinearArgs a, int ksplit) {
+  const int quads = a.ldp / 4;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)a.T * quads) return;
+  const int tok = (int)(i / quads);
+  int n = 4 * (int)(i % quads), gi = 0;
+  for (; gi < a.ngroups - 1 && n >= a.g[gi].N; ++gi) n -= a.g[gi].N;
+  const LinearGroup G = a.g[gi];
+  f4v x = {0.f, 0.f, 0.f, 0.f};
+  for (int ks = 0; ks < ksplit; ++ks) {
+    const f4v p = *(const f4v*)(a.part + ((size_t)ks * a.T + tok) * a.ldp + 4 * (i % quads));
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x[e] += p[e];
+  }
+  if (G.bias) {
+    const f4v b = load4(G.bias, n, a.w_dt);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x[e] += b[e];
+  }
+  if (a.R) {
+    const f4v r = load4(a.R, (size_t)tok * a.ldr + n, a.r_dt);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x[e] += r[e];
+  }
+  store4(G.C, (size_t)tok * G.ldc + n, x, a.c_dt);
+}
+
 template <int AM, int WT, bool CFM>
 hipError_t launch_bn(const LinearArgs& a, hipStream_t s) {
   const int tiles_m = (a.T + 255) / 256;
@@ -243,10 +296,25 @@ hipError_t launch_bn(const LinearArgs& a, hipStream_t s) {
   for (int i = 0; i < a.ngroups; ++i) { n128 += (a.g[i].N + 127) / 128; n64 += (a.g[i].N + 63) / 64; }
   // narrow tiles when the wide ones would leave compute units idle
   const bool narrow = (long)tiles_m * n128 < 320;
+  // one tile row and room for partial sums: split the contraction so that about one workgroup per compute unit runs
+  int ksplit = 1;
+  if (!CFM && a.part && tiles_m == 1 && a.ldp > 0) {
+    const int kchunks = (a.K + kChunkK - 1) / kChunkK;
+    const size_t room = a.part_bytes / ((size_t)a.T * a.ldp * 4);
+    ksplit = 256 / n64;
+    if (ksplit > kchunks / 2) ksplit = kchunks / 2;          // at least two 64-wide chunks per part
+    if ((size_t)ksplit > room) ksplit = (int)room;
+    if (ksplit < 1 || !narrow) ksplit = 1;
+  }
   if (narrow) {
-    hipLaunchKernelGGL((linear_kernel<AM, WT, 64, CFM>), dim3(tiles_m * n64), dim3(256), 0, s, a, tiles_m, n64);
+    hipLaunchKernelGGL((linear_kernel<AM, WT, 64, CFM>), dim3(tiles_m * n64 * ksplit), dim3(256), 0, s, a, tiles_m, n64, ksplit);
   } else {
-    hipLaunchKernelGGL((linear_kernel<AM, WT, 128, CFM>), dim3(tiles_m * n128), dim3(256), 0, s, a, tiles_m, n128);
+    hipLaunchKernelGGL((linear_kernel<AM, WT, 128, CFM>), dim3(tiles_m * n128), dim3(256), 0, s, a, tiles_m, n128, 1);
+  }
+  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  if (ksplit > 1) {
+    const size_t quads = (size_t)a.T * (a.ldp / 4);
+    hipLaunchKernelGGL(linear_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, a, ksplit);
   }
   return hipGetLastError();
 }

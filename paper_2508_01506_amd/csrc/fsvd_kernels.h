@@ -36,6 +36,11 @@ struct LinearArgs {
   int r_dt;
   int ngroups;
   LinearGroup g[3];
+  // optional, row-major output and T <= 256 only: room for fp32 partial sums [parts][T][ldp] when the contraction is
+  // split over workgroups (ldp = sum of the groups' N); nullptr = never split
+  float* part;
+  size_t part_bytes;
+  int ldp;
 };
 hipError_t launch_linear(const LinearArgs& a, hipStream_t s);
 
@@ -76,7 +81,7 @@ FfnCorePlan ffn_core_plan(int T, int r1, int r2, int F);
 hipError_t launch_ffn_core(const FfnCoreArgs& a, hipStream_t s);
 
 // ---- decoding step against a rank-space KV cache (layouts and kernels: fsvd_decode.hip)
-inline size_t decode_vcache_seq_bytes(size_t t_max, size_t r_v) { return ((r_v + 31) / 32) * ((t_max + 31) / 32) * 2048; }
+inline size_t decode_vcache_seq_bytes(size_t t_max, size_t r_v) { return ((t_max + 31) / 32) * ((r_v + 31) / 32) * 2048; }
 struct DecodeCoreArgs {
   const void* W;          // absorbed queries, per sequence the fragment-major layout of [32, r_k] (fp16)
   const void* kcache;     // per sequence: fragment-major P_k [t_max, r_k]
@@ -94,7 +99,8 @@ hipError_t launch_decode_core(const DecodeCoreArgs& a, hipStream_t s);
 hipError_t launch_decode_merge(const float* stats, const void* upart, int B, int nsplit, int H, int r_v, float* u_out, hipStream_t s);
 hipError_t launch_decode_value(const float* u, const void* Vv, const void* bv, int w_dt, int B, int D, int H, int r_v, void* ctx,
                                hipStream_t s);
-hipError_t launch_decode_count(const int32_t* t_len, int B, int32_t* n_keys, hipStream_t s);
+hipError_t launch_decode_append(const void* pk, const void* pv, const int32_t* t_len, int B, int t_max, int r_k, int r_v,
+                                void* kcache, void* vcache, int32_t* n_keys, hipStream_t s);
 
 // ---- LayerNorm over the last axis of a row-major [T, D]; writes a row-major copy and/or an FM copy
 struct LayerNormArgs {

@@ -64,10 +64,10 @@ def k_cache_image(P, t_max):
 
 
 def v_cache_image(P, t_max):
-    """The documented V-cache layout of one sequence: rank tile x key tile blocks of 2 KiB in operand order."""
+    """The documented V-cache layout of one sequence: key tile x rank tile blocks of 2 KiB in operand order."""
     t, r = P.shape
     ktiles = (t_max + 31) // 32
-    img = np.zeros((r // 32, ktiles, 2, 64, 8), np.float16)
+    img = np.zeros((ktiles, r // 32, 2, 64, 8), np.float16)
     slot_keys = [0, 1, 2, 3, 8, 9, 10, 11]
     for tok in range(t):
         kq = tok % 32
@@ -75,7 +75,7 @@ def v_cache_image(P, t_max):
         g = (o // 4) % 2
         i = slot_keys.index(o - 4 * g)
         for rho in range(r):
-            img[rho // 32, tok // 32, s, 32 * g + rho % 32, i] = P[tok, rho]
+            img[tok // 32, rho // 32, s, 32 * g + rho % 32, i] = P[tok, rho]
     return img.reshape(-1)
 
 

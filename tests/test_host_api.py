@@ -183,6 +183,42 @@ def test_tiled_weight_layout_contract():
     assert L.fsvd_linear_tiled(16, 40, 16, 256, 0, 256, None, 0, None, 0, 256, 0, None) == UNSUPPORTED
 
 
+def test_decode_entry_points_contract():
+    """Sizes of the rank-space KV cache and argument validation of the decoding step (no GPU needed)."""
+    L = fb.lib()
+    assert L.fsvd_decode_kcache_bytes(2, 70, 64) == 2 * 3 * 1 * 4096          # fragment-major [70, 64] per sequence
+    assert L.fsvd_decode_kcache_bytes(16, 4096, 1024) == 16 * 4096 * 1024 * 2
+    assert L.fsvd_decode_vcache_bytes(2, 70, 96) == 2 * 3 * 3 * 2048          # 3 rank tiles x 3 key tiles of 2 KiB
+    assert L.fsvd_decode_vcache_bytes(16, 4096, 1024) == 16 * 4096 * 1024 * 2
+    assert L.fsvd_decode_kcache_bytes(2, 70, 48) == 0 and L.fsvd_decode_vcache_bytes(2, 70, 48) == 0
+    assert L.fsvd_decode_kcache_bytes(0, 70, 64) == 0
+    d = fb.make_desc(16, 4096, 4096, 32, 16, torch.bfloat16)                     # M is the cache capacity
+    q = fac(4096, 1024, 4096)
+    need = fb.fsvd_decode_attention_workspace(d, 1024, 1024, 1024, 1024)
+    assert need > 0 and need % 256 == 0
+    # the 2 t r scalars of cache per sequence against the 2 t D of full-width keys and values (appendix, KV-cache cost)
+    assert L.fsvd_decode_kcache_bytes(1, 4096, 1024) + L.fsvd_decode_vcache_bytes(1, 4096, 1024) == 2 * 4096 * 1024 * 2
+    call = lambda dd, x, kk, kc, tl, ws, n: L.fsvd_decode_attention(C.byref(dd), x, C.byref(q), C.byref(kk), C.byref(q), C.byref(q),
+                                                                    kc, 256, tl, 256, ws, n, None)
+    assert call(d, None, q, 256, 256, 256, need) == INVALID
+    assert call(d, 256, q, None, 256, 256, need) == INVALID
+    assert call(d, 256, q, 256, None, 256, need) == INVALID
+    assert call(d, 256, q, 256, 256, 256, need - 1) == WORKSPACE
+    assert call(d, 256, q, 264, 256, 256, need) == INVALID                      # cache not 16-byte aligned
+    assert call(d, 256, fac(4096, 1040, 4096), 256, 256, 256, 1 << 40) == UNSUPPORTED     # r_k % 64
+    assert call(d, 256, fac(4096, 2048, 4096), 256, 256, 256, 1 << 40) == UNSUPPORTED     # r_k > 1024
+    tiled_v = fb.fsvd_factor(q.U, q.V, q.bias, q.in_dim, q.rank, q.out_dim, 0, 1)
+    assert call(d, 256, tiled_v, 256, 256, 256, need) == UNSUPPORTED            # V_k is read row by row here
+    assert fb.fsvd_decode_attention_workspace(fb.make_desc(16, 4096, 4096, 64, 16, torch.bfloat16), 1024, 1024, 1024, 1024) == 0   # H > 32
+    assert L.fsvd_decode_cache_write(2, 70, 64, 1, None, 256, 0, 256, None) == INVALID
+    assert L.fsvd_decode_cache_write(2, 70, 64, 1, 256, 256, 2, 256, None) == INVALID
+    assert L.fsvd_decode_cache_write(2, 70, 48, 1, 256, 256, 0, 256, None) == UNSUPPORTED
+    cw = fb.fsvd_decode_core_workspace(d, 1024, 1024)
+    assert cw > 0 and cw <= need
+    assert L.fsvd_decode_attention_core(C.byref(d), 1024, 1024, 256, 256, 256, 256, 256, 256, cw - 1, None) == WORKSPACE
+    assert L.fsvd_decode_attention_core(C.byref(d), 1024, 1024, None, 256, 256, 256, 256, 256, cw, None) == INVALID
+
+
 def test_per_head_attention_entry_point_contract():
     """Workspace of the per-head entry point = packed X / context + P_q | P_k | P_v with H * rank columns each; the same
     validation as the whole-matrix entry point."""
