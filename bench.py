@@ -95,14 +95,17 @@ def bench_decode(args):
     Wabs = torch.randn(w.B * (w.r // 64) * 2048, device="cuda:0").mul_(0.05).to(torch.float16).view(torch.uint8)
     u = torch.empty((w.B, w.H, w.r), dtype=torch.float32, device="cuda:0")
     cws = torch.empty(fb.fsvd_decode_core_workspace(d, w.r, w.r), dtype=torch.uint8, device="cuda:0")
-    flush = torch.empty(512 << 20, device="cuda:0", dtype=torch.uint8)
+    # the last-level cache (256 MiB) would otherwise still hold most of the 256 MiB cache from the previous launch; it is
+    # flushed by READING another 512 MiB (clean lines: a fill would leave dirty lines whose write-back competes with the
+    # timed kernel's reads)
+    flush = torch.zeros(128 << 20, device="cuda:0", dtype=torch.int32)
     core = lambda: fb.fsvd_decode_attention_core(d, w.r, w.r, Wabs, kc, vc, n_keys, out=u, workspace=cws)
     n_k = max(3, min(args.steps, 20))
     for _ in range(2):
-        flush.zero_(); core()
+        flush.max(); core()
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_k)]
     for e0, e1 in ev:
-        flush.zero_()
+        flush.max()
         e0.record(); core(); e1.record()
     torch.cuda.synchronize()
     core_ms = sum(e0.elapsed_time(e1) for e0, e1 in ev) / n_k

@@ -151,15 +151,18 @@ __global__ void __launch_bounds__(512, 1) decode_core_kernel(DecodeCoreArgs a) {
     }
     __syncthreads();
     int par = 0;
-    for (int j = j0; j < j1; ++j) {
-      request(j + 1 < j1 ? j + 1 : j, kn, vn);            // the last tile is requested twice; nothing is read out of range
+    // one key tile: operands kc / vc of tile j are in registers, those of tile j + 1 are requested into kx / vx and are
+    // first touched in the next call (the two register sets swap roles instead of being copied, so nothing waits for a
+    // load before its first real use)
+    auto tile_step = [&](int j, h8 (&kc)[NCK][4], h8 (&vc)[NVT][2], h8 (&kx)[NCK][4], h8 (&vx)[NVT][2]) {
+      request(j + 1 < j1 ? j + 1 : j, kx, vx);            // the last tile is requested twice; nothing is read out of range
       // ---- partial scores of this wavefront's rank chunks
       f16v sp_ = zero16();
 #pragma unroll
       for (int i = 0; i < NCK; ++i)
         if (wave + 8 * i < kch) {                          // wave-uniform; LDS past the last chunk was never written
 #pragma unroll
-          for (int kk = 0; kk < 4; ++kk) sp_ = mfma32(kf[i][kk], wlds[(wave + 8 * i) * 4 + kk][lane], sp_);   // rows keys, cols heads
+          for (int kk = 0; kk < 4; ++kk) sp_ = mfma32(kc[i][kk], wlds[(wave + 8 * i) * 4 + kk][lane], sp_);   // rows keys, cols heads
         }
 #pragma unroll
       for (int qd = 0; qd < 4; ++qd) {
@@ -217,15 +220,11 @@ __global__ void __launch_bounds__(512, 1) decode_core_kernel(DecodeCoreArgs a) {
 #pragma unroll
       for (int i = 0; i < NVT; ++i)
 #pragma unroll
-        for (int t = 0; t < 2; ++t) u[i] = mfma32(vf[i][t], pf[t], u[i]);   // rows ranks, cols heads
-#pragma unroll
-      for (int i = 0; i < NCK; ++i)
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) kf[i][kk] = kn[i][kk];
-#pragma unroll
-      for (int i = 0; i < NVT; ++i)
-#pragma unroll
-        for (int t = 0; t < 2; ++t) vf[i][t] = vn[i][t];
+        for (int t = 0; t < 2; ++t) u[i] = mfma32(vc[i][t], pf[t], u[i]);   // rows ranks, cols heads
+    };
+    for (int j = j0; j < j1; j += 2) {
+      tile_step(j, kf, vf, kn, vn);
+      if (j + 1 < j1) tile_step(j + 1, kn, vn, kf, vf);
     }
   }
 
