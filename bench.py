@@ -159,6 +159,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--weights", choices=["tiled", "row"], default="tiled")
+    ap.add_argument("--part", choices=["layer", "attention", "ffn"], default="layer",
+                    help="time one block of the layer instead of the whole layer (value is then that block's tokens/s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-traffic", action="store_true",
                     help="also launch a plain copy of known size (fsvd_pack_fm of a 512 MiB fp16 matrix: reads 512 MiB, "
@@ -191,6 +193,13 @@ def main():
     out = torch.empty((w.B, w.M, w.D), dtype=torch.float32, device="cuda:0")
 
     def step():
+        if args.part == "ffn":
+            fb.fsvd_ffn(d, dev["X"], dev["w1"], dev["w2"], out=out, workspace=ws)
+            return
+        if args.part == "attention":
+            (fb.fsvd_attention_heads if per_head else fb.fsvd_attention)(d, dev["X"], dev["q"], dev["k"], dev["v"], dev["o"],
+                                                                         out=out, workspace=ws)
+            return
         layer = fb.fsvd_layer_heads if per_head else fb.fsvd_layer
         layer(d, dev["X"], dev["q"], dev["k"], dev["v"], dev["o"], dev["ln1_gamma"], dev["ln1_beta"],
               dev["w1"], dev["w2"], dev["ln2_gamma"], dev["ln2_beta"], out=out, workspace=ws)
@@ -274,7 +283,7 @@ def main():
         "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "M": w.M, "D": w.D, "H": w.H, "F": w.F, "r_attn": ra, "r_ffn": rf,
-                   "storage": w.dtype, "mask": w.mask, "norm": w.norm,
+                   "storage": w.dtype, "mask": w.mask, "norm": w.norm, "part": args.part,
                    "weights": ("prepacked tile images where accepted (" + ", ".join(
                        f"{n}.{'U' if u else ''}{'V' if v else ''}" for n, (u, v) in fb.TILED_OK.items()) + ")")
                    if args.weights == "tiled" else "row-major",
@@ -300,8 +309,8 @@ def main():
             for b in range(w.B - 1, -1, -1):
                 t0 = time.perf_counter()
                 ref = (oracle_call(dict(inp, X=inp["X"][b:b + 1], key_len=None if inp["key_len"] is None
-                                    else inp["key_len"][b:b + 1]), "layer")[0, rows] if per_head
-                   else oracle_rows(inp, b, rows, "layer"))
+                                    else inp["key_len"][b:b + 1]), args.part)[0, rows] if per_head
+                   else oracle_rows(inp, b, rows, args.part))
                 dt += time.perf_counter() - t0
                 got = out[b, w.M - n_rows:].cpu().numpy()
                 err = max(err, float(np.abs(got - ref).max() / np.sqrt(np.mean(ref ** 2))))

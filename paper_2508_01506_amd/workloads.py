@@ -111,6 +111,14 @@ _register(_wl(9, 2, name="ph_tiny_d128_r32", B=1, M=270, D=256, H=2, F=512, r_at
               r_head=32))
 
 
+# The paper's FFN rank ablation (table "Computation-efficiency ablation": batch 16, BERT-base widths, sequence
+# 128 .. 1024, FFN ranks 768 / 384 / 192 / 96): the FFN block alone is of interest, the attention ranks are a filler.
+FFN_GRID = [(m, r) for m in (128, 256, 512, 1024) for r in (768, 384, 192, 96)]
+for _i, (_m, _r) in enumerate(FFN_GRID):
+    _register(_wl(10, _i, name=f"ffn_grid_b16_m{_m}_r{_r}", B=16, M=_m, D=768, H=12, F=3072, r_attn=64, r_ffn=_r,
+                  dtype="fp16"))
+
+
 def get_workload(name: str, **overrides) -> Workload:
     w = WORKLOADS[name]
     return replace(w, **overrides) if overrides else w

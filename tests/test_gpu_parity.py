@@ -356,6 +356,18 @@ def test_full_size_sampled_rows(fb, name, weights):
         assert err < tol_for(w, part), (name, part, err)
 
 
+@pytest.mark.parametrize("m,r", W.FFN_GRID)
+def test_ffn_block_on_the_rank_ablation_grid(fb, m, r):
+    """The FFN block (Alg. 2 with its two plain projections) on the sequence lengths and ranks of the paper's FFN rank
+    ablation, prepacked weights, sampled rows against the oracle."""
+    w, inp, dev = workload(f"ffn_grid_b16_m{m}_r{r}", fb, "tiled")
+    got = gpu_call(dev, "ffn").cpu().numpy()
+    assert np.isfinite(got).all()
+    for b in (0, w.B - 1):
+        rows = sample_rows(w, 10, seed=b)
+        assert rel_err(got[b, rows], oracle_rows(inp, b, rows, "ffn")) < tol_for(w, "ffn"), (m, r, b)
+
+
 def test_full_size_padding_property(fb):
     """Tokens at masked key positions cannot influence the context of any row (bitwise)."""
     w, inp, dev = workload("cfg2u_bert_base_b16_m512_pad_unit", fb)
