@@ -197,8 +197,12 @@ def attention_per_head(X, q, k, v, o, H, causal=False, key_len=None, scale=None)
     U_a^(h) [D, r], V_a^(h) [r, d_h]; Sec. FlashSVDAttention / Alg. 1 with V_a in r x d_h): q, k, v hold
     U [D, H r] (head h = columns h r ..), V [H, r, d_h] and b [D]; o is a whole-matrix factor.
 
-    Written as the plain definition: per head Q_h = (X U_h) V_h + b_h and likewise K_h, V_h; scores, masking and
-    softmax per query row; heads concatenated; factored output projection."""
+    Grouped heads (appendix, grouped-head compression: the H heads are compressed jointly in G groups of H / G heads,
+    interpolating between one factor pair for all heads, G = 1, and one per head, G = H) are the same with
+    V [G, r, D / G] and U [D, G r]: group g's pair rebuilds the D / G columns of its heads.  G is V.shape[0].
+
+    Written as the plain definition: per group the full-width columns (X U_g) V_g + b_g, split into its heads; scores,
+    masking and softmax per query row and head; heads concatenated; factored output projection."""
     X = _f64(X)
     B, M, D = X.shape
     d_h = D // H
@@ -206,8 +210,10 @@ def attention_per_head(X, q, k, v, o, H, causal=False, key_len=None, scale=None)
     out = np.empty((B, M, D), dtype=F64)
 
     def project(x, fac, h):
-        r = fac["V"].shape[1]
-        y = (x @ _f64(fac["U"])[:, h * r:(h + 1) * r]) @ _f64(fac["V"])[h]
+        G, r, width = np.shape(fac["V"])
+        hpg = H // G                              # heads per group
+        g, j = h // hpg, h % hpg
+        y = ((x @ _f64(fac["U"])[:, g * r:(g + 1) * r]) @ _f64(fac["V"])[g])[:, j * d_h:(j + 1) * d_h]
         if fac.get("b") is not None:
             y = y + _f64(fac["b"])[h * d_h:(h + 1) * d_h]
         return y

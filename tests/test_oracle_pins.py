@@ -274,6 +274,34 @@ def test_per_head_attention_equals_torch_dense_attention(mask):
     assert sum(f["U"].size + f["V"].size for f in (q, k, v)) == 3 * H * r * (D + d_h)
 
 
+@pytest.mark.parametrize("G", [1, 2, 4])
+def test_grouped_head_factors_interpolate_between_whole_matrix_and_per_head(G):
+    """G groups of H / G heads: G = 1 must be the whole-matrix block (the independently pinned O.attention), any G must
+    equal the dense block obtained by multiplying the group factors out (torch), and the parameter count follows the
+    grouped-head memory bound's G r (D + D / G) per projection."""
+    rng = np.random.default_rng(77 + G)
+    B, M, D, H, r = 2, 7, 32, 4, 3
+    d_h = D // H
+    X = rng.standard_normal((B, M, D))
+    gf = lambda: {"U": rng.standard_normal((D, G * r)) / np.sqrt(D), "V": rng.standard_normal((G, r, D // G)) / np.sqrt(r),
+                  "b": 0.1 * rng.standard_normal(D)}
+    q, k, v = gf(), gf(), gf()
+    o = {"U": rng.standard_normal((D, 5)) / np.sqrt(D), "V": rng.standard_normal((5, D)) / np.sqrt(5), "b": 0.1 * rng.standard_normal(D)}
+    key_len = np.array([4, 7])
+    got = O.attention_per_head(X, q, k, v, o, H, causal=True, key_len=key_len)
+    dense = lambda f: np.concatenate([f["U"][:, g * r:(g + 1) * r] @ f["V"][g] for g in range(G)], axis=1)
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    qq, kk, vv = (TF.linear(t(X), t(dense(f)).T, t(f["b"])).view(B, M, H, d_h).transpose(1, 2) for f in (q, k, v))
+    m = torch.tril(torch.ones(M, M, dtype=torch.bool))[None, None] & (torch.arange(M)[None, :] < torch.as_tensor(key_len)[:, None])[:, None, None, :]
+    c = TF.scaled_dot_product_attention(qq, kk, vv, attn_mask=m)
+    ref = TF.linear(c.transpose(1, 2).reshape(B, M, D), t(o["U"] @ o["V"]).T, t(o["b"])).numpy()
+    assert np.abs(got - ref).max() < 1e-10
+    if G == 1:
+        whole = lambda f: {"U": f["U"], "V": f["V"][0], "b": f["b"]}
+        assert np.abs(got - O.attention(X, whole(q), whole(k), whole(v), o, H, causal=True, key_len=key_len)).max() < 1e-12
+    assert q["U"].size + q["V"].size == G * r * (D + D // G)
+
+
 def test_softmax_rows():
     rng = np.random.default_rng(1)
     s = rng.standard_normal((5, 9)) * 4
