@@ -40,7 +40,7 @@ def useful_flops(w, mean_pairs):
     T, D, F, ra, rf = w.T, w.D, w.F, w.r_attn, w.r_ffn
     f = {
         # per-head factors of q, k, v: H r columns per projection, each head rebuilt from its own r ranks
-        "rank_proj_qkv": 6.0 * T * D * (w.H * w.r_head if w.r_head > 0 else ra),
+        "rank_proj_qkv": 6.0 * T * D * ((w.head_groups or w.H) * w.r_head if w.r_head > 0 else ra),
         "rebuild_qkv": 6.0 * T * (w.r_head if w.r_head > 0 else ra) * D,
         "attn_core": 4.0 * D * mean_pairs,
         "out_proj": 4.0 * T * D * ra,
@@ -187,7 +187,7 @@ def main():
     ra, rf = w.r_attn, w.r_ffn
     per_head = w.r_head > 0       # per-head factors of q, k, v: the layer goes through fsvd_layer_heads
     rh = w.r_head
-    ws_bytes = (fb.fsvd_layer_heads_workspace(d, rh, rh, rh, ra, rf, rf) if per_head
+    ws_bytes = (fb.fsvd_layer_groups_workspace(d, w.head_groups, rh, rh, rh, ra, rf, rf) if per_head
                 else fb.fsvd_layer_workspace(d, ra, ra, ra, ra, rf, rf))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
     out = torch.empty((w.B, w.M, w.D), dtype=torch.float32, device="cuda:0")
@@ -276,7 +276,7 @@ def main():
     stream_bytes = T * D * (2 if w.norm == "none" else 4)
     unfused = stream_bytes + T * D * 2 + max(T * 3 * ra * 2 + 3 * T * D * 2, 2 * T * rf * 2 + T * F * 2)
     if per_head:      # P_q | P_k | P_v have H r columns each
-        unfused = stream_bytes + T * D * 2 + max(T * 3 * w.H * rh * 2 + 3 * T * D * 2, 2 * T * rf * 2 + T * F * 2)
+        unfused = stream_bytes + T * D * 2 + max(T * 3 * (w.head_groups or w.H) * rh * 2 + 3 * T * D * 2, 2 * T * rf * 2 + T * F * 2)
     result = {
         "metric": "fused low-rank layer tokens/s + peak transient activation MB; % MFMA peak",
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -287,7 +287,7 @@ def main():
                    "weights": ("prepacked tile images where accepted (" + ", ".join(
                        f"{n}.{'U' if u else ''}{'V' if v else ''}" for n, (u, v) in fb.TILED_OK.items()) + ")")
                    if args.weights == "tiled" else "row-major",
-                   **({"r_head": rh, "qkv_factors": "per head"} if per_head else {})},
+                   **({"r_head": rh, "qkv_factors": (f"{w.head_groups} head groups" if w.head_groups else "per head")} if per_head else {})},
         "useful_tflops": round(fl["total"] / (ms * 1e-3) / 1e12, 2),
         "mfma_peak_frac": round(fl["total"] / (ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS, 4),
         "transient_mb": round(ws_bytes / 2 ** 20, 2), "unfused_transient_mb": round(unfused / 2 ** 20, 2),

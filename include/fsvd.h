@@ -84,6 +84,7 @@ typedef struct {
   int32_t out_dim;
   int32_t u_layout;   /* fsvd_layout of U */
   int32_t v_layout;   /* fsvd_layout of V */
+  int32_t groups;     /* only read by the *_heads entry points: number of head groups G (0 = one group per head) */
 } fsvd_factor;
 
 /* Problem descriptor (host memory). */
@@ -140,8 +141,16 @@ fsvd_status fsvd_attention(const fsvd_desc *desc, const void *X, const fsvd_fact
  * r_a ranks, so the on-chip rebuild costs 2 * r_a * d_h FLOPs per key and tile instead of 2 * r * d_h with a
  * whole-matrix rank r.  Ranks are multiples of 16 (r_a <= d_h is the intended range, larger values work).
  * Same conventions, limits and errors as fsvd_attention; additionally H * rank * D < 2^29.
+ *
+ * Grouped heads (appendix, grouped-head compression): with `groups` = G (a divisor of H, the same for q, k, v) the
+ * heads are compressed jointly in G groups of H / G consecutive heads; `rank` is then the rank of ONE group,
+ * U = [U^(1) | ... | U^(G)] [D, G * rank] and V = [G, rank, D / G] (group g's pair rebuilds the columns of its heads).
+ * G = H (or 0) is the per-head layout above, G = 1 computes the same as fsvd_attention.  The workspace of a grouped
+ * call is sized by the *_groups_workspace functions (the *_heads_workspace functions are the case G = H).
  */
 size_t fsvd_attention_heads_workspace(const fsvd_desc *desc, int32_t r_q, int32_t r_k, int32_t r_v, int32_t r_o);
+size_t fsvd_attention_groups_workspace(const fsvd_desc *desc, int32_t groups, int32_t r_q, int32_t r_k, int32_t r_v,
+                                       int32_t r_o);
 fsvd_status fsvd_attention_heads(const fsvd_desc *desc, const void *X, const fsvd_factor *q, const fsvd_factor *k,
                                  const fsvd_factor *v, const fsvd_factor *o, void *out, void *workspace,
                                  size_t workspace_bytes, void *hip_stream);
@@ -174,6 +183,8 @@ fsvd_status fsvd_layer(const fsvd_desc *desc, const void *X, const fsvd_factor *
 /* The same layer with per-head factors of q, k and v (see fsvd_attention_heads); o, w1, w2 as in fsvd_layer. */
 size_t fsvd_layer_heads_workspace(const fsvd_desc *desc, int32_t r_q, int32_t r_k, int32_t r_v, int32_t r_o,
                                   int32_t r_1, int32_t r_2);
+size_t fsvd_layer_groups_workspace(const fsvd_desc *desc, int32_t groups, int32_t r_q, int32_t r_k, int32_t r_v,
+                                   int32_t r_o, int32_t r_1, int32_t r_2);
 fsvd_status fsvd_layer_heads(const fsvd_desc *desc, const void *X, const fsvd_factor *q, const fsvd_factor *k,
                              const fsvd_factor *v, const fsvd_factor *o, const void *ln1_gamma, const void *ln1_beta,
                              const fsvd_factor *w1, const fsvd_factor *w2, const void *ln2_gamma, const void *ln2_beta,

@@ -32,7 +32,8 @@ EXPORTS = ["fsvd_attention_workspace", "fsvd_ffn_workspace", "fsvd_layer_workspa
            "fsvd_ffn_core", "fsvd_ffn_core_workspace", "fsvd_layernorm", "fsvd_status_string", "fsvd_version", "fsvd_fm_bytes", "fsvd_pack_fm",
            "fsvd_unpack_fm", "fsvd_tiled_bytes", "fsvd_pack_tiled", "fsvd_linear_tiled", "fsvd_decode_kcache_bytes",
            "fsvd_decode_vcache_bytes", "fsvd_decode_cache_write", "fsvd_decode_attention_workspace", "fsvd_decode_attention",
-           "fsvd_decode_core_workspace", "fsvd_decode_attention_core"]
+           "fsvd_decode_core_workspace", "fsvd_decode_attention_core",
+           "fsvd_attention_groups_workspace", "fsvd_layer_groups_workspace"]
 
 
 class FsvdError(RuntimeError):
@@ -44,7 +45,7 @@ class FsvdError(RuntimeError):
 class fsvd_factor(C.Structure):
     _fields_ = [("U", C.c_void_p), ("V", C.c_void_p), ("bias", C.c_void_p),
                 ("in_dim", C.c_int32), ("rank", C.c_int32), ("out_dim", C.c_int32),
-                ("u_layout", C.c_int32), ("v_layout", C.c_int32)]
+                ("u_layout", C.c_int32), ("v_layout", C.c_int32), ("groups", C.c_int32)]
 
 
 class fsvd_desc(C.Structure):
@@ -80,6 +81,10 @@ def lib():
         L.fsvd_attention.argtypes = [D, P, F, F, F, F, P, P, sz, P]
         L.fsvd_attention_heads_workspace.restype = sz
         L.fsvd_attention_heads_workspace.argtypes = [D, i32, i32, i32, i32]
+        L.fsvd_attention_groups_workspace.restype = sz
+        L.fsvd_attention_groups_workspace.argtypes = [D, i32, i32, i32, i32, i32]
+        L.fsvd_layer_groups_workspace.restype = sz
+        L.fsvd_layer_groups_workspace.argtypes = [D, i32, i32, i32, i32, i32, i32, i32]
         L.fsvd_attention_heads.restype = C.c_int
         L.fsvd_attention_heads.argtypes = [D, P, F, F, F, F, P, P, sz, P]
         L.fsvd_ffn.restype = C.c_int
@@ -173,16 +178,17 @@ class Factor:
 
 @dataclass
 class HeadFactor(Factor):
-    """Per-head factors of one attention projection: U [D, H r], V [H, r, d_h], b [D] or None."""
+    """Per-head or grouped-head factors of one attention projection: U [D, G r], V [G, r, D / G], b [D] or None
+    (G = H: one pair per head)."""
 
     def c(self) -> fsvd_factor:
         for t in (self.U, self.V, self.b):
             assert t is None or (t.is_contiguous() and t.is_cuda)
-        H, r, d_h = self.V.shape
-        assert self.U.shape[1] == H * r and self.V_tiled is None
+        G, r, width = self.V.shape
+        assert self.U.shape[1] == G * r and self.V_tiled is None
         u = self.U if self.U_tiled is None else self.U_tiled
         return fsvd_factor(u.data_ptr(), self.V.data_ptr(), 0 if self.b is None else self.b.data_ptr(),
-                           self.U.shape[0], r, H * d_h, int(self.U_tiled is not None), 0)
+                           self.U.shape[0], r, G * width, int(self.U_tiled is not None), 0, G)
 
     def with_tiled(self, u: bool = False, v: bool = False) -> "HeadFactor":
         assert not v, "V of a per-head factor stays row-major"
@@ -239,12 +245,16 @@ def fsvd_attention_heads_workspace(desc, r_q, r_k, r_v, r_o) -> int:
     return lib().fsvd_attention_heads_workspace(C.byref(desc), r_q, r_k, r_v, r_o)
 
 
+def fsvd_attention_groups_workspace(desc, groups, r_q, r_k, r_v, r_o) -> int:
+    return lib().fsvd_attention_groups_workspace(C.byref(desc), groups, r_q, r_k, r_v, r_o)
+
+
 def fsvd_attention_heads(desc, X, q: HeadFactor, k: HeadFactor, v: HeadFactor, o: Factor, out=None, workspace=None):
     """Attention block with per-head factors of q, k, v (o: whole-matrix factor)."""
     if out is None:
         out = torch.empty(X.shape, dtype=_out_dtype(desc), device=X.device)
     if workspace is None:
-        workspace = _workspace(fsvd_attention_heads_workspace(desc, q.rank, k.rank, v.rank, o.rank), X.device)
+        workspace = _workspace(fsvd_attention_groups_workspace(desc, q.V.shape[0], q.rank, k.rank, v.rank, o.rank), X.device)
     fq, fk, fv, fo = q.c(), k.c(), v.c(), o.c()
     _check(lib().fsvd_attention_heads(C.byref(desc), _ptr(X), C.byref(fq), C.byref(fk), C.byref(fv), C.byref(fo),
                                       _ptr(out), _ptr(workspace), workspace.numel(), _stream()), "fsvd_attention_heads")
@@ -297,12 +307,17 @@ def fsvd_layer_heads_workspace(desc, r_q, r_k, r_v, r_o, r_1, r_2) -> int:
     return lib().fsvd_layer_heads_workspace(C.byref(desc), r_q, r_k, r_v, r_o, r_1, r_2)
 
 
+def fsvd_layer_groups_workspace(desc, groups, r_q, r_k, r_v, r_o, r_1, r_2) -> int:
+    return lib().fsvd_layer_groups_workspace(C.byref(desc), groups, r_q, r_k, r_v, r_o, r_1, r_2)
+
+
 def fsvd_layer_heads(desc, X, q, k, v, o, ln1_gamma, ln1_beta, w1, w2, ln2_gamma, ln2_beta, out=None, workspace=None):
     """One layer with per-head factors of q, k, v (HeadFactor); o, w1, w2 whole-matrix factors."""
     if out is None:
         out = torch.empty(X.shape, dtype=_out_dtype(desc), device=X.device)
     if workspace is None:
-        workspace = _workspace(fsvd_layer_heads_workspace(desc, q.rank, k.rank, v.rank, o.rank, w1.rank, w2.rank), X.device)
+        workspace = _workspace(fsvd_layer_groups_workspace(desc, q.V.shape[0], q.rank, k.rank, v.rank, o.rank, w1.rank, w2.rank),
+                               X.device)
     fq, fk, fv, fo, f1, f2 = q.c(), k.c(), v.c(), o.c(), w1.c(), w2.c()
     _check(lib().fsvd_layer_heads(C.byref(desc), _ptr(X), C.byref(fq), C.byref(fk), C.byref(fv), C.byref(fo),
                                   _ptr(ln1_gamma), _ptr(ln1_beta), C.byref(f1), C.byref(f2), _ptr(ln2_gamma),

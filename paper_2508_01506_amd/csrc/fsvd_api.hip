@@ -74,13 +74,17 @@ fsvd_status check_attn(const fsvd_desc* d, const fsvd_factor* q, const fsvd_fact
   if (q->v_layout != k->v_layout || q->v_layout != v->v_layout) return FSVD_ERR_UNSUPPORTED;
   return FSVD_OK;
 }
-// per-head factors of q, k, v: in_dim = out_dim = D, `rank` is the rank of ONE head
+// number of groups of a grouped factor: the `groups` member, 0 meaning one group per head
+inline int groups_of(const fsvd_desc* d, const fsvd_factor* f) { return f->groups > 0 ? f->groups : d->H; }
+// grouped (per-head) factors of q, k, v: in_dim = out_dim = D, `rank` is the rank of ONE group
 fsvd_status check_attn_heads(const fsvd_desc* d, const fsvd_factor* q, const fsvd_factor* k, const fsvd_factor* v,
                              const fsvd_factor* o, bool ptrs) {
   FSVD_TRY(check_desc(d, false));
   for (const fsvd_factor* f : {q, k, v}) {
-    FSVD_TRY(check_factor(f, d->D, d->D, ptrs, ptrs, 1));      // U [D, H r] feeds a plain projection; V stays row-major
-    if ((long long)f->rank * d->H * d->D >= (1LL << 29)) return FSVD_ERR_UNSUPPORTED;
+    FSVD_TRY(check_factor(f, d->D, d->D, ptrs, ptrs, 1));      // U [D, G r] feeds a plain projection; V stays row-major
+    if (f->groups < 0 || d->H % groups_of(d, f) != 0) return FSVD_ERR_INVALID_ARG;
+    if (f->groups != q->groups) return FSVD_ERR_UNSUPPORTED;
+    if ((long long)f->rank * groups_of(d, f) * d->D >= (1LL << 29)) return FSVD_ERR_UNSUPPORTED;
   }
   if (q->u_layout != k->u_layout || q->u_layout != v->u_layout) return FSVD_ERR_UNSUPPORTED;
   FSVD_TRY(check_factor(o, d->D, d->D, ptrs, ptrs, 3));
@@ -136,8 +140,8 @@ fsvd_status run_attention(const fsvd_desc* d, const void* x_fm, const fsvd_facto
   const int T = d->B * d->M, D = d->D;
   // per-head factors: U [D, H r] is one projection matrix with H r columns, head h's rank-space activations are
   // columns h r .. of P; V [H, r, d_h] is read per head by the attention core
-  const int hq = per_head ? d->H * q->rank : q->rank, hk = per_head ? d->H * k->rank : k->rank,
-            hv = per_head ? d->H * v->rank : v->rank;
+  const int G = per_head ? groups_of(d, q) : 1;
+  const int hq = G * q->rank, hk = G * k->rank, hv = G * v->rank;
   const AttnPlan pl = plan_attn(T, D, hq, hk, hv, o->rank);
   char* Pq = rank_buf;
   char* Pk = rank_buf + (pl.pk - pl.p);
@@ -155,7 +159,7 @@ fsvd_status run_attention(const fsvd_desc* d, const void* x_fm, const fsvd_facto
 
   AttnCoreArgs ca{};
   ca.Pq = Pq; ca.Pk = Pk; ca.Pv = Pv;
-  ca.rq = q->rank; ca.rk = k->rank; ca.rv = v->rank; ca.per_head = per_head ? 1 : 0;
+  ca.rq = q->rank; ca.rk = k->rank; ca.rv = v->rank; ca.per_head = per_head ? d->H / G : 0;
   ca.Vq = q->V; ca.Vk = k->V; ca.Vv = v->V;
   ca.bq = q->bias; ca.bk = k->bias; ca.bv = v->bias;
   ca.w_dt = d->io_dtype; ca.tiled = q->v_layout == FSVD_TILED;
@@ -279,10 +283,15 @@ fsvd_status fsvd_attention(const fsvd_desc* d, const void* X, const fsvd_factor*
   return run_attention(d, w + pl.c, q, k, v, o, nullptr, 0, out, d->out_dtype, false, w + pl.c, w + pl.p, s);
 }
 
-size_t fsvd_attention_heads_workspace(const fsvd_desc* d, int32_t rq, int32_t rk, int32_t rv, int32_t ro) {
+size_t fsvd_attention_groups_workspace(const fsvd_desc* d, int32_t groups, int32_t rq, int32_t rk, int32_t rv, int32_t ro) {
   if (check_desc(d, false) != FSVD_OK) return 0;
   if (check_rank(rq) || check_rank(rk) || check_rank(rv) || check_rank(ro)) return 0;
-  return plan_attn((size_t)d->B * d->M, d->D, (size_t)d->H * rq, (size_t)d->H * rk, (size_t)d->H * rv, ro).total;
+  const size_t G = groups > 0 ? groups : d->H;
+  if (groups < 0 || d->H % G != 0) return 0;
+  return plan_attn((size_t)d->B * d->M, d->D, G * rq, G * rk, G * rv, ro).total;
+}
+size_t fsvd_attention_heads_workspace(const fsvd_desc* d, int32_t rq, int32_t rk, int32_t rv, int32_t ro) {
+  return fsvd_attention_groups_workspace(d, 0, rq, rk, rv, ro);
 }
 
 fsvd_status fsvd_attention_heads(const fsvd_desc* d, const void* X, const fsvd_factor* q, const fsvd_factor* k,
@@ -291,7 +300,8 @@ fsvd_status fsvd_attention_heads(const fsvd_desc* d, const void* X, const fsvd_f
   FSVD_TRY(check_attn_heads(d, q, k, v, o, true));
   if (!X || !out || mis16(X) || mis16(out)) return FSVD_ERR_INVALID_ARG;
   const int T = d->B * d->M;
-  const AttnPlan pl = plan_attn(T, d->D, (size_t)d->H * q->rank, (size_t)d->H * k->rank, (size_t)d->H * v->rank, o->rank);
+  const size_t G = groups_of(d, q);
+  const AttnPlan pl = plan_attn(T, d->D, G * q->rank, G * k->rank, G * v->rank, o->rank);
   FSVD_TRY(check_ws(ws, ws_bytes, pl.total));
   hipStream_t s = (hipStream_t)stream;
   char* w = (char*)ws;
@@ -319,7 +329,7 @@ fsvd_status layer_impl(const fsvd_desc* d, const void* X, const fsvd_factor* q, 
   if (!X || !out || mis16(X) || mis16(out)) return FSVD_ERR_INVALID_ARG;
   if (d->norm != FSVD_NORM_NONE && (!g1 || !b1 || !g2 || !b2)) return FSVD_ERR_INVALID_ARG;
   if (mis16(g1) || mis16(b1) || mis16(g2) || mis16(b2)) return FSVD_ERR_INVALID_ARG;
-  const size_t hm = per_head ? (size_t)d->H : 1;     // per-head factors: H * rank columns of P per projection
+  const size_t hm = per_head ? (size_t)groups_of(d, q) : 1;     // grouped factors: G * rank columns of P per projection
   const LayerPlan pl = plan_layer(d, hm * q->rank, hm * k->rank, hm * v->rank, o->rank, w1->rank, w2->rank);
   FSVD_TRY(check_ws(ws, ws_bytes, pl.total));
   hipStream_t s = (hipStream_t)stream;
@@ -370,11 +380,16 @@ fsvd_status fsvd_layer(const fsvd_desc* d, const void* X, const fsvd_factor* q, 
   return layer_impl(d, X, q, k, v, o, g1, b1, w1, w2, g2, b2, out, ws, ws_bytes, stream, false);
 }
 
-size_t fsvd_layer_heads_workspace(const fsvd_desc* d, int32_t rq, int32_t rk, int32_t rv, int32_t ro, int32_t r1, int32_t r2) {
+size_t fsvd_layer_groups_workspace(const fsvd_desc* d, int32_t groups, int32_t rq, int32_t rk, int32_t rv, int32_t ro, int32_t r1,
+                                   int32_t r2) {
   if (check_desc(d, true) != FSVD_OK) return 0;
   if (check_rank(rq) || check_rank(rk) || check_rank(rv) || check_rank(ro) || check_rank(r1) || check_rank(r2)) return 0;
-  const size_t H = d->H;
-  return plan_layer(d, H * rq, H * rk, H * rv, ro, r1, r2).total;
+  const size_t G = groups > 0 ? groups : d->H;
+  if (groups < 0 || d->H % G != 0) return 0;
+  return plan_layer(d, G * rq, G * rk, G * rv, ro, r1, r2).total;
+}
+size_t fsvd_layer_heads_workspace(const fsvd_desc* d, int32_t rq, int32_t rk, int32_t rv, int32_t ro, int32_t r1, int32_t r2) {
+  return fsvd_layer_groups_workspace(d, 0, rq, rk, rv, ro, r1, r2);
 }
 
 fsvd_status fsvd_layer_heads(const fsvd_desc* d, const void* X, const fsvd_factor* q, const fsvd_factor* k,
@@ -457,7 +472,9 @@ fsvd_status attention_core_impl(const fsvd_desc* d, const void* Pq, const void* 
   if (!Pq || !Pk || !Pv || !context || mis16(Pq) || mis16(Pk) || mis16(Pv) || mis16(context)) return FSVD_ERR_INVALID_ARG;
   AttnCoreArgs ca{};
   ca.Pq = Pq; ca.Pk = Pk; ca.Pv = Pv;
-  ca.rq = q->rank; ca.rk = k->rank; ca.rv = v->rank; ca.per_head = per_head ? 1 : 0;
+  if (per_head && (q->groups < 0 || d->H % groups_of(d, q) != 0 || k->groups != q->groups || v->groups != q->groups))
+    return FSVD_ERR_INVALID_ARG;
+  ca.rq = q->rank; ca.rk = k->rank; ca.rv = v->rank; ca.per_head = per_head ? d->H / groups_of(d, q) : 0;
   ca.Vq = q->V; ca.Vk = k->V; ca.Vv = v->V; ca.bq = q->bias; ca.bk = k->bias; ca.bv = v->bias;
   ca.w_dt = d->io_dtype; ca.tiled = q->v_layout == FSVD_TILED; ca.B = d->B; ca.M = d->M; ca.D = d->D; ca.H = d->H;
   ca.causal = d->causal; ca.key_len = d->key_len; ca.scale = resolve_scale(d);

@@ -113,10 +113,10 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
       for (int qt = 0; qt < QT; ++qt) acc[dt][qt] = zero16();
     // rank window of this head in V_q / P_q: all of [0, r_q) for whole-matrix factors, [h r_q, (h+1) r_q) of the
     // concatenated ranks for per-head factors; chunks are 64 ranks of the concatenated axis
-    const int lo = a.per_head ? h * a.rq : 0, hi = lo + a.rq;
+    const int lo = a.per_head ? (h / a.per_head) * a.rq : 0, hi = lo + a.rq;
     const int c0 = lo / kChunkK, nc = (hi - 1) / kChunkK - c0 + 1;
-    const int ld = a.per_head ? DH : D, wcol0 = a.per_head ? 0 : col0;
-    const int rtot = a.per_head ? a.H * a.rq : a.rq;
+    const int ld = a.per_head ? a.per_head * DH : D, wcol0 = a.per_head ? (h % a.per_head) * DH : col0;
+    const int rtot = a.per_head ? (a.H / a.per_head) * a.rq : a.rq;
     const int pchq = (rtot + kChunkK - 1) / kChunkK;
     const long long p_total = (long long)fm_bytes(T, rtot);
     const long long w_total = (long long)rtot * ld * 2;
@@ -211,12 +211,12 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
   const char* const Psrc = which ? uniform_ptr(a.Pv) : uniform_ptr(a.Pk);
   const char* const bsel = which ? uniform_ptr(a.bv) : uniform_ptr(a.bk);
   // rank windows of this head in (V_k, P_k) and (V_v, P_v), as in the Q phase
-  const int lo_k = a.per_head ? h * a.rk : 0, hi_k = lo_k + a.rk;
-  const int lo_v = a.per_head ? h * a.rv : 0, hi_v = lo_v + a.rv;
+  const int lo_k = a.per_head ? (h / a.per_head) * a.rk : 0, hi_k = lo_k + a.rk;
+  const int lo_v = a.per_head ? (h / a.per_head) * a.rv : 0, hi_v = lo_v + a.rv;
   const int c0_k = lo_k / kChunkK, nch_k = (hi_k - 1) / kChunkK - c0_k + 1;
   const int c0_v = lo_v / kChunkK, nch_v = (hi_v - 1) / kChunkK - c0_v + 1;
-  const int ld = a.per_head ? DH : D, wcol0 = a.per_head ? 0 : col0;
-  const int rtot_k = a.per_head ? a.H * a.rk : a.rk, rtot_v = a.per_head ? a.H * a.rv : a.rv;
+  const int ld = a.per_head ? a.per_head * DH : D, wcol0 = a.per_head ? (h % a.per_head) * DH : col0;
+  const int rtot_k = a.per_head ? (a.H / a.per_head) * a.rk : a.rk, rtot_v = a.per_head ? (a.H / a.per_head) * a.rv : a.rv;
   const long long wt_k = (long long)rtot_k * ld * 2, wt_v = (long long)rtot_v * ld * 2;
   // the P operands of this wavefront's role
   const int rtot_p = which ? rtot_v : rtot_k;

@@ -46,9 +46,10 @@ hipError_t launch_linear(const LinearArgs& a, hipStream_t s);
 
 // ---- streaming attention core (Alg. 1 Part II): FM P_q, P_k, P_v -> FM context C [T, D]
 struct AttnCoreArgs {
-  const void* Pq; const void* Pk; const void* Pv;   // FM [B*M, r_x] (per-head factors: [B*M, H * r_x], head h = columns h r_x ..)
+  const void* Pq; const void* Pk; const void* Pv;   // FM [B*M, r_x] (grouped factors: [B*M, G * r_x], group g = columns g r_x ..)
   int rq, rk, rv;
-  int per_head;            // 0: whole-matrix factors, V_x [r_x, D]; 1: per-head factors, V_x [H, r_x, d_h]
+  int per_head;            // 0: whole-matrix factors, V_x [r_x, D]; n >= 1: grouped factors with n heads per group,
+                           // V_x [H / n, r_x, n d_h] (n = 1: one pair per head)
   const void* Vq; const void* Vk; const void* Vv;   // stored in w_dt
   const void* bq; const void* bk; const void* bv;   // [D] in w_dt or nullptr
   int w_dt;

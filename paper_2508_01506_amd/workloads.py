@@ -43,8 +43,10 @@ class Workload:
     norm: str = "post_ln"       # "post_ln" | "pre_ln" | "none"
     factors: str = "gaussian"   # "gaussian" | "spectrum" | "spectrum_unit"
     min_len: int = 0            # padding mask: key_len ~ integers U[min_len, M]
-    r_head: int = 0             # > 0: q, k, v are factored per head with this rank (U [D, H r], V [H, r, d_h]);
-                                # the output projection keeps a whole-matrix factorisation of rank r_attn
+    r_head: int = 0             # > 0: q, k, v are factored per head (or per head group) with this rank
+                                # (U [D, G r], V [G, r, D / G]); the output projection keeps a whole-matrix
+                                # factorisation of rank r_attn
+    head_groups: int = 0        # with r_head > 0: number of head groups G sharing one factor pair (0 = one per head)
     seed: int = 1506
     ln_eps: float = 1e-5
 
@@ -117,6 +119,19 @@ FFN_GRID = [(m, r) for m in (128, 256, 512, 1024) for r in (768, 384, 192, 96)]
 for _i, (_m, _r) in enumerate(FFN_GRID):
     _register(_wl(10, _i, name=f"ffn_grid_b16_m{_m}_r{_r}", B=16, M=_m, D=768, H=12, F=3072, r_attn=64, r_ffn=_r,
                   dtype="fp16"))
+
+
+# Grouped heads (appendix, grouped-head compression): G groups of H / G heads share one rank-r pair per projection.
+_register(_wl(11, name="gh_bert_base_b16_m512_g4_r96", B=16, M=512, D=768, H=12, F=3072, r_attn=192, r_ffn=384,
+              dtype="fp16", mask="padding", min_len=256, r_head=96, head_groups=4))
+_register(_wl(11, 1, name="gh_bert_base_b16_m512_g2_r192", B=16, M=512, D=768, H=12, F=3072, r_attn=192, r_ffn=384,
+              dtype="fp16", mask="padding", min_len=256, r_head=192, head_groups=2))
+_register(_wl(11, 2, name="gh_tiny_g2_r48_causal", B=2, M=150, D=256, H=4, F=256, r_attn=48, r_ffn=64, dtype="bf16",
+              mask="causal", r_head=48, head_groups=2))
+_register(_wl(11, 3, name="gh_tiny_d128_g2_r80", B=1, M=270, D=512, H=4, F=512, r_attn=80, r_ffn=64, dtype="fp16",
+              mask="padding", min_len=100, r_head=80, head_groups=2))
+_register(_wl(11, 4, name="gh_tiny_g1_r64", B=2, M=100, D=128, H=2, F=256, r_attn=48, r_ffn=64, dtype="fp16",
+              r_head=64, head_groups=1))
 
 
 def get_workload(name: str, **overrides) -> Workload:
@@ -227,11 +242,12 @@ def make_inputs(w: Workload) -> dict:
         out[name + "_beta"] = round_to_storage(0.02 * rng.standard_normal(w.D), st)
 
     def head_factor(name: str):
-        # per head: U_h ~ N(0, 1/D) [D, r], V_h ~ N(0, 1/r) [r, d_h]; stored as U [D, H r] (head h = columns h r ..)
-        # and V [H, r, d_h]
+        # per group (per head when G = H): U_g ~ N(0, 1/D) [D, r], V_g ~ N(0, 1/r) [r, D / G]; stored as U [D, G r]
+        # (group g = columns g r ..) and V [G, r, D / G]
         r = w.r_head
-        u = rng.standard_normal((w.D, w.H * r)) / np.sqrt(w.D)
-        v = rng.standard_normal((w.H, r, w.d_h)) / np.sqrt(r)
+        G = w.head_groups if w.head_groups > 0 else w.H
+        u = rng.standard_normal((w.D, G * r)) / np.sqrt(w.D)
+        v = rng.standard_normal((G, r, w.D // G)) / np.sqrt(r)
         b = 0.02 * rng.standard_normal(w.D)
         out[name] = {"U": round_to_storage(u, st), "V": round_to_storage(v, st), "b": round_to_storage(b, st)}
 

@@ -272,6 +272,36 @@ def test_attention_with_per_head_factors_encoder_shapes(fb, name):
         assert rel_err(got[b:b + 1], ref) < attn_block_tol(w, ref)
 
 
+@pytest.mark.parametrize("name", ["gh_tiny_g2_r48_causal", "gh_tiny_d128_g2_r80", "gh_tiny_g1_r64"])
+def test_attention_and_layer_with_grouped_head_factors_small(fb, name):
+    """Grouped heads (G groups of H / G heads share one factor pair): every element of the block and of the layer; the
+    group's rank window straddles 64-rank chunks (48, 80), both head widths, G = 1 included."""
+    w, inp, dev = workload(name, fb)
+    got = gpu_call(dev, "attention").cpu().numpy()
+    ref = oracle_call(inp, "attention")
+    assert np.isfinite(got).all()
+    assert rel_err(got, ref) < attn_block_tol(w, ref)
+    assert rel_err(gpu_call(dev, "layer").cpu().numpy(), oracle_call(inp, "layer")) < TOL_LAYER
+
+
+def test_one_group_of_all_heads_equals_the_whole_matrix_block(fb):
+    """G = 1 is the whole-matrix factorisation: the grouped entry point must agree with fsvd_attention on the same factors."""
+    w, inp, dev = workload("gh_tiny_g1_r64", fb)
+    whole = {n: fb.Factor(dev[n].U, dev[n].V[0].contiguous(), dev[n].b) for n in "qkv"}
+    a = fb.fsvd_attention_heads(dev["desc"], dev["X"], dev["q"], dev["k"], dev["v"], dev["o"])
+    b = fb.fsvd_attention(dev["desc"], dev["X"], whole["q"], whole["k"], whole["v"], dev["o"])
+    assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("name", ["gh_bert_base_b16_m512_g4_r96", "gh_bert_base_b16_m512_g2_r192"])
+def test_layer_with_grouped_head_factors_encoder_shapes(fb, name):
+    w, inp, dev = workload(name, fb, "tiled")
+    got = gpu_call(dev, "layer").cpu().numpy()
+    for b in (0, w.B - 1):
+        one = dict(inp, X=inp["X"][b:b + 1], key_len=None if inp["key_len"] is None else inp["key_len"][b:b + 1])
+        assert rel_err(got[b:b + 1], oracle_call(one, "layer")) < TOL_LAYER
+
+
 @pytest.mark.parametrize("norm", ["post_ln", "pre_ln"])
 @pytest.mark.parametrize("name", ["ph_tiny_r16", "ph_tiny_r48_causal", "ph_tiny_d128_r32"])
 def test_layer_with_per_head_attention_meets_the_gate(fb, name, norm):

@@ -183,6 +183,26 @@ def test_tiled_weight_layout_contract():
     assert L.fsvd_linear_tiled(16, 40, 16, 256, 0, 256, None, 0, None, 0, 256, 0, None) == UNSUPPORTED
 
 
+def test_grouped_head_factors_contract():
+    """`groups` of the *_heads entry points: a divisor of H, the same for q, k, v; 0 means one group per head."""
+    L = fb.lib()
+    d = desc()                                                                  # H = 12
+    o = fac(768, 64, 768)
+    need = fb.fsvd_attention_heads_workspace(d, 96, 96, 96, 64)
+
+    def grp(g, r=96):
+        f = fac(768, r, 768)
+        return fb.fsvd_factor(f.U, f.V, f.bias, f.in_dim, f.rank, f.out_dim, 0, 0, g)
+    call = lambda a, b, c: L.fsvd_attention_heads(C.byref(d), None, C.byref(a), C.byref(b), C.byref(c), C.byref(o), 256, 256, need, None)
+    for g in (0, 1, 2, 3, 4, 6, 12):
+        assert call(grp(g), grp(g), grp(g)) == INVALID                          # passes the factor checks, then X is NULL
+    ok = lambda a, b, c: L.fsvd_attention_heads(C.byref(d), 256, C.byref(a), C.byref(b), C.byref(c), C.byref(o), 256, 256, 16, None)
+    assert ok(grp(4), grp(4), grp(4)) == WORKSPACE                              # valid factors: only the workspace is short
+    assert ok(grp(5), grp(5), grp(5)) == INVALID                                # 5 does not divide 12
+    assert ok(grp(-1), grp(-1), grp(-1)) == INVALID
+    assert ok(grp(4), grp(2), grp(4)) == UNSUPPORTED                            # q, k, v are grouped alike
+
+
 def test_decode_entry_points_contract():
     """Sizes of the rank-space KV cache and argument validation of the decoding step (no GPU needed)."""
     L = fb.lib()
