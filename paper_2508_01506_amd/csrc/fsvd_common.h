@@ -240,18 +240,25 @@ __device__ __forceinline__ int tr_lane_off_swz(int lane, int seg) {
 // voff_l) go to LDS byte address lds_addr + 16 l (lds_addr wave-uniform).  Issued as inline assembly so that the
 // compiler's wait-count bookkeeping does not see it: the compiler would otherwise wait for ALL such loads before any
 // LDS read and before every barrier, which defeats requesting tiles ahead.  The caller orders these loads against
-// their consumers with lds_dma_wait_barrier<N>() (they complete in issue order and are counted by vmcnt).
+// their consumers with lds_dma_wait_barrier<N>() (they complete in issue order and are counted by vmcnt).  The
+// statement is volatile (it keeps its place among the other requests and the wait/barrier statements) but does not
+// clobber memory: ordinary LDS reads of other buffers may be scheduled across it.
 __device__ __forceinline__ u4 lds_dma_rsrc(const void* base, unsigned bytes) {
   const unsigned long long b = (unsigned long long)base;
-  u4 r;
-  r[0] = (unsigned)b; r[1] = (unsigned)(b >> 32) & 0xffffu; r[2] = bytes; r[3] = 0x00020000u;
+  u4 r;      // pinned to scalar registers: the load's resource operand cannot be a vector register
+  r[0] = __builtin_amdgcn_readfirstlane((unsigned)b);
+  r[1] = __builtin_amdgcn_readfirstlane((unsigned)(b >> 32) & 0xffffu);
+  r[2] = __builtin_amdgcn_readfirstlane(bytes);
+  r[3] = 0x00020000u;
   return r;
 }
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"   // m0 is reserved; naming it documents that the statement overwrites it
 __device__ __forceinline__ void lds_dma16(u4 rsrc, unsigned lds_addr, int voff, int soff) {
+  lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+  soff = __builtin_amdgcn_readfirstlane(soff);
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
+               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "m0");
 }
 #pragma clang diagnostic pop
 // wait until at most N of this wavefront's vector-memory operations are outstanding and all its LDS operations are
