@@ -196,14 +196,16 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
 
   // =================================== KV loop ===================================
   f16v o[DT32][QT];
+  // Softmax state per query (lane): reference maximum and row sum.
   float m_run[QT], l_run[QT];
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
-    m_run[qt] = -1e30f;
+    m_run[qt] = 0.f;
     l_run[qt] = 0.f;
 #pragma unroll
     for (int dt = 0; dt < DT32; ++dt) o[dt][qt] = zero16();
   }
+  bool first = true;       // no key block has been folded in yet (wave-uniform)
 
   const int which = wave & 1;                 // 0: keys, 1: values
   const int kt0 = ((wave >> 1) / NDG) * KTW;  // first key tile of this wavefront
@@ -368,14 +370,26 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
           }
         }
       }
-#pragma unroll
-      for (int i = 0; i < KTW; ++i)
-#pragma unroll
-        for (int j = 0; j < DTW; ++j) acc[i][j] = zero16();
       __syncthreads();
 
       // ---- scores, streaming softmax, context for this wavefront's queries
       const int qlast = qw + 32 * QT - 1;
+      // The reference maximum is subtracted by the matrix core: one more contraction step whose K-side operand is 1 in
+      // two slots and whose Q-side operand holds -m_run of the lane's query, split into an fp16 head and tail (together
+      // they carry m_run to about 2^-22 relative).  The scores then leave the accumulators as S - m_run at the price of
+      // one MFMA per score tile instead of 16 vector subtractions.
+      h8 kone = {}, qneg[QT];
+      kone[0] = g == 0 ? (_Float16)1.0f : (_Float16)0.0f;
+      kone[1] = kone[0];
+      auto set_qneg = [&](int qt) {
+        const _Float16 hi = (_Float16)(-m_run[qt]);
+        const _Float16 lo = (_Float16)(-m_run[qt] - (float)hi);
+        qneg[qt] = h8{};
+        qneg[qt][0] = g == 0 ? hi : (_Float16)0.0f;
+        qneg[qt][1] = g == 0 ? lo : (_Float16)0.0f;
+      };
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) set_qneg(qt);
 #pragma unroll 1
       for (int ks = 0; ks < NKT; ++ks) {
         const int key0 = step * BKV + 32 * ks;
@@ -383,12 +397,12 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
         if (a.causal && key0 > qlast) break;
         f16v s[QT];
 #pragma unroll
-        for (int qt = 0; qt < QT; ++qt) s[qt] = zero16();
+        for (int qt = 0; qt < QT; ++qt) s[qt] = mfma32(kone, qneg[qt], zero16());   // -m_run in every row of the query's column
 #pragma unroll
         for (int ds = 0; ds < DST; ++ds) {
           const h8 kf = ktile[ks][ds][lane];
 #pragma unroll
-          for (int qt = 0; qt < QT; ++qt) s[qt] = mfma32(kf, qf[ds][qt], s[qt]);   // S^T: rows keys, cols queries
+          for (int qt = 0; qt < QT; ++qt) s[qt] = mfma32(kf, qf[ds][qt], s[qt]);   // S^T - m: rows keys, cols queries
         }
         const bool need_mask = (key0 + 32 > kv_len) || (a.causal && key0 + 31 > qw);
         if (need_mask) {
@@ -405,37 +419,44 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
         // Lazy running maximum (log2 domain): the reference maximum of a row is raised, and O and l rescaled, only when
         // the slab's maximum exceeds it by more than 8; until then the probabilities are at most 2^8, which fp16
         // holds with full relative precision.  The softmax does not depend on the reference, so nothing changes
-        // but the number of rescalings (one per row for most inputs instead of one per slab).
+        // but the number of rescalings (one per row for most inputs instead of one per slab).  s already is S - m_run.
+        // The first slab sets the reference to its own maximum (key 0 is visible to every query, so it is finite).
         h8 pf[QT][2];
         float mx[QT];
-        bool raise = false;
+        bool raise = first;
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
           float m = s[qt][0];
 #pragma unroll
           for (int v = 1; v < 16; ++v) m = fmaxf(m, s[qt][v]);
           mx[qt] = fmaxf(m, __shfl_xor(m, 32, 64));
-          raise = raise || (mx[qt] > m_run[qt] + 8.0f);
+          raise = raise || (mx[qt] > 8.0f);
         }
         if (__any(raise)) {
 #pragma unroll
           for (int qt = 0; qt < QT; ++qt) {
-            const float m_new = fmaxf(m_run[qt], mx[qt]);
-            const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
-            m_run[qt] = m_new;
+            // first slab: move the reference to the slab's maximum wherever it is (O and l are still zero);
+            // later: only upwards
+            const float delta = first ? fmaxf(mx[qt], -1e30f) : fmaxf(mx[qt], 0.f);
+            const float alpha = first ? 0.f : __builtin_amdgcn_exp2f(-delta);
+            m_run[qt] += delta;
             l_run[qt] *= alpha;
+            set_qneg(qt);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s[qt][v] -= delta;
 #pragma unroll
             for (int dt = 0; dt < DT32; ++dt)
 #pragma unroll
               for (int v = 0; v < 16; ++v) o[dt][qt][v] *= alpha;
           }
         }
+        first = false;
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
           float sum = 0.f;
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
-            const float p = __builtin_amdgcn_exp2f(s[qt][v] - m_run[qt]);
+            const float p = __builtin_amdgcn_exp2f(s[qt][v]);
             s[qt][v] = p;
             sum += p;
           }
@@ -453,6 +474,11 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
             for (int qt = 0; qt < QT; ++qt) o[dt][qt] = mfma32(vf, pf[qt][t], o[dt][qt]);   // O^T: rows d, cols queries
           }
       }
+      // the rebuild accumulators are cleared only now, so that their registers are free during the softmax above
+#pragma unroll
+      for (int i = 0; i < KTW; ++i)
+#pragma unroll
+        for (int j = 0; j < DTW; ++j) acc[i][j] = zero16();
     }
     step = nstep;
     c = ncn;
