@@ -127,6 +127,23 @@ FfnPlan plan_ffn(size_t T, size_t r1, size_t r2, size_t F) {
   return pl;
 }
 
+// LayerNorm to be applied to the block's output (after the residual add).  When the block's last projection can be
+// fused with it (prepacked V, supported width) the block writes the normalised rows and sets `done`; otherwise the
+// block writes its plain output and the caller normalises it.
+struct LnFuse {
+  const void* gamma; const void* beta; float eps;
+  void* y_row; int y_dt;      // normalised rows, row-major (or nullptr)
+  void* y_fm;                 // fragment-major fp16 copy (or nullptr)
+  bool done;
+};
+// The fused projection + residual + LayerNorm kernel gives every workgroup all D output columns of 32 or 64 tokens, so
+// each workgroup re-reads the whole [rank, D] matrix from the last-level cache: it wins over the GEMM followed by the
+// LayerNorm kernel (one more round trip of [T, D] through HBM) while that matrix is small and the tokens fill the chip.
+bool ln_fusable(const fsvd_desc* d, const fsvd_factor* last) {
+  return last->v_layout == FSVD_TILED && linear_ln_supported(d->D) && d->B * d->M >= 2048 &&
+         (long long)last->rank * d->D <= 320 * 1024;
+}
+
 float resolve_scale(const fsvd_desc* d) {
   return d->softmax_scale > 0.f ? d->softmax_scale : 1.0f / sqrtf((float)(d->D / d->H));
 }
@@ -136,7 +153,8 @@ float resolve_scale(const fsvd_desc* d) {
 // The last GEMM writes `out` row-major in c_dt (+ residual) or, when out_fm is set, fragment-major fp16.
 fsvd_status run_attention(const fsvd_desc* d, const void* x_fm, const fsvd_factor* q, const fsvd_factor* k,
                           const fsvd_factor* v, const fsvd_factor* o, const void* residual, int r_dt, void* out,
-                          int c_dt, bool out_fm, char* c_buf, char* rank_buf, hipStream_t s, bool per_head = false) {
+                          int c_dt, bool out_fm, char* c_buf, char* rank_buf, hipStream_t s, bool per_head = false,
+                          LnFuse* lnf = nullptr) {
   const int T = d->B * d->M, D = d->D;
   // per-head factors: U [D, H r] is one projection matrix with H r columns, head h's rank-space activations are
   // columns h r .. of P; V [H, r, d_h] is read per head by the attention core
@@ -175,6 +193,15 @@ fsvd_status run_attention(const fsvd_desc* d, const void* x_fm, const fsvd_facto
   h3a.g[0] = {o->U, nullptr, To, o->rank, o->rank, 0};
   FSVD_HIP(launch_linear(h3a, s));
 
+  if (lnf && ln_fusable(d, o)) {
+    LinearLnArgs f{};
+    f.A = To; f.T = T; f.K = o->rank; f.D = D; f.W = o->V; f.bias = o->bias; f.w_dt = d->io_dtype;
+    f.R = residual; f.r_dt = r_dt; f.gamma = lnf->gamma; f.beta = lnf->beta; f.p_dt = d->io_dtype; f.eps = lnf->eps;
+    f.Yrow = lnf->y_row; f.yrow_dt = lnf->y_dt; f.Yfm = lnf->y_fm;
+    FSVD_HIP(launch_linear_ln(f, s));
+    lnf->done = true;
+    return FSVD_OK;
+  }
   LinearArgs h3b{};
   h3b.A = To; h3b.a_layout = LAYOUT_FM; h3b.lda = o->rank; h3b.a_dt = DT_F16; h3b.T = T; h3b.K = o->rank;
   h3b.w_dt = d->io_dtype; h3b.w_tiled = o->v_layout == FSVD_TILED; h3b.c_layout = out_fm ? LAYOUT_FM : LAYOUT_ROW; h3b.c_dt = c_dt;
@@ -187,7 +214,7 @@ fsvd_status run_attention(const fsvd_desc* d, const void* x_fm, const fsvd_facto
 // FFN block on `A_in` (fragment-major fp16, or row-major in a_dt) -> row-major `out` in c_dt (+ residual).
 fsvd_status run_ffn(const fsvd_desc* d, const void* A_in, int a_layout, int a_dt, const fsvd_factor* w1,
                     const fsvd_factor* w2, const void* residual, int r_dt, void* out, int c_dt, char* scratch,
-                    hipStream_t s) {
+                    hipStream_t s, LnFuse* lnf = nullptr) {
   const int T = d->B * d->M, D = d->D;
   const FfnPlan pl = plan_ffn(T, w1->rank, w2->rank, d->F);
   char* P1 = scratch + pl.p1;
@@ -206,6 +233,15 @@ fsvd_status run_ffn(const fsvd_desc* d, const void* A_in, int a_layout, int a_dt
   fa.Zpart = (float*)(scratch + pl.part);
   FSVD_HIP(launch_ffn_core(fa, s));
 
+  if (lnf && ln_fusable(d, w2)) {
+    LinearLnArgs f{};
+    f.A = Z; f.T = T; f.K = w2->rank; f.D = D; f.W = w2->V; f.bias = w2->bias; f.w_dt = d->io_dtype;
+    f.R = residual; f.r_dt = r_dt; f.gamma = lnf->gamma; f.beta = lnf->beta; f.p_dt = d->io_dtype; f.eps = lnf->eps;
+    f.Yrow = lnf->y_row; f.yrow_dt = lnf->y_dt; f.Yfm = lnf->y_fm;
+    FSVD_HIP(launch_linear_ln(f, s));
+    lnf->done = true;
+    return FSVD_OK;
+  }
   LinearArgs h7{};
   h7.A = Z; h7.a_layout = LAYOUT_FM; h7.lda = w2->rank; h7.a_dt = DT_F16; h7.T = T; h7.K = w2->rank; h7.w_dt = d->io_dtype;
   h7.w_tiled = w2->v_layout == FSVD_TILED;
@@ -351,10 +387,13 @@ fsvd_status layer_impl(const fsvd_desc* d, const void* X, const fsvd_factor* q, 
   if (d->norm == FSVD_NORM_POST_LN) {
     // S1 = X + Attn(X) (fp32 stream) -> Y1 = LN1(S1) in place + FM copy -> S2 = Y1 + FFN(Y1) in place -> out = LN2(S2)
     FSVD_HIP(launch_pack_fm(X, io, T, D, c_buf, s));
-    FSVD_TRY(run_attention(d, c_buf, q, k, v, o, X, io, stream_buf, DT_F32, false, c_buf, rank_buf, s, per_head));
-    FSVD_TRY(ln(stream_buf, DT_F32, g1, b1, stream_buf, DT_F32, c_buf));
-    FSVD_TRY(run_ffn(d, c_buf, LAYOUT_FM, DT_F16, w1, w2, stream_buf, DT_F32, stream_buf, DT_F32, rank_buf, s));
-    FSVD_TRY(ln(stream_buf, DT_F32, g2, b2, out, d->out_dtype, nullptr));
+    // (each LayerNorm is fused into the projection before it when that projection's V is prepacked and D allows)
+    LnFuse f1{g1, b1, d->ln_eps, stream_buf, DT_F32, c_buf, false};
+    FSVD_TRY(run_attention(d, c_buf, q, k, v, o, X, io, stream_buf, DT_F32, false, c_buf, rank_buf, s, per_head, &f1));
+    if (!f1.done) FSVD_TRY(ln(stream_buf, DT_F32, g1, b1, stream_buf, DT_F32, c_buf));
+    LnFuse f2{g2, b2, d->ln_eps, out, d->out_dtype, nullptr, false};
+    FSVD_TRY(run_ffn(d, c_buf, LAYOUT_FM, DT_F16, w1, w2, stream_buf, DT_F32, stream_buf, DT_F32, rank_buf, s, &f2));
+    if (!f2.done) FSVD_TRY(ln(stream_buf, DT_F32, g2, b2, out, d->out_dtype, nullptr));
   } else if (d->norm == FSVD_NORM_PRE_LN) {
     // N1 = LN1(X) (FM) -> X1 = X + Attn(N1) (fp32 stream) -> N2 = LN2(X1) (FM) -> out = X1 + FFN(N2)
     FSVD_TRY(ln(X, io, g1, b1, nullptr, 0, c_buf));

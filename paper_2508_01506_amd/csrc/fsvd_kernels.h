@@ -44,6 +44,20 @@ struct LinearArgs {
 };
 hipError_t launch_linear(const LinearArgs& a, hipStream_t s);
 
+// ---- Y = LN(A W + bias + R) in one kernel (fsvd_gemm_ln.hip): A fragment-major fp16 [T, K], W tile images of [K, D]
+struct LinearLnArgs {
+  const void* A; int T, K, D;
+  const void* W;                       // prepacked tile images of [K, D]
+  const void* bias; int w_dt;          // [D] in w_dt or nullptr
+  const void* R; int r_dt;             // residual [T, D] row-major or nullptr
+  const void* gamma; const void* beta; int p_dt;
+  float eps;
+  void* Yrow; int yrow_dt;             // row-major output or nullptr (may alias R: every row is read before it is written)
+  void* Yfm;                           // fragment-major fp16 output or nullptr
+};
+bool linear_ln_supported(int D);
+hipError_t launch_linear_ln(const LinearLnArgs& a, hipStream_t s);
+
 // ---- streaming attention core (Alg. 1 Part II): FM P_q, P_k, P_v -> FM context C [T, D]
 struct AttnCoreArgs {
   const void* Pq; const void* Pk; const void* Pv;   // FM [B*M, r_x] (grouped factors: [B*M, G * r_x], group g = columns g r_x ..)

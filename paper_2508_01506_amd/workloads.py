@@ -100,6 +100,16 @@ _register(_wl(7, 4, name="small_causal_d64", B=1, M=700, D=256, H=4, F=1024, r_a
               r_ffn=272, dtype="bf16", mask="causal", norm="none"))
 
 
+# Widths 512 and 1024 at test size (the fused projection + LayerNorm kernel is specialised per D / 256).
+# Widths 256..1024 with at least 2048 ragged tokens and small rank-by-width products: the shapes for which the last
+# projection of a block, the residual add and the LayerNorm run as one kernel (prepacked weights, post-LN).
+_register(_wl(7, 5, name="fuse_d512_pad", B=4, M=530, D=512, H=8, F=256, r_attn=80, r_ffn=96, dtype="bf16",
+              mask="padding", min_len=40))
+_register(_wl(7, 6, name="fuse_d1024", B=1, M=2100, D=1024, H=8, F=512, r_attn=64, r_ffn=112, dtype="fp16"))
+_register(_wl(7, 7, name="fuse_d256_causal", B=3, M=700, D=256, H=4, F=512, r_attn=48, r_ffn=80, dtype="fp16",
+              mask="causal"))
+_register(_wl(7, 8, name="fuse_d768", B=2, M=1040, D=768, H=12, F=384, r_attn=96, r_ffn=64, dtype="bf16"))
+
 # Per-head factorisation of q, k, v (the paper's attention setting: one rank-r pair per head, r <= d_h), the encoder
 # shapes of its attention-kernel sweep: batch 16 or 64, sequence 128..1024, per-head ranks 64, 32, 16.
 for _i, (_b, _m, _r) in enumerate(((16, 512, 32), (16, 512, 64), (16, 512, 16), (64, 128, 32), (16, 1024, 48))):

@@ -360,6 +360,24 @@ def test_layer_gate_on_small_shapes_both_norms(fb, name, norm):
     assert rel_err(gpu_call(dev, "layer").cpu().numpy(), oracle_call(inp, "layer")) < TOL_LAYER
 
 
+@pytest.mark.parametrize("name", ["fuse_d256_causal", "fuse_d512_pad", "fuse_d768", "fuse_d1024", "cfg1_bert_base_b2_m128"])
+def test_post_ln_layer_with_projection_and_layernorm_fused(fb, name):
+    """Post-LN layers of width 256, 512, 768 or 1024 with at least 2048 tokens and a small rank-by-width product run the
+    last projection of each block, the residual add and the LayerNorm as one kernel when the weights are prepacked:
+    every element against the oracle, and the same layer with row-major weights (separate projection and LayerNorm
+    kernels) for comparison; ragged token counts.  The last case (256 tokens) stays on the separate kernels."""
+    w = W.get_workload(name, norm="post_ln")
+    inp = W.make_inputs(w)
+    ref = oracle_call(inp, "layer")
+    fused = gpu_call(fb.to_device(inp, DEV, tiled=True), "layer").cpu().numpy()
+    plain = gpu_call(fb.to_device(inp, DEV), "layer").cpu().numpy()
+    assert np.isfinite(fused).all()
+    assert rel_err(fused, ref) < TOL_LAYER
+    assert rel_err(plain, ref) < TOL_LAYER
+    # same arithmetic up to the order of the fp32 row statistics; one unit in the fp16 rounding of an intermediate is 1e-3
+    assert rel_err(fused, plain) < TOL_LAYER
+
+
 # ------------------------------------------------------------------ benchmark sizes, sampled rows
 FULL = ["cfg1_bert_base_b2_m128", "cfg2_bert_base_b16_m512_pad", "cfg2u_bert_base_b16_m512_pad_unit",
         "cfg3_bert_large_b32_m512_r128", "cfg3_bert_large_b32_m512_r256", "cfg3_bert_large_b32_m512_r512",
