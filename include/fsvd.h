@@ -167,6 +167,22 @@ fsvd_status fsvd_ffn(const fsvd_desc *desc, const void *X, const fsvd_factor *w1
                      void *out, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Feed-forward block, FlashSVDFFN V2 (Alg. 3; section "FlashSVDFFN V2"): the same function as fsvd_ffn,
+ *   out = phi((X U_1) V_1 + b_1) U_2 V_2 + b_2,
+ * computed by ONE kernel per block of 32 or 64 tokens: the rank projection X U_1 and the up-projection Z V_2 run inside
+ * the kernel too, so neither the rank-space activations (P, Z) nor the hidden activation are ever written to device
+ * memory and the call needs no workspace.  The price is that every workgroup streams all four factor matrices
+ * (they are not reused across as many tokens as in fsvd_ffn), the latency / memory trade the paper reports for V2.
+ * X [B, M, D] row-major in io_dtype -> out [B, M, D] in out_dtype; desc->H is not used beyond the common checks.
+ * Requirements: U and V of BOTH factors are prepacked tile images (FSVD_TILED, see fsvd_pack_tiled); biases stay in
+ * io_dtype (or NULL); ranks are multiples of 16 and at most 1024.  Anything else -> FSVD_ERR_UNSUPPORTED before any
+ * launch.  Results agree with fsvd_ffn to the rounding of the fp16 intermediates (P, hidden, Z), which both round the
+ * same way.  Device pointers, borrowed for the call; asynchronous on hip_stream.
+ */
+fsvd_status fsvd_ffn_v2(const fsvd_desc *desc, const void *X, const fsvd_factor *w1, const fsvd_factor *w2,
+                        void *out, void *hip_stream);
+
+/*
  * One transformer layer built from the two blocks above.  The residual / LayerNorm wiring is
  * not part of the paper's method (it only notes that these ops remain once the blocks are fused,
  * section "FlashSVDFFN V2"); desc->norm selects

@@ -33,7 +33,7 @@ EXPORTS = ["fsvd_attention_workspace", "fsvd_ffn_workspace", "fsvd_layer_workspa
            "fsvd_unpack_fm", "fsvd_tiled_bytes", "fsvd_pack_tiled", "fsvd_linear_tiled", "fsvd_decode_kcache_bytes",
            "fsvd_decode_vcache_bytes", "fsvd_decode_cache_write", "fsvd_decode_attention_workspace", "fsvd_decode_attention",
            "fsvd_decode_core_workspace", "fsvd_decode_attention_core",
-           "fsvd_attention_groups_workspace", "fsvd_layer_groups_workspace"]
+           "fsvd_attention_groups_workspace", "fsvd_layer_groups_workspace", "fsvd_ffn_v2"]
 
 
 class FsvdError(RuntimeError):
@@ -89,6 +89,8 @@ def lib():
         L.fsvd_attention_heads.argtypes = [D, P, F, F, F, F, P, P, sz, P]
         L.fsvd_ffn.restype = C.c_int
         L.fsvd_ffn.argtypes = [D, P, F, F, P, P, sz, P]
+        L.fsvd_ffn_v2.restype = C.c_int
+        L.fsvd_ffn_v2.argtypes = [D, P, F, F, P, P]
         L.fsvd_layer.restype = C.c_int
         L.fsvd_layer.argtypes = [D, P, F, F, F, F, P, P, F, F, P, P, P, P, sz, P]
         L.fsvd_layer_heads_workspace.restype = sz
@@ -288,6 +290,15 @@ def fsvd_ffn(desc, X, w1: Factor, w2: Factor, out=None, workspace=None):
     f1, f2 = w1.c(), w2.c()
     _check(lib().fsvd_ffn(C.byref(desc), _ptr(X), C.byref(f1), C.byref(f2), _ptr(out), _ptr(workspace),
                           workspace.numel(), _stream()), "fsvd_ffn")
+    return out
+
+
+def fsvd_ffn_v2(desc, X, w1: Factor, w2: Factor, out=None):
+    """The FFN block as one kernel without workspace; both factors need U and V as tile images."""
+    if out is None:
+        out = torch.empty(X.shape, dtype=_out_dtype(desc), device=X.device)
+    f1, f2 = w1.c(), w2.c()
+    _check(lib().fsvd_ffn_v2(C.byref(desc), _ptr(X), C.byref(f1), C.byref(f2), _ptr(out), _stream()), "fsvd_ffn_v2")
     return out
 
 

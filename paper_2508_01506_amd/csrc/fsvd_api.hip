@@ -353,6 +353,22 @@ fsvd_status fsvd_ffn(const fsvd_desc* d, const void* X, const fsvd_factor* w1, c
   return run_ffn(d, X, LAYOUT_ROW, d->io_dtype, w1, w2, nullptr, 0, out, d->out_dtype, (char*)ws, (hipStream_t)stream);
 }
 
+fsvd_status fsvd_ffn_v2(const fsvd_desc* d, const void* X, const fsvd_factor* w1, const fsvd_factor* w2, void* out,
+                        void* stream) {
+  FSVD_TRY(check_ffn(d, w1, w2, true));
+  if (!X || !out || mis16(X) || mis16(out)) return FSVD_ERR_INVALID_ARG;
+  for (const fsvd_factor* f : {w1, w2})
+    if (f->u_layout != FSVD_TILED || f->v_layout != FSVD_TILED) return FSVD_ERR_UNSUPPORTED;
+  if (!ffn_v2_supported(d->D, d->F, w1->rank, w2->rank)) return FSVD_ERR_UNSUPPORTED;
+  FfnV2Args a{};
+  a.X = X; a.x_dt = d->io_dtype;
+  a.U1 = w1->U; a.V1 = w1->V; a.U2 = w2->U; a.V2 = w2->V; a.b1 = w1->bias; a.b2 = w2->bias; a.w_dt = d->io_dtype;
+  a.T = d->B * d->M; a.D = d->D; a.F = d->F; a.r1 = w1->rank; a.r2 = w2->rank; a.act = d->act;
+  a.out = out; a.out_dt = d->out_dtype;
+  FSVD_HIP(launch_ffn_v2(a, (hipStream_t)stream));
+  return FSVD_OK;
+}
+
 }  // extern "C"
 
 namespace {

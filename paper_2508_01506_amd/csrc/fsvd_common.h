@@ -271,6 +271,26 @@ __device__ __forceinline__ unsigned lds_addr_of(const void* p) {
   return (unsigned)(size_t)(__attribute__((address_space(3))) const void*)p;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Activation functions of the FFN (applied to fp32 accumulators).
+// Exact (erf) GELU as  max(x, 0) - |x| * Q(|x|),  Q(t) = 0.5 erfc(t / sqrt 2)  the upper Gaussian tail, with
+// log2 Q(t) replaced on [0, 6] by a degree-6 polynomial (weighted least-squares fit on Chebyshev nodes, weight t Q(t)):
+// 6 FMAs and one hardware exp2 per element.  |error| <= 5e-7 over the whole real line in fp32 (beyond t = 6 the tail
+// is below 1e-9 and the clamp keeps the polynomial inside its interval).
+__device__ constexpr float kGeluTail[7] = {-0.999994874f, -1.15118682f, -0.458807677f, -0.0533762164f,
+                                           0.00806691311f, -0.000768144673f, 3.33612952e-05f};
+__device__ __forceinline__ float gelu_erf_f(float x) {
+  const float t = fminf(fabsf(x), 6.0f);
+  float p = kGeluTail[6];
+#pragma unroll
+  for (int k = 5; k >= 0; --k) p = fmaf(p, t, kGeluTail[k]);
+  return fmaf(-fabsf(x), __builtin_amdgcn_exp2f(p), fmaxf(x, 0.f));
+}
+__device__ __forceinline__ float gelu_tanh_f(float x) {
+  const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+  return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-2.0f * u * 1.4426950408889634f));
+}
+
 // Contraction-slot mapping inside one 64-wide chunk: MFMA step kk (0..3), lane group g (0..1),
 // slot s (0..7) stand for chunk offset 32*g + 8*kk + s.  An activation lane therefore reads 64
 // contiguous bytes of its row over the four steps of a chunk.

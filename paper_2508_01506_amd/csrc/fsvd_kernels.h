@@ -95,6 +95,17 @@ struct FfnCorePlan { int nslices, slice_w, ns, ns2, fsplit; size_t partial_bytes
 FfnCorePlan ffn_core_plan(int T, int r1, int r2, int F);
 hipError_t launch_ffn_core(const FfnCoreArgs& a, hipStream_t s);
 
+// ---- whole factored FFN in one kernel (Alg. 3): row-major X [T, D] -> row-major out [T, D], no intermediates in memory
+struct FfnV2Args {
+  const void* X; int x_dt;                // [T, D] row-major
+  const void *U1, *V1, *U2, *V2;          // prepacked fp16 tile images of [D, r1], [r1, F], [F, r2], [r2, D]
+  const void *b1, *b2; int w_dt;          // [F], [D] in w_dt or nullptr
+  int T, D, F, r1, r2, act;
+  void* out; int out_dt;                  // [T, D] row-major
+};
+bool ffn_v2_supported(int D, int F, int r1, int r2);
+hipError_t launch_ffn_v2(const FfnV2Args& a, hipStream_t s);
+
 // ---- decoding step against a rank-space KV cache (layouts and kernels: fsvd_decode.hip)
 inline size_t decode_vcache_seq_bytes(size_t t_max, size_t r_v) { return ((t_max + 31) / 32) * ((r_v + 31) / 32) * 2048; }
 struct DecodeCoreArgs {

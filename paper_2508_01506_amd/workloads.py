@@ -110,6 +110,14 @@ _register(_wl(7, 7, name="fuse_d256_causal", B=3, M=700, D=256, H=4, F=512, r_at
               mask="causal"))
 _register(_wl(7, 8, name="fuse_d768", B=2, M=1040, D=768, H=12, F=384, r_attn=96, r_ffn=64, dtype="bf16"))
 
+# Shapes for the one-kernel FFN (FlashSVDFFN V2): ranks above 512 (two slabs of ranks), widths above 512 (two slabs of
+# X and of the output), F that is not a multiple of the 128-, 256- or 512-wide units, ragged token counts, and enough
+# tokens for the 64-token variant.
+_register(_wl(7, 9, name="v2_two_rank_slabs", B=2, M=75, D=640, H=10, F=1104, r_attn=32, r_ffn=528, dtype="bf16"))
+_register(_wl(7, 10, name="v2_max_rank", B=1, M=100, D=1024, H=8, F=2064, r_attn=32, r_ffn=1024, dtype="fp16"))
+_register(_wl(7, 11, name="v2_many_tokens", B=26, M=500, D=128, H=2, F=400, r_attn=32, r_ffn=96, dtype="fp16"))
+_register(_wl(7, 12, name="v2_many_tokens_r512", B=13, M=1001, D=576, H=9, F=784, r_attn=32, r_ffn=512, dtype="bf16"))
+
 # Per-head factorisation of q, k, v (the paper's attention setting: one rank-r pair per head, r <= d_h), the encoder
 # shapes of its attention-kernel sweep: batch 16 or 64, sequence 128..1024, per-head ranks 64, 32, 16.
 for _i, (_b, _m, _r) in enumerate(((16, 512, 32), (16, 512, 64), (16, 512, 16), (64, 128, 32), (16, 1024, 48))):

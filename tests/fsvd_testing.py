@@ -50,6 +50,8 @@ def gpu_call(dev, part="layer"):
         return fn(d, dev["X"], dev["q"], dev["k"], dev["v"], dev["o"])
     if part == "ffn":
         return fb.fsvd_ffn(d, dev["X"], dev["w1"], dev["w2"])
+    if part == "ffn_v2":
+        return fb.fsvd_ffn_v2(d, dev["X"], dev["w1"], dev["w2"])
     fn = fb.fsvd_layer_heads if isinstance(dev["q"], fb.HeadFactor) else fb.fsvd_layer
     return fn(d, dev["X"], dev["q"], dev["k"], dev["v"], dev["o"], dev["ln1_gamma"], dev["ln1_beta"],
               dev["w1"], dev["w2"], dev["ln2_gamma"], dev["ln2_beta"])

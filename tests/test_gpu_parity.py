@@ -416,6 +416,52 @@ def test_ffn_block_on_the_rank_ablation_grid(fb, m, r):
         assert rel_err(got[b, rows], oracle_rows(inp, b, rows, "ffn")) < tol_for(w, "ffn"), (m, r, b)
 
 
+V2_SMALL = SMALL + ["v2_two_rank_slabs", "v2_max_rank", "v2_many_tokens", "v2_many_tokens_r512", "fuse_d768"]
+
+
+@pytest.mark.parametrize("name", V2_SMALL)
+def test_ffn_as_one_kernel_small(fb, name):
+    """FlashSVDFFN V2 (Alg. 3): X -> out in one kernel without workspace, every element against the oracle's FFN and
+    against the V1 entry point (the same fp16 hand-offs)."""
+    w, inp, dev = workload(name, fb, "tiled")
+    got = gpu_call(dev, "ffn_v2").cpu().numpy()
+    assert np.isfinite(got).all()
+    err = rel_err(got, oracle_call(inp, "ffn"))
+    assert err < tol_for(w, "ffn")
+    # the two kernels sum in different orders, so their fp16 hand-offs round differently here and there
+    err_v1 = rel_err(got, gpu_call(dev, "ffn").cpu().numpy())
+    assert err_v1 < tol_for(w, "ffn")
+
+
+def test_ffn_as_one_kernel_activations_and_types(fb):
+    """Other activation functions, 16-bit output and missing biases."""
+    w, inp, dev = workload("tiny_pad", fb, "tiled")
+    for act in ("gelu_tanh", "relu"):
+        d = fb.make_desc(w.B, w.M, w.D, w.H, w.F, dev["X"].dtype, torch.float32, act=act)
+        assert rel_err(fb.fsvd_ffn_v2(d, dev["X"], dev["w1"], dev["w2"]).cpu().numpy(),
+                       O.ffn(inp["X"], inp["w1"], inp["w2"], act=act)) < TOL["ffn"]
+    d16 = fb.make_desc(w.B, w.M, w.D, w.H, w.F, dev["X"].dtype, torch.float16)
+    ref = oracle_call(inp, "ffn")
+    got16 = fb.fsvd_ffn_v2(d16, dev["X"], dev["w1"], dev["w2"])
+    assert got16.dtype == torch.float16 and rel_err(got16.float().cpu().numpy(), ref) < TOL["ffn"] + 1e-3
+    w1, w2 = dev["w1"], dev["w2"]
+    nobias = [fb.Factor(f.U, f.V, None, f.U_tiled, f.V_tiled) for f in (w1, w2)]
+    zero = [dict(inp[k], b=np.zeros_like(inp[k]["b"])) for k in ("w1", "w2")]
+    assert rel_err(fb.fsvd_ffn_v2(dev["desc"], dev["X"], *nobias).cpu().numpy(), O.ffn(inp["X"], *zero)) < TOL["ffn"]
+
+
+@pytest.mark.parametrize("name", ["cfg1_bert_base_b2_m128", "cfg2u_bert_base_b16_m512_pad_unit", "cfg3_bert_large_b32_m512_r128",
+                                  "cfg3_bert_large_b32_m512_r512", "cfg4_long_b4_m8192", "ffn_grid_b16_m512_r384"])
+def test_ffn_as_one_kernel_full_size_sampled(fb, name):
+    """The one-kernel FFN at benchmark sizes (32- and 64-token variants), sampled rows against the oracle."""
+    w, inp, dev = workload(name, fb, "tiled")
+    got = gpu_call(dev, "ffn_v2").cpu().numpy()
+    assert np.isfinite(got).all()
+    for b in (0, w.B - 1):
+        rows = sample_rows(w, 10, seed=b)
+        assert rel_err(got[b, rows], oracle_rows(inp, b, rows, "ffn")) < tol_for(w, "ffn"), (name, b)
+
+
 def test_full_size_padding_property(fb):
     """Tokens at masked key positions cannot influence the context of any row (bitwise)."""
     w, inp, dev = workload("cfg2u_bert_base_b16_m512_pad_unit", fb)

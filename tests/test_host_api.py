@@ -183,6 +183,27 @@ def test_tiled_weight_layout_contract():
     assert L.fsvd_linear_tiled(16, 40, 16, 256, 0, 256, None, 0, None, 0, 256, 0, None) == UNSUPPORTED
 
 
+def test_one_kernel_ffn_contract():
+    """fsvd_ffn_v2 takes only tile images of all four matrices and ranks up to 1024, and says so before any launch."""
+    L = fb.lib()
+    d = desc()
+
+    def lay(f, u=1, v=1):
+        return fb.fsvd_factor(f.U, f.V, f.bias, f.in_dim, f.rank, f.out_dim, u, v)
+    w1, w2 = fac(768, 64, 3072), fac(3072, 64, 768)
+    call = lambda a, b, x=256, out=256: L.fsvd_ffn_v2(C.byref(d), x, C.byref(a), C.byref(b), out, None)
+    assert call(lay(w1), lay(w2), x=None) == INVALID                      # valid factors, then X is NULL
+    assert call(lay(w1), lay(w2), out=264) == INVALID                     # misaligned result
+    assert call(lay(w1, u=0), lay(w2)) == UNSUPPORTED                     # every matrix must be a tile image
+    assert call(lay(w1), lay(w2, v=0)) == UNSUPPORTED
+    assert call(w1, w2) == UNSUPPORTED
+    big1, big2 = fac(768, 1040, 3072), fac(3072, 1040, 768)
+    assert call(lay(big1), lay(w2)) == UNSUPPORTED                        # ranks above 1024
+    assert call(lay(w1), lay(big2)) == UNSUPPORTED
+    assert call(lay(fac(768, 24, 3072)), lay(w2)) == UNSUPPORTED          # rank not a multiple of 16
+    assert call(lay(fac(512, 64, 3072)), lay(w2)) == INVALID              # shapes that do not match the descriptor
+
+
 def test_grouped_head_factors_contract():
     """`groups` of the *_heads entry points: a divisor of H, the same for q, k, v; 0 means one group per head."""
     L = fb.lib()
@@ -272,11 +293,11 @@ def test_missing_library_fails_loudly(monkeypatch):
 
 
 def test_gelu_tail_polynomial_of_the_kernel_is_erf_accurate():
-    """The FFN kernel evaluates erf-GELU as max(x,0) - |x| 2^p(min(|x|,6)); its coefficients, read from the source,
+    """The FFN kernels evaluate erf-GELU as max(x,0) - |x| 2^p(min(|x|,6)); its coefficients, read from the source,
     must reproduce 0.5 x (1 + erf(x / sqrt 2)) (scipy) to 1e-6 when evaluated in float32 as the kernel does."""
     import re
     from scipy.special import erf
-    src = open(os.path.join(ROOT, "paper_2508_01506_amd", "csrc", "fsvd_ffn.hip")).read()
+    src = open(os.path.join(ROOT, "paper_2508_01506_amd", "csrc", "fsvd_common.h")).read()
     body = re.search(r"kGeluTail\[7\]\s*=\s*\{([^}]*)\}", src).group(1)
     c = [np.float32(v.strip().rstrip("f")) for v in body.split(",")]
     assert len(c) == 7
