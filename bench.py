@@ -159,8 +159,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--weights", choices=["tiled", "row"], default="tiled")
-    ap.add_argument("--part", choices=["layer", "attention", "ffn"], default="layer",
-                    help="time one block of the layer instead of the whole layer (value is then that block's tokens/s)")
+    ap.add_argument("--part", choices=["layer", "attention", "ffn", "ffn_v2"], default="layer",
+                    help="time one block of the layer instead of the whole layer (value is then that block's tokens/s); "
+                         "ffn_v2 is the FFN block as one kernel without workspace (fsvd_ffn_v2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-traffic", action="store_true",
                     help="also launch a plain copy of known size (fsvd_pack_fm of a 512 MiB fp16 matrix: reads 512 MiB, "
@@ -192,7 +193,16 @@ def main():
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
     out = torch.empty((w.B, w.M, w.D), dtype=torch.float32, device="cuda:0")
 
+    if args.part == "ffn":            # the block's own workspace: what the latency / memory trade against ffn_v2 is about
+        ws_bytes = fb.fsvd_ffn_workspace(d, rf, rf)
+    elif args.part == "ffn_v2":
+        ws_bytes = 0
+    oracle_part = "ffn" if args.part == "ffn_v2" else args.part
+
     def step():
+        if args.part == "ffn_v2":
+            fb.fsvd_ffn_v2(d, dev["X"], dev["w1"], dev["w2"], out=out)
+            return
         if args.part == "ffn":
             fb.fsvd_ffn(d, dev["X"], dev["w1"], dev["w2"], out=out, workspace=ws)
             return
@@ -309,8 +319,8 @@ def main():
             for b in range(w.B - 1, -1, -1):
                 t0 = time.perf_counter()
                 ref = (oracle_call(dict(inp, X=inp["X"][b:b + 1], key_len=None if inp["key_len"] is None
-                                    else inp["key_len"][b:b + 1]), args.part)[0, rows] if per_head
-                   else oracle_rows(inp, b, rows, args.part))
+                                    else inp["key_len"][b:b + 1]), oracle_part)[0, rows] if per_head
+                   else oracle_rows(inp, b, rows, oracle_part))
                 dt += time.perf_counter() - t0
                 got = out[b, w.M - n_rows:].cpu().numpy()
                 err = max(err, float(np.abs(got - ref).max() / np.sqrt(np.mean(ref ** 2))))

@@ -9,8 +9,8 @@
 // "transposed" so that tokens lie along the lanes: the accumulators of one product, rounded to fp16, are the operand
 // registers of the next.  The activations between two products stay in LDS as ready operand fragments
 // ([16-wide contraction step][token tile][lane] x 16 bytes): X is staged in slabs of 512 / MT columns, P1^T (later Z^T) takes
-// 64 KiB, the activated hidden chunk (512 / MT features) 32 KiB.  All weights are prepacked tile images; one step of
-// 16 contraction rows x 512 columns (16 KiB) at a time is copied straight into LDS, three buffers, two steps ahead, as
+// up to 64 KiB, the activated hidden chunk (512 / MT features) 32 KiB; what is left of the 160 KiB holds weight steps.  All weights are prepacked tile images; one step of
+// 16 contraction rows x 512 columns (16 KiB) at a time is copied straight into LDS, NB buffers, NB - 1 steps ahead, as
 // ONE request stream over the whole kernel (a cursor walks the same loop nest as the consumers), so that the copies never
 // drain between the products.  Within a 512-column slab wavefront w owns columns 64 w .. 64 w + 63.
 //   step 1: P1^T = U_1^T X^T                         (sum over D in slabs; all slabs of r1 per X slab)
@@ -19,6 +19,7 @@
 // Limits: r1, r2 <= 1024 / MT (the register and LDS budget of Z^T and P1^T).
 #include "fsvd_common.h"
 #include "fsvd_kernels.h"
+#include <type_traits>
 
 namespace fsvd {
 
@@ -28,22 +29,70 @@ constexpr int kV2Threads = 512;
 constexpr int kV2StepBytes = 16 * 512 * 2;     // one staged step: 4 tile images x 16 rows x 256 bytes
 
 // The request stream of the kernel below: which 16-row x 512-column step of which factor matrix is copied into LDS
-// next.  The cursor walks the loop nest of the four products in the order in which the consumer loops use the steps;
-// all of it is wave-uniform (scalar registers).
-template <int MT>
+// next.  A pass is a run of consecutive 16-row steps of one matrix under one block of columns; the passes follow the
+// loop nest of the four products in the order in which the consumer loops use the steps.  Inside a pass the next
+// request is the previous one plus constants (a few scalar instructions per step); the loop nest is only consulted
+// when a pass ends.  All of it is wave-uniform (scalar registers).
+template <int MT, int NB>
 struct WeightStream {
   static constexpr int KS = 32 / MT, FC = 16 * KS;
   u4 rs_u1, rs_v1, rs_u2, rs_v2;               // buffer descriptors of the four tile-image arrays
   int ntn_u1, ntn_v1, ntn_u2, ntn_v2;          // tile images per row of tiles
   int D, F, nxs, nsl1, nk1, nch, nsl2, nk2, nds;
-  int ph, i0, i1, ks;                          // cursor: product, outer index (X slab, chunk of F, slab of D), rank slab, step
+  int ph, i0, i1;                              // pass cursor: product, outer index (X slab, chunk of F, slab of D), rank slab
+  // the pass being requested
+  u4 rs;                                       // its matrix
+  int soff[2];                                 // byte offsets of this wavefront's two 1 KiB pieces of the next step
+  unsigned ldst[2];                            // where they go inside a buffer
+  int left;                                    // steps of the pass not yet requested
+  int krow;                                    // 16-row position of the next step inside its 128-row tile
+  int jump;                                    // added when the next step enters the next row of tiles
+  unsigned req_buf, lds_w0;                    // LDS address of the buffer of the next request; of buffer 0
   int buf;                                     // buffer of the step being consumed
   int wave, voff;
-  unsigned lds_w0;
+  int pvoff[2];                                // per-lane offset of each piece: voff, or out of range for tile images right of the matrix
 
   __device__ __forceinline__ int steps_in(int total, int part) const {   // 16-row steps of part `part` (FC wide) of an axis
     const int k = (total - FC * part + 15) / 16;
     return k < KS ? k : KS;
+  }
+  // describe the pass the cursor points at
+  __device__ __forceinline__ void load_pass() {
+    int ntn, k0, n0, nimg = 4;
+    const int xs = i0, ch = i0, ds = i0;
+    if (ph == 0)      { rs = rs_u1; ntn = ntn_u1; k0 = FC * xs; n0 = 512 * i1; left = steps_in(D, xs); }
+    else if (ph == 1) { rs = rs_v1; ntn = ntn_v1; k0 = 0; n0 = FC * ch; nimg = FC / 128; left = nk1; }
+    else if (ph == 2) { rs = rs_u2; ntn = ntn_u2; k0 = FC * ch; n0 = 512 * i1; left = steps_in(F, ch); }
+    else if (ph == 3) { rs = rs_v2; ntn = ntn_v2; k0 = 0; n0 = 512 * ds; left = nk2; }
+    else              { rs = rs_v2; ntn = 1; k0 = 0; n0 = 0; left = 1 << 30; }   // past the end: requests nobody consumes
+#pragma unroll
+    for (int i = 0; i < 4; ++i) rs[i] = __builtin_amdgcn_readfirstlane(rs[i]);   // the selected descriptor stays in scalar registers
+    krow = 0;                                          // every pass starts on a tile boundary (k0 is a multiple of 128)
+    jump = ph < 4 ? (ntn - 1) * kTileImageBytes : -8 * 4096;   // past the end: the same tile again and again
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int q = (wave + 8 * i) & (4 * nimg - 1);   // piece: tile image q / 4, 4-row part q % 4 (narrow passes: twice the same)
+      int nt = (n0 >> 7) + (q >> 2);
+      pvoff[i] = nt < ntn ? voff : kOobOffset;         // images right of the matrix: nothing is read, the piece is filled with zeros
+      nt = nt < ntn ? nt : ntn - 1;
+      soff[i] = __builtin_amdgcn_readfirstlane(((k0 >> 7) * ntn + nt) * kTileImageBytes + 4 * (q & 3) * 256);
+      ldst[i] = __builtin_amdgcn_readfirstlane((q >> 2) * 4096 + (q & 3) * 1024);
+    }
+    left = __builtin_amdgcn_readfirstlane(left);
+    jump = __builtin_amdgcn_readfirstlane(jump);
+  }
+  __device__ __forceinline__ void next_pass() {
+    if (ph == 0) {
+      if (++i1 == nsl1) { i1 = 0; if (++i0 == nxs) { i0 = 0; ph = 1; } }
+    } else if (ph == 1) {
+      i1 = 0; ph = 2;
+    } else if (ph == 2) {
+      if (++i1 == nsl2) { i1 = 0; if (++i0 == nch) { i0 = 0; ph = 3; } else ph = 1; }
+    } else if (ph == 3) {
+      if (++i0 == nds) ph = 4;
+    }
+    ph = __builtin_amdgcn_readfirstlane(ph); i0 = __builtin_amdgcn_readfirstlane(i0); i1 = __builtin_amdgcn_readfirstlane(i1);
+    load_pass();
   }
   __device__ __forceinline__ void init(const FfnV2Args& a, int wave_, int lane, unsigned lds_w0_) {
     D = a.D; F = a.F;
@@ -55,68 +104,43 @@ struct WeightStream {
     nxs = (a.D + FC - 1) / FC; nsl1 = (a.r1 + 511) / 512; nk1 = (a.r1 + 15) / 16;
     nch = (a.F + FC - 1) / FC; nsl2 = (a.r2 + 511) / 512; nk2 = (a.r2 + 15) / 16;
     nds = (a.D + 511) / 512;
-    ph = i0 = i1 = ks = 0; buf = 0;
-    wave = wave_; voff = lane * 16; lds_w0 = lds_w0_;
+    ph = i0 = i1 = 0; buf = 0;
+    wave = wave_; voff = lane * 16; lds_w0 = lds_w0_; req_buf = lds_w0_;
+    load_pass();
   }
-  __device__ __forceinline__ void request(int b) const {
-    u4 rs; int ntn, k, n0, nimg = 4;
-    if (ph == 0)      { rs = rs_u1; ntn = ntn_u1; k = FC * i0 + 16 * ks; n0 = 512 * i1; }
-    else if (ph == 1) { rs = rs_v1; ntn = ntn_v1; k = 16 * ks; n0 = FC * i0; nimg = FC / 128; }
-    else if (ph == 2) { rs = rs_u2; ntn = ntn_u2; k = FC * i0 + 16 * ks; n0 = 512 * i1; }
-    else if (ph == 3) { rs = rs_v2; ntn = ntn_v2; k = 16 * ks; n0 = 512 * i0; }
-    else              { rs = rs_v2; ntn = ntn_v2; k = 0; n0 = 0; }            // past the end: never consumed
+  // request the next step of the stream into the next buffer
+  __device__ __forceinline__ void request() {
+    lds_dma16(rs, req_buf + ldst[0], pvoff[0], soff[0]);
+    lds_dma16(rs, req_buf + ldst[1], pvoff[1], soff[1]);
+    req_buf = req_buf + kV2StepBytes == lds_w0 + NB * kV2StepBytes ? lds_w0 : req_buf + kV2StepBytes;
+    soff[0] += 4096; soff[1] += 4096;
+    if (++krow == 8) { krow = 0; soff[0] += jump; soff[1] += jump; }
+    if (--left == 0) next_pass();
+  }
+  __device__ __forceinline__ void start() {      // the first NB - 1 steps; returns with step 0 in LDS
 #pragma unroll
-    for (int i = 0; i < 4; ++i) rs[i] = __builtin_amdgcn_readfirstlane(rs[i]);   // the selected descriptor stays in scalar registers
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int q = (wave + 8 * i) & (4 * nimg - 1);   // piece: tile image q / 4, 4-row part q % 4 (narrow steps: twice the same)
-      int nt = (n0 >> 7) + (q >> 2);
-      nt = nt < ntn ? nt : ntn - 1;                    // images right of the matrix: any valid one (their columns are not used)
-      lds_dma16(rs, lds_w0 + b * kV2StepBytes + (q >> 2) * 4096 + (q & 3) * 1024, voff,
-                ((k >> 7) * ntn + nt) * kTileImageBytes + ((k & 127) + 4 * (q & 3)) * 256);
-    }
+    for (int b = 0; b < NB - 1; ++b) request();
+    lds_dma_wait_barrier<2 * (NB - 2)>();
   }
-  __device__ __forceinline__ void advance() {
-    ++ks;
-    if (ph == 0) {
-      if (ks == steps_in(D, i0)) { ks = 0; if (++i1 == nsl1) { i1 = 0; if (++i0 == nxs) { i0 = 0; ph = 1; } } }
-    } else if (ph == 1) {
-      if (ks == nk1) { ks = 0; i1 = 0; ph = 2; }
-    } else if (ph == 2) {
-      if (ks == steps_in(F, i0)) {
-        ks = 0;
-        if (++i1 == nsl2) { i1 = 0; if (++i0 == nch) { i0 = 0; ph = 3; } else ph = 1; }
-      }
-    } else if (ph == 3) {
-      if (ks == nk2) { ks = 0; if (++i0 == nds) ph = 4; }
-    }
-    ph = __builtin_amdgcn_readfirstlane(ph); i0 = __builtin_amdgcn_readfirstlane(i0);
-    i1 = __builtin_amdgcn_readfirstlane(i1); ks = __builtin_amdgcn_readfirstlane(ks);
-  }
-  __device__ __forceinline__ void start() {      // the first two steps; returns with step 0 in LDS
-    request(0); advance();
-    request(1); advance();
-    lds_dma_wait_barrier<2>();
-  }
-  __device__ __forceinline__ void begin_step() {
-    request(buf >= 1 ? buf - 1 : 2);             // (buf + 2) % 3: read during the step before this one, free since its barrier
-    advance();
-  }
+  // the request issued while step s is consumed is step s + NB - 1, into the buffer read during step s - 1 (free since its barrier)
+  __device__ __forceinline__ void begin_step() { request(); }
+  // Ends step s: all but the newest NB - 2 requests (two loads each) have landed, so step s + 1 is in LDS after the barrier.
   __device__ __forceinline__ void end_step() {
-    lds_dma_wait_barrier<2>();                   // all but the newest request have landed: the next step's rows are in LDS
-    buf = buf == 2 ? 0 : buf + 1;
+    lds_dma_wait_barrier<2 * (NB - 2)>();
+    buf = buf == NB - 1 ? 0 : buf + 1;
   }
 };
 
-template <int MT>
+template <int MT, int NB>
 __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
+  constexpr int PK = 160 - 32 - 16 * NB;       // fragments (KiB) left for P1^T / Z^T: ranks up to 16 PK / MT
   constexpr int KS = 32 / MT;                  // contraction steps per X slab and per chunk of F (gfr holds KS * MT fragments)
   constexpr int FC = 16 * KS;                  // chunk of F, and X slab width
   constexpr int NTA = 2 / MT;                  // 32-feature tiles per wavefront in the hidden product
   constexpr int NSL = 2 / MT;                  // 512-column slabs of the ranks
-  __shared__ __attribute__((aligned(16))) h8 pfr[64][64];                  // P1^T, later Z^T: [step * MT + tile][lane]
+  __shared__ __attribute__((aligned(16))) h8 pfr[PK][64];                  // P1^T, later Z^T: [step * MT + tile][lane]
   __shared__ __attribute__((aligned(16))) h8 gfr[32][64];                  // X slab, later the activated chunk
-  __shared__ __attribute__((aligned(16))) _Float16 wbuf[3][4][16][128];    // [buffer][tile image][row][column]
+  __shared__ __attribute__((aligned(16))) _Float16 wbuf[NB][4][16][128];    // [buffer][tile image][row][column]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, l32 = lane & 31, g = lane >> 5;
@@ -124,7 +148,7 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
   const int T = a.T, D = a.D, F = a.F, r1 = a.r1, r2 = a.r2;
   const int tok0 = blockIdx.x * 32 * MT;
 
-  WeightStream<MT> ws;
+  WeightStream<MT, NB> ws;
   ws.init(a, wave, lane, lds_addr_of(&wbuf[0][0][0][0]));
   const int nxs = ws.nxs, nsl1 = ws.nsl1, nk1 = ws.nk1, nch = ws.nch, nsl2 = ws.nsl2, nk2 = ws.nk2, nds = ws.nds;
   auto steps_in = [&](int total, int part) __attribute__((always_inline)) { return ws.steps_in(total, part); };
@@ -143,10 +167,40 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
     const int col = 32 * NTA * wave + 32 * j;
     troffA[j] = (col >> 7) * (16 * 128) + tr_lane_off_swz(lane, (col & 127) >> 5) + 4 * g * 128;
   }
-  auto wfrag = [&](int off) __attribute__((always_inline)) {
-    const _Float16* wt = &wbuf[0][0][0][0] + ws.buf * (kV2StepBytes / 2) + off;
+  auto wfrag = [&](int bufi, int off) __attribute__((always_inline)) {
+    const _Float16* wt = &wbuf[0][0][0][0] + bufi * (kV2StepBytes / 2) + off;
     return tr_frag(wt, wt + 8 * 128);
   };
+  // One pass: acc[j][mt] += (column tile j of the staged steps)^T . act, `nsteps` steps; n_on of this wavefront's NT tiles
+  // lie inside the matrix.
+  auto mm_pass = [&](auto& acc, const int* toff, auto ntc, int n_on, int nsteps, const h8* act) __attribute__((always_inline)) {
+    constexpr int NT = decltype(ntc)::value;
+    if (n_on == 0) {                                   // no tile of this wavefront inside the matrix: requests and barriers only
+      for (int ks = 0; ks < nsteps; ++ks) { begin_step(); end_step(); }
+      return;
+    }
+    for (int ks = 0; ks < nsteps; ++ks) {
+      begin_step();
+      h8 b[NT], af[MT];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) af[mt] = act[(ks * MT + mt) * 64 + lane];
+#pragma unroll
+      for (int j = 0; j < NT; ++j) b[j] = wfrag(ws.buf, toff[j]);       // (a wavefront with one tile inside the matrix reads both)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        if (j < n_on) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) acc[j][mt] = mfma32(b[j], af[mt], acc[j][mt]);
+        }
+      end_step();
+    }
+  };
+  auto tiles_on = [&](int first, int n, int nt) __attribute__((always_inline)) {   // how many of nt 32-wide tiles from `first` start below n
+    const int k = (n - first + 31) / 32;
+    return k < 0 ? 0 : (k < nt ? k : nt);
+  };
+  typedef std::integral_constant<int, 2> two_tiles;
+  typedef std::integral_constant<int, NTA> hidden_tiles;
 
   f16v zacc[NSL][2][MT];                       // P1^T in step 1, Z^T in step 2: slab, column tile, token tile
   auto clear_z = [&]() __attribute__((always_inline)) {
@@ -179,24 +233,7 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
   };
   // one slab of a rank-space product: z += W^T[512 sl .., steps] . act
   auto rank_pass = [&](f16v (&z)[2][MT], int sl, int nsteps, int n, const h8* act) __attribute__((always_inline)) {
-    const bool on0 = 512 * sl + 64 * wave < n, on1 = 512 * sl + 64 * wave + 32 < n;
-    for (int ks = 0; ks < nsteps; ++ks) {
-      begin_step();
-      if (on0) {
-        h8 af[MT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) af[mt] = act[(ks * MT + mt) * 64 + lane];
-        const h8 b0 = wfrag(troff[0]);
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) z[0][mt] = mfma32(b0, af[mt], z[0][mt]);
-        if (on1) {
-          const h8 b1 = wfrag(troff[1]);
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) z[1][mt] = mfma32(b1, af[mt], z[1][mt]);
-        }
-      }
-      end_step();
-    }
+    mm_pass(z, troff, two_tiles{}, tiles_on(512 * sl + 64 * wave, n, 2), nsteps, act);
   };
 
   ws.start();
@@ -236,25 +273,11 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) hacc[j][mt] = zero16();
     const int f0 = FC * ch + 32 * NTA * wave;   // first feature of this wavefront
+    const int nf_on = tiles_on(f0, F, NTA);
     bool onf[NTA];
 #pragma unroll
-    for (int j = 0; j < NTA; ++j) onf[j] = f0 + 32 * j < F;
-    for (int ks = 0; ks < nk1; ++ks) {
-      begin_step();
-      if (onf[0]) {
-        h8 af[MT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) af[mt] = pfr[ks * MT + mt][lane];
-#pragma unroll
-        for (int j = 0; j < NTA; ++j)
-          if (onf[j]) {
-            const h8 b = wfrag(troffA[j]);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) hacc[j][mt] = mfma32(b, af[mt], hacc[j][mt]);
-          }
-      }
-      end_step();
-    }
+    for (int j = 0; j < NTA; ++j) onf[j] = j < nf_on;
+    mm_pass(hacc, troffA, hidden_tiles{}, nf_on, nk1, &pfr[0][0]);
     // + b_1, activation, fp16 -> operand fragments of the second product (the last barrier has retired every read of gfr)
 #pragma unroll
     for (int j = 0; j < NTA; ++j)
@@ -296,24 +319,7 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) oacc[j][mt] = zero16();
     const int n0 = 512 * ds + 64 * wave;
-    const bool on0 = n0 < D, on1 = n0 + 32 < D;
-    for (int ks = 0; ks < nk2; ++ks) {
-      begin_step();
-      if (on0) {
-        h8 af[MT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) af[mt] = pfr[ks * MT + mt][lane];
-        const h8 b0 = wfrag(troff[0]);
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) oacc[0][mt] = mfma32(b0, af[mt], oacc[0][mt]);
-        if (on1) {
-          const h8 b1 = wfrag(troff[1]);
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) oacc[1][mt] = mfma32(b1, af[mt], oacc[1][mt]);
-        }
-      }
-      end_step();
-    }
+    mm_pass(oacc, troff, two_tiles{}, tiles_on(n0, D, 2), nk2, &pfr[0][0]);
 #pragma unroll
     for (int j = 0; j < 2; ++j)
       if (n0 + 32 * j < D) {
@@ -343,11 +349,23 @@ bool ffn_v2_supported(int D, int F, int r1, int r2) {
 
 hipError_t launch_ffn_v2(const FfnV2Args& a, hipStream_t s) {
   if (!ffn_v2_supported(a.D, a.F, a.r1, a.r2) || a.T <= 0) return hipErrorInvalidValue;
-  // 64 tokens per workgroup halve the weight traffic; they need both ranks <= 512 and enough tokens to fill the chip
-  if (a.r1 <= 512 && a.r2 <= 512 && (a.T + 63) / 64 >= 200)
-    hipLaunchKernelGGL(ffn_v2_kernel<2>, dim3((a.T + 63) / 64), dim3(kV2Threads), 0, s, a);
-  else
-    hipLaunchKernelGGL(ffn_v2_kernel<1>, dim3((a.T + 31) / 32), dim3(kV2Threads), 0, s, a);
+  const int r = a.r1 > a.r2 ? a.r1 : a.r2;
+  // 64 tokens per workgroup halve the weight traffic; they need both ranks <= 512 and enough tokens to fill the chip.
+  // The LDS that the rank-space fragments do not need holds more weight steps in flight (4, 6 or 7 buffers of 16 KiB).
+  const bool wide = r <= 512 && (a.T + 63) / 64 >= 200;
+  const dim3 grid(wide ? (a.T + 63) / 64 : (a.T + 31) / 32), block(kV2Threads);
+  const int rm = wide ? 2 * r : r;             // fragments of P1^T / Z^T in KiB = rm / 16
+  if (wide) {
+    if (rm <= 256) hipLaunchKernelGGL((ffn_v2_kernel<2, 7>), grid, block, 0, s, a);
+    else if (rm <= 512) hipLaunchKernelGGL((ffn_v2_kernel<2, 6>), grid, block, 0, s, a);
+    else if (rm <= 768) hipLaunchKernelGGL((ffn_v2_kernel<2, 5>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((ffn_v2_kernel<2, 4>), grid, block, 0, s, a);
+  } else {
+    if (rm <= 256) hipLaunchKernelGGL((ffn_v2_kernel<1, 7>), grid, block, 0, s, a);
+    else if (rm <= 512) hipLaunchKernelGGL((ffn_v2_kernel<1, 6>), grid, block, 0, s, a);
+    else if (rm <= 768) hipLaunchKernelGGL((ffn_v2_kernel<1, 5>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((ffn_v2_kernel<1, 4>), grid, block, 0, s, a);
+  }
   return hipGetLastError();
 }
 
