@@ -59,33 +59,46 @@ __global__ void __launch_bounds__(256) decode_cache_write_kernel(const _Float16*
 // ---------------------------------------------------------------------------------------------------------------
 // Absorbed queries: W[b, h, rho] = scale log2(e) * sum_d V_k[rho, h d_h + d] * q[b, h d_h + d], written as the
 // fragment-major layout of a [32 (heads, padded), r_k] matrix per sequence (columns of heads >= H are left untouched:
-// their scores are never used).  One workgroup per (64 ranks, head): V_k is read once for the whole batch.
+// their scores are never used).  One workgroup per (64 ranks, head), so V_k is read once for the whole batch; the
+// product runs on the matrix cores as W^T [ranks, sequences] = V_k[ranks, head columns] q^T: both operands are
+// contiguous along d (16-byte loads straight into operand registers).  Wavefront w: rank tile w % 2, sequence tiles
+// w / 2, w / 2 + 2, ...
 // ---------------------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) decode_absorb_kernel(const _Float16* __restrict__ q, const void* __restrict__ Vk, int w_dt,
                                                             int B, int D, int H, int r_k, float qs, _Float16* W) {
-  __shared__ float qh[64][128];              // up to 64 sequences x d_h at a time
   const int dh = D / H, c = blockIdx.x, h = blockIdx.y;
-  const int rl = threadIdx.x >> 2, part = threadIdx.x & 3, dq = dh / 4;
-  const int rho = 64 * c + rl;
-  float vk[32];
+  const int lane = threadIdx.x & 63, l32 = lane & 31, g = lane >> 5, wave = threadIdx.x >> 6;
+  const int rho = 64 * c + 32 * (wave & 1) + l32;
+  const int nst = dh / 16;                       // contraction steps (d_h is 64 or 128)
+  h8 vf[8];
 #pragma unroll
-  for (int i = 0; i < 32; ++i) vk[i] = (i < dq && rho < r_k) ? load_param(Vk, (size_t)rho * D + h * dh + part * dq + i, w_dt) : 0.f;
+  for (int s = 0; s < 8; ++s) {
+    u4 raw = {0u, 0u, 0u, 0u};
+    if (s < nst && rho < r_k) raw = *(const u4*)((const uint16_t*)Vk + (size_t)rho * D + h * dh + 16 * s + 8 * g);
+    vf[s] = w_dt == DT_BF16 ? raw_to_h8<DT_BF16>(raw) : raw_to_h8<DT_F16>(raw);
+  }
   const size_t w_seq = (size_t)((r_k + 63) / 64) * 2048;   // halves per sequence
-  const int off = rl, g = off >> 5, kk = (off >> 3) & 3;
-  for (int b0 = 0; b0 < B; b0 += 64) {
-    const int nb = B - b0 < 64 ? B - b0 : 64;
-    __syncthreads();
-    for (int i = threadIdx.x; i < nb * dh; i += 256) qh[i / dh][i % dh] = (float)q[(size_t)(b0 + i / dh) * D + h * dh + i % dh];
-    __syncthreads();
-    for (int b = 0; b < nb; ++b) {
-      float s = 0.f;
+  for (int bt = wave >> 1; 32 * bt < B; bt += 2) {
+    const int b = 32 * bt + l32;
+    f16v acc = zero16();
 #pragma unroll
-      for (int i = 0; i < 32; ++i)
-        if (i < dq) s = fmaf(vk[i], qh[b][part * dq + i], s);
-      s += __shfl_xor(s, 1, 64);
-      s += __shfl_xor(s, 2, 64);
-      if (part == 0 && rho < r_k)
-        W[(size_t)(b0 + b) * w_seq + (size_t)c * 2048 + (kk * 64 + 32 * g + h) * 8 + (off & 7)] = (_Float16)(s * qs);
+    for (int s = 0; s < 8; ++s)
+      if (s < nst) {
+        h8 qf = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (b < B) qf = *(const h8*)(q + (size_t)b * D + h * dh + 16 * s + 8 * g);
+        acc = mfma32(vf[s], qf, acc);
+      }
+    if (b < B) {
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int off = 32 * (wave & 1) + 8 * jj + 4 * g;          // rank inside the 64-rank chunk, a multiple of 4
+        if (64 * c + off < r_k) {
+          h4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = (_Float16)(acc[4 * jj + e] * qs);
+          *(h4*)(W + (size_t)b * w_seq + (size_t)c * 2048 + (((off >> 3) & 3) * 64 + 32 * (off >> 5) + h) * 8 + (off & 7)) = o;
+        }
+      }
     }
   }
 }
@@ -305,44 +318,64 @@ __global__ void __launch_bounds__(256) decode_merge_kernel(const float* __restri
 }
 
 // context[b, h d_h + d] = sum_rho u[b, h, rho] V_v[rho, h d_h + d] + b_v[h d_h + d], fp16 row-major [B, D].
-// One workgroup per (head, 32 columns): its [r_v, 32] piece of V_v is brought into LDS with all requests in flight at
-// once, then, 16 sequences at a time, their u rows; thread (column, rank group) walks every eighth rank and the eight
-// groups are added through LDS.
+// One workgroup per (head, 32 columns), on the matrix cores as ctx^T [columns, sequences] = V_v[:, columns]^T u^T: the
+// ranks are dealt to the four wavefronts in chunks of 64; a wavefront copies its [64, 32] piece of V_v into its own
+// part of LDS (rows padded as for the other staged weight tiles) and reads it back with the transposing read, the
+// u operands (rounded to fp16) come straight from memory.  The four partial tiles are added through LDS.
 __global__ void __launch_bounds__(256) decode_value_kernel(const float* __restrict__ u, const void* __restrict__ Vv, const void* __restrict__ bv,
                                                            int w_dt, int B, int D, int H, int r_v, _Float16* ctx) {
-  __shared__ float ul[16][1024];
-  __shared__ __attribute__((aligned(16))) uint16_t vt[1024][32];
-  __shared__ float red[8][16][33];
-  const int dh = D / H, h = blockIdx.x, col0 = h * dh + 32 * blockIdx.y, c = threadIdx.x & 31, grp = threadIdx.x >> 5;
-  for (int i = threadIdx.x; i < r_v * 4; i += 256)
-    *(u4*)&vt[i >> 2][8 * (i & 3)] = *(const u4*)((const uint16_t*)Vv + (size_t)(i >> 2) * D + col0 + 8 * (i & 3));
-  for (int b0 = 0; b0 < B; b0 += 16) {
-    const int nb = B - b0 < 16 ? B - b0 : 16;
-    __syncthreads();
-    for (int i = threadIdx.x; i < 16 * r_v; i += 256) {
-      const int bb = i / r_v, rho = i % r_v;
-      ul[bb][rho] = bb < nb ? u[((size_t)(b0 + bb) * H + h) * r_v + rho] : 0.f;
+  constexpr int WS = wtile_stride(32);          // halves per staged row
+  __shared__ __attribute__((aligned(16))) _Float16 vt[4][64 * WS];
+  __shared__ float red[4][16][64];
+  const int dh = D / H, h = blockIdx.x, col0 = h * dh + 32 * blockIdx.y;
+  const int lane = threadIdx.x & 63, l32 = lane & 31, g = lane >> 5, wave = threadIdx.x >> 6;
+  const int nch = (r_v + 63) / 64;
+  const int tr = tr_lane_off(lane, WS) + 8 * g * WS;
+  _Float16* mine = &vt[wave][0];
+  for (int b0 = 0; b0 < B; b0 += 32) {
+    const int b = b0 + l32;
+    f16v acc = zero16();
+    for (int ch = wave; ch < nch; ch += 4) {
+      // rows 64 ch .., 32 columns: lane -> row lane / 4 (+ 16 per pass), 8 columns from 8 (lane % 4)
+#pragma unroll
+      for (int pss = 0; pss < 4; ++pss) {
+        const int row = 16 * pss + (lane >> 2), rho = 64 * ch + row;
+        u4 raw = {0u, 0u, 0u, 0u};
+        if (rho < r_v) raw = *(const u4*)((const uint16_t*)Vv + (size_t)rho * D + col0 + 8 * (lane & 3));
+        if (w_dt == DT_BF16) stage_store16<DT_BF16>(mine + row * WS + 8 * (lane & 3), raw);
+        else stage_store16<DT_F16>(mine + row * WS + 8 * (lane & 3), raw);
+      }
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const int rho = 64 * ch + 16 * s + 8 * g;
+        h8 uf = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (b < B && rho < r_v) {
+          const f4v* up = (const f4v*)(u + ((size_t)b * H + h) * r_v + rho);
+          const f4v lo = up[0], hi = up[1];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) { uf[i] = (_Float16)lo[i]; uf[4 + i] = (_Float16)hi[i]; }
+        }
+        const h8 vf = tr_frag(mine + tr + 16 * s * WS, mine + tr + (16 * s + 4) * WS);
+        acc = mfma32(vf, uf, acc);
+      }
     }
+    __syncthreads();                             // the previous sequence tile's sums have been read
+#pragma unroll
+    for (int v = 0; v < 16; ++v) red[wave][v][lane] = acc[v];
     __syncthreads();
-    float acc[16];
+    if (wave == 0 && b < B) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-#pragma unroll 4
-    for (int rho = grp; rho < r_v; rho += 8) {
-      const uint16_t raw = vt[rho][c];
-      const float w = w_dt == DT_BF16 ? bf16_bits_to_float(raw) : (float)__builtin_bit_cast(_Float16, raw);
+      for (int jj = 0; jj < 4; ++jj) {
+        const int d = 8 * jj + 4 * g;
+        h4 o;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc[i] = fmaf(ul[i][rho], w, acc[i]);
-    }
-#pragma unroll
-    for (int i = 0; i < 16; ++i) red[grp][i][c] = acc[i];
-    __syncthreads();
-    for (int i = threadIdx.x; i < nb * 32; i += 256) {
-      const int bb = i >> 5, cc = i & 31;
-      float s = bv ? load_param(bv, (size_t)col0 + cc, w_dt) : 0.f;
-#pragma unroll
-      for (int g2 = 0; g2 < 8; ++g2) s += red[g2][bb][cc];
-      ctx[(size_t)(b0 + bb) * D + col0 + cc] = (_Float16)s;
+        for (int e = 0; e < 4; ++e) {
+          const int v = 4 * jj + e;
+          const float sum = red[0][v][lane] + red[1][v][lane] + red[2][v][lane] + red[3][v][lane];
+          o[e] = (_Float16)(sum + (bv ? load_param(bv, (size_t)col0 + d + e, w_dt) : 0.f));
+        }
+        *(h4*)(ctx + (size_t)b * D + col0 + d) = o;
+      }
     }
   }
 }
