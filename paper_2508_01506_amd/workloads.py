@@ -117,6 +117,8 @@ _register(_wl(7, 9, name="v2_two_rank_slabs", B=2, M=75, D=640, H=10, F=1104, r_
 _register(_wl(7, 10, name="v2_max_rank", B=1, M=100, D=1024, H=8, F=2064, r_attn=32, r_ffn=1024, dtype="fp16"))
 _register(_wl(7, 11, name="v2_many_tokens", B=26, M=500, D=128, H=2, F=400, r_attn=32, r_ffn=96, dtype="fp16"))
 _register(_wl(7, 12, name="v2_many_tokens_r512", B=13, M=1001, D=576, H=9, F=784, r_attn=32, r_ffn=512, dtype="bf16"))
+_register(_wl(7, 13, name="v2_llm_width_r1024", B=1, M=2048, D=4096, H=32, F=16384, r_attn=64, r_ffn=1024, dtype="bf16",
+              norm="pre_ln"))
 
 # Per-head factorisation of q, k, v (the paper's attention setting: one rank-r pair per head, r <= d_h), the encoder
 # shapes of its attention-kernel sweep: batch 16 or 64, sequence 128..1024, per-head ranks 64, 32, 16.

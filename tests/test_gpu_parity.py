@@ -451,7 +451,8 @@ def test_ffn_as_one_kernel_activations_and_types(fb):
 
 
 @pytest.mark.parametrize("name", ["cfg1_bert_base_b2_m128", "cfg2u_bert_base_b16_m512_pad_unit", "cfg3_bert_large_b32_m512_r128",
-                                  "cfg3_bert_large_b32_m512_r512", "cfg4_long_b4_m8192", "ffn_grid_b16_m512_r384"])
+                                  "cfg3_bert_large_b32_m512_r512", "cfg4_long_b4_m8192", "ffn_grid_b16_m512_r384",
+                                  "v2_llm_width_r1024"])
 def test_ffn_as_one_kernel_full_size_sampled(fb, name):
     """The one-kernel FFN at benchmark sizes (32- and 64-token variants), sampled rows against the oracle."""
     w, inp, dev = workload(name, fb, "tiled")
