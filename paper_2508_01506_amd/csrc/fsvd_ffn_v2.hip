@@ -8,11 +8,12 @@
 //   Out^T [N, tokens] = W^T [N, K] . In^T [K, tokens],
 // "transposed" so that tokens lie along the lanes: the accumulators of one product, rounded to fp16, are the operand
 // registers of the next.  The activations between two products stay in LDS as ready operand fragments
-// ([16-wide contraction step][token tile][lane] x 16 bytes): X is staged in slabs of 512 / MT columns, P1^T (later Z^T) takes
-// up to 64 KiB, the activated hidden chunk (512 / MT features) 32 KiB; what is left of the 160 KiB holds weight steps.  All weights are prepacked tile images; one step of
-// 16 contraction rows x 512 columns (16 KiB) at a time is copied straight into LDS, NB buffers, NB - 1 steps ahead, as
-// ONE request stream over the whole kernel (a cursor walks the same loop nest as the consumers), so that the copies never
-// drain between the products.  Within a 512-column slab wavefront w owns columns 64 w .. 64 w + 63.
+// ([16-wide contraction step][token tile][lane] x 16 bytes): X is staged in slabs of 512 / MT columns, P1^T (later Z^T)
+// takes up to 64 KiB, the activated hidden chunk (512 / MT features) 32 KiB; what is left of the 160 KiB holds weight
+// steps.  All weights are prepacked tile images; one step of 16 contraction rows x 512 columns (16 KiB) at a time is
+// copied straight into LDS, NB buffers, NB - 1 steps ahead, as ONE request stream over the whole kernel (a cursor walks
+// the same loop nest as the consumers), so that the copies never drain between the products.  Within a 512-column slab
+// wavefront w owns columns 64 w .. 64 w + 63.
 //   step 1: P1^T = U_1^T X^T                         (sum over D in slabs; all slabs of r1 per X slab)
 //   step 2: per chunk of F: H^T = V_1^T P1^T + b_1, G = phi(H) -> LDS;  Z^T += U_2^T G^T  (Z^T stays in registers)
 //   step 3: out^T = V_2^T Z^T + b_2 per 512-column slab of D, written row-major.
@@ -38,7 +39,7 @@ struct WeightStream {
   static constexpr int KS = 32 / MT, FC = 16 * KS;
   u4 rs_u1, rs_v1, rs_u2, rs_v2;               // buffer descriptors of the four tile-image arrays
   int ntn_u1, ntn_v1, ntn_u2, ntn_v2;          // tile images per row of tiles
-  int D, F, nxs, nsl1, nk1, nch, nsl2, nk2, nds;
+  int D, F, r1, r2, nxs, nsl1, nk1, nch, nsl2, nk2, nds;
   int ph, i0, i1;                              // pass cursor: product, outer index (X slab, chunk of F, slab of D), rank slab
   // the pass being requested
   u4 rs;                                       // its matrix
@@ -46,6 +47,7 @@ struct WeightStream {
   unsigned ldst[2];                            // where they go inside a buffer
   int left;                                    // steps of the pass not yet requested
   int krow;                                    // 16-row position of the next step inside its 128-row tile
+  int kinc, adv;                               // 16-row units and bytes per step: 1 and 4096 (wide), 2 and 8192 (narrow)
   int jump;                                    // added when the next step enters the next row of tiles
   unsigned req_buf, lds_w0;                    // LDS address of the buffer of the next request; of buffer 0
   int buf;                                     // buffer of the step being consumed
@@ -56,30 +58,41 @@ struct WeightStream {
     const int k = (total - FC * part + 15) / 16;
     return k < KS ? k : KS;
   }
+  // A pass whose block of columns is at most 256 wide is NARROW: its steps are 32 rows x 256 columns (two tile images)
+  // instead of 16 x 512 (four), so that all eight wavefronts own a 32-column tile and the pass has half as many steps.
+  static __device__ __forceinline__ bool is_narrow(int width) { return width <= 256; }
+  static __device__ __forceinline__ int pass_steps(int k16, bool narrow) { return narrow ? (k16 + 1) >> 1 : k16; }
   // describe the pass the cursor points at
   __device__ __forceinline__ void load_pass() {
-    int ntn, k0, n0, nimg = 4;
+    int ntn, k0, n0, k16, width;
     const int xs = i0, ch = i0, ds = i0;
-    if (ph == 0)      { rs = rs_u1; ntn = ntn_u1; k0 = FC * xs; n0 = 512 * i1; left = steps_in(D, xs); }
-    else if (ph == 1) { rs = rs_v1; ntn = ntn_v1; k0 = 0; n0 = FC * ch; nimg = FC / 128; left = nk1; }
-    else if (ph == 2) { rs = rs_u2; ntn = ntn_u2; k0 = FC * ch; n0 = 512 * i1; left = steps_in(F, ch); }
-    else if (ph == 3) { rs = rs_v2; ntn = ntn_v2; k0 = 0; n0 = 512 * ds; left = nk2; }
-    else              { rs = rs_v2; ntn = 1; k0 = 0; n0 = 0; left = 1 << 30; }   // past the end: requests nobody consumes
+    if (ph == 0)      { rs = rs_u1; ntn = ntn_u1; k0 = FC * xs; n0 = 512 * i1; k16 = steps_in(D, xs); width = r1 - n0; }
+    else if (ph == 1) { rs = rs_v1; ntn = ntn_v1; k0 = 0; n0 = FC * ch; k16 = nk1; width = FC; }
+    else if (ph == 2) { rs = rs_u2; ntn = ntn_u2; k0 = FC * ch; n0 = 512 * i1; k16 = steps_in(F, ch); width = r2 - n0; }
+    else if (ph == 3) { rs = rs_v2; ntn = ntn_v2; k0 = 0; n0 = 512 * ds; k16 = nk2; width = D - n0; }
+    else              { rs = rs_v2; ntn = 1; k0 = 0; n0 = 0; k16 = 1 << 30; width = 512; }   // past the end: requests nobody consumes
 #pragma unroll
     for (int i = 0; i < 4; ++i) rs[i] = __builtin_amdgcn_readfirstlane(rs[i]);   // the selected descriptor stays in scalar registers
+    const bool narrow = is_narrow(width);
+    left = pass_steps(k16, narrow);
+    kinc = narrow ? 2 : 1;
+    adv = narrow ? 8192 : 4096;
     krow = 0;                                          // every pass starts on a tile boundary (k0 is a multiple of 128)
     jump = ph < 4 ? (ntn - 1) * kTileImageBytes : -8 * 4096;   // past the end: the same tile again and again
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      const int q = (wave + 8 * i) & (4 * nimg - 1);   // piece: tile image q / 4, 4-row part q % 4 (narrow passes: twice the same)
-      int nt = (n0 >> 7) + (q >> 2);
+      const int q = wave + 8 * i;                      // piece: 4 rows of one tile image
+      const int img = narrow ? q >> 3 : q >> 2, part = narrow ? q & 7 : q & 3;
+      int nt = (n0 >> 7) + img;
       pvoff[i] = nt < ntn ? voff : kOobOffset;         // images right of the matrix: nothing is read, the piece is filled with zeros
       nt = nt < ntn ? nt : ntn - 1;
-      soff[i] = __builtin_amdgcn_readfirstlane(((k0 >> 7) * ntn + nt) * kTileImageBytes + 4 * (q & 3) * 256);
-      ldst[i] = __builtin_amdgcn_readfirstlane((q >> 2) * 4096 + (q & 3) * 1024);
+      soff[i] = __builtin_amdgcn_readfirstlane(((k0 >> 7) * ntn + nt) * kTileImageBytes + 4 * part * 256);
+      ldst[i] = __builtin_amdgcn_readfirstlane(img * (narrow ? 8192 : 4096) + part * 1024);
     }
     left = __builtin_amdgcn_readfirstlane(left);
     jump = __builtin_amdgcn_readfirstlane(jump);
+    kinc = __builtin_amdgcn_readfirstlane(kinc);
+    adv = __builtin_amdgcn_readfirstlane(adv);
   }
   __device__ __forceinline__ void next_pass() {
     if (ph == 0) {
@@ -95,7 +108,7 @@ struct WeightStream {
     load_pass();
   }
   __device__ __forceinline__ void init(const FfnV2Args& a, int wave_, int lane, unsigned lds_w0_) {
-    D = a.D; F = a.F;
+    D = a.D; F = a.F; r1 = a.r1; r2 = a.r2;
     rs_u1 = lds_dma_rsrc(a.U1, (unsigned)tiled_bytes(a.D, a.r1));
     rs_v1 = lds_dma_rsrc(a.V1, (unsigned)tiled_bytes(a.r1, a.F));
     rs_u2 = lds_dma_rsrc(a.U2, (unsigned)tiled_bytes(a.F, a.r2));
@@ -113,8 +126,9 @@ struct WeightStream {
     lds_dma16(rs, req_buf + ldst[0], pvoff[0], soff[0]);
     lds_dma16(rs, req_buf + ldst[1], pvoff[1], soff[1]);
     req_buf = req_buf + kV2StepBytes == lds_w0 + NB * kV2StepBytes ? lds_w0 : req_buf + kV2StepBytes;
-    soff[0] += 4096; soff[1] += 4096;
-    if (++krow == 8) { krow = 0; soff[0] += jump; soff[1] += jump; }
+    soff[0] += adv; soff[1] += adv;
+    krow += kinc;
+    if (krow == 8) { krow = 0; soff[0] += jump; soff[1] += jump; }
     if (--left == 0) next_pass();
   }
   __device__ __forceinline__ void start() {      // the first NB - 1 steps; returns with step 0 in LDS
@@ -156,38 +170,58 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
   auto end_step = [&]() __attribute__((always_inline)) { ws.end_step(); };
   // transposing-read offsets of this lane (halves inside one staged step): rows 4 g .. + 3 and 8 + 4 g .. + 3 of the step, which
   // is the order in which an accumulator tile, rounded to fp16, supplies the contraction slots of the next product
-  int troff[2], troffA[NTA];
+  int troff[2], troffN;                        // wide steps: column tiles 64 w + 32 j; narrow steps: column tile 32 w
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const int col = 64 * wave + 32 * j;
     troff[j] = (col >> 7) * (16 * 128) + tr_lane_off_swz(lane, (col & 127) >> 5) + 4 * g * 128;
   }
-#pragma unroll
-  for (int j = 0; j < NTA; ++j) {
-    const int col = 32 * NTA * wave + 32 * j;
-    troffA[j] = (col >> 7) * (16 * 128) + tr_lane_off_swz(lane, (col & 127) >> 5) + 4 * g * 128;
-  }
+  troffN = (wave >> 2) * (32 * 128) + tr_lane_off_swz(lane, wave & 3) + 4 * g * 128;
   auto wfrag = [&](int bufi, int off) __attribute__((always_inline)) {
     const _Float16* wt = &wbuf[0][0][0][0] + bufi * (kV2StepBytes / 2) + off;
     return tr_frag(wt, wt + 8 * 128);
   };
-  // One pass: acc[j][mt] += (column tile j of the staged steps)^T . act, `nsteps` steps; n_on of this wavefront's NT tiles
-  // lie inside the matrix.
-  auto mm_pass = [&](auto& acc, const int* toff, auto ntc, int n_on, int nsteps, const h8* act) __attribute__((always_inline)) {
-    constexpr int NT = decltype(ntc)::value;
+  // One pass over `k16` 16-row contraction steps of a block of columns `width` wide that starts at this wavefront's
+  // first column tile `first` of a matrix `n` columns wide: acc[j][mt] += (column tile)^T . act.  Wide blocks: two tiles
+  // per wavefront (j = 0, 1), one contraction step per staged step; narrow blocks (see WeightStream): tile j = 0 only,
+  // two contraction steps per staged step.
+  auto mm_pass = [&](auto& acc, bool narrow, int n_on, int k16, const h8* act) __attribute__((always_inline)) {
+    const int nsteps = ws.pass_steps(k16, narrow);
     if (n_on == 0) {                                   // no tile of this wavefront inside the matrix: requests and barriers only
       for (int ks = 0; ks < nsteps; ++ks) { begin_step(); end_step(); }
       return;
     }
+    if (narrow) {
+      for (int ks = 0; ks < nsteps; ++ks) {
+        begin_step();
+        const bool two = 2 * ks + 1 < k16;             // an odd number of contraction steps: the last staged step holds one
+        h8 b[2], af[2][MT];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int kk = two ? 2 * ks + u : 2 * ks;
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) af[u][mt] = act[(kk * MT + mt) * 64 + lane];
+          b[u] = wfrag(ws.buf, troffN + u * 16 * 128);
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[0][mt] = mfma32(b[0], af[0][mt], acc[0][mt]);
+        if (two) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) acc[0][mt] = mfma32(b[1], af[1][mt], acc[0][mt]);
+        }
+        end_step();
+      }
+      return;
+    }
     for (int ks = 0; ks < nsteps; ++ks) {
       begin_step();
-      h8 b[NT], af[MT];
+      h8 b[2], af[MT];
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) af[mt] = act[(ks * MT + mt) * 64 + lane];
 #pragma unroll
-      for (int j = 0; j < NT; ++j) b[j] = wfrag(ws.buf, toff[j]);       // (a wavefront with one tile inside the matrix reads both)
+      for (int j = 0; j < 2; ++j) b[j] = wfrag(ws.buf, troff[j]);       // (a wavefront with one tile inside the matrix reads both)
 #pragma unroll
-      for (int j = 0; j < NT; ++j)
+      for (int j = 0; j < 2; ++j)
         if (j < n_on) {
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) acc[j][mt] = mfma32(b[j], af[mt], acc[j][mt]);
@@ -195,12 +229,12 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
       end_step();
     }
   };
-  auto tiles_on = [&](int first, int n, int nt) __attribute__((always_inline)) {   // how many of nt 32-wide tiles from `first` start below n
-    const int k = (n - first + 31) / 32;
+  // first column (relative to the block start) and number of this wavefront's tiles of a block `width` wide
+  auto first_col = [&](bool narrow) __attribute__((always_inline)) { return narrow ? 32 * wave : 64 * wave; };
+  auto tiles_on = [&](int first, int width, bool narrow) __attribute__((always_inline)) {   // tiles of this wavefront that start inside the block
+    const int k = (width - first + 31) / 32, nt = narrow ? 1 : 2;
     return k < 0 ? 0 : (k < nt ? k : nt);
   };
-  typedef std::integral_constant<int, 2> two_tiles;
-  typedef std::integral_constant<int, NTA> hidden_tiles;
 
   f16v zacc[NSL][2][MT];                       // P1^T in step 1, Z^T in step 2: slab, column tile, token tile
   auto clear_z = [&]() __attribute__((always_inline)) {
@@ -214,11 +248,12 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
   // rank-space accumulators -> operand fragments of the next product (ranks below `n` only)
   auto publish_z = [&](int n) __attribute__((always_inline)) {
 #pragma unroll
-    for (int sl = 0; sl < NSL; ++sl)
+    for (int sl = 0; sl < NSL; ++sl) {
+      const bool narrow = ws.is_narrow(n - 512 * sl);
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
-        const int row0 = 512 * sl + 64 * wave + 32 * j;
-        if (row0 < n) {
+        const int row0 = 512 * sl + first_col(narrow) + 32 * j;
+        if (row0 < n && !(narrow && j > 0)) {
 #pragma unroll
           for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
@@ -230,10 +265,12 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
             }
         }
       }
+    }
   };
   // one slab of a rank-space product: z += W^T[512 sl .., steps] . act
-  auto rank_pass = [&](f16v (&z)[2][MT], int sl, int nsteps, int n, const h8* act) __attribute__((always_inline)) {
-    mm_pass(z, troff, two_tiles{}, tiles_on(512 * sl + 64 * wave, n, 2), nsteps, act);
+  auto rank_pass = [&](f16v (&z)[2][MT], int sl, int k16, int n, const h8* act) __attribute__((always_inline)) {
+    const bool narrow = ws.is_narrow(n - 512 * sl);
+    mm_pass(z, narrow, tiles_on(first_col(narrow), n - 512 * sl, narrow), k16, act);
   };
 
   ws.start();
@@ -267,17 +304,20 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
 
   // ================= step 2: chunks of F =================
   for (int ch = 0; ch < nch; ++ch) {
-    f16v hacc[NTA][MT];
+    f16v hacc[2][MT];                           // (narrow chunks use tile 0 only)
 #pragma unroll
-    for (int j = 0; j < NTA; ++j)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) hacc[j][mt] = zero16();
-    const int f0 = FC * ch + 32 * NTA * wave;   // first feature of this wavefront
-    const int nf_on = tiles_on(f0, F, NTA);
+    constexpr bool narrowA = FC <= 256;
+    const int fl = narrowA ? 32 * wave : 64 * wave;          // first feature of this wavefront inside the chunk
+    const int f0 = FC * ch + fl;
+    const int wchunk = F - FC * ch < FC ? F - FC * ch : FC;   // width of this chunk
+    const int nf_on = tiles_on(fl, wchunk, narrowA);
     bool onf[NTA];
 #pragma unroll
     for (int j = 0; j < NTA; ++j) onf[j] = j < nf_on;
-    mm_pass(hacc, troffA, hidden_tiles{}, nf_on, nk1, &pfr[0][0]);
+    mm_pass(hacc, narrowA, nf_on, nk1, &pfr[0][0]);
     // + b_1, activation, fp16 -> operand fragments of the second product (the last barrier has retired every read of gfr)
 #pragma unroll
     for (int j = 0; j < NTA; ++j)
@@ -299,7 +339,7 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
               const float y = a.act == 0 ? gelu_erf_f(x) : (a.act == 1 ? gelu_tanh_f(x) : fmaxf(x, 0.f));
               o[i] = (_Float16)y;
             }
-            gfr[(2 * NTA * wave + 2 * j + s2) * MT + mt][lane] = o;
+            gfr[(fl / 16 + 2 * j + s2) * MT + mt][lane] = o;
           }
       }
     __syncthreads();
@@ -318,11 +358,13 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) oacc[j][mt] = zero16();
-    const int n0 = 512 * ds + 64 * wave;
-    mm_pass(oacc, troff, two_tiles{}, tiles_on(n0, D, 2), nk2, &pfr[0][0]);
+    const bool narrowD = ws.is_narrow(D - 512 * ds);
+    const int n0 = 512 * ds + first_col(narrowD);
+    const int nd_on = tiles_on(first_col(narrowD), D - 512 * ds, narrowD);
+    mm_pass(oacc, narrowD, nd_on, nk2, &pfr[0][0]);
 #pragma unroll
     for (int j = 0; j < 2; ++j)
-      if (n0 + 32 * j < D) {
+      if (j < nd_on) {
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
           const int n = n0 + 32 * j + 8 * jj + 4 * g;
