@@ -433,6 +433,30 @@ def test_ffn_as_one_kernel_small(fb, name):
     assert err_v1 < tol_for(w, "ffn")
 
 
+@pytest.mark.parametrize("T,D,F,r1,r2,dt", [
+    (1, 64, 16, 16, 16, torch.float16),             # one token, one step of everything
+    (33, 64, 48, 32, 16, torch.bfloat16),           # a second, nearly empty token tile
+    (100, 192, 608, 96, 640, torch.float16),        # narrow first rank, two slabs (wide + narrow) of the second
+    (70, 128, 528, 784, 128, torch.bfloat16),       # the other way round; F ends inside a 512-wide chunk
+    (257, 320, 1040, 272, 1024, torch.float16),     # odd number of 16-row steps in a narrow block, maximum second rank
+])
+def test_ffn_as_one_kernel_edge_shapes(fb, T, D, F, r1, r2, dt):
+    """Shapes chosen around the kernel's block boundaries (32-token tiles, 256- and 512-column blocks, 16- and 32-row
+    steps), with different ranks for the two factors: every element against the oracle."""
+    g = torch.Generator().manual_seed(T * 1000 + r1 + r2)
+    rn = lambda *shape, scale=1.0: (torch.randn(*shape, generator=g) * scale).to(dt)
+    X = rn(1, T, D)
+    raw = {"w1": (rn(D, r1, scale=D ** -0.5), rn(r1, F, scale=r1 ** -0.5), rn(F, scale=0.02)),
+           "w2": (rn(F, r2, scale=F ** -0.5), rn(r2, D, scale=r2 ** -0.5), rn(D, scale=0.02))}
+    fac = {k: fb.Factor(*(t.to(DEV) for t in v)).with_tiled(True, True) for k, v in raw.items()}
+    ora = {k: dict(U=v[0].double().numpy(), V=v[1].double().numpy(), b=v[2].double().numpy()) for k, v in raw.items()}
+    d = fb.make_desc(1, T, D, D // 64, F, dt, torch.float32, norm="none")
+    got = fb.fsvd_ffn_v2(d, X.to(DEV), fac["w1"], fac["w2"]).cpu().numpy()
+    ref = O.ffn(X.double().numpy(), ora["w1"], ora["w2"])
+    assert np.isfinite(got).all()
+    assert rel_err(got, ref) < TOL["ffn"]
+
+
 def test_ffn_as_one_kernel_activations_and_types(fb):
     """Other activation functions, 16-bit output and missing biases."""
     w, inp, dev = workload("tiny_pad", fb, "tiled")
