@@ -321,6 +321,7 @@ DECODE_WORKLOADS = {w.name: w for w in [
     DecodeWorkload("decode_base_b32_t1024_r256", 32, 1024, 768, 12, 256, "fp16", 1, 1023, 7508),
     DecodeWorkload("decode_tiny_d64", 3, 80, 128, 2, 64, "fp16", 0, 79, 7509),
     DecodeWorkload("decode_tiny_d128", 5, 300, 512, 4, 128, "bf16", 0, 299, 7510),
+    DecodeWorkload("decode_tiny_b70", 70, 64, 128, 2, 64, "fp16", 0, 63, 7511),       # more than two sequence tiles
 ]}
 
 

@@ -109,7 +109,7 @@ def run_step(fb, dev):
                                     dev["lens"]).cpu().numpy()
 
 
-@pytest.mark.parametrize("name", ["decode_tiny_d64", "decode_tiny_d128", "decode_base_b32_t1024_r256"])
+@pytest.mark.parametrize("name", ["decode_tiny_d64", "decode_tiny_d128", "decode_tiny_b70", "decode_base_b32_t1024_r256"])
 def test_decode_step_every_element(fb, name):
     """Ragged cache lengths from an empty cache to a full one; every output element against the oracle."""
     inp = W.make_decode_inputs(W.DECODE_WORKLOADS[name])
