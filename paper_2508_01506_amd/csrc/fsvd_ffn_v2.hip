@@ -10,10 +10,12 @@
 // registers of the next.  The activations between two products stay in LDS as ready operand fragments
 // ([16-wide contraction step][token tile][lane] x 16 bytes): X is staged in slabs of 512 / MT columns, P1^T (later Z^T)
 // takes up to 64 KiB, the activated hidden chunk (512 / MT features) 32 KiB; what is left of the 160 KiB holds weight
-// steps.  All weights are prepacked tile images; one step of 16 contraction rows x 512 columns (16 KiB) at a time is
-// copied straight into LDS, NB buffers, NB - 1 steps ahead, as ONE request stream over the whole kernel (a cursor walks
-// the same loop nest as the consumers), so that the copies never drain between the products.  Within a 512-column slab
-// wavefront w owns columns 64 w .. 64 w + 63.
+// steps.  All weights are prepacked tile images, copied straight into LDS one step at a time (16 contraction rows x 512
+// columns, 16 KiB per workgroup) as ONE request stream over the whole kernel, NB - 1 steps ahead (a cursor walks the same
+// loop nest as the consumers), so that the copies never drain between the products.  Within a 512-column block
+// wavefront w owns columns 64 w .. 64 w + 63, and every wavefront requests, waits for and reads ITS OWN columns of a
+// step (2 KiB, in a private part of LDS): no workgroup barrier separates the steps, the wavefronts drift apart inside a
+// pass and meet only where the shared activation fragments change hands.
 //   step 1: P1^T = U_1^T X^T                         (sum over D in slabs; all slabs of r1 per X slab)
 //   step 2: per chunk of F: H^T = V_1^T P1^T + b_1, G = phi(H) -> LDS;  Z^T += U_2^T G^T  (Z^T stays in registers)
 //   step 3: out^T = V_2^T Z^T + b_2 per 512-column slab of D, written row-major.
@@ -27,7 +29,8 @@ namespace fsvd {
 namespace {
 
 constexpr int kV2Threads = 512;
-constexpr int kV2StepBytes = 16 * 512 * 2;     // one staged step: 4 tile images x 16 rows x 256 bytes
+constexpr int kV2StepBytes = 16 * 512 * 2;     // one staged step of the workgroup: 16 rows x 512 columns (or 32 x 256)
+constexpr int kV2WaveStepBytes = kV2StepBytes / 8;   // a wavefront's part of it
 
 // The request stream of the kernel below: which 16-row x 512-column step of which factor matrix is copied into LDS
 // next.  A pass is a run of consecutive 16-row steps of one matrix under one block of columns; the passes follow the
@@ -43,16 +46,16 @@ struct WeightStream {
   int ph, i0, i1;                              // pass cursor: product, outer index (X slab, chunk of F, slab of D), rank slab
   // the pass being requested
   u4 rs;                                       // its matrix
-  int soff[2];                                 // byte offsets of this wavefront's two 1 KiB pieces of the next step
-  unsigned ldst[2];                            // where they go inside a buffer
+  int soff;                                    // byte offset (in the matrix) of the tile-image rows of the next step
   int left;                                    // steps of the pass not yet requested
   int krow;                                    // 16-row position of the next step inside its 128-row tile
   int kinc, adv;                               // 16-row units and bytes per step: 1 and 4096 (wide), 2 and 8192 (narrow)
   int jump;                                    // added when the next step enters the next row of tiles
-  unsigned req_buf, lds_w0;                    // LDS address of the buffer of the next request; of buffer 0
+  unsigned req_buf, lds_w0;                    // LDS address of this wavefront's buffer of the next request; of its buffer 0
   int buf;                                     // buffer of the step being consumed
-  int wave, voff;
-  int pvoff[2];                                // per-lane offset of each piece: voff, or out of range for tile images right of the matrix
+  int wave;
+  int voff_wide, voff_narrow;                  // this lane's source offset inside a group of 8 (wide) or 16 (narrow) image rows
+  int pvoff;                                   // the one in use, or out of range when the wavefront's tile image lies right of the matrix
 
   __device__ __forceinline__ int steps_in(int total, int part) const {   // 16-row steps of part `part` (FC wide) of an axis
     const int k = (total - FC * part + 15) / 16;
@@ -79,16 +82,11 @@ struct WeightStream {
     adv = narrow ? 8192 : 4096;
     krow = 0;                                          // every pass starts on a tile boundary (k0 is a multiple of 128)
     jump = ph < 4 ? (ntn - 1) * kTileImageBytes : -8 * 4096;   // past the end: the same tile again and again
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int q = wave + 8 * i;                      // piece: 4 rows of one tile image
-      const int img = narrow ? q >> 3 : q >> 2, part = narrow ? q & 7 : q & 3;
-      int nt = (n0 >> 7) + img;
-      pvoff[i] = nt < ntn ? voff : kOobOffset;         // images right of the matrix: nothing is read, the piece is filled with zeros
-      nt = nt < ntn ? nt : ntn - 1;
-      soff[i] = __builtin_amdgcn_readfirstlane(((k0 >> 7) * ntn + nt) * kTileImageBytes + 4 * part * 256);
-      ldst[i] = __builtin_amdgcn_readfirstlane(img * (narrow ? 8192 : 4096) + part * 1024);
-    }
+    // this wavefront's columns: tile image (n0 / 128 + w / 2) wide, (n0 / 128 + w / 4) narrow
+    int nt = (n0 >> 7) + (narrow ? wave >> 2 : wave >> 1);
+    pvoff = nt < ntn ? (narrow ? voff_narrow : voff_wide) : kOobOffset;   // right of the matrix: nothing is read, zeros arrive
+    nt = nt < ntn ? nt : ntn - 1;
+    soff = __builtin_amdgcn_readfirstlane(((k0 >> 7) * ntn + nt) * kTileImageBytes);
     left = __builtin_amdgcn_readfirstlane(left);
     jump = __builtin_amdgcn_readfirstlane(jump);
     kinc = __builtin_amdgcn_readfirstlane(kinc);
@@ -107,7 +105,7 @@ struct WeightStream {
     ph = __builtin_amdgcn_readfirstlane(ph); i0 = __builtin_amdgcn_readfirstlane(i0); i1 = __builtin_amdgcn_readfirstlane(i1);
     load_pass();
   }
-  __device__ __forceinline__ void init(const FfnV2Args& a, int wave_, int lane, unsigned lds_w0_) {
+  __device__ __forceinline__ void init(const FfnV2Args& a, int wave_, int vw, int vn, unsigned lds_w0_) {
     D = a.D; F = a.F; r1 = a.r1; r2 = a.r2;
     rs_u1 = lds_dma_rsrc(a.U1, (unsigned)tiled_bytes(a.D, a.r1));
     rs_v1 = lds_dma_rsrc(a.V1, (unsigned)tiled_bytes(a.r1, a.F));
@@ -118,31 +116,32 @@ struct WeightStream {
     nch = (a.F + FC - 1) / FC; nsl2 = (a.r2 + 511) / 512; nk2 = (a.r2 + 15) / 16;
     nds = (a.D + 511) / 512;
     ph = i0 = i1 = 0; buf = 0;
-    wave = wave_; voff = lane * 16; lds_w0 = lds_w0_; req_buf = lds_w0_;
+    wave = wave_; voff_wide = vw; voff_narrow = vn; lds_w0 = lds_w0_; req_buf = lds_w0_;
     load_pass();
   }
-  // request the next step of the stream into the next buffer
+  // request the next step of the stream (this wavefront's 2 KiB of it) into the next buffer: two loads of 1 KiB, the
+  // first and the second half of the step's rows
   __device__ __forceinline__ void request() {
-    lds_dma16(rs, req_buf + ldst[0], pvoff[0], soff[0]);
-    lds_dma16(rs, req_buf + ldst[1], pvoff[1], soff[1]);
-    req_buf = req_buf + kV2StepBytes == lds_w0 + NB * kV2StepBytes ? lds_w0 : req_buf + kV2StepBytes;
-    soff[0] += adv; soff[1] += adv;
+    lds_dma16(rs, req_buf, pvoff, soff);
+    lds_dma16(rs, req_buf + 1024, pvoff, soff + (adv >> 1));
+    req_buf = req_buf + kV2WaveStepBytes == lds_w0 + NB * kV2WaveStepBytes ? lds_w0 : req_buf + kV2WaveStepBytes;
+    soff += adv;
     krow += kinc;
-    if (krow == 8) { krow = 0; soff[0] += jump; soff[1] += jump; }
+    if (krow == 8) { krow = 0; soff += jump; }
     if (--left == 0) next_pass();
   }
-  __device__ __forceinline__ void start() {      // the first NB - 1 steps; returns with step 0 in LDS
+  __device__ __forceinline__ void start() {      // the first NB - 1 steps
 #pragma unroll
     for (int b = 0; b < NB - 1; ++b) request();
-    lds_dma_wait_barrier<2 * (NB - 2)>();
   }
-  // the request issued while step s is consumed is step s + NB - 1, into the buffer read during step s - 1 (free since its barrier)
-  __device__ __forceinline__ void begin_step() { request(); }
-  // Ends step s: all but the newest NB - 2 requests (two loads each) have landed, so step s + 1 is in LDS after the barrier.
-  __device__ __forceinline__ void end_step() {
-    lds_dma_wait_barrier<2 * (NB - 2)>();
-    buf = buf == NB - 1 ? 0 : buf + 1;
+  // Begins step s: requests step s + NB - 1 into the buffer this wavefront read during step s - 1 (those reads were
+  // issued long before the new data can arrive), then waits until all but the newest NB - 1 requests (two loads each)
+  // have landed: step s is in LDS.  Nobody else reads or writes this wavefront's buffers, so there is no barrier.
+  __device__ __forceinline__ void begin_step() {
+    request();
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * (NB - 1)) : "memory");
   }
+  __device__ __forceinline__ void end_step() { buf = buf == NB - 1 ? 0 : buf + 1; }
 };
 
 template <int MT, int NB>
@@ -154,7 +153,7 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
   constexpr int NSL = 2 / MT;                  // 512-column slabs of the ranks
   __shared__ __attribute__((aligned(16))) h8 pfr[PK][64];                  // P1^T, later Z^T: [step * MT + tile][lane]
   __shared__ __attribute__((aligned(16))) h8 gfr[32][64];                  // X slab, later the activated chunk
-  __shared__ __attribute__((aligned(16))) _Float16 wbuf[NB][4][16][128];    // [buffer][tile image][row][column]
+  __shared__ __attribute__((aligned(16))) _Float16 wbuf[8][NB][kV2WaveStepBytes / 2];   // [wavefront][buffer][its part of a step]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, l32 = lane & 31, g = lane >> 5;
@@ -162,24 +161,39 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
   const int T = a.T, D = a.D, F = a.F, r1 = a.r1, r2 = a.r2;
   const int tok0 = blockIdx.x * 32 * MT;
 
+  // Where a lane's 16 bytes of a request come from (the 16-byte slot l of the 1 KiB that one load writes is LDS offset
+  // 16 l).  A wavefront's part of a step is kept in blocks of 4 rows; inside a block the 64-byte segments (one row of one
+  // 32-column tile) are ordered tile-major, row-minor, so that the four rows a transposing read touches lie in four
+  // different groups of banks.  In the tile image, row k holds its 32-column segments permuted by k % 4.
+  //   wide (8 rows x 128 bytes per load):  slot -> block l / 32, tile j = (l % 32) / 16, row (l % 16) / 4, piece l % 4
+  //   narrow (16 rows x 64 bytes per load): slot -> block l / 16, row (l % 16) / 4, piece l % 4
+  int vw, vn;
+  {
+    const int blk = lane >> 5, j = (lane >> 4) & 1, row = (lane >> 2) & 3, piece = lane & 3;
+    vw = (4 * blk + row) * 256 + (((2 * (wave & 1) + j) ^ row) * 64) + piece * 16;
+    const int blkn = lane >> 4;
+    vn = (4 * blkn + row) * 256 + (((wave & 3) ^ row) * 64) + piece * 16;
+  }
   WeightStream<MT, NB> ws;
-  ws.init(a, wave, lane, lds_addr_of(&wbuf[0][0][0][0]));
+  ws.init(a, wave, vw, vn, lds_addr_of(&wbuf[wave][0][0]));
   const int nxs = ws.nxs, nsl1 = ws.nsl1, nk1 = ws.nk1, nch = ws.nch, nsl2 = ws.nsl2, nk2 = ws.nk2, nds = ws.nds;
   auto steps_in = [&](int total, int part) __attribute__((always_inline)) { return ws.steps_in(total, part); };
   auto begin_step = [&]() __attribute__((always_inline)) { ws.begin_step(); };
   auto end_step = [&]() __attribute__((always_inline)) { ws.end_step(); };
-  // transposing-read offsets of this lane (halves inside one staged step): rows 4 g .. + 3 and 8 + 4 g .. + 3 of the step, which
-  // is the order in which an accumulator tile, rounded to fp16, supplies the contraction slots of the next product
-  int troff[2], troffN;                        // wide steps: column tiles 64 w + 32 j; narrow steps: column tile 32 w
+  // transposing-read offsets of this lane (halves inside this wavefront's part of a step).  A lane reads rows
+  // 4 g .. 4 g + 3 and 8 + 4 g .. + 3 of a 16-row contraction step: the order in which an accumulator tile, rounded to
+  // fp16, supplies the contraction slots of the next product.  Wide: 4-row blocks of 256 halves, tile j at + 128 j;
+  // narrow: 4-row blocks of 128 halves.
+  const int trl = ((lane & 15) >> 2) * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  int troff[2], troffN;
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int col = 64 * wave + 32 * j;
-    troff[j] = (col >> 7) * (16 * 128) + tr_lane_off_swz(lane, (col & 127) >> 5) + 4 * g * 128;
-  }
-  troffN = (wave >> 2) * (32 * 128) + tr_lane_off_swz(lane, wave & 3) + 4 * g * 128;
-  auto wfrag = [&](int bufi, int off) __attribute__((always_inline)) {
-    const _Float16* wt = &wbuf[0][0][0][0] + bufi * (kV2StepBytes / 2) + off;
-    return tr_frag(wt, wt + 8 * 128);
+  for (int j = 0; j < 2; ++j) troff[j] = trl + 128 * j + 256 * g;
+  troffN = trl + 128 * g;
+  // operand registers of one column tile for one 16-row contraction step: `off` = the lane's offset of rows 4 g .. + 3,
+  // `second` = distance to rows 8 + 4 g .. + 3 (two blocks further on)
+  auto wfrag = [&](int bufi, int off, int second) __attribute__((always_inline)) {
+    const _Float16* wt = &wbuf[wave][0][0] + bufi * (kV2WaveStepBytes / 2) + off;
+    return tr_frag(wt, wt + second);
   };
   // One pass over `k16` 16-row contraction steps of a block of columns `width` wide that starts at this wavefront's
   // first column tile `first` of a matrix `n` columns wide: acc[j][mt] += (column tile)^T . act.  Wide blocks: two tiles
@@ -201,7 +215,7 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
           const int kk = two ? 2 * ks + u : 2 * ks;
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) af[u][mt] = act[(kk * MT + mt) * 64 + lane];
-          b[u] = wfrag(ws.buf, troffN + u * 16 * 128);
+          b[u] = wfrag(ws.buf, troffN + u * 4 * 128, 2 * 128);
         }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[0][mt] = mfma32(b[0], af[0][mt], acc[0][mt]);
@@ -219,7 +233,7 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) af[mt] = act[(ks * MT + mt) * 64 + lane];
 #pragma unroll
-      for (int j = 0; j < 2; ++j) b[j] = wfrag(ws.buf, troff[j]);       // (a wavefront with one tile inside the matrix reads both)
+      for (int j = 0; j < 2; ++j) b[j] = wfrag(ws.buf, troff[j], 2 * 256);   // (a wavefront with one tile inside the matrix reads both)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
         if (j < n_on) {
@@ -297,6 +311,7 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
 #pragma unroll
     for (int sl = 0; sl < NSL; ++sl)
       if (sl < nsl1) rank_pass(zacc[sl], sl, kc, r1, &gfr[0][0]);
+    __syncthreads();                             // every wavefront is done with this X slab
   }
   publish_z(r1);
   clear_z();
@@ -318,7 +333,8 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
 #pragma unroll
     for (int j = 0; j < NTA; ++j) onf[j] = j < nf_on;
     mm_pass(hacc, narrowA, nf_on, nk1, &pfr[0][0]);
-    // + b_1, activation, fp16 -> operand fragments of the second product (the last barrier has retired every read of gfr)
+    // + b_1, activation, fp16 -> operand fragments of the second product, once no wavefront reads the previous chunk's any more
+    __syncthreads();
 #pragma unroll
     for (int j = 0; j < NTA; ++j)
       if (onf[j]) {
