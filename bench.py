@@ -29,8 +29,8 @@ PEAK_HBM_GBS = 8000.0
 # a copy of known size gives; summary in profiles/hbm_traffic_cores_<workload>.md).  Counters cannot be read from inside
 # this process, so the figure is the one of the committed profile; workloads without one report null.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg5_llm_b1_m4096_causal", "ffn_core_kernel"): int((496.5 * 2.0 + 64.0) * 2 ** 20),
-    ("cfg5_llm_b1_m4096_causal", "attn_core_kernel"): int((345.9 * 2.0 + 32.0) * 2 ** 20),
+    ("cfg5_llm_b1_m4096_causal", "ffn_core_kernel"): int((1282.5 * 2.0 + 64.0) * 2 ** 20),
+    ("cfg5_llm_b1_m4096_causal", "attn_core_kernel"): int((357.2 * 2.0 + 32.0) * 2 ** 20),
 }
 DEFAULT_WORKLOAD = "cfg5_llm_b1_m4096_causal"   # the largest configuration: the one the MFMA-peak target is stated on
 

@@ -260,14 +260,6 @@ __device__ __forceinline__ void lds_dma16(u4 rsrc, unsigned lds_addr, int voff, 
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "m0");
 }
-// The same load with the non-temporal cache hint: the line is the first candidate for eviction from the L2.  For data
-// that is streamed once per workgroup next to data that the workgroup re-reads all the time.
-__device__ __forceinline__ void lds_dma16_stream(u4 rsrc, unsigned lds_addr, int voff, int soff) {
-  lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
-  soff = __builtin_amdgcn_readfirstlane(soff);
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen nt lds"
-               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "m0");
-}
 #pragma clang diagnostic pop
 // wait until at most N of this wavefront's vector-memory operations are outstanding and all its LDS operations are
 // done, then the workgroup barrier

@@ -165,7 +165,7 @@ __global__ void __launch_bounds__(512, 1) ffn_core_kernel(FfnCoreArgs a, int nsl
         const u4 r = lds_dma_rsrc((const void*)(base + (unsigned long long)tile * kTileImageBytes), kTileImageBytes);
         const unsigned dst = lds_w0 + buf * kTileImageBytes + wave * 1024;
 #pragma unroll
-        for (int p = 0; p < 8; ++p) lds_dma16_stream(r, dst + p * 4096, voff, (4 * p + wave) * 1024);
+        for (int p = 0; p < 8; ++p) lds_dma16(r, dst + p * 4096, voff, (4 * p + wave) * 1024);
       };
       const int ptiles = (T + 31) / 32;
       const u4 rP = lds_dma_rsrc(uniform_ptr(a.P1), (unsigned)fm_bytes(T, r1));
