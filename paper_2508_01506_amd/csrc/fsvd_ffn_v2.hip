@@ -138,6 +138,7 @@ struct WeightStream {
   // issued long before the new data can arrive), then waits until all but the newest NB - 1 requests (two loads each)
   // have landed: step s is in LDS.  Nobody else reads or writes this wavefront's buffers, so there is no barrier.
   __device__ __forceinline__ void begin_step() {
+    asm volatile("" ::: "memory");               // the previous step's LDS reads stay ahead of the request in program order
     request();
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * (NB - 1)) : "memory");
   }
