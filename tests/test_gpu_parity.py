@@ -599,6 +599,43 @@ def test_run_to_run_determinism(fb):
         assert torch.equal(gpu_call(dev, part), gpu_call(dev, part))
 
 
+def test_layer_and_one_kernel_ffn_replay_from_a_captured_graph(fb):
+    """The library only launches kernels on the caller's stream (no allocation, no memset, no host synchronisation), so a
+    caller may capture a call in a graph: replays with new input values, with eager work in between, equal the eager
+    results bit for bit."""
+    w, inp, dev = workload("tiny_pad", fb, "tiled")
+    d = dev["desc"]
+    args = (dev["q"], dev["k"], dev["v"], dev["o"], dev["ln1_gamma"], dev["ln1_beta"], dev["w1"], dev["w2"],
+            dev["ln2_gamma"], dev["ln2_beta"])
+    need = fb.fsvd_layer_workspace(d, w.r_attn, w.r_attn, w.r_attn, w.r_attn, w.r_ffn, w.r_ffn)
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    X = dev["X"].clone()
+    out = torch.empty((w.B, w.M, w.D), dtype=torch.float32, device=DEV)
+    out2 = torch.empty_like(out)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up outside the capture, as torch asks
+        fb.fsvd_layer(d, X, *args, out=out, workspace=ws)
+        fb.fsvd_ffn_v2(d, X, dev["w1"], dev["w2"], out=out2)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fb.fsvd_layer(d, X, *args, out=out, workspace=ws)
+        fb.fsvd_ffn_v2(d, X, dev["w1"], dev["w2"], out=out2)
+    gen = torch.Generator(device=DEV).manual_seed(7)
+    for rep in range(3):
+        X.copy_(torch.randn(X.shape, generator=gen, device=DEV).to(X.dtype))
+        graph.replay()
+        torch.cuda.synchronize()
+        got, got2 = out.clone(), out2.clone()
+        eager = fb.fsvd_layer(d, X, *args)             # eager work between the replays (own workspace and output)
+        eager2 = fb.fsvd_ffn_v2(d, X, dev["w1"], dev["w2"])
+        torch.cuda.synchronize()
+        assert torch.equal(got, eager), rep
+        assert torch.equal(got2, eager2), rep
+
+
 def test_rank_padding_invariance(fb):
     """Zero-padding every rank to a larger multiple of 16 leaves the result bitwise unchanged."""
     w = W.get_workload("tiny_h2_d64")
