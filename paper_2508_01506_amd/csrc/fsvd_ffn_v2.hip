@@ -181,17 +181,15 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
   auto steps_in = [&](int total, int part) __attribute__((always_inline)) { return ws.steps_in(total, part); };
   auto begin_step = [&]() __attribute__((always_inline)) { ws.begin_step(); };
   auto end_step = [&]() __attribute__((always_inline)) { ws.end_step(); };
-  // transposing-read offsets of this lane (halves inside this wavefront's part of a step).  A lane reads rows
-  // 4 g .. 4 g + 3 and 8 + 4 g .. + 3 of a 16-row contraction step: the order in which an accumulator tile, rounded to
-  // fp16, supplies the contraction slots of the next product.  Wide: 4-row blocks of 256 halves, tile j at + 128 j;
-  // narrow: 4-row blocks of 128 halves.
+  // Transposing-read offsets of this lane (halves inside this wavefront's part of a step).  Wide steps are kept in 4-row
+  // blocks of 256 halves (tile j at + 128 j), narrow steps in 4-row blocks of 128 halves.  Which rows a lane reads
+  // depends on where the activation operand comes from:
+  //   accumulator order (every product but the first): rows 4 g .. + 3 and 8 + 4 g .. + 3 of a 16-row contraction step, the
+  //     order in which an accumulator tile, rounded to fp16, supplies the contraction slots of the next product;
+  //   plain order (the first product, whose X operand is staged from row-major memory): rows 8 g .. + 3 and 8 g + 4 .. + 3.
   const int trl = ((lane & 15) >> 2) * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  int troff[2], troffN;
-#pragma unroll
-  for (int j = 0; j < 2; ++j) troff[j] = trl + 128 * j + 256 * g;
-  troffN = trl + 128 * g;
-  // operand registers of one column tile for one 16-row contraction step: `off` = the lane's offset of rows 4 g .. + 3,
-  // `second` = distance to rows 8 + 4 g .. + 3 (two blocks further on)
+  // operand registers of one column tile for one 16-row contraction step: `off` = the lane's offset of its first four
+  // rows, `second` = distance to its other four
   auto wfrag = [&](int bufi, int off, int second) __attribute__((always_inline)) {
     const _Float16* wt = &wbuf[wave][0][0] + bufi * (kV2WaveStepBytes / 2) + off;
     return tr_frag(wt, wt + second);
@@ -200,13 +198,15 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
   // first column tile `first` of a matrix `n` columns wide: acc[j][mt] += (column tile)^T . act.  Wide blocks: two tiles
   // per wavefront (j = 0, 1), one contraction step per staged step; narrow blocks (see WeightStream): tile j = 0 only,
   // two contraction steps per staged step.
-  auto mm_pass = [&](auto& acc, bool narrow, int n_on, int k16, const h8* act) __attribute__((always_inline)) {
+  auto mm_pass = [&](auto& acc, auto plain_c, bool narrow, int n_on, int k16, const h8* act) __attribute__((always_inline)) {
+    constexpr bool PLAIN = decltype(plain_c)::value;
     const int nsteps = ws.pass_steps(k16, narrow);
     if (n_on == 0) {                                   // no tile of this wavefront inside the matrix: requests and barriers only
       for (int ks = 0; ks < nsteps; ++ks) { begin_step(); end_step(); }
       return;
     }
     if (narrow) {
+      const int off = trl + (PLAIN ? 256 : 128) * g, second = PLAIN ? 128 : 256;
       for (int ks = 0; ks < nsteps; ++ks) {
         begin_step();
         const bool two = 2 * ks + 1 < k16;             // an odd number of contraction steps: the last staged step holds one
@@ -216,7 +216,7 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
           const int kk = two ? 2 * ks + u : 2 * ks;
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) af[u][mt] = act[(kk * MT + mt) * 64 + lane];
-          b[u] = wfrag(ws.buf, troffN + u * 4 * 128, 2 * 128);
+          b[u] = wfrag(ws.buf, off + u * 4 * 128, second);
         }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[0][mt] = mfma32(b[0], af[0][mt], acc[0][mt]);
@@ -228,13 +228,14 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
       }
       return;
     }
+    const int off = trl + (PLAIN ? 512 : 256) * g, second = PLAIN ? 256 : 512;
     for (int ks = 0; ks < nsteps; ++ks) {
       begin_step();
       h8 b[2], af[MT];
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) af[mt] = act[(ks * MT + mt) * 64 + lane];
 #pragma unroll
-      for (int j = 0; j < 2; ++j) b[j] = wfrag(ws.buf, troff[j], 2 * 256);   // (a wavefront with one tile inside the matrix reads both)
+      for (int j = 0; j < 2; ++j) b[j] = wfrag(ws.buf, off + 128 * j, second);   // (a wavefront with one tile inside the matrix reads both)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
         if (j < n_on) {
@@ -283,10 +284,12 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
     }
   };
   // one slab of a rank-space product: z += W^T[512 sl .., steps] . act
-  auto rank_pass = [&](f16v (&z)[2][MT], int sl, int k16, int n, const h8* act) __attribute__((always_inline)) {
+  auto rank_pass = [&](f16v (&z)[2][MT], auto plain_c, int sl, int k16, int n, const h8* act) __attribute__((always_inline)) {
     const bool narrow = ws.is_narrow(n - 512 * sl);
-    mm_pass(z, narrow, tiles_on(first_col(narrow), n - 512 * sl, narrow), k16, act);
+    mm_pass(z, plain_c, narrow, tiles_on(first_col(narrow), n - 512 * sl, narrow), k16, act);
   };
+  typedef std::true_type plain_order;
+  typedef std::false_type acc_order;
 
   ws.start();
 
@@ -294,24 +297,26 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
   clear_z();
   for (int xs = 0; xs < nxs; ++xs) {
     const int kc = steps_in(D, xs);
-    // X slab -> operand fragments: lane (token, g) of step ks holds columns 16 ks + 4 g + {0..3} and + 8 of its token
-    for (int ks = wave; ks < kc; ks += 8) {
+    // X slab -> operand fragments in the plain order: lane (token, g) of step s holds columns 16 s + 8 g .. + 7 of its
+    // token.  The slab is 32 MT rows x FC columns; a wavefront copies blocks of 8 rows x 64 columns (128 contiguous
+    // bytes per row), 16 bytes per lane, four blocks each.
+    {
+      constexpr int CB = FC / 64;                      // 64-column blocks per row of the slab
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const int tok = tok0 + 32 * mt + l32;
-        const size_t e = (size_t)tok * D + FC * xs + 16 * ks + 4 * g;
-        f4v lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
-        if (tok < T) { lo = load4(a.X, e, a.x_dt); hi = load4(a.X, e + 8, a.x_dt); }
-        h8 o;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { o[i] = (_Float16)lo[i]; o[4 + i] = (_Float16)hi[i]; }
-        gfr[ks * MT + mt][lane] = o;
+      for (int i = 0; i < 4; ++i) {
+        const int blk = wave + 8 * i;                  // 32 blocks: (row group, column block)
+        const int row = 8 * (blk / CB) + (lane & 7), pc = 8 * (blk % CB) + (lane >> 3);   // pc: 16-byte piece of the slab row
+        const int tok = tok0 + row, col = FC * xs + 8 * pc;
+        u4 raw = {0u, 0u, 0u, 0u};
+        if (tok < T && col < D) raw = *(const u4*)((const uint16_t*)a.X + (size_t)tok * D + col);
+        const h8 v = a.x_dt == DT_BF16 ? raw_to_h8<DT_BF16>(raw) : raw_to_h8<DT_F16>(raw);
+        gfr[(pc >> 1) * MT + (row >> 5)][(row & 31) + 32 * (pc & 1)] = v;
       }
     }
     __syncthreads();
 #pragma unroll
     for (int sl = 0; sl < NSL; ++sl)
-      if (sl < nsl1) rank_pass(zacc[sl], sl, kc, r1, &gfr[0][0]);
+      if (sl < nsl1) rank_pass(zacc[sl], plain_order{}, sl, kc, r1, &gfr[0][0]);
     __syncthreads();                             // every wavefront is done with this X slab
   }
   publish_z(r1);
@@ -333,7 +338,7 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
     bool onf[NTA];
 #pragma unroll
     for (int j = 0; j < NTA; ++j) onf[j] = j < nf_on;
-    mm_pass(hacc, narrowA, nf_on, nk1, &pfr[0][0]);
+    mm_pass(hacc, acc_order{}, narrowA, nf_on, nk1, &pfr[0][0]);
     // + b_1, activation, fp16 -> operand fragments of the second product, once no wavefront reads the previous chunk's any more
     __syncthreads();
 #pragma unroll
@@ -363,7 +368,7 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
     const int kc = steps_in(F, ch);
 #pragma unroll
     for (int sl = 0; sl < NSL; ++sl)
-      if (sl < nsl2) rank_pass(zacc[sl], sl, kc, r2, &gfr[0][0]);
+      if (sl < nsl2) rank_pass(zacc[sl], acc_order{}, sl, kc, r2, &gfr[0][0]);
   }
 
   // ================= step 3: out^T = V_2^T Z^T + b_2 =================
@@ -378,21 +383,32 @@ __global__ void __launch_bounds__(kV2Threads, 1) ffn_v2_kernel(FfnV2Args a) {
     const bool narrowD = ws.is_narrow(D - 512 * ds);
     const int n0 = 512 * ds + first_col(narrowD);
     const int nd_on = tiles_on(first_col(narrowD), D - 512 * ds, narrowD);
-    mm_pass(oacc, narrowD, nd_on, nk2, &pfr[0][0]);
+    mm_pass(oacc, acc_order{}, narrowD, nd_on, nk2, &pfr[0][0]);
+    // + b_2, then row-major stores.  The accumulators have lane = token; each 32 x 32 block goes through a
+    // wavefront-private fp32 patch in the (now idle) activation area so that a store instruction covers 128-byte row
+    // segments.  Element (token t, column c) of the patch sits at 32 t + (c ^ 4 (t % 8)): both the 16-byte writes
+    // (lane = token) and the 16-byte reads (lane = row part) then use every bank equally.
+    float* const patch = (float*)&gfr[4 * wave][0];
 #pragma unroll
     for (int j = 0; j < 2; ++j)
       if (j < nd_on) {
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-          const int n = n0 + 32 * j + 8 * jj + 4 * g;
-          const f4v b = a.b2 ? load4(a.b2, n, a.w_dt) : f4v{0.f, 0.f, 0.f, 0.f};
+        for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
-            const int tok = tok0 + 32 * mt + l32;
+          for (int jj = 0; jj < 4; ++jj) {
+            const int c = 8 * jj + 4 * g;
+            const f4v b = a.b2 ? load4(a.b2, n0 + 32 * j + c, a.w_dt) : f4v{0.f, 0.f, 0.f, 0.f};
             f4v y;
 #pragma unroll
             for (int e = 0; e < 4; ++e) y[e] = oacc[j][mt][4 * jj + e] + b[e];
-            if (tok < T) store4(a.out, (size_t)tok * D + n, y, a.out_dt);
+            *(f4v*)&patch[32 * l32 + (c ^ (4 * (l32 & 7)))] = y;
+          }
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int r = (lane >> 3) + 8 * i, c = 4 * (lane & 7);
+            const f4v y = *(const f4v*)&patch[32 * r + (c ^ (4 * (r & 7)))];
+            const int tok = tok0 + 32 * mt + r;
+            if (tok < T) store4(a.out, (size_t)tok * D + n0 + 32 * j + c, y, a.out_dt);
           }
         }
       }
