@@ -294,8 +294,9 @@ hipError_t launch_bn(const LinearArgs& a, hipStream_t s) {
   const int tiles_m = (a.T + 255) / 256;
   int n128 = 0, n64 = 0;
   for (int i = 0; i < a.ngroups; ++i) { n128 += (a.g[i].N + 127) / 128; n64 += (a.g[i].N + 63) / 64; }
-  // narrow tiles when the wide ones would leave compute units idle
-  const bool narrow = (long)tiles_m * n128 < 320;
+  // narrow tiles when the wide ones would leave compute units idle or unevenly loaded (two wide or four narrow
+  // workgroups fit on a compute unit)
+  const bool narrow = (long)tiles_m * n128 < 512;
   // one tile row and room for partial sums: split the contraction so that about one workgroup per compute unit runs
   int ksplit = 1;
   if (!CFM && a.part && tiles_m == 1 && a.ldp > 0) {
