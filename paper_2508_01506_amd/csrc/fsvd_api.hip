@@ -141,7 +141,7 @@ struct LnFuse {
 // LayerNorm kernel (one more round trip of [T, D] through HBM) while that matrix is small and the tokens fill the chip.
 bool ln_fusable(const fsvd_desc* d, const fsvd_factor* last) {
   return last->v_layout == FSVD_TILED && linear_ln_supported(d->D) && d->B * d->M >= 2048 &&
-         (long long)last->rank * d->D <= 320 * 1024;
+         (long long)last->rank * d->D <= 768 * 1024 && linear_ln_fits((long long)d->B * d->M, d->D);
 }
 
 float resolve_scale(const fsvd_desc* d) {

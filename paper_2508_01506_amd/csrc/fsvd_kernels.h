@@ -56,6 +56,7 @@ struct LinearLnArgs {
   void* Yfm;                           // fragment-major fp16 output or nullptr
 };
 bool linear_ln_supported(int D);
+bool linear_ln_fits(long long T, int D);   // [T, D] small enough for the kernel's 32-bit offsets
 hipError_t launch_linear_ln(const LinearLnArgs& a, hipStream_t s);
 
 // ---- streaming attention core (Alg. 1 Part II): FM P_q, P_k, P_v -> FM context C [T, D]

@@ -109,6 +109,12 @@ _register(_wl(7, 6, name="fuse_d1024", B=1, M=2100, D=1024, H=8, F=512, r_attn=6
 _register(_wl(7, 7, name="fuse_d256_causal", B=3, M=700, D=256, H=4, F=512, r_attn=48, r_ffn=80, dtype="fp16",
               mask="causal"))
 _register(_wl(7, 8, name="fuse_d768", B=2, M=1040, D=768, H=12, F=384, r_attn=96, r_ffn=64, dtype="bf16"))
+# 16468 tokens = 514 full 32-token tiles and 20 rows: the one-kernel hand-off then runs 64 tokens per workgroup, the last
+# workgroup holding a partial tile and a tile that does not exist.
+_register(_wl(7, 14, name="fuse_wide_d256", B=4, M=4117, D=256, H=4, F=256, r_attn=48, r_ffn=64, dtype="fp16"))
+_register(_wl(7, 15, name="fuse_wide_d512", B=2, M=8234, D=512, H=8, F=256, r_attn=64, r_ffn=96, dtype="bf16"))
+_register(_wl(7, 16, name="fuse_wide_d1024", B=4, M=4117, D=1024, H=8, F=512, r_attn=64, r_ffn=80, dtype="bf16",
+              mask="causal"))
 
 # Shapes for the one-kernel FFN (FlashSVDFFN V2): ranks above 512 (two slabs of ranks), widths above 512 (two slabs of
 # X and of the output), F that is not a multiple of the 128-, 256- or 512-wide units, ragged token counts, and enough

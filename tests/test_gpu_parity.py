@@ -378,6 +378,20 @@ def test_post_ln_layer_with_projection_and_layernorm_fused(fb, name):
     assert rel_err(fused, plain) < TOL_LAYER
 
 
+@pytest.mark.parametrize("name", ["fuse_wide_d256", "fuse_wide_d512", "fuse_wide_d1024"])
+def test_fused_projection_and_layernorm_with_64_token_workgroups(fb, name):
+    """From 16384 tokens on the fused kernel takes 64 tokens per workgroup: 16468 tokens (an odd number of 32-token
+    tiles, the last one partial), sampled rows of the first and last sequence including the very last rows."""
+    w, inp, dev = workload(name, fb, "tiled")
+    assert w.B * w.M == 16468
+    got = gpu_call(dev, "layer").cpu().numpy()
+    assert np.isfinite(got).all()
+    for b in (0, w.B - 1):
+        rows = sample_rows(w, 12, seed=b)
+        ref = oracle_rows(inp, b, rows, "layer")
+        assert rel_err(got[b, rows], ref) < TOL_LAYER, (name, b)
+
+
 # ------------------------------------------------------------------ benchmark sizes, sampled rows
 FULL = ["cfg1_bert_base_b2_m128", "cfg2_bert_base_b16_m512_pad", "cfg2u_bert_base_b16_m512_pad_unit",
         "cfg3_bert_large_b32_m512_r128", "cfg3_bert_large_b32_m512_r256", "cfg3_bert_large_b32_m512_r512",
