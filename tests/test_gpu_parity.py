@@ -606,6 +606,20 @@ def test_sixteen_bit_outputs_round_the_fp32_result(fb, odt, eps):
     assert torch.equal(got, ref32.to(odt))
 
 
+@pytest.mark.parametrize("odt", [torch.float16, torch.bfloat16])
+@pytest.mark.parametrize("name", ["fuse_d768", "fuse_d256_causal"])
+def test_sixteen_bit_outputs_of_the_fused_projection_and_layernorm(fb, name, odt):
+    """The one-kernel hand-off (prepacked weights, at least 2048 tokens) writes the layer's 16-bit output itself: the
+    fp32 result of the same path, rounded to nearest."""
+    w, inp, dev = workload(name, fb, "tiled")
+    ref32 = gpu_call(dev, "layer")
+    d16 = fb.make_desc(w.B, w.M, w.D, w.H, w.F, dev["X"].dtype, out_dtype=odt, key_len=dev["key_len"], norm=w.norm,
+                       ln_eps=w.ln_eps, causal=(w.mask == "causal"))
+    got = gpu_call(dict(dev, desc=d16), "layer")
+    assert got.dtype == odt
+    assert torch.equal(got, ref32.to(odt))
+
+
 def test_run_to_run_determinism(fb):
     """No atomics anywhere: two runs are bitwise equal."""
     w, inp, dev = workload("small_multi_qblock", fb)
