@@ -138,9 +138,10 @@ struct LnFuse {
 };
 // The fused projection + residual + LayerNorm kernel gives every workgroup all D output columns of 32 or 64 tokens, so
 // each workgroup re-reads the whole [rank, D] matrix from the last-level cache: it wins over the GEMM followed by the
-// LayerNorm kernel (one more round trip of [T, D] through HBM) while that matrix is small and the tokens fill the chip.
+// LayerNorm kernel (one more round trip of [T, D] through HBM, one more launch) while that matrix is moderate; measured
+// from 256 tokens up and for rank x D up to 768 Ki.
 bool ln_fusable(const fsvd_desc* d, const fsvd_factor* last) {
-  return last->v_layout == FSVD_TILED && linear_ln_supported(d->D) && d->B * d->M >= 2048 &&
+  return last->v_layout == FSVD_TILED && linear_ln_supported(d->D) && d->B * d->M >= 256 &&
          (long long)last->rank * d->D <= 768 * 1024 && linear_ln_fits((long long)d->B * d->M, d->D);
 }
 

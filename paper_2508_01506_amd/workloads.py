@@ -101,7 +101,7 @@ _register(_wl(7, 4, name="small_causal_d64", B=1, M=700, D=256, H=4, F=1024, r_a
 
 
 # Widths 512 and 1024 at test size (the fused projection + LayerNorm kernel is specialised per D / 256).
-# Widths 256..1024 with at least 2048 ragged tokens and small rank-by-width products: the shapes for which the last
+# Widths 256..1024 with ragged token counts and small rank-by-width products: the shapes for which the last
 # projection of a block, the residual add and the LayerNorm run as one kernel (prepacked weights, post-LN).
 _register(_wl(7, 5, name="fuse_d512_pad", B=4, M=530, D=512, H=8, F=256, r_attn=80, r_ffn=96, dtype="bf16",
               mask="padding", min_len=40))

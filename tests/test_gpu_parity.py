@@ -362,10 +362,10 @@ def test_layer_gate_on_small_shapes_both_norms(fb, name, norm):
 
 @pytest.mark.parametrize("name", ["fuse_d256_causal", "fuse_d512_pad", "fuse_d768", "fuse_d1024", "cfg1_bert_base_b2_m128"])
 def test_post_ln_layer_with_projection_and_layernorm_fused(fb, name):
-    """Post-LN layers of width 256, 512, 768 or 1024 with at least 2048 tokens and a small rank-by-width product run the
+    """Post-LN layers of width 256, 512, 768 or 1024 with at least 256 tokens and a moderate rank-by-width product run the
     last projection of each block, the residual add and the LayerNorm as one kernel when the weights are prepacked:
     every element against the oracle, and the same layer with row-major weights (separate projection and LayerNorm
-    kernels) for comparison; ragged token counts.  The last case (256 tokens) stays on the separate kernels."""
+    kernels) for comparison; ragged token counts.  The last case has exactly 256 tokens."""
     w = W.get_workload(name, norm="post_ln")
     inp = W.make_inputs(w)
     ref = oracle_call(inp, "layer")
@@ -609,7 +609,7 @@ def test_sixteen_bit_outputs_round_the_fp32_result(fb, odt, eps):
 @pytest.mark.parametrize("odt", [torch.float16, torch.bfloat16])
 @pytest.mark.parametrize("name", ["fuse_d768", "fuse_d256_causal"])
 def test_sixteen_bit_outputs_of_the_fused_projection_and_layernorm(fb, name, odt):
-    """The one-kernel hand-off (prepacked weights, at least 2048 tokens) writes the layer's 16-bit output itself: the
+    """The one-kernel hand-off (prepacked weights, at least 256 tokens) writes the layer's 16-bit output itself: the
     fp32 result of the same path, rounded to nearest."""
     w, inp, dev = workload(name, fb, "tiled")
     ref32 = gpu_call(dev, "layer")
