@@ -64,6 +64,7 @@ def gelu_erf(x):
 
 
 def gelu_tanh(x):
+    """Tanh form of GELU, 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))) (the "arbitrary phi" of FlashSVDFFN V1)."""
     x = _f64(x)
     return 0.5 * x * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (x + 0.044715 * x ** 3)))
 
@@ -206,7 +207,7 @@ def attention_per_head(X, q, k, v, o, H, causal=False, key_len=None, scale=None)
     X = _f64(X)
     B, M, D = X.shape
     d_h = D // H
-    sc = (1.0 / np.sqrt(d_h)) if scale is None else float(scale)
+    sc = (1.0 / np.sqrt(d_h)) if (scale is None or scale == 0) else float(scale)   # 0 selects the default, as in attention()
     out = np.empty((B, M, D), dtype=F64)
 
     def project(x, fac, h):

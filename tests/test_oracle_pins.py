@@ -302,6 +302,23 @@ def test_grouped_head_factors_interpolate_between_whole_matrix_and_per_head(G):
     assert q["U"].size + q["V"].size == G * r * (D + D // G)
 
 
+def test_scale_convention_is_one_reading():
+    """scale None and scale 0 both select 1/sqrt(d_h), in the whole-matrix oracle, the per-head one and the decoding step
+    (the boundary's softmax_scale = 0 means "default"); any other value is taken as given."""
+    rng = np.random.default_rng(5)
+    B, M, D, H, r = 1, 6, 8, 2, 4
+    X = rng.standard_normal((B, M, D))
+    mk = lambda *shape: rng.standard_normal(shape) / 2
+    whole = {n: {"U": mk(D, r), "V": mk(r, D), "b": mk(D)} for n in "qkvo"}
+    heads = {n: {"U": mk(D, H * r), "V": mk(H, r, D // H), "b": mk(D)} for n in "qkv"}
+    explicit = 1.0 / math.sqrt(D // H)
+    for fn, f in ((O.attention, whole), (O.attention_per_head, dict(heads, o=whole["o"]))):
+        base = fn(X, f["q"], f["k"], f["v"], f["o"], H, True, None, explicit)
+        for sc in (None, 0, 0.0):
+            np.testing.assert_array_equal(fn(X, f["q"], f["k"], f["v"], f["o"], H, True, None, sc), base)
+        assert np.abs(fn(X, f["q"], f["k"], f["v"], f["o"], H, True, None, 0.05) - base).max() > 1e-3
+
+
 def test_softmax_rows():
     rng = np.random.default_rng(1)
     s = rng.standard_normal((5, 9)) * 4
@@ -324,7 +341,17 @@ def test_gelu_and_activations():
     # standard normal CDF values: Phi(1) = 0.841344746..., Phi(-2) = 0.0227501319...
     np.testing.assert_allclose(O.gelu_erf(1.0), 0.8413447460685429, rtol=1e-13)
     np.testing.assert_allclose(O.gelu_erf(-2.0), -2 * 0.022750131948179195, rtol=1e-12)
-    assert np.abs(O.gelu_tanh(xs) - O.gelu_erf(xs)).max() < 5e-3
+    # tanh form: hand-computed values (math.tanh, fp64) and torch's own implementation; a wrong cubic coefficient
+    # (0.044715) or a wrong sqrt(2/pi) moves these by 1e-4 .. 1e-2
+    hand = {0.5: 0.34571400982514394, -0.5: -0.15428599017485606, 1.0: 0.8411919906082768, 2.0: 1.954597694087775,
+            3.0: 2.996362607918227, -3.0: -0.0036373920817729943}
+    for x, y in hand.items():
+        np.testing.assert_allclose(O.gelu_tanh(x), y, rtol=1e-13)
+    np.testing.assert_allclose(O.gelu_tanh(xs), TF.gelu(torch.from_numpy(xs), approximate="tanh").numpy(), rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(O.activation(xs, "gelu_tanh"), O.gelu_tanh(xs), rtol=0, atol=0)
+    # the two forms differ by at most 4.8e-4 (near |x| = 2.6..3): a bound a wrong coefficient breaks
+    gap = np.abs(O.gelu_tanh(xs) - O.gelu_erf(xs)).max()
+    assert 3e-4 < gap < 5e-4, gap
     np.testing.assert_array_equal(O.activation(xs, "relu"), np.maximum(xs, 0))
 
 
@@ -396,13 +423,28 @@ def test_paper_parameter_counts():
 
 
 def test_transient_memory_closed_forms():
-    """3 B M r for streaming attention, 2 B M r for the FFN; unfused adds 3 B M D (+ B H M^2) and B M F."""
-    B, M, D, H, F, r = 16, 512, 768, 12, 3072, 384
-    assert O.attention_transient_scalars(B, M, D, H, r, True) == 3 * B * M * r
-    assert O.attention_transient_scalars(B, M, D, H, r, False) == 3 * B * M * r + 3 * B * M * D
-    assert O.attention_transient_scalars(B, M, D, H, r, False, True) == 3 * B * M * (r + D) + B * H * M * M
-    assert O.ffn_transient_scalars(B, M, F, r, True) == 2 * B * M * r
-    assert O.ffn_transient_scalars(B, M, F, r, False) == 2 * B * M * r + B * M * F
+    """Memory theorems (FlashSVDAttention: 3 B M r; FFN V1: 2 B M r; vanilla SVD adds 3 B M D (+ B H M^2) and B M F),
+    checked against numbers worked out by hand for two of the benchmark shapes, in stored scalars and in MiB of
+    16-bit elements.  The block totals add the context C [T, D] and T_o = C U_o [T, r], which both dataflows hold."""
+    MiB = 2 ** 20
+    # BERT-base, B 16, M 512 (T = 8192), D 768, H 12, F 3072, attention rank 384, FFN rank 768
+    assert O.attention_transient_scalars(16, 512, 768, 12, 384, True) == 9437184            # 3 * 8192 * 384
+    assert O.attention_transient_scalars(16, 512, 768, 12, 384, False) == 28311552          # + 3 * 8192 * 768
+    assert O.attention_transient_scalars(16, 512, 768, 12, 384, False, True) == 78643200    # + 16 * 12 * 512^2
+    assert O.ffn_transient_scalars(16, 512, 3072, 768, True) == 12582912                    # 2 * 8192 * 768
+    assert O.ffn_transient_scalars(16, 512, 3072, 768, False) == 37748736                   # + 8192 * 3072
+    ctx = 8192 * (768 + 384)
+    assert (O.attention_transient_scalars(16, 512, 768, 12, 384, True) + ctx) * 2 == 36 * MiB
+    assert (O.attention_transient_scalars(16, 512, 768, 12, 384, False) + ctx) * 2 == 72 * MiB
+    assert O.ffn_transient_scalars(16, 512, 3072, 768, False) * 2 == 72 * MiB
+    # decoder shape, B 1, M 4096, D 4096, H 32, F 16384, attention rank 1024, FFN rank 2048
+    assert O.attention_transient_scalars(1, 4096, 4096, 32, 1024, True) == 12582912
+    ctx = 4096 * (4096 + 1024)
+    assert (O.attention_transient_scalars(1, 4096, 4096, 32, 1024, True) + ctx) * 2 == 64 * MiB
+    assert (O.attention_transient_scalars(1, 4096, 4096, 32, 1024, False) + ctx) * 2 == 160 * MiB
+    assert (O.attention_transient_scalars(1, 4096, 4096, 32, 1024, False, True) + ctx) * 2 == 1184 * MiB
+    assert O.ffn_transient_scalars(1, 4096, 16384, 2048, True) * 2 == 32 * MiB
+    assert O.ffn_transient_scalars(1, 4096, 16384, 2048, False) * 2 == 160 * MiB
     for w in W.WORKLOADS.values():
         assert O.attention_transient_scalars(w.B, w.M, w.D, w.H, w.r_attn, True) < \
             O.attention_transient_scalars(w.B, w.M, w.D, w.H, w.r_attn, False)
