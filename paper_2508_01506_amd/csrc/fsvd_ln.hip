@@ -108,6 +108,12 @@ __global__ void __launch_bounds__(256) pack_fm_kernel(const void* src, int src_d
   const size_t blk = u >> 8;
   const int c = blk % kchunks, tile = blk / kchunks;
   const int t = tile * 32 + (lane & 31), k = 64 * c + 32 * (lane >> 5) + 8 * kk;
+  if (src_dt == DT_BF16) {   // the widening every kernel applies to bf16 operands (toward zero: saturates, never infinite)
+    u4 raw = {0u, 0u, 0u, 0u};
+    if (t < T && k < K) raw = *(const u4*)((const uint16_t*)src + (size_t)t * K + k);
+    *(h8*)(dst + u * 8) = raw_to_h8<DT_BF16>(raw);
+    return;
+  }
   float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (t < T && k < K) load8(src, (size_t)t * K + k, src_dt, x);
   store8(dst, u * 8, DT_F16, x);
