@@ -25,13 +25,40 @@ for p in (ROOT, os.path.join(ROOT, "tests")):
 
 PEAK_MFMA_TFLOPS = 2500.0   # MI355X dense fp16 / bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
-# HBM bytes per launch of the roofline kernel from hardware counters (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors
-# a copy of known size gives; summary in profiles/hbm_traffic_cores_<workload>.md).  Counters cannot be read from inside
-# this process, so the figure is the one of the committed profile; workloads without one report null.
-MEASURED_TRAFFIC_BYTES = {
-    ("cfg5_llm_b1_m4096_causal", "ffn_core_kernel"): int((1282.5 * 2.0 + 64.0) * 2 ** 20),
-    ("cfg5_llm_b1_m4096_causal", "attn_core_kernel"): int((357.2 * 2.0 + 32.0) * 2 ** 20),
-}
+# HBM bytes per launch of the roofline kernel come from hardware counters (two rocprofv3 --pmc runs: FETCH_SIZE, WRITE_SIZE,
+# each scaled by what the same counter reads for a copy of known size).  Counters cannot be read from inside this process,
+# so the figure is parsed from the committed summary profiles/hbm_traffic_cores_<workload>.md; workloads without one
+# report null.
+
+
+def traffic_from_profile(workload, kernel):
+    """(bytes per launch, source file) of `kernel` ("ffn_core" or "attn_core") from the committed counter summary, or
+    (None, None).  The summary's table rows read `| kernel | dispatches | FETCH_SIZE MiB | WRITE_SIZE MiB |` and its
+    `calibration:` line gives the two scale factors."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_cores_{workload}.md")
+    if not os.path.exists(path):
+        return None, None
+    text = open(path).read()
+    cal = re.search(r"calibration:\s*fetch_factor=([0-9.]+)\s+write_factor=([0-9.]+)", text)
+    if not cal:
+        return None, None
+    best = None
+    for line in text.splitlines():
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) == 4 and kernel in cells[0]:
+            try:
+                n, fetch, write = int(cells[1]), float(cells[2]), float(cells[3])
+            except ValueError:
+                continue
+            if best is None or n > best[0]:        # the row with the most dispatches: the shape the layer launches
+                best = (n, fetch, write)
+    if best is None:
+        return None, None
+    total = (best[1] * float(cal.group(1)) + best[2] * float(cal.group(2))) * 2 ** 20
+    return int(total), os.path.relpath(path, ROOT)
+
+
 DEFAULT_WORKLOAD = "cfg5_llm_b1_m4096_causal"   # the largest configuration: the one the MFMA-peak target is stated on
 
 
@@ -214,15 +241,53 @@ def main():
         layer(d, dev["X"], dev["q"], dev["k"], dev["v"], dev["o"], dev["ln1_gamma"], dev["ln1_beta"],
               dev["w1"], dev["w2"], dev["ln2_gamma"], dev["ln2_beta"], out=out, workspace=ws)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    def time_steps():
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    ms = time_steps()
     tokens_per_s = w.T / (ms * 1e-3)
+
+    # ---- measured peak of device memory around one step whose output and workspace are allocated inside the region
+    # (torch's allocator is the only one in the process: the library allocates nothing)
+    measured_peak = None
+    if args.part == "layer":
+        layer = fb.fsvd_layer_heads if per_head else fb.fsvd_layer
+        largs = (d, dev["X"], dev["q"], dev["k"], dev["v"], dev["o"], dev["ln1_gamma"], dev["ln1_beta"],
+                 dev["w1"], dev["w2"], dev["ln2_gamma"], dev["ln2_beta"])
+        torch.cuda.synchronize()
+        torch.cuda.reset_peak_memory_stats()
+        base = torch.cuda.memory_allocated()
+        tmp = layer(*largs)
+        torch.cuda.synchronize()
+        measured_peak = torch.cuda.max_memory_allocated() - base - tmp.numel() * tmp.element_size()
+        del tmp
+
+    # ---- the same layer with every factor left row-major, as the problem is stated (the default hands over the
+    # matrices the library accepts as prepacked tile images)
+    row_ms = None
+    if args.weights == "tiled" and args.part == "layer":
+        dev_tiled = dev
+        dev = fb.to_device(inp, "cuda:0", tiled=False)
+        row_ms = time_steps()
+        dev = dev_tiled
+
+    # ---- matrix-core rate this part sustains: a loop of nothing but MFMAs on registers, two wavefronts per SIMD
+    probe_out = torch.empty(512 * 256, dtype=torch.float32, device="cuda:0")
+    probe_tflops = 0.0
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flop = fb.fsvd_mfma_probe(512, 20000, probe_out)
+        e1.record()
+        torch.cuda.synchronize()
+        probe_tflops = max(probe_tflops, flop / (e0.elapsed_time(e1) * 1e-3) / 1e12)
 
     # ---- attended (query, key) pairs, for the FLOP model
     if inp["causal"]:
@@ -275,9 +340,12 @@ def main():
     else:
         kname, kflops, kms = "attn_core_kernel", fl["rebuild_qkv"] + fl["attn_core"], attn_ms
     achieved = kflops / (kms * 1e-3) / 1e12
+    traffic, traffic_src = traffic_from_profile(w.name, kname.replace("_kernel", ""))
     roofline = {"bound": "mfma", "kernel": kname, "achieved": round(achieved, 2), "peak": PEAK_MFMA_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_TFLOPS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, kname)),
+                "traffic": traffic, "traffic_source": traffic_src,
+                "peak_measured": round(probe_tflops, 1), "frac_of_measured": round(achieved / probe_tflops, 4),
+                "peak_measured_how": "fsvd_mfma_probe: 512 workgroups x 4 wavefronts of v_mfma_f32_32x32x16_f16 on registers, best of 3",
                 "kernel_ms": round(kms, 4), "algorithmic_flops": kflops,
                 "other_kernel_ms": {"ffn_core_kernel": round(ffn_ms, 4), "attn_core_kernel": round(attn_ms, 4)}}
 
@@ -294,13 +362,18 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "M": w.M, "D": w.D, "H": w.H, "F": w.F, "r_attn": ra, "r_ffn": rf,
                    "storage": w.dtype, "mask": w.mask, "norm": w.norm, "part": args.part,
+                   "arith": "fp16 MFMA with fp32 accumulation; bf16 storage is widened to fp16 on load "
+                            "(exact for 2^-14 <= |x| <= 65504, saturating beyond)",
                    "weights": ("prepacked tile images where accepted (" + ", ".join(
                        f"{n}.{'U' if u else ''}{'V' if v else ''}" for n, (u, v) in fb.TILED_OK.items()) + ")")
                    if args.weights == "tiled" else "row-major",
                    **({"r_head": rh, "qkv_factors": (f"{w.head_groups} head groups" if w.head_groups else "per head")} if per_head else {})},
         "useful_tflops": round(fl["total"] / (ms * 1e-3) / 1e12, 2),
         "mfma_peak_frac": round(fl["total"] / (ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS, 4),
+        "mfma_peak_frac_of_measured": round(fl["total"] / (ms * 1e-3) / 1e12 / probe_tflops, 4),
         "transient_mb": round(ws_bytes / 2 ** 20, 2), "unfused_transient_mb": round(unfused / 2 ** 20, 2),
+        "measured_peak_transient_mb": None if measured_peak is None else round(measured_peak / 2 ** 20, 2),
+        "row_major_weights_ms_per_step": None if row_ms is None else round(row_ms, 4),
         "roofline": roofline,
     }
 

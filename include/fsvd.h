@@ -31,8 +31,16 @@
  *  - Types.  X, U, V, bias, gamma and beta are stored in `io_dtype` (FSVD_F16
  *    or FSVD_BF16).  All contractions run on the fp16 matrix cores with fp32
  *    accumulation; bf16 inputs are widened to fp16 on load, which is exact for
- *    2^-14 <= |x| <= 65504 and loses at most 2^-25 absolute below that.  `out`
- *    is written in `out_dtype` (FSVD_F16, FSVD_BF16 or FSVD_F32).
+ *    2^-14 <= |x| <= 65504 (the range precondition of bf16 models).  Outside
+ *    it nothing is reported and the behaviour is: a bf16 element of X, U or
+ *    V (row-major or through fsvd_pack_tiled) is converted with rounding
+ *    toward zero, so |x| > 65504 saturates to +-65504 (never to infinity) and
+ *    |x| < 2^-14 is truncated to fp16's subnormal grid (spacing 2^-24; below
+ *    2^-24 it becomes 0).  Biases and LayerNorm parameters are used as fp32
+ *    and have no such limit; fp16 hand-offs between the kernels (rank-space
+ *    activations, context) round to nearest and can overflow to infinity if
+ *    such inputs drive them beyond 65504.  `out` is written in `out_dtype`
+ *    (FSVD_F16, FSVD_BF16 or FSVD_F32).
  *  - Streams.  All work is enqueued on `hip_stream` (a hipStream_t passed as
  *    void*; NULL is the default stream).  No call synchronises the host.
  *  - Errors.  Arguments are validated before anything is launched; a call
@@ -329,6 +337,13 @@ fsvd_status fsvd_decode_attention_core(const fsvd_desc *desc, int32_t r_k, int32
 fsvd_status fsvd_layernorm(int32_t T, int32_t D, const void *X, fsvd_dtype x_dtype, const void *gamma,
                            const void *beta, fsvd_dtype p_dtype, float eps, void *Y, fsvd_dtype y_dtype,
                            void *hip_stream);
+
+/* Measurement aid (no part of the method): launches `workgroups` workgroups of four wavefronts that each execute
+ * iters x 4 v_mfma_f32_32x32x16_f16 instructions (32768 FLOP each) on register-resident operands, nothing read from
+ * memory; total FLOP = workgroups * 4 * iters * 4 * 32768.  The benchmark times it to state the matrix-core rate the
+ * part sustains under load beside the published peak.  out: device float[workgroups * 256], overwritten.
+ * workgroups in [1, 65536], iters in [1, 2^20]. */
+fsvd_status fsvd_mfma_probe(int32_t workgroups, int32_t iters, void *out, void *hip_stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char *fsvd_status_string(fsvd_status status);

@@ -33,7 +33,7 @@ EXPORTS = ["fsvd_attention_workspace", "fsvd_ffn_workspace", "fsvd_layer_workspa
            "fsvd_unpack_fm", "fsvd_tiled_bytes", "fsvd_pack_tiled", "fsvd_linear_tiled", "fsvd_decode_kcache_bytes",
            "fsvd_decode_vcache_bytes", "fsvd_decode_cache_write", "fsvd_decode_attention_workspace", "fsvd_decode_attention",
            "fsvd_decode_core_workspace", "fsvd_decode_attention_core",
-           "fsvd_attention_groups_workspace", "fsvd_layer_groups_workspace", "fsvd_ffn_v2"]
+           "fsvd_attention_groups_workspace", "fsvd_layer_groups_workspace", "fsvd_ffn_v2", "fsvd_mfma_probe"]
 
 
 class FsvdError(RuntimeError):
@@ -89,6 +89,8 @@ def lib():
         L.fsvd_attention_heads.argtypes = [D, P, F, F, F, F, P, P, sz, P]
         L.fsvd_ffn.restype = C.c_int
         L.fsvd_ffn.argtypes = [D, P, F, F, P, P, sz, P]
+        L.fsvd_mfma_probe.restype = C.c_int
+        L.fsvd_mfma_probe.argtypes = [i32, i32, P, P]
         L.fsvd_ffn_v2.restype = C.c_int
         L.fsvd_ffn_v2.argtypes = [D, P, F, F, P, P]
         L.fsvd_layer.restype = C.c_int
@@ -291,6 +293,12 @@ def fsvd_ffn(desc, X, w1: Factor, w2: Factor, out=None, workspace=None):
     _check(lib().fsvd_ffn(C.byref(desc), _ptr(X), C.byref(f1), C.byref(f2), _ptr(out), _ptr(workspace),
                           workspace.numel(), _stream()), "fsvd_ffn")
     return out
+
+
+def fsvd_mfma_probe(workgroups: int, iters: int, out):
+    """Launch the matrix-core rate probe; returns the FLOP it executes.  out: float32 tensor of workgroups * 256 elements."""
+    _check(lib().fsvd_mfma_probe(workgroups, iters, _ptr(out), _stream()), "fsvd_mfma_probe")
+    return workgroups * 4 * iters * 4 * 32768
 
 
 def fsvd_ffn_v2(desc, X, w1: Factor, w2: Factor, out=None):

@@ -117,13 +117,17 @@ AttnPlan plan_attn(size_t T, size_t D, size_t rq, size_t rk, size_t rv, size_t r
   pl.total = smax(p_end, pl.to + align_up(fm_bytes(T, ro)));
   return pl;
 }
+// The size queries do not know the weight layout: room for the larger of the two kernels' partial sums.
+size_t ffn_core_partial_bytes(int T, int r1, int r2, int F) {
+  return smax(ffn_core_plan(T, r1, r2, F, false).partial_bytes, ffn_core_plan(T, r1, r2, F, true).partial_bytes);
+}
 struct FfnPlan { size_t p1, z, part, total; };   // P1 | Z | fp32 partial sums of Z (only when the core splits F)
 FfnPlan plan_ffn(size_t T, size_t r1, size_t r2, size_t F) {
   FfnPlan pl;
   pl.p1 = 0;
   pl.z = align_up(fm_bytes(T, r1));
   pl.part = pl.z + align_up(fm_bytes(T, r2));
-  pl.total = pl.part + align_up(ffn_core_plan((int)T, (int)r1, (int)r2, (int)F).partial_bytes);
+  pl.total = pl.part + align_up(ffn_core_partial_bytes((int)T, (int)r1, (int)r2, (int)F));
   return pl;
 }
 
@@ -553,7 +557,7 @@ fsvd_status fsvd_attention_heads_core(const fsvd_desc* d, const void* Pq, const 
 size_t fsvd_ffn_core_workspace(const fsvd_desc* d, int32_t r1, int32_t r2) {
   if (check_desc(d, true) != FSVD_OK) return 0;
   if (check_rank(r1) || check_rank(r2)) return 0;
-  return align_up(ffn_core_plan(d->B * d->M, r1, r2, d->F).partial_bytes);
+  return align_up(ffn_core_partial_bytes(d->B * d->M, r1, r2, d->F));
 }
 
 fsvd_status fsvd_ffn_core(const fsvd_desc* d, const void* P1, const fsvd_factor* w1, const fsvd_factor* w2, void* Z,
@@ -722,6 +726,13 @@ fsvd_status fsvd_decode_attention(const fsvd_desc* d, const void* x_new, const f
   ob.g[0] = {o->V, o->bias, out, D, D, D};
   ob.part = (float*)(w + pl.part); ob.part_bytes = pl.part_bytes; ob.ldp = D;
   FSVD_HIP(launch_linear(ob, s));
+  return FSVD_OK;
+}
+
+fsvd_status fsvd_mfma_probe(int32_t workgroups, int32_t iters, void* out, void* stream) {
+  if (!out || mis16(out)) return FSVD_ERR_INVALID_ARG;
+  if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 20)) return FSVD_ERR_INVALID_ARG;
+  FSVD_HIP(launch_mfma_probe(workgroups, iters, (float*)out, (hipStream_t)stream));
   return FSVD_OK;
 }
 

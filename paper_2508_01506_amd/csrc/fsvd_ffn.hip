@@ -23,6 +23,8 @@
 #include "fsvd_common.h"
 #include "fsvd_kernels.h"
 
+#include <stdlib.h>
+
 namespace fsvd {
 
 namespace {
@@ -478,14 +480,47 @@ hipError_t launch_ns(const FfnCoreArgs& a, const FfnCorePlan& pl, hipStream_t s)
 }
 }  // namespace
 
+// Which kernel serves prepacked weights: the all-wavefront kernel (fsvd_ffn_wide.hip) where a workgroup has to cover
+// more than 512 output ranks (there the two-role kernel parks half of its accumulators in the loader wavefronts and
+// runs their MFMAs in stages of their own); measured on one machine, it is ahead from r2 = 1024 on (the decoder shape:
+// 1.14 ms against 1.18 ms) and behind for r2 <= 768 (cfg2u 0.213 against 0.187 ms), where the two-role kernel stays.
+// FSVD_FFN_CORE=wide / tworole overrides the choice (a tuning switch).
+static bool ffn_core_use_wide(int T, int r1, int r2, int F) {
+  (void)T; (void)r1; (void)F;
+  const char* e = getenv("FSVD_FFN_CORE");
+  if (e && e[0] == 't') return false;
+  if (e && e[0] == 'w') return true;
+  return r2 >= 1024;
+}
+
 // Launch shape: W sub-tiles of 128 ranks per workgroup (up to 4 on the compute wavefronts, up to 4 more on the loader
 // wavefronts), the slices of r2 that follow from W, and the number of parts F is split into.  Splitting F needs fp32
 // partial sums in the workspace; they may take at most T * F bytes (half of what the hidden activation itself would).
 // The choice minimises (rounds of workgroups over the 256 compute units) x (weight tiles and GELU passes per workgroup).
-FfnCorePlan ffn_core_plan(int T, int r1, int r2, int F) {
+FfnCorePlan ffn_core_plan(int T, int r1, int r2, int F, bool tiled) {
   const int tiles = (T + kFfnBT - 1) / kFfnBT;
-  const int nsub = (r2 + kTile - 1) / kTile, nA = (r1 + kTile - 1) / kTile, nchunks = (F + kFfnBF - 1) / kFfnBF;
   const size_t zpad = (size_t)((r2 + 63) / 64) * 64;
+  if (tiled && ffn_core_use_wide(T, r1, r2, F)) {
+    // all-wavefront kernel: groups of 256 ranks, at most four per workgroup; chunks of 256 features
+    const int ngroups = (r2 + 255) / 256, nsl = (ngroups + 3) / 4, np = (ngroups + nsl - 1) / nsl;
+    const int nA = (r1 + 63) / 64, nchunks = (F + 255) / 256;
+    FfnCorePlan best{};
+    double best_cost = 0.0;
+    for (int fsplit = 1; fsplit <= nchunks; fsplit *= 2) {
+      const size_t part = fsplit > 1 ? (size_t)fsplit * zpad * T * 4 : 0;
+      if (part > (size_t)T * F) break;
+      const long wgs = (long)tiles * nsl * fsplit;
+      const double rounds = (double)((wgs + 255) / 256);
+      const double cost = rounds * ((nchunks + fsplit - 1) / fsplit) * (nA + 4.0 * np + 3.0) + 4.0 * (fsplit > 1);
+      if (best.nslices == 0 || cost < best_cost - 1e-9) {
+        best_cost = cost;
+        best.nslices = nsl; best.slice_w = 256 * np; best.ns = 0; best.ns2 = 0; best.fsplit = fsplit; best.wide = np;
+        best.partial_bytes = part;
+      }
+    }
+    return best;
+  }
+  const int nsub = (r2 + kTile - 1) / kTile, nA = (r1 + kTile - 1) / kTile, nchunks = (F + kFfnBF - 1) / kFfnBF;
   FfnCorePlan best{};
   double best_cost = 0.0;
   for (int W = 1; W <= 8; ++W) {
@@ -505,6 +540,7 @@ FfnCorePlan ffn_core_plan(int T, int r1, int r2, int F) {
       if (best.nslices == 0 || cost < best_cost - 1e-9) {
         best_cost = cost;
         best.nslices = nsl; best.slice_w = slice_w; best.ns = W - on_loader; best.ns2 = on_loader; best.fsplit = fsplit;
+        best.wide = 0;
         best.partial_bytes = part;
       }
     }
@@ -513,10 +549,11 @@ FfnCorePlan ffn_core_plan(int T, int r1, int r2, int F) {
 }
 
 hipError_t launch_ffn_core(const FfnCoreArgs& a, hipStream_t s) {
-  const FfnCorePlan pl = ffn_core_plan(a.T, a.r1, a.r2, a.F);
+  const FfnCorePlan pl = ffn_core_plan(a.T, a.r1, a.r2, a.F, a.tiled != 0);
   if (pl.fsplit > 1 && !a.Zpart) return hipErrorInvalidValue;
   hipError_t e = hipErrorInvalidValue;
-  switch (pl.ns * 8 + pl.ns2) {
+  if (pl.wide > 0) e = launch_ffn_core_wide(a, pl, s);
+  else switch (pl.ns * 8 + pl.ns2) {
     case 1 * 8 + 0: e = launch_ns<1, 0>(a, pl, s); break;
     case 2 * 8 + 0: e = launch_ns<2, 0>(a, pl, s); break;
     case 3 * 8 + 0: e = launch_ns<3, 0>(a, pl, s); break;

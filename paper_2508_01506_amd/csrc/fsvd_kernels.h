@@ -92,9 +92,12 @@ struct FfnCoreArgs {
   float* Zpart;      // fp32 partial sums, FfnCorePlan::partial_bytes (needed when the plan splits F)
 };
 // launch shape of the FFN core for a problem size (host-side, no device needed)
-struct FfnCorePlan { int nslices, slice_w, ns, ns2, fsplit; size_t partial_bytes; };
-FfnCorePlan ffn_core_plan(int T, int r1, int r2, int F);
+// wide > 0: the all-wavefront kernel for prepacked weights (fsvd_ffn_wide.hip) with `wide` 256-rank groups per workgroup
+// (slice_w = 256 wide); wide == 0: the two-role kernel (fsvd_ffn.hip) with ns + ns2 128-rank sub-tiles per workgroup
+struct FfnCorePlan { int nslices, slice_w, ns, ns2, fsplit, wide; size_t partial_bytes; };
+FfnCorePlan ffn_core_plan(int T, int r1, int r2, int F, bool tiled);
 hipError_t launch_ffn_core(const FfnCoreArgs& a, hipStream_t s);
+hipError_t launch_ffn_core_wide(const FfnCoreArgs& a, const FfnCorePlan& pl, hipStream_t s);
 
 // ---- whole factored FFN in one kernel (Alg. 3): row-major X [T, D] -> row-major out [T, D], no intermediates in memory
 struct FfnV2Args {
@@ -146,5 +149,9 @@ hipError_t launch_pack_tiled(const void* src, int src_dt, int K, int N, void* ds
 // ---- layout conversion: row-major [T, K] (F16 / BF16 / F32) <-> FM fp16
 hipError_t launch_pack_fm(const void* src, int src_dt, int T, int K, void* dst_fm, hipStream_t s);
 hipError_t launch_unpack_fm(const void* src_fm, int T, int K, void* dst, int dst_dt, hipStream_t s);
+
+// ---- matrix-core rate probe: workgroups x 4 wavefronts, each iters x 4 MFMAs (32x32x16 fp16) on registers;
+// out: float[workgroups * 256]
+hipError_t launch_mfma_probe(int workgroups, int iters, float* out, hipStream_t s);
 
 }  // namespace fsvd
