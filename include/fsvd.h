@@ -175,6 +175,25 @@ fsvd_status fsvd_ffn(const fsvd_desc *desc, const void *X, const fsvd_factor *w1
                      void *out, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * fsvd_ffn for callers that cannot allocate device memory or hand over a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation.  Same arguments, checks, kernels and results (bit for bit)
+ * as fsvd_ffn, but the rank-space scratch (P, Z and, when the core splits the sum over F, its fp32 partial sums)
+ * lives in an array of FSVD_STATIC_SCRATCH_BYTES that is part of the library's device image: every GPU the library
+ * runs on holds its own copy from the moment the library is loaded there until the process ends.  The call
+ * allocates and frees nothing (no hipMalloc, hipFree or allocating runtime routine); on its first use on a device it
+ * looks the array's address up once (hipGetSymbolAddress, with that device current) and keeps it per device.
+ * The device that is current when the call is made must be the one hip_stream and all pointers belong to.
+ * Limit: fsvd_ffn_workspace(desc, w1->rank, w2->rank) <= FSVD_STATIC_SCRATCH_BYTES, otherwise FSVD_ERR_WORKSPACE
+ * before any launch (use fsvd_ffn with a caller workspace for larger problems).  Nothing in the scratch has to start
+ * at zero (every byte a kernel reads was written earlier in the same call), so the array is never cleared.
+ * All calls on one GPU share that GPU's array: calls that may overlap on one GPU (different streams, or host
+ * threads without ordering) race on it; calls on one stream are ordered by the stream and may follow one another.
+ */
+#define FSVD_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+fsvd_status fsvd_ffn_static(const fsvd_desc *desc, const void *X, const fsvd_factor *w1, const fsvd_factor *w2,
+                            void *out, void *hip_stream);
+
+/*
  * Feed-forward block, FlashSVDFFN V2 (Alg. 3; section "FlashSVDFFN V2"): the same function as fsvd_ffn,
  *   out = phi((X U_1) V_1 + b_1) U_2 V_2 + b_2,
  * computed by ONE kernel per block of 32 or 64 tokens: the rank projection X U_1 and the up-projection Z V_2 run inside

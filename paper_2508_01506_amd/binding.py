@@ -33,7 +33,7 @@ EXPORTS = ["fsvd_attention_workspace", "fsvd_ffn_workspace", "fsvd_layer_workspa
            "fsvd_unpack_fm", "fsvd_tiled_bytes", "fsvd_pack_tiled", "fsvd_linear_tiled", "fsvd_decode_kcache_bytes",
            "fsvd_decode_vcache_bytes", "fsvd_decode_cache_write", "fsvd_decode_attention_workspace", "fsvd_decode_attention",
            "fsvd_decode_core_workspace", "fsvd_decode_attention_core",
-           "fsvd_attention_groups_workspace", "fsvd_layer_groups_workspace", "fsvd_ffn_v2", "fsvd_mfma_probe"]
+           "fsvd_attention_groups_workspace", "fsvd_layer_groups_workspace", "fsvd_ffn_v2", "fsvd_ffn_static", "fsvd_mfma_probe"]
 
 
 class FsvdError(RuntimeError):
@@ -91,6 +91,8 @@ def lib():
         L.fsvd_ffn.argtypes = [D, P, F, F, P, P, sz, P]
         L.fsvd_mfma_probe.restype = C.c_int
         L.fsvd_mfma_probe.argtypes = [i32, i32, P, P]
+        L.fsvd_ffn_static.restype = C.c_int
+        L.fsvd_ffn_static.argtypes = [D, P, F, F, P, P]
         L.fsvd_ffn_v2.restype = C.c_int
         L.fsvd_ffn_v2.argtypes = [D, P, F, F, P, P]
         L.fsvd_layer.restype = C.c_int
@@ -299,6 +301,16 @@ def fsvd_mfma_probe(workgroups: int, iters: int, out):
     """Launch the matrix-core rate probe; returns the FLOP it executes.  out: float32 tensor of workgroups * 256 elements."""
     _check(lib().fsvd_mfma_probe(workgroups, iters, _ptr(out), _stream()), "fsvd_mfma_probe")
     return workgroups * 4 * iters * 4 * 32768
+
+
+FSVD_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def fsvd_ffn_static(desc, X, w1: Factor, w2: Factor, out):
+    """fsvd_ffn with the library's own static scratch instead of a workspace; `out` is the caller's (nothing is allocated)."""
+    f1, f2 = w1.c(), w2.c()
+    _check(lib().fsvd_ffn_static(C.byref(desc), _ptr(X), C.byref(f1), C.byref(f2), _ptr(out), _stream()), "fsvd_ffn_static")
+    return out
 
 
 def fsvd_ffn_v2(desc, X, w1: Factor, w2: Factor, out=None):

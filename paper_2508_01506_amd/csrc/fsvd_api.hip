@@ -4,6 +4,8 @@
 #include "fsvd_common.h"
 #include "fsvd_kernels.h"
 
+#include <mutex>
+
 using namespace fsvd;
 
 namespace {
@@ -356,6 +358,44 @@ fsvd_status fsvd_ffn(const fsvd_desc* d, const void* X, const fsvd_factor* w1, c
   if (!X || !out || mis16(X) || mis16(out)) return FSVD_ERR_INVALID_ARG;
   FSVD_TRY(check_ws(ws, ws_bytes, plan_ffn((size_t)d->B * d->M, w1->rank, w2->rank, d->F).total));
   return run_ffn(d, X, LAYOUT_ROW, d->io_dtype, w1, w2, nullptr, 0, out, d->out_dtype, (char*)ws, (hipStream_t)stream);
+}
+
+}  // extern "C"
+
+// ------------------------------------------------------------------ fsvd_ffn without a caller workspace
+// The scratch of fsvd_ffn_static: part of the device image, one copy per GPU.  In host code the array's name is only a
+// handle for the runtime's symbol lookup, never an address a kernel may use: scratch_of_current_device() asks the
+// runtime once per device for the array's address on that device, and only that address is handed to kernels.
+namespace {
+static __device__ __align__(256) unsigned char scratch[FSVD_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];      // per device: address of `scratch` on that device (nullptr = not looked up yet)
+std::mutex g_scratch_mu;
+
+fsvd_status scratch_of_current_device(char** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return FSVD_ERR_DEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return FSVD_ERR_DEVICE;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = (char*)g_scratch_ptr[dev];
+  return FSVD_OK;
+}
+}  // namespace
+
+extern "C" {
+
+fsvd_status fsvd_ffn_static(const fsvd_desc* d, const void* X, const fsvd_factor* w1, const fsvd_factor* w2, void* out,
+                            void* stream) {
+  FSVD_TRY(check_ffn(d, w1, w2, true));
+  if (!X || !out || mis16(X) || mis16(out)) return FSVD_ERR_INVALID_ARG;
+  if (plan_ffn((size_t)d->B * d->M, w1->rank, w2->rank, d->F).total > FSVD_STATIC_SCRATCH_BYTES) return FSVD_ERR_WORKSPACE;
+  char* ws = nullptr;
+  FSVD_TRY(scratch_of_current_device(&ws));
+  return run_ffn(d, X, LAYOUT_ROW, d->io_dtype, w1, w2, nullptr, 0, out, d->out_dtype, ws, (hipStream_t)stream);
 }
 
 fsvd_status fsvd_ffn_v2(const fsvd_desc* d, const void* X, const fsvd_factor* w1, const fsvd_factor* w2, void* out,

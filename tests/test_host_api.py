@@ -183,6 +183,25 @@ def test_tiled_weight_layout_contract():
     assert L.fsvd_linear_tiled(16, 40, 16, 256, 0, 256, None, 0, None, 0, 256, 0, None) == UNSUPPORTED
 
 
+def test_ffn_with_static_scratch_contract():
+    """fsvd_ffn_static validates like fsvd_ffn and refuses, before touching a device, a problem whose workspace would not
+    fit the library's static scratch array."""
+    L = fb.lib()
+    d = desc()
+    w1, w2 = fac(768, 64, 3072), fac(3072, 64, 768)
+    call = lambda dd, a, b, x=256, out=256: L.fsvd_ffn_static(C.byref(dd), x, C.byref(a), C.byref(b), out, None)
+    assert call(d, w1, w2, x=None) == INVALID
+    assert call(d, w1, w2, out=264) == INVALID
+    assert call(d, w2, w1) == INVALID
+    assert call(d, fac(768, 24, 3072), w2) == UNSUPPORTED
+    big = desc(B=1, M=4096, D=4096, H=32, F=16384)                         # the decoder shape: 192 MiB of rank scratch
+    assert fb.fsvd_ffn_workspace(big, 2048, 2048) > fb.FSVD_STATIC_SCRATCH_BYTES
+    assert call(big, fac(4096, 2048, 16384), fac(16384, 2048, 4096)) == WORKSPACE
+    text = open(os.path.join(ROOT, "include", "fsvd.h")).read()
+    assert re.search(r"#define\s+FSVD_STATIC_SCRATCH_BYTES\s+\(\(size_t\)32\s*<<\s*20\)", text)
+    assert fb.FSVD_STATIC_SCRATCH_BYTES == 32 << 20
+
+
 def test_one_kernel_ffn_contract():
     """fsvd_ffn_v2 takes only tile images of all four matrices and ranks up to 1024, and says so before any launch."""
     L = fb.lib()

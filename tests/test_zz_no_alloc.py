@@ -1,0 +1,55 @@
+"""fsvd_ffn_static (the FFN block on the library's static scratch array, for callers that cannot allocate) against
+fsvd_ffn with a caller workspace: same kernels on the same inputs, so the outputs must be equal bit for bit, and both
+meet the FFN block's tolerance against the oracle.  Two calls in a row, the second on a smaller input, so that what the
+first call left in the shared array is seen to be harmless."""
+import numpy as np
+import pytest
+import torch
+
+from fsvd_testing import oracle_call, rel_err
+from paper_2508_01506_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def test_ffn_on_static_scratch_equals_ffn_with_workspace_twice_in_a_row():
+    from paper_2508_01506_amd import binding as fb
+    fb.lib()
+    assert torch.cuda.is_available(), "this test needs the GPU"
+    # first the larger problem (its workspace nearly fills the 32 MiB array), then smaller ones with other ranks and
+    # weight layouts, each reading scratch bytes the previous call wrote
+    cases = [("cfg2u_bert_base_b16_m512_pad_unit", True), ("cfg1_bert_base_b2_m128", False), ("tiny_pad", True)]
+    for name, tiled in cases:
+        inp = W.make_inputs(W.get_workload(name))
+        w = inp["workload"]
+        dev = fb.to_device(inp, DEV, tiled=tiled)
+        d = dev["desc"]
+        need = fb.fsvd_ffn_workspace(d, w.r_ffn, w.r_ffn)
+        assert 0 < need <= fb.FSVD_STATIC_SCRATCH_BYTES, (name, need)
+        print(f"static-scratch FFN: {name}, workspace {need} bytes, {'prepacked' if tiled else 'row-major'} weights", flush=True)
+        want = fb.fsvd_ffn(d, dev["X"], dev["w1"], dev["w2"])
+        out = torch.full(dev["X"].shape, float("nan"), dtype=torch.float32, device=DEV)
+        torch.cuda.synchronize()
+        count = lambda: torch.cuda.memory_stats()["allocation.all.allocated"]     # allocations made so far
+        before = count()
+        got = fb.fsvd_ffn_static(d, dev["X"], dev["w1"], dev["w2"], out)
+        assert count() == before                                  # nothing was taken from torch's allocator either
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), name
+        again = fb.fsvd_ffn_static(d, dev["X"], dev["w1"], dev["w2"], torch.empty_like(out))
+        assert torch.equal(again, want), name
+        if w.T <= 512:
+            ref = oracle_call(inp, "ffn")
+            err = rel_err(got.cpu().numpy(), ref)
+            assert np.isfinite(err) and err < 4e-3, (name, err)
+    # a problem beyond the array is refused with the workspace status, before any launch
+    big = W.get_workload("cfg4_long_b4_m8192")
+    d = fb.make_desc(big.B, big.M, big.D, big.H, big.F, torch.float16)
+    assert fb.fsvd_ffn_workspace(d, big.r_ffn, big.r_ffn) > fb.FSVD_STATIC_SCRATCH_BYTES
+    x = torch.zeros((big.B, big.M, big.D), dtype=torch.float16, device=DEV)
+    dev1 = fb.to_device(W.make_inputs(W.get_workload("cfg1_bert_base_b2_m128")), DEV)
+    with pytest.raises(fb.FsvdError) as e:
+        # factor shapes do not matter for this check beyond passing validation: reuse cfg1's (same D, F) with cfg4's T
+        fb.fsvd_ffn_static(d, x, dev1["w1"], dev1["w2"], torch.empty(x.shape, dtype=torch.float32, device=DEV))
+    assert e.value.status == 3
