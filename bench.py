@@ -289,6 +289,25 @@ def main():
         torch.cuda.synchronize()
         probe_tflops = max(probe_tflops, flop / (e0.elapsed_time(e1) * 1e-3) / 1e12)
 
+    # ---- the rate at which the L2s can feed the compute units with direct-to-LDS loads (what bounds the fused cores in
+    # practice: every weight tile is re-read by every 64-token workgroup), alone and with the operand reads and MFMAs of
+    # an FFN-core stage as concurrent work
+    region = 16 << 20
+    probe_src = torch.zeros(8 * region, dtype=torch.uint8, device="cuda:0")
+    dma_out = torch.empty(256 * 512, dtype=torch.float32, device="cuda:0")
+    dma_tbs = []
+    for with_work in (False, True):
+        best = 0.0
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            nbytes = fb.fsvd_dma_probe(256, 2000, with_work, probe_src, region, dma_out)
+            e1.record()
+            torch.cuda.synchronize()
+            best = max(best, nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        dma_tbs.append(round(best, 2))
+    del probe_src
+
     # ---- attended (query, key) pairs, for the FLOP model
     if inp["causal"]:
         pairs = w.B * w.M * (w.M + 1) / 2
@@ -346,6 +365,8 @@ def main():
                 "traffic": traffic, "traffic_source": traffic_src,
                 "peak_measured": round(probe_tflops, 1), "frac_of_measured": round(achieved / probe_tflops, 4),
                 "peak_measured_how": "fsvd_mfma_probe: 512 workgroups x 4 wavefronts of v_mfma_f32_32x32x16_f16 on registers, best of 3",
+                "l2_to_lds_measured_tbs": {"loads_only": dma_tbs[0], "with_stage_work": dma_tbs[1],
+                                           "how": "fsvd_dma_probe: 256 workgroups, 32 KiB steps straight into LDS, 16 MiB per XCD"},
                 "kernel_ms": round(kms, 4), "algorithmic_flops": kflops,
                 "other_kernel_ms": {"ffn_core_kernel": round(ffn_ms, 4), "attn_core_kernel": round(attn_ms, 4)}}
 

@@ -364,6 +364,17 @@ fsvd_status fsvd_layernorm(int32_t T, int32_t D, const void *X, fsvd_dtype x_dty
  * workgroups in [1, 65536], iters in [1, 2^20]. */
 fsvd_status fsvd_mfma_probe(int32_t workgroups, int32_t iters, void *out, void *hip_stream);
 
+/* Measurement aid (no part of the method): the rate at which a compute unit can be fed from the L2 with the
+ * direct-to-LDS loads the fused kernels use.  Launches `workgroups` workgroups of eight wavefronts; each copies `steps`
+ * steps of 32 KiB straight into LDS (four 1 KiB loads per wavefront and step, two steps in flight, no barrier), all
+ * workgroups of one XCD walking the same region of `region_bytes` bytes of `src` (eight regions, one per XCD, so the
+ * data comes out of that XCD's L2 after the first touch); with_work != 0 adds twelve 16-byte LDS reads and eight
+ * MFMAs per wavefront and step, the operand traffic and matrix-core load of a stage of the fused FFN core.  Bytes
+ * moved = workgroups * steps * 32768.  src: device buffer of 8 * region_bytes bytes; region_bytes a multiple of 32768,
+ * at most 2^30; out: device float[workgroups * 512], overwritten.  workgroups in [1, 65536], steps in [1, 2^20]. */
+fsvd_status fsvd_dma_probe(int32_t workgroups, int32_t steps, int32_t with_work, const void *src, size_t region_bytes,
+                           void *out, void *hip_stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *fsvd_status_string(fsvd_status status);
 

@@ -33,7 +33,7 @@ EXPORTS = ["fsvd_attention_workspace", "fsvd_ffn_workspace", "fsvd_layer_workspa
            "fsvd_unpack_fm", "fsvd_tiled_bytes", "fsvd_pack_tiled", "fsvd_linear_tiled", "fsvd_decode_kcache_bytes",
            "fsvd_decode_vcache_bytes", "fsvd_decode_cache_write", "fsvd_decode_attention_workspace", "fsvd_decode_attention",
            "fsvd_decode_core_workspace", "fsvd_decode_attention_core",
-           "fsvd_attention_groups_workspace", "fsvd_layer_groups_workspace", "fsvd_ffn_v2", "fsvd_ffn_static", "fsvd_mfma_probe"]
+           "fsvd_attention_groups_workspace", "fsvd_layer_groups_workspace", "fsvd_ffn_v2", "fsvd_ffn_static", "fsvd_mfma_probe", "fsvd_dma_probe"]
 
 
 class FsvdError(RuntimeError):
@@ -89,6 +89,8 @@ def lib():
         L.fsvd_attention_heads.argtypes = [D, P, F, F, F, F, P, P, sz, P]
         L.fsvd_ffn.restype = C.c_int
         L.fsvd_ffn.argtypes = [D, P, F, F, P, P, sz, P]
+        L.fsvd_dma_probe.restype = C.c_int
+        L.fsvd_dma_probe.argtypes = [i32, i32, i32, P, sz, P, P]
         L.fsvd_mfma_probe.restype = C.c_int
         L.fsvd_mfma_probe.argtypes = [i32, i32, P, P]
         L.fsvd_ffn_static.restype = C.c_int
@@ -301,6 +303,13 @@ def fsvd_mfma_probe(workgroups: int, iters: int, out):
     """Launch the matrix-core rate probe; returns the FLOP it executes.  out: float32 tensor of workgroups * 256 elements."""
     _check(lib().fsvd_mfma_probe(workgroups, iters, _ptr(out), _stream()), "fsvd_mfma_probe")
     return workgroups * 4 * iters * 4 * 32768
+
+
+def fsvd_dma_probe(workgroups: int, steps: int, with_work: bool, src, region_bytes: int, out):
+    """Launch the L2 -> LDS delivery probe; returns the bytes it moves.  src: 8 * region_bytes bytes; out: float32[workgroups * 512]."""
+    assert src.numel() * src.element_size() >= 8 * region_bytes
+    _check(lib().fsvd_dma_probe(workgroups, steps, int(with_work), _ptr(src), region_bytes, _ptr(out), _stream()), "fsvd_dma_probe")
+    return workgroups * steps * 32768
 
 
 FSVD_STATIC_SCRATCH_BYTES = 32 << 20

@@ -776,6 +776,15 @@ fsvd_status fsvd_mfma_probe(int32_t workgroups, int32_t iters, void* out, void* 
   return FSVD_OK;
 }
 
+fsvd_status fsvd_dma_probe(int32_t workgroups, int32_t steps, int32_t with_work, const void* src, size_t region_bytes, void* out,
+                           void* stream) {
+  if (!src || !out || mis16(src) || mis16(out)) return FSVD_ERR_INVALID_ARG;
+  if (workgroups < 1 || workgroups > 65536 || steps < 1 || steps > (1 << 20)) return FSVD_ERR_INVALID_ARG;
+  if (region_bytes == 0 || region_bytes % 32768 != 0 || region_bytes > ((size_t)1 << 30)) return FSVD_ERR_INVALID_ARG;
+  FSVD_HIP(launch_dma_probe(workgroups, steps, with_work, src, (unsigned)region_bytes, (float*)out, (hipStream_t)stream));
+  return FSVD_OK;
+}
+
 fsvd_status fsvd_layernorm(int32_t T, int32_t D, const void* X, fsvd_dtype x_dtype, const void* gamma, const void* beta,
                            fsvd_dtype p_dtype, float eps, void* Y, fsvd_dtype y_dtype, void* stream) {
   if (T <= 0 || D <= 0 || !X || !gamma || !beta || !Y) return FSVD_ERR_INVALID_ARG;

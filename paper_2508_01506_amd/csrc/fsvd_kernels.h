@@ -153,5 +153,8 @@ hipError_t launch_unpack_fm(const void* src_fm, int T, int K, void* dst, int dst
 // ---- matrix-core rate probe: workgroups x 4 wavefronts, each iters x 4 MFMAs (32x32x16 fp16) on registers;
 // out: float[workgroups * 256]
 hipError_t launch_mfma_probe(int workgroups, int iters, float* out, hipStream_t s);
+// ---- L2 -> LDS delivery probe: workgroups x `steps` steps of 32 KiB copied straight into LDS from one of eight regions
+// of `region_bytes` (a multiple of 32 KiB) of src; out: float[workgroups * 512]
+hipError_t launch_dma_probe(int workgroups, int steps, int with_work, const void* src, unsigned region_bytes, float* out, hipStream_t s);
 
 }  // namespace fsvd

@@ -202,6 +202,17 @@ def test_ffn_with_static_scratch_contract():
     assert fb.FSVD_STATIC_SCRATCH_BYTES == 32 << 20
 
 
+def test_probe_entry_points_validate_their_arguments():
+    L = fb.lib()
+    assert L.fsvd_mfma_probe(0, 10, 256, None) == INVALID
+    assert L.fsvd_mfma_probe(4, 0, 256, None) == INVALID
+    assert L.fsvd_mfma_probe(4, 10, None, None) == INVALID
+    assert L.fsvd_dma_probe(4, 10, 0, None, 32768, 256, None) == INVALID
+    assert L.fsvd_dma_probe(4, 10, 0, 256, 1000, 256, None) == INVALID          # region not a multiple of 32 KiB
+    assert L.fsvd_dma_probe(4, 10, 0, 256, 0, 256, None) == INVALID
+    assert L.fsvd_dma_probe(0, 10, 0, 256, 32768, 256, None) == INVALID
+
+
 def test_one_kernel_ffn_contract():
     """fsvd_ffn_v2 takes only tile images of all four matrices and ranks up to 1024, and says so before any launch."""
     L = fb.lib()
