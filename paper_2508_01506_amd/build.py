@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libfsvd.so")
-SOURCES = ["fsvd_api.hip", "fsvd_gemm.hip", "fsvd_attn.hip", "fsvd_ffn.hip", "fsvd_ffn_wide.hip", "fsvd_ln.hip", "fsvd_decode.hip", "fsvd_gemm_ln.hip", "fsvd_ffn_v2.hip", "fsvd_probe.hip"]
+SOURCES = ["fsvd_api.hip", "fsvd_gemm.hip", "fsvd_attn.hip", "fsvd_attn_absorbed.hip", "fsvd_ffn.hip", "fsvd_ffn_wide.hip", "fsvd_ln.hip", "fsvd_decode.hip", "fsvd_gemm_ln.hip", "fsvd_ffn_v2.hip", "fsvd_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

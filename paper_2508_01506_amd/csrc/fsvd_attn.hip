@@ -23,6 +23,8 @@
 #include "fsvd_common.h"
 #include "fsvd_kernels.h"
 
+#include <stdlib.h>
+
 namespace fsvd {
 
 namespace {
@@ -527,6 +529,12 @@ hipError_t launch_qt(const AttnCoreArgs& a, hipStream_t s) {
 
 hipError_t launch_attn_core(const AttnCoreArgs& a, hipStream_t s) {
   const int dh = a.D / a.H;
+  // one factor pair per head with k / v ranks <= 64 <= d_h: the absorbed schedule, which rebuilds no K or V tile at all
+  // (FSVD_ATTN_ABSORBED=0 keeps the rebuilding kernel: a switch for comparisons)
+  if (attn_absorbed_supported(a)) {
+    const char* e = getenv("FSVD_ATTN_ABSORBED");
+    if (!(e && e[0] == '0')) return launch_attn_absorbed(a, s);
+  }
   if (dh == 64) return a.M <= 256 ? launch_qt<64, 1>(a, s) : launch_qt<64, 2>(a, s);
   if (dh == 128) return launch_qt<128, 1>(a, s);
   return hipErrorInvalidValue;

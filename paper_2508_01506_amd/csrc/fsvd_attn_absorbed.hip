@@ -1,0 +1,344 @@
+// Streaming attention for per-head factors of rank r <= 64 in the "absorbed" schedule (Alg. 1 in its own per-head
+// setting, V_a in r x d_h; appendix on multi-head low-rank activations): no Q, K or V tile is ever rebuilt, every
+// product of the loop contracts over a rank axis.
+//   M_h   = V_q^h (V_k^h)^T                      [r_q, r_k]       once per workgroup (a few matrix-core steps)
+//   w_h   = scale * (P_q^h M_h + b_q^h (V_k^h)^T) [queries, r_k]  = scale * q_h (V_k^h)^T: the key projection absorbed
+//                                                                 into the queries; the term q_h . b_k is the same for
+//                                                                 every key of a row and cancels in the softmax
+//   S     = w_h (P_k^h)^T                        [queries, keys]  contraction over r_k instead of d_h
+//   u_h   = sum_j alpha_j P_v^h[j] / l           [queries, r_v]   streaming softmax, accumulated in rank space
+//   ctx_h = u_h V_v^h + b_v^h                                     the value projection applied once, at the end; the
+//                                                                 weights alpha sum to one, so b_v passes through
+// P_a^h are columns [h r_a, (h+1) r_a) of the concatenated rank axis of P_a [T, H r_a] (fragment-major).
+//
+// One workgroup (4 wavefronts) owns one (sequence, head, block of 128 queries); every wavefront owns 32 queries.  All
+// products are transposed (keys / ranks / features along accumulator rows, queries along lanes), so that an accumulator
+// is the next product's operand without leaving its registers.  A fragment-major 16-byte unit holds 8 consecutive ranks
+// of one token: to make such a unit one operand register set, rows and columns of M_h are computed in a permuted order
+// (sigma below), after which the accumulator rows of w_h come out in exactly the order of P_k's units.  P_q and P_k
+// operands are therefore loaded straight from memory; only P_v (needed with keys as the contraction index) and V_v
+// (needed transposed) go through LDS and its transposing read.
+#include "fsvd_common.h"
+#include "fsvd_kernels.h"
+
+namespace fsvd {
+
+namespace {
+
+constexpr int kAbsWaves = 4;
+constexpr int kAbsThreads = kAbsWaves * 64;
+constexpr int kAbsBQ = kAbsWaves * 32;       // queries per workgroup
+constexpr int kAbsBKV = 128;                 // keys per step
+constexpr float kLog2eA = 1.4426950408889634f;
+constexpr int kPvStride = wtile_stride(64);  // halves per row of the P_v tile [key][rank], padded like a weight tile
+
+// byte offset of the 16-byte unit (token, octet o of the contraction axis) of a fragment-major tensor with kchunks chunks
+__device__ __forceinline__ int fm_unit_off(int tok, int kchunks, int o) {
+  return ((tok >> 5) * kchunks + (o >> 3)) * kFmChunkBytes + (o & 3) * kFmStepBytes + ((((o >> 2) & 1) << 5) + (tok & 31)) * 16;
+}
+
+template <int DH, int WT>
+__global__ void __launch_bounds__(kAbsThreads, 3) attn_absorbed_kernel(AttnCoreArgs a, int nqb) {
+  constexpr int DT32 = DH / 32, DST = DH / 16;
+  constexpr int WS = wtile_stride(DH);
+
+  __shared__ __attribute__((aligned(16))) _Float16 wv[64 * WS];                    // V_v^h [rank][DH], zero rows from r_v on
+  __shared__ __attribute__((aligned(16))) _Float16 pv[kAbsBKV * kPvStride];        // P_v^h [key][rank], zero columns from r_v on
+
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int BH = a.B * a.H;
+  const int bh = blockIdx.x % BH;
+  const int qb = nqb - 1 - blockIdx.x / BH;   // late query blocks (most keys under a causal mask) first
+  const int b = bh / a.H, h = bh % a.H;
+  const int M = a.M, D = a.D, T = a.B * a.M;
+  const int q0 = qb * kAbsBQ, qw = q0 + wave * 32;
+  int kv_len = a.key_len ? a.key_len[b] : M;
+  kv_len = kv_len < 1 ? 1 : (kv_len > M ? M : kv_len);
+  int kv_end = kv_len;
+  if (a.causal && q0 + kAbsBQ < kv_end) kv_end = q0 + kAbsBQ;
+  const int nsteps = (kv_end + kAbsBKV - 1) / kAbsBKV;
+  const int tok0 = b * M, col0 = h * DH;
+  const int rq = a.rq, rk = a.rk, rv = a.rv;
+  const int TQ = (rq + 31) >> 5, TK = (rk + 31) >> 5, TU = (rv + 31) >> 5;      // 32-rank tiles: 1 or 2
+  const int KSq = rq >> 4, KSk = rk >> 4, KSv = rv >> 4;                          // matrix-core steps of 16 ranks: 1..4
+  const int pch_q = (a.H * rq + kChunkK - 1) / kChunkK, pch_k = (a.H * rk + kChunkK - 1) / kChunkK,
+            pch_v = (a.H * rv + kChunkK - 1) / kChunkK;
+  const rsrc_t rsPq = rsrc_at(a.Pq, (long long)fm_bytes(T, a.H * rq), 0);
+  const rsrc_t rsPk = rsrc_at(a.Pk, (long long)fm_bytes(T, a.H * rk), 0);
+  const rsrc_t rsPv = rsrc_at(a.Pv, (long long)fm_bytes(T, a.H * rv), 0);
+  const int oq0 = (h * rq) >> 3, ok0 = (h * rk) >> 3, ov0 = (h * rv) >> 3;        // first octet of the head's rank windows
+
+  // ---- P_v staging: unit u = tid + 256 j -> (key u >> ob, octet u & (2^ob - 1)) of the step's [128 keys][8 or 4 octets]
+  const int ob = TU == 2 ? 3 : 2, nj = TU == 2 ? 4 : 2;
+  u4 v_raw[4];
+  auto issue_pv = [&](int step) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (j < nj) {
+        const int u = tid + kAbsThreads * j, oct = u & ((1 << ob) - 1);
+        int key = step * kAbsBKV + (u >> ob);
+        key = key < M ? key : M - 1;
+        v_raw[j] = buf_load16(rsPv, 8 * oct < rv ? fm_unit_off(tok0 + key, pch_v, ov0 + oct) : kOobOffset);
+      }
+    }
+  };
+  auto commit_pv = [&]() {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (j < nj) {
+        const int u = tid + kAbsThreads * j, oct = u & ((1 << ob) - 1);
+        *(u4*)&pv[(u >> ob) * kPvStride + 8 * oct] = v_raw[j];
+      }
+    }
+  };
+  // ---- P_k operands of one tile of 32 keys: lane (key, g) of step s holds octet 2 s + g of the head's window
+  auto load_pk = [&](u4 (&dst)[4], int key0) {
+    int key = key0 + l32;
+    key = key < M ? key : M - 1;
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      if (s < KSk) dst[s] = buf_load16(rsPk, fm_unit_off(tok0 + key, pch_k, ok0 + 2 * s + g));
+  };
+
+  issue_pv(0);
+  u4 kreg[4];
+  load_pk(kreg, 0);
+  u4 pq_raw[4];
+  {
+    int q = qw + l32;
+    q = q < M ? q : M - 1;
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      if (s < KSq) pq_raw[s] = buf_load16(rsPq, fm_unit_off(tok0 + q, pch_q, oq0 + 2 * s + g));
+  }
+  // ---- V_v^h -> LDS as it lies in memory (16 bytes per lane); rows from r_v on are zeros
+  {
+    constexpr int LPR = DH / 8, NU = 64 * LPR / kAbsThreads;
+    const rsrc_t rs = rsrc_at(a.Vv, (long long)a.H * rv * DH * 2, 0);
+#pragma unroll
+    for (int j = 0; j < NU; ++j) {
+      const int u = tid + kAbsThreads * j, row = u / LPR, c8 = 8 * (u % LPR);
+      const u4 raw = buf_load16(rs, row < rv ? ((h * rv + row) * DH + c8) * 2 : kOobOffset);
+      stage_store16<WT>(&wv[row * WS + c8], raw);
+    }
+  }
+
+  // =================================== absorbed queries: W^T [r_k, 32 queries] ===================================
+  // Row / column c of a 32-rank tile of M_h stands for rank 32 tile + sigma(c), sigma = c with bits 2 and 3 swapped:
+  // accumulator register v of lane group g is row 8 (v / 4) + 4 g + v % 4, so registers 8 t .. 8 t + 7 are then the 8
+  // consecutive ranks 16 t + 8 g .. of the tile: one fragment-major unit of P_q (for M_h's rows) or P_k (for W's rows).
+  h8 wq[4];
+  {
+    const int sig = (l32 & ~12) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
+    const rsrc_t rsVq = rsrc_at(a.Vq, (long long)a.H * rq * DH * 2, 0);
+    const rsrc_t rsVk = rsrc_at(a.Vk, (long long)a.H * rk * DH * 2, 0);
+    const rsrc_t rsBq = rsrc_at(a.bq, a.bq ? (long long)D * 2 : 0, 0);
+    const float qs = a.scale * kLog2eA;
+#pragma unroll
+    for (int tk = 0; tk < 2; ++tk) {               // one 32-rank tile of W^T at a time: its two tiles of M_h stay short-lived
+      h8 w0 = {}, w1 = {};
+      if (tk < TK) {
+        f16v macc[2], wacc = zero16();
+        macc[0] = zero16();
+        macc[1] = zero16();
+        const int rowk = 32 * tk + sig;
+#pragma unroll
+        for (int ds = 0; ds < DST; ++ds) {
+          const int dof = (16 * ds + 8 * g) * 2;
+          const h8 vk = raw_to_h8<WT>(buf_load16(rsVk, rowk < rk ? (h * rk + rowk) * DH * 2 + dof : kOobOffset));
+          const h8 bqf = raw_to_h8<WT>(buf_load16(rsBq, col0 * 2 + dof));     // zeros without a bias
+          wacc = mfma32(vk, bqf, wacc);                    // b_q (V_k^h)^T, the same in every column
+#pragma unroll
+          for (int tq = 0; tq < 2; ++tq) {
+            if (tq < TQ) {
+              const int rowq = 32 * tq + sig;
+              const h8 vq = raw_to_h8<WT>(buf_load16(rsVq, rowq < rq ? (h * rq + rowq) * DH * 2 + dof : kOobOffset));
+              macc[tq] = mfma32(vq, vk, macc[tq]);         // rows r_q, cols r_k
+            }
+          }
+        }
+#pragma unroll
+        for (int tq = 0; tq < 2; ++tq)
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            if (2 * tq + t < KSq) {
+              h8 mf;
+#pragma unroll
+              for (int i = 0; i < 8; ++i) mf[i] = (_Float16)macc[tq][8 * t + i];
+              wacc = mfma32(mf, __builtin_bit_cast(h8, pq_raw[2 * tq + t]), wacc);     // rows r_k, cols queries
+            }
+          }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          w0[i] = (_Float16)(wacc[i] * qs);
+          w1[i] = (_Float16)(wacc[8 + i] * qs);
+        }
+        if (2 * tk + 1 >= KSk) w1 = h8{};
+      }
+      wq[2 * tk] = w0;
+      wq[2 * tk + 1] = w1;
+    }
+  }
+
+  // =================================== key / value loop ===================================
+  const int trV = tr_lane_off(lane, kPvStride) + 4 * g * kPvStride;
+  f16v u[2];
+  u[0] = zero16();
+  u[1] = zero16();
+  float m_run = 0.f, l_run = 0.f;
+  bool first = true;
+  h8 kone = {}, qneg;
+  kone[0] = g == 0 ? (_Float16)1.0f : (_Float16)0.0f;
+  kone[1] = kone[0];
+  auto set_qneg = [&]() {      // -m_run as an fp16 head + tail in two contraction slots: the matrix core subtracts the reference
+    const _Float16 hi = (_Float16)(-m_run);
+    const _Float16 lo = (_Float16)(-m_run - (float)hi);
+    qneg = h8{};
+    qneg[0] = g == 0 ? hi : (_Float16)0.0f;
+    qneg[1] = g == 0 ? lo : (_Float16)0.0f;
+  };
+  set_qneg();
+  const int qlast = qw + 31;
+
+  for (int step = 0; step < nsteps; ++step) {
+    __syncthreads();                 // every wavefront is done with the previous step's tile
+    commit_pv();
+    if (step + 1 < nsteps) issue_pv(step + 1);
+    __syncthreads();
+#pragma unroll 1
+    for (int ks = 0; ks < 4; ++ks) {
+      const int key0 = step * kAbsBKV + 32 * ks;
+      if (key0 >= kv_end) break;
+      if (a.causal && key0 > qlast) break;
+      f16v s = mfma32(kone, qneg, zero16());
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (i < KSk) s = mfma32(__builtin_bit_cast(h8, kreg[i]), wq[i], s);       // S^T - m: rows keys, cols queries
+      load_pk(kreg, key0 + 32);      // the next tile's operands (clamped to the sequence: an unused tile costs one read)
+      const bool need_mask = (key0 + 32 > kv_len) || (a.causal && key0 + 31 > qw);
+      if (need_mask) {
+        const int q = qw + l32;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = key0 + 8 * (v >> 2) + 4 * g + (v & 3);
+          if (key >= kv_len || (a.causal && key > q)) s[v] = -INFINITY;
+        }
+      }
+      // lazily raised reference maximum in the log2 domain, as in the rebuilding kernel
+      float mx = s[0];
+#pragma unroll
+      for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[v]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      if (__any(first || mx > 8.0f)) {
+        const float delta = first ? fmaxf(mx, -1e30f) : fmaxf(mx, 0.f);
+        const float alpha = first ? 0.f : __builtin_amdgcn_exp2f(-delta);
+        m_run += delta;
+        l_run *= alpha;
+        set_qneg();
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[v] -= delta;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) u[i][v] *= alpha;
+      }
+      first = false;
+      float sum = 0.f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float p = __builtin_amdgcn_exp2f(s[v]);
+        s[v] = p;
+        sum += p;
+      }
+      l_run += sum;
+      h8 pf[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pf[t][e] = (_Float16)s[8 * t + e];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        if (i < TU) {
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            const _Float16* vq = pv + (32 * ks + 16 * t) * kPvStride + trV + 32 * i;
+            u[i] = mfma32(tr_frag(vq, vq + 8 * kPvStride), pf[t], u[i]);      // U^T: rows ranks, cols queries
+          }
+        }
+      }
+    }
+  }
+
+  // =================================== value projection, once ===================================
+  // ctx^T [DH, queries] = (V_v^h)^T U^T: the normalised accumulators are the operand as they are
+  f16v o[DT32];
+#pragma unroll
+  for (int dt = 0; dt < DT32; ++dt) o[dt] = zero16();
+  {
+    const float l = l_run + __shfl_xor(l_run, 32, 64);
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
+    const int trW = tr_lane_off(lane, WS) + 4 * g * WS;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      if (s < KSv) {
+        h8 uf;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) uf[i] = (_Float16)(u[s >> 1][8 * (s & 1) + i] * inv);
+#pragma unroll
+        for (int dt = 0; dt < DT32; ++dt) {
+          const _Float16* wp = wv + 16 * s * WS + trW + 32 * dt;
+          o[dt] = mfma32(tr_frag(wp, wp + 8 * WS), uf, o[dt]);
+        }
+      }
+    }
+  }
+
+  // ---- + b_v, write the context fragment-major: 4 consecutive features per 8-byte store
+  {
+    _Float16* C = (_Float16*)a.C;
+    const int cch = D / 64;
+    const int q = qw + l32;
+    const rsrc_t rsBv = rsrc_at(a.bv, a.bv ? (long long)D * 2 : 0, 0);
+    if (q < M) {
+      const int tok = tok0 + q;
+#pragma unroll
+      for (int dt = 0; dt < DT32; ++dt) {
+        const int dabs = col0 + 32 * dt;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const f4v bias = raw_to_f4<WT>(buf_load8(rsBv, (dabs + 8 * jj + 4 * g) * 2));
+          const size_t unit = ((size_t)((tok >> 5) * cch + (dabs >> 6)) * 4 + jj) * 64 + ((dabs >> 5) & 1) * 32 + (tok & 31);
+          h4 r;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) r[i] = (_Float16)(o[dt][4 * jj + i] + bias[i]);
+          *(h4*)(C + unit * 8 + 4 * g) = r;
+        }
+      }
+    }
+  }
+}
+
+template <int DH>
+hipError_t launch_abs(const AttnCoreArgs& a, hipStream_t s) {
+  const int nqb = (a.M + kAbsBQ - 1) / kAbsBQ;
+  const dim3 grid(a.B * a.H * nqb), block(kAbsThreads);
+  if (a.w_dt == DT_F16) hipLaunchKernelGGL((attn_absorbed_kernel<DH, DT_F16>), grid, block, 0, s, a, nqb);
+  else hipLaunchKernelGGL((attn_absorbed_kernel<DH, DT_BF16>), grid, block, 0, s, a, nqb);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool attn_absorbed_supported(const AttnCoreArgs& a) {
+  const int dh = a.H > 0 ? a.D / a.H : 0;
+  return a.per_head == 1 && !a.tiled && (dh == 64 || dh == 128) && a.rk <= 64 && a.rv <= 64 && a.rk % 16 == 0 &&
+         a.rv % 16 == 0 && a.rq % 16 == 0 && a.rq <= 64;
+}
+
+hipError_t launch_attn_absorbed(const AttnCoreArgs& a, hipStream_t s) {
+  if (!attn_absorbed_supported(a)) return hipErrorInvalidValue;
+  return a.D / a.H == 64 ? launch_abs<64>(a, s) : launch_abs<128>(a, s);
+}
+
+}  // namespace fsvd

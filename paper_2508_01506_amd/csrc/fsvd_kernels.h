@@ -76,6 +76,9 @@ struct AttnCoreArgs {
   void* C;                 // FM [B*M, D]
 };
 hipError_t launch_attn_core(const AttnCoreArgs& a, hipStream_t s);
+// the absorbed schedule for one factor pair per head with ranks <= 64 (fsvd_attn_absorbed.hip): no K / V rebuild
+bool attn_absorbed_supported(const AttnCoreArgs& a);
+hipError_t launch_attn_absorbed(const AttnCoreArgs& a, hipStream_t s);
 
 // ---- fused FFN core (Alg. 2 inner loops): FM P1 [T, r1] -> FM Z [T, r2] = phi(P1 V1 + b1) U2
 struct FfnCoreArgs {

@@ -350,11 +350,13 @@ def test_layer_with_per_head_attention_encoder_shapes(fb, name, weights):
         assert rel_err(got[b:b + 1], oracle_call(one, "layer")) < TOL_LAYER
 
 
-def test_per_head_factors_agree_with_block_diagonal_whole_matrix_factors(fb):
-    """The same projections written as whole-matrix factors (V block diagonal) go through fsvd_attention: both entry
-    points must agree to rounding (they differ only in how many zero ranks the rebuild multiplies)."""
+def test_per_head_factors_agree_with_block_diagonal_whole_matrix_factors(fb, monkeypatch):
+    """The same projections written as whole-matrix factors (V block diagonal) go through fsvd_attention.  With the
+    rebuilding schedule forced, both entry points must agree to rounding (they differ only in how many zero ranks the
+    rebuild multiplies); the absorbed schedule, which per-head ranks <= 64 take by default, rounds other intermediates
+    (M_h, w_h and u_h instead of q, K and V), so it agrees with the rebuilding one to two blocks' worth of hand-off
+    noise and with the oracle to the block's tolerance."""
     w, inp, dev = workload("ph_tiny_r16", fb)
-    got = gpu_call(dev, "attention").cpu().numpy()
     H, r, d_h = inp["q"]["V"].shape
     def whole(f):
         V = np.zeros((H * r, w.D), dtype=np.float32)
@@ -363,7 +365,29 @@ def test_per_head_factors_agree_with_block_diagonal_whole_matrix_factors(fb):
         up = lambda a: torch.from_numpy(a).to(device=DEV, dtype=dev["X"].dtype).contiguous()
         return fb.Factor(up(f["U"]), up(V), up(f["b"]))
     same = fb.fsvd_attention(dev["desc"], dev["X"], whole(inp["q"]), whole(inp["k"]), whole(inp["v"]), dev["o"]).cpu().numpy()
-    assert rel_err(got, same) < 1e-3
+    absorbed = gpu_call(dev, "attention").cpu().numpy()
+    monkeypatch.setenv("FSVD_ATTN_ABSORBED", "0")
+    rebuilt = gpu_call(dev, "attention").cpu().numpy()
+    monkeypatch.delenv("FSVD_ATTN_ABSORBED")
+    assert rel_err(rebuilt, same) < 1e-3
+    assert not np.array_equal(absorbed, rebuilt)          # the switch really selects another kernel
+    assert rel_err(absorbed, rebuilt) < 1.5 * TOL["attention"]
+
+
+@pytest.mark.parametrize("name", ["ph_tiny_r16", "ph_tiny_r48_causal", "ph_tiny_d128_r32", "ph_bert_base_b16_m512_r32",
+                                  "ph_bert_base_b16_m1024_r48"])
+def test_rebuilding_schedule_still_serves_per_head_factors(fb, name, monkeypatch):
+    """Per-head ranks <= 64 take the absorbed schedule by default; the rebuilding kernel stays reachable through
+    FSVD_ATTN_ABSORBED=0 and must meet the same bars (block tolerance, layer gate)."""
+    monkeypatch.setenv("FSVD_ATTN_ABSORBED", "0")
+    w, inp, dev = workload(name, fb)
+    got = gpu_call(dev, "attention").cpu().numpy()
+    lay = gpu_call(dev, "layer").cpu().numpy()
+    for b in sorted({0, w.B - 1}):
+        one = dict(inp, X=inp["X"][b:b + 1], key_len=None if inp["key_len"] is None else inp["key_len"][b:b + 1])
+        ref = oracle_call(one, "attention")
+        assert rel_err(got[b:b + 1], ref) < attn_block_tol(w, ref)
+        assert rel_err(lay[b:b + 1], oracle_call(one, "layer")) < TOL_LAYER
 
 
 # ------------------------------------------------------------------ entry points, small shapes, every element
