@@ -368,7 +368,10 @@ def main():
                 "l2_to_lds_measured_tbs": {"loads_only": dma_tbs[0], "with_stage_work": dma_tbs[1],
                                            "how": "fsvd_dma_probe: 256 workgroups, 32 KiB steps straight into LDS, 16 MiB per XCD"},
                 "kernel_ms": round(kms, 4), "algorithmic_flops": kflops,
-                "other_kernel_ms": {"ffn_core_kernel": round(ffn_ms, 4), "attn_core_kernel": round(attn_ms, 4)}}
+                "other_kernel_ms": {"ffn_core_kernel": round(ffn_ms, 4), "attn_core_kernel": round(attn_ms, 4)},
+                # one factor pair per head with ranks <= 64 is served by the absorbed schedule (attn_absorbed_kernel)
+                "attention_schedule": ("absorbed" if per_head and w.head_groups in (0, w.H) and rh <= 64 and w.d_h in (64, 128)
+                                       and os.environ.get("FSVD_ATTN_ABSORBED", "1")[:1] != "0" else "rebuild")}
 
     # ---- transient memory: the caller's workspace is the only scratch the library uses
     T, D, F = w.T, w.D, w.F

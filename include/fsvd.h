@@ -148,6 +148,13 @@ fsvd_status fsvd_attention(const fsvd_desc *desc, const void *X, const fsvd_fact
  * The rank-space activations P_a are [B*M, H * rank]; a head's K and V tiles are rebuilt from its own block of
  * r_a ranks, so the on-chip rebuild costs 2 * r_a * d_h FLOPs per key and tile instead of 2 * r * d_h with a
  * whole-matrix rank r.  Ranks are multiples of 16 (r_a <= d_h is the intended range, larger values work).
+ * With one pair per head and all three ranks <= 64 the core runs Alg. 1's schedule for r <= d_h with everything
+ * absorbed: M_h = V_q^(h) V_k^(h)^T once per workgroup, w = scale * (P_q^(h) M_h + b_q^(h) V_k^(h)^T), scores
+ * w . P_k^(h)[key] contracted over r_k (the q . b_k term is constant per row and cancels in the softmax), the
+ * context accumulated in rank space as u = softmax . P_v^(h) and projected once, u V_v^(h) + b_v^(h).  No Q, K or V
+ * tile exists, on chip or off; the fp16 hand-offs are then M_h, w, the probabilities and u.  The environment
+ * variable FSVD_ATTN_ABSORBED=0, read at every call, keeps the rebuilding schedule for such factors (a switch for
+ * comparisons; both meet the same tolerances).
  * Same conventions, limits and errors as fsvd_attention; additionally H * rank * D < 2^29.
  *
  * Grouped heads (appendix, grouped-head compression): with `groups` = G (a divisor of H, the same for q, k, v) the

@@ -30,20 +30,38 @@ constexpr int kAbsThreads = kAbsWaves * 64;
 constexpr int kAbsBQ = kAbsWaves * 32;       // queries per workgroup
 constexpr int kAbsBKV = 128;                 // keys per step
 constexpr float kLog2eA = 1.4426950408889634f;
-constexpr int kPvStride = wtile_stride(64);  // halves per row of the P_v tile [key][rank], padded like a weight tile
 
 // byte offset of the 16-byte unit (token, octet o of the contraction axis) of a fragment-major tensor with kchunks chunks
 __device__ __forceinline__ int fm_unit_off(int tok, int kchunks, int o) {
   return ((tok >> 5) * kchunks + (o >> 3)) * kFmChunkBytes + (o & 3) * kFmStepBytes + ((((o >> 2) & 1) << 5) + (tok & 31)) * 16;
 }
+// both halves of the wavefront combined: lane l and lane l ^ 32 receive op(x[l % 32], x[l % 32 + 32])
+__device__ __forceinline__ float halves_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float halves_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 
-template <int DH, int WT>
-__global__ void __launch_bounds__(kAbsThreads, 3) attn_absorbed_kernel(AttnCoreArgs a, int nqb) {
+// KS: matrix-core steps of 16 ranks that cover the largest of r_q, r_k, r_v (1..4); smaller ranks leave zero operands
+// wavefronts per SIMD the register budget is set for (= workgroups per compute unit): what the LDS tiles leave room for
+constexpr int abs_occupancy(int DH, int KS) { return KS <= 2 ? 4 : (DH == 128 ? 2 : 3); }
+
+template <int DH, int WT, int KS>
+__global__ void __launch_bounds__(kAbsThreads, abs_occupancy(DH, KS)) attn_absorbed_kernel(AttnCoreArgs a, int nqb) {
   constexpr int DT32 = DH / 32, DST = DH / 16;
+  constexpr int NT = (KS + 1) / 2;                       // 32-rank tiles
   constexpr int WS = wtile_stride(DH);
+  constexpr int PVS = NT == 1 ? 32 : wtile_stride(64);   // halves per row of the P_v tile: 64-byte rows need no padding
+  constexpr int OB = NT == 1 ? 2 : 3;                    // log2 of the octets staged per key of P_v
+  constexpr int NJV = (kAbsBKV << OB) / kAbsThreads;     // P_v units per thread and step
+  constexpr int NJK = kAbsBKV * 2 * KS / kAbsThreads;    // P_k units per thread and step (= KS)
 
-  __shared__ __attribute__((aligned(16))) _Float16 wv[64 * WS];                    // V_v^h [rank][DH], zero rows from r_v on
-  __shared__ __attribute__((aligned(16))) _Float16 pv[kAbsBKV * kPvStride];        // P_v^h [key][rank], zero columns from r_v on
+  __shared__ __attribute__((aligned(16))) _Float16 wv[16 * KS * WS];               // V_v^h [rank][DH], zero rows from r_v on
+  __shared__ __attribute__((aligned(16))) _Float16 pv[kAbsBKV * PVS];              // P_v^h [key][rank], zero columns from r_v on
+  __shared__ __attribute__((aligned(16))) u4 pk[4][KS][64];                        // P_k^h operands [key tile][step][lane]
 
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -60,8 +78,6 @@ __global__ void __launch_bounds__(kAbsThreads, 3) attn_absorbed_kernel(AttnCoreA
   const int nsteps = (kv_end + kAbsBKV - 1) / kAbsBKV;
   const int tok0 = b * M, col0 = h * DH;
   const int rq = a.rq, rk = a.rk, rv = a.rv;
-  const int TQ = (rq + 31) >> 5, TK = (rk + 31) >> 5, TU = (rv + 31) >> 5;      // 32-rank tiles: 1 or 2
-  const int KSq = rq >> 4, KSk = rk >> 4, KSv = rv >> 4;                          // matrix-core steps of 16 ranks: 1..4
   const int pch_q = (a.H * rq + kChunkK - 1) / kChunkK, pch_k = (a.H * rk + kChunkK - 1) / kChunkK,
             pch_v = (a.H * rv + kChunkK - 1) / kChunkK;
   const rsrc_t rsPq = rsrc_at(a.Pq, (long long)fm_bytes(T, a.H * rq), 0);
@@ -69,58 +85,56 @@ __global__ void __launch_bounds__(kAbsThreads, 3) attn_absorbed_kernel(AttnCoreA
   const rsrc_t rsPv = rsrc_at(a.Pv, (long long)fm_bytes(T, a.H * rv), 0);
   const int oq0 = (h * rq) >> 3, ok0 = (h * rk) >> 3, ov0 = (h * rv) >> 3;        // first octet of the head's rank windows
 
-  // ---- P_v staging: unit u = tid + 256 j -> (key u >> ob, octet u & (2^ob - 1)) of the step's [128 keys][8 or 4 octets]
-  const int ob = TU == 2 ? 3 : 2, nj = TU == 2 ? 4 : 2;
-  u4 v_raw[4];
-  auto issue_pv = [&](int step) {
+  // ---- staging of one step of 128 keys.  P_v: unit u = tid + 256 j -> (key u >> OB, octet u % 2^OB), written as rows
+  // [key][rank].  P_k: unit u -> (key tile, matrix-core step s, lane) in operand order: lane (key, g) of step s holds
+  // octet 2 s + g of the head's window.  Octets from the rank on are zeros.
+  u4 v_raw[NJV], k_raw[NJK];
+  auto issue_kv = [&](int step) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (j < nj) {
-        const int u = tid + kAbsThreads * j, oct = u & ((1 << ob) - 1);
-        int key = step * kAbsBKV + (u >> ob);
-        key = key < M ? key : M - 1;
-        v_raw[j] = buf_load16(rsPv, 8 * oct < rv ? fm_unit_off(tok0 + key, pch_v, ov0 + oct) : kOobOffset);
-      }
+    for (int j = 0; j < NJV; ++j) {
+      const int u = tid + kAbsThreads * j, oct = u & ((1 << OB) - 1);
+      int key = step * kAbsBKV + (u >> OB);
+      key = key < M ? key : M - 1;
+      v_raw[j] = buf_load16(rsPv, 8 * oct < rv ? fm_unit_off(tok0 + key, pch_v, ov0 + oct) : kOobOffset);
+    }
+#pragma unroll
+    for (int j = 0; j < NJK; ++j) {
+      const int u = tid + kAbsThreads * j, ln = u & 63, st = (u >> 6) % KS, kt = (u >> 6) / KS, oct = 2 * st + (ln >> 5);
+      int key = step * kAbsBKV + 32 * kt + (ln & 31);
+      key = key < M ? key : M - 1;
+      k_raw[j] = buf_load16(rsPk, 8 * oct < rk ? fm_unit_off(tok0 + key, pch_k, ok0 + oct) : kOobOffset);
     }
   };
-  auto commit_pv = [&]() {
+  auto commit_kv = [&]() {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (j < nj) {
-        const int u = tid + kAbsThreads * j, oct = u & ((1 << ob) - 1);
-        *(u4*)&pv[(u >> ob) * kPvStride + 8 * oct] = v_raw[j];
-      }
+    for (int j = 0; j < NJV; ++j) {
+      const int u = tid + kAbsThreads * j, oct = u & ((1 << OB) - 1);
+      *(u4*)&pv[(u >> OB) * PVS + 8 * oct] = v_raw[j];
     }
-  };
-  // ---- P_k operands of one tile of 32 keys: lane (key, g) of step s holds octet 2 s + g of the head's window
-  auto load_pk = [&](u4 (&dst)[4], int key0) {
-    int key = key0 + l32;
-    key = key < M ? key : M - 1;
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
-      if (s < KSk) dst[s] = buf_load16(rsPk, fm_unit_off(tok0 + key, pch_k, ok0 + 2 * s + g));
+    for (int j = 0; j < NJK; ++j) (&pk[0][0][0])[tid + kAbsThreads * j] = k_raw[j];
   };
 
-  issue_pv(0);
-  u4 kreg[4];
-  load_pk(kreg, 0);
-  u4 pq_raw[4];
+  issue_kv(0);
+  u4 pq_raw[KS];
   {
     int q = qw + l32;
     q = q < M ? q : M - 1;
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
-      if (s < KSq) pq_raw[s] = buf_load16(rsPq, fm_unit_off(tok0 + q, pch_q, oq0 + 2 * s + g));
+    for (int s = 0; s < KS; ++s)
+      pq_raw[s] = buf_load16(rsPq, 16 * s + 8 * g < rq ? fm_unit_off(tok0 + q, pch_q, oq0 + 2 * s + g) : kOobOffset);
   }
   // ---- V_v^h -> LDS as it lies in memory (16 bytes per lane); rows from r_v on are zeros
   {
-    constexpr int LPR = DH / 8, NU = 64 * LPR / kAbsThreads;
+    constexpr int LPR = DH / 8, NU = (16 * KS * LPR + kAbsThreads - 1) / kAbsThreads;
     const rsrc_t rs = rsrc_at(a.Vv, (long long)a.H * rv * DH * 2, 0);
 #pragma unroll
     for (int j = 0; j < NU; ++j) {
       const int u = tid + kAbsThreads * j, row = u / LPR, c8 = 8 * (u % LPR);
-      const u4 raw = buf_load16(rs, row < rv ? ((h * rv + row) * DH + c8) * 2 : kOobOffset);
-      stage_store16<WT>(&wv[row * WS + c8], raw);
+      if (row < 16 * KS) {
+        const u4 raw = buf_load16(rs, row < rv ? ((h * rv + row) * DH + c8) * 2 : kOobOffset);
+        stage_store16<WT>(&wv[row * WS + c8], raw);
+      }
     }
   }
 
@@ -128,64 +142,68 @@ __global__ void __launch_bounds__(kAbsThreads, 3) attn_absorbed_kernel(AttnCoreA
   // Row / column c of a 32-rank tile of M_h stands for rank 32 tile + sigma(c), sigma = c with bits 2 and 3 swapped:
   // accumulator register v of lane group g is row 8 (v / 4) + 4 g + v % 4, so registers 8 t .. 8 t + 7 are then the 8
   // consecutive ranks 16 t + 8 g .. of the tile: one fragment-major unit of P_q (for M_h's rows) or P_k (for W's rows).
-  h8 wq[4];
+  h8 wq[KS];
   {
+    constexpr int DSB = (NT == 2 && WT == DT_BF16) ? 2 : (DST < 4 ? DST : 4);   // contraction steps whose operands are requested together
+    const float qs = a.scale * kLog2eA;
     const int sig = (l32 & ~12) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
     const rsrc_t rsVq = rsrc_at(a.Vq, (long long)a.H * rq * DH * 2, 0);
     const rsrc_t rsVk = rsrc_at(a.Vk, (long long)a.H * rk * DH * 2, 0);
     const rsrc_t rsBq = rsrc_at(a.bq, a.bq ? (long long)D * 2 : 0, 0);
-    const float qs = a.scale * kLog2eA;
 #pragma unroll
-    for (int tk = 0; tk < 2; ++tk) {               // one 32-rank tile of W^T at a time: its two tiles of M_h stay short-lived
-      h8 w0 = {}, w1 = {};
-      if (tk < TK) {
-        f16v macc[2], wacc = zero16();
-        macc[0] = zero16();
-        macc[1] = zero16();
-        const int rowk = 32 * tk + sig;
+    for (int tk = 0; tk < NT; ++tk) {
+      f16v macc[NT], wacc = zero16();
 #pragma unroll
-        for (int ds = 0; ds < DST; ++ds) {
-          const int dof = (16 * ds + 8 * g) * 2;
-          const h8 vk = raw_to_h8<WT>(buf_load16(rsVk, rowk < rk ? (h * rk + rowk) * DH * 2 + dof : kOobOffset));
-          const h8 bqf = raw_to_h8<WT>(buf_load16(rsBq, col0 * 2 + dof));     // zeros without a bias
-          wacc = mfma32(vk, bqf, wacc);                    // b_q (V_k^h)^T, the same in every column
+      for (int tq = 0; tq < NT; ++tq) macc[tq] = zero16();
 #pragma unroll
-          for (int tq = 0; tq < 2; ++tq) {
-            if (tq < TQ) {
-              const int rowq = 32 * tq + sig;
-              const h8 vq = raw_to_h8<WT>(buf_load16(rsVq, rowq < rq ? (h * rq + rowq) * DH * 2 + dof : kOobOffset));
-              macc[tq] = mfma32(vq, vk, macc[tq]);         // rows r_q, cols r_k
-            }
+      for (int d0 = 0; d0 < DST; d0 += DSB) {
+        if (d0 > 0) __builtin_amdgcn_sched_barrier(0);
+        u4 vq_raw[NT][DSB], vk_raw[DSB], bq_raw[DSB];
+#pragma unroll
+        for (int ds = 0; ds < DSB; ++ds) {
+          const int dof = (16 * (d0 + ds) + 8 * g) * 2;
+          const int rowk = 32 * tk + sig;
+          vk_raw[ds] = buf_load16(rsVk, rowk < rk ? (h * rk + rowk) * DH * 2 + dof : kOobOffset);
+          bq_raw[ds] = buf_load16(rsBq, col0 * 2 + dof);                             // zeros without a bias
+#pragma unroll
+          for (int tq = 0; tq < NT; ++tq) {
+            const int rowq = 32 * tq + sig;
+            vq_raw[tq][ds] = buf_load16(rsVq, rowq < rq ? (h * rq + rowq) * DH * 2 + dof : kOobOffset);
           }
         }
 #pragma unroll
-        for (int tq = 0; tq < 2; ++tq)
+        for (int ds = 0; ds < DSB; ++ds) {
+          const h8 vk = raw_to_h8<WT>(vk_raw[ds]);
+          wacc = mfma32(vk, raw_to_h8<WT>(bq_raw[ds]), wacc);                      // b_q (V_k^h)^T, the same in every column
 #pragma unroll
-          for (int t = 0; t < 2; ++t) {
-            if (2 * tq + t < KSq) {
-              h8 mf;
-#pragma unroll
-              for (int i = 0; i < 8; ++i) mf[i] = (_Float16)macc[tq][8 * t + i];
-              wacc = mfma32(mf, __builtin_bit_cast(h8, pq_raw[2 * tq + t]), wacc);     // rows r_k, cols queries
-            }
-          }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          w0[i] = (_Float16)(wacc[i] * qs);
-          w1[i] = (_Float16)(wacc[8 + i] * qs);
+          for (int tq = 0; tq < NT; ++tq) macc[tq] = mfma32(raw_to_h8<WT>(vq_raw[tq][ds]), vk, macc[tq]);     // rows r_q, cols r_k
         }
-        if (2 * tk + 1 >= KSk) w1 = h8{};
       }
-      wq[2 * tk] = w0;
-      wq[2 * tk + 1] = w1;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        h8 mf;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) mf[i] = (_Float16)macc[s >> 1][8 * (s & 1) + i];
+        wacc = mfma32(mf, __builtin_bit_cast(h8, pq_raw[s]), wacc);                 // rows r_k, cols queries
+      }
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        if (2 * tk + t < KS) {
+          h8 r;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) r[i] = (_Float16)(wacc[8 * t + i] * qs);
+          wq[2 * tk + t] = r;
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);       // keep the next tile's operand requests behind this tile's products
     }
   }
 
   // =================================== key / value loop ===================================
-  const int trV = tr_lane_off(lane, kPvStride) + 4 * g * kPvStride;
-  f16v u[2];
-  u[0] = zero16();
-  u[1] = zero16();
+  const int trV = tr_lane_off(lane, PVS) + 4 * g * PVS;
+  f16v u[NT];
+#pragma unroll
+  for (int i = 0; i < NT; ++i) u[i] = zero16();
   float m_run = 0.f, l_run = 0.f;
   bool first = true;
   h8 kone = {}, qneg;
@@ -202,9 +220,9 @@ __global__ void __launch_bounds__(kAbsThreads, 3) attn_absorbed_kernel(AttnCoreA
   const int qlast = qw + 31;
 
   for (int step = 0; step < nsteps; ++step) {
-    __syncthreads();                 // every wavefront is done with the previous step's tile
-    commit_pv();
-    if (step + 1 < nsteps) issue_pv(step + 1);
+    __syncthreads();                 // every wavefront is done with the previous step's tiles
+    commit_kv();
+    if (step + 1 < nsteps) issue_kv(step + 1);
     __syncthreads();
 #pragma unroll 1
     for (int ks = 0; ks < 4; ++ks) {
@@ -213,9 +231,7 @@ __global__ void __launch_bounds__(kAbsThreads, 3) attn_absorbed_kernel(AttnCoreA
       if (a.causal && key0 > qlast) break;
       f16v s = mfma32(kone, qneg, zero16());
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if (i < KSk) s = mfma32(__builtin_bit_cast(h8, kreg[i]), wq[i], s);       // S^T - m: rows keys, cols queries
-      load_pk(kreg, key0 + 32);      // the next tile's operands (clamped to the sequence: an unused tile costs one read)
+      for (int i = 0; i < KS; ++i) s = mfma32(__builtin_bit_cast(h8, pk[ks][i][lane]), wq[i], s);   // S^T - m: rows keys, cols queries
       const bool need_mask = (key0 + 32 > kv_len) || (a.causal && key0 + 31 > qw);
       if (need_mask) {
         const int q = qw + l32;
@@ -229,7 +245,7 @@ __global__ void __launch_bounds__(kAbsThreads, 3) attn_absorbed_kernel(AttnCoreA
       float mx = s[0];
 #pragma unroll
       for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[v]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      mx = halves_max(mx);
       if (__any(first || mx > 8.0f)) {
         const float delta = first ? fmaxf(mx, -1e30f) : fmaxf(mx, 0.f);
         const float alpha = first ? 0.f : __builtin_amdgcn_exp2f(-delta);
@@ -239,7 +255,7 @@ __global__ void __launch_bounds__(kAbsThreads, 3) attn_absorbed_kernel(AttnCoreA
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[v] -= delta;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < NT; ++i)
 #pragma unroll
           for (int v = 0; v < 16; ++v) u[i][v] *= alpha;
       }
@@ -258,13 +274,11 @@ __global__ void __launch_bounds__(kAbsThreads, 3) attn_absorbed_kernel(AttnCoreA
 #pragma unroll
         for (int e = 0; e < 8; ++e) pf[t][e] = (_Float16)s[8 * t + e];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        if (i < TU) {
+      for (int i = 0; i < NT; ++i) {
 #pragma unroll
-          for (int t = 0; t < 2; ++t) {
-            const _Float16* vq = pv + (32 * ks + 16 * t) * kPvStride + trV + 32 * i;
-            u[i] = mfma32(tr_frag(vq, vq + 8 * kPvStride), pf[t], u[i]);      // U^T: rows ranks, cols queries
-          }
+        for (int t = 0; t < 2; ++t) {
+          const _Float16* vq = pv + (32 * ks + 16 * t) * PVS + trV + 32 * i;
+          u[i] = mfma32(tr_frag(vq, vq + 8 * PVS), pf[t], u[i]);      // U^T: rows ranks, cols queries
         }
       }
     }
@@ -276,20 +290,18 @@ __global__ void __launch_bounds__(kAbsThreads, 3) attn_absorbed_kernel(AttnCoreA
 #pragma unroll
   for (int dt = 0; dt < DT32; ++dt) o[dt] = zero16();
   {
-    const float l = l_run + __shfl_xor(l_run, 32, 64);
+    const float l = halves_sum(l_run);
     const float inv = l > 0.f ? 1.0f / l : 0.f;
     const int trW = tr_lane_off(lane, WS) + 4 * g * WS;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      if (s < KSv) {
-        h8 uf;
+    for (int s = 0; s < KS; ++s) {
+      h8 uf;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) uf[i] = (_Float16)(u[s >> 1][8 * (s & 1) + i] * inv);
+      for (int i = 0; i < 8; ++i) uf[i] = (_Float16)(u[s >> 1][8 * (s & 1) + i] * inv);
 #pragma unroll
-        for (int dt = 0; dt < DT32; ++dt) {
-          const _Float16* wp = wv + 16 * s * WS + trW + 32 * dt;
-          o[dt] = mfma32(tr_frag(wp, wp + 8 * WS), uf, o[dt]);
-        }
+      for (int dt = 0; dt < DT32; ++dt) {
+        const _Float16* wp = wv + 16 * s * WS + trW + 32 * dt;
+        o[dt] = mfma32(tr_frag(wp, wp + 8 * WS), uf, o[dt]);
       }
     }
   }
@@ -319,26 +331,36 @@ __global__ void __launch_bounds__(kAbsThreads, 3) attn_absorbed_kernel(AttnCoreA
   }
 }
 
-template <int DH>
+template <int DH, int KS>
 hipError_t launch_abs(const AttnCoreArgs& a, hipStream_t s) {
   const int nqb = (a.M + kAbsBQ - 1) / kAbsBQ;
   const dim3 grid(a.B * a.H * nqb), block(kAbsThreads);
-  if (a.w_dt == DT_F16) hipLaunchKernelGGL((attn_absorbed_kernel<DH, DT_F16>), grid, block, 0, s, a, nqb);
-  else hipLaunchKernelGGL((attn_absorbed_kernel<DH, DT_BF16>), grid, block, 0, s, a, nqb);
+  if (a.w_dt == DT_F16) hipLaunchKernelGGL((attn_absorbed_kernel<DH, DT_F16, KS>), grid, block, 0, s, a, nqb);
+  else hipLaunchKernelGGL((attn_absorbed_kernel<DH, DT_BF16, KS>), grid, block, 0, s, a, nqb);
   return hipGetLastError();
+}
+template <int DH>
+hipError_t launch_abs_dh(const AttnCoreArgs& a, hipStream_t s) {
+  const int rmax = a.rq > a.rk ? (a.rq > a.rv ? a.rq : a.rv) : (a.rk > a.rv ? a.rk : a.rv);
+  switch ((rmax + 15) / 16) {
+    case 1: return launch_abs<DH, 1>(a, s);
+    case 2: return launch_abs<DH, 2>(a, s);
+    case 3: return launch_abs<DH, 3>(a, s);
+    default: return launch_abs<DH, 4>(a, s);
+  }
 }
 
 }  // namespace
 
 bool attn_absorbed_supported(const AttnCoreArgs& a) {
   const int dh = a.H > 0 ? a.D / a.H : 0;
-  return a.per_head == 1 && !a.tiled && (dh == 64 || dh == 128) && a.rk <= 64 && a.rv <= 64 && a.rk % 16 == 0 &&
-         a.rv % 16 == 0 && a.rq % 16 == 0 && a.rq <= 64;
+  return a.per_head == 1 && !a.tiled && (dh == 64 || dh == 128) && a.rq <= 64 && a.rk <= 64 && a.rv <= 64 &&
+         a.rq % 16 == 0 && a.rk % 16 == 0 && a.rv % 16 == 0;
 }
 
 hipError_t launch_attn_absorbed(const AttnCoreArgs& a, hipStream_t s) {
   if (!attn_absorbed_supported(a)) return hipErrorInvalidValue;
-  return a.D / a.H == 64 ? launch_abs<64>(a, s) : launch_abs<128>(a, s);
+  return a.D / a.H == 64 ? launch_abs_dh<64>(a, s) : launch_abs_dh<128>(a, s);
 }
 
 }  // namespace fsvd

@@ -137,6 +137,10 @@ _register(_wl(9, 1, name="ph_tiny_r48_causal", B=2, M=300, D=192, H=3, F=384, r_
               mask="causal", r_head=48))
 _register(_wl(9, 2, name="ph_tiny_d128_r32", B=1, M=270, D=256, H=2, F=512, r_attn=80, r_ffn=64, dtype="bf16",
               r_head=32))
+_register(_wl(9, 3, name="ph_tiny_d128_r64", B=2, M=200, D=256, H=2, F=512, r_attn=80, r_ffn=64, dtype="fp16",
+              mask="padding", min_len=3, r_head=64))
+_register(_wl(9, 4, name="ph_tiny_d128_r48_causal", B=1, M=330, D=384, H=3, F=512, r_attn=80, r_ffn=64, dtype="bf16",
+              mask="causal", r_head=48))
 
 
 # The paper's FFN rank ablation (table "Computation-efficiency ablation": batch 16, BERT-base widths, sequence

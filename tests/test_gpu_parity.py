@@ -18,6 +18,8 @@ benchmark configurations (whole sequences, reported by test_full_size_sampled_ro
 """
 import os
 
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -277,10 +279,11 @@ def attn_block_tol(w, ref):
 
 
 @pytest.mark.parametrize("weights", WEIGHTS)
-@pytest.mark.parametrize("name", ["ph_tiny_r16", "ph_tiny_r48_causal", "ph_tiny_d128_r32"])
+@pytest.mark.parametrize("name", ["ph_tiny_r16", "ph_tiny_r48_causal", "ph_tiny_d128_r32", "ph_tiny_d128_r64",
+                                  "ph_tiny_d128_r48_causal"])
 def test_attention_with_per_head_factors_small(fb, name, weights):
     """Every element of the attention block with per-head factors (ranks 16, 48 - which straddles the 64-rank
-    chunks - and 32 with 128-wide heads) against the per-head oracle."""
+    chunks - and 32, 48, 64 with 128-wide heads) against the per-head oracle."""
     w, inp, dev = workload(name, fb, weights)
     got = gpu_call(dev, "attention").cpu().numpy()
     assert np.isfinite(got).all()
@@ -331,8 +334,34 @@ def test_layer_with_grouped_head_factors_encoder_shapes(fb, name):
         assert rel_err(got[b:b + 1], oracle_call(one, "layer")) < TOL_LAYER
 
 
+@pytest.mark.parametrize("ranks", [(32, 16, 48), (16, 64, 32), (64, 48, 16)])
+@pytest.mark.parametrize("name", ["ph_tiny_d128_r64", "ph_bert_base_b16_m512_r64"])
+def test_per_head_factors_with_three_different_ranks(fb, name, ranks):
+    """r_q, r_k and r_v differ (the first ranks of every head's pair are kept): the rank windows of the three
+    projections then lie at different places of their concatenated axes."""
+    w, inp, _ = workload(name, fb)
+    inp = dict(inp)
+    if w.B > 2:
+        inp["X"] = inp["X"][:2]
+        inp["key_len"] = None if inp["key_len"] is None else inp["key_len"][:2]
+        w = dataclasses.replace(w, B=2)
+        inp["workload"] = w
+    for nm, r in zip("qkv", ranks):
+        f = inp[nm]
+        H, r0, d_h = f["V"].shape
+        inp[nm] = {"U": np.ascontiguousarray(f["U"].reshape(w.D, H, r0)[:, :, :r].reshape(w.D, H * r)),
+                   "V": np.ascontiguousarray(f["V"][:, :r]), "b": f["b"]}
+    dev = fb.to_device(inp, DEV)
+    got = gpu_call(dev, "attention").cpu().numpy()
+    ref = oracle_call(inp, "attention")
+    assert np.isfinite(got).all()
+    assert rel_err(got, ref) < attn_block_tol(w, ref)
+    assert rel_err(gpu_call(dev, "layer").cpu().numpy(), oracle_call(inp, "layer")) < TOL_LAYER
+
+
 @pytest.mark.parametrize("norm", ["post_ln", "pre_ln"])
-@pytest.mark.parametrize("name", ["ph_tiny_r16", "ph_tiny_r48_causal", "ph_tiny_d128_r32"])
+@pytest.mark.parametrize("name", ["ph_tiny_r16", "ph_tiny_r48_causal", "ph_tiny_d128_r32", "ph_tiny_d128_r64",
+                                  "ph_tiny_d128_r48_causal"])
 def test_layer_with_per_head_attention_meets_the_gate(fb, name, norm):
     w = W.get_workload(name, norm=norm)
     inp = W.make_inputs(w)
