@@ -673,7 +673,7 @@ fsvd_status run_decode_core(const fsvd_desc* d, int r_k, int r_v, const void* W,
   ca.B = d->B; ca.t_max = d->M; ca.r_k = r_k; ca.r_v = r_v; ca.nsplit = pl.nsplit;
   ca.stats = (float*)(ws + pl.stats); ca.upart = (_Float16*)(ws + pl.upart);
   FSVD_HIP(launch_decode_core(ca, s));
-  FSVD_HIP(launch_decode_merge(ca.stats, ca.upart, d->B, pl.nsplit, d->H, r_v, u_out, s));
+  FSVD_HIP(launch_decode_merge(ca.stats, ca.upart, n_keys, d->B, d->M, pl.nsplit, d->H, r_v, u_out, s));
   return FSVD_OK;
 }
 }  // namespace

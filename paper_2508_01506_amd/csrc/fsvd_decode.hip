@@ -104,6 +104,60 @@ __global__ void __launch_bounds__(256) decode_absorb_kernel(const _Float16* __re
 }
 
 // ---------------------------------------------------------------------------------------------------------------
+// How the keys of the B sequences are dealt to the G = B * nsplit workgroups of the pass over the cache.  Sequences
+// differ in length, so an equal number of parts per sequence leaves the workgroups of short sequences idle while the
+// longest one finishes.  Instead every sequence gets parts in proportion to its tiles of 32 keys: with `tpw` a (nearly)
+// smallest number of tiles per workgroup for which sum_b parts_b <= G, parts_b = clamp(ceil(tiles_b / tpw), 1, 32),
+// sequence b owns the slots first_b .. first_b + parts_b - 1 (first = exclusive prefix sum) and its part s the tiles
+// s * ceil(tiles_b / parts_b) ...  Computed by every wavefront for itself from n_keys (lane = sequence, B <= 64; the
+// core and the merge kernel must agree, and both evaluate exactly this function); for B > 64 every sequence has
+// nsplit parts.  All 64 lanes must call it; lane b < B receives its sequence's values.
+// ---------------------------------------------------------------------------------------------------------------
+__device__ __forceinline__ int wave_sum(int x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+__device__ __forceinline__ void decode_parts_of_lane(const int32_t* __restrict__ n_keys, int B, int t_max, int nsplit, int lane,
+                                                     int& parts, int& first) {
+  if (B > 64) {                           // not balanced: caller indexes by sequence
+    parts = nsplit;
+    first = 0;
+    return;
+  }
+  const int G = B * nsplit;
+  int nt = 0;
+  if (lane < B) {
+    int n = n_keys[lane];
+    n = n < 0 ? 0 : (n > t_max ? t_max : n);
+    nt = (n + 31) >> 5;
+  }
+  const int total = wave_sum(nt);
+  // ceil(total / (G - B)) tiles per workgroup always fit (sum_b ceil(tiles_b / tpw) <= total / tpw + B <= G; G >= 4 B here);
+  // a few smaller values are tried, the smallest that still fits is kept
+  auto parts_at = [&](int t) {
+    int q = (nt + t - 1) / t;
+    q = q < 1 ? 1 : (q > 32 ? 32 : q);
+    return lane < B ? q : 0;
+  };
+  int tpw = (total + (G - B) - 1) / (G - B);
+  tpw = tpw < 1 ? 1 : tpw;
+  for (int it = 0; it < 8 && tpw > 1; ++it) {
+    if (wave_sum(parts_at(tpw - 1)) > G) break;
+    --tpw;
+  }
+  const int p = parts_at(tpw);
+  int incl = p;                           // inclusive prefix sum over the lanes
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int y = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += y;
+  }
+  parts = p;
+  first = incl - p;
+}
+
+// ---------------------------------------------------------------------------------------------------------------
 // The pass over the cache.  One workgroup (8 wavefronts) = one sequence x one part of its keys, all heads at once.
 // Per tile of 32 keys:
 //   S^T [32 keys, 32 heads] = P_k tile x W^T: the contraction over r_k is split over the wavefronts (64-rank chunks
@@ -121,12 +175,31 @@ __global__ void __launch_bounds__(512, 1) decode_core_kernel(DecodeCoreArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int b = blockIdx.x / a.nsplit, sp = blockIdx.x % a.nsplit;
+  // this workgroup's (sequence, part): slot blockIdx.x of the balanced split (a workgroup past the last slot has nothing to do)
+  int b, sp, nparts;
+  {
+    int parts, first;
+    decode_parts_of_lane(a.n_keys, a.B, a.t_max, a.nsplit, lane, parts, first);
+    if (a.B > 64) {
+      b = blockIdx.x / a.nsplit;
+      sp = blockIdx.x % a.nsplit;
+      nparts = a.nsplit;
+    } else {
+      const unsigned long long mine = __ballot((int)blockIdx.x >= first && (int)blockIdx.x < first + parts);
+      if (mine == 0) return;              // the same in every wavefront: the whole workgroup leaves
+      b = __builtin_ctzll(mine);
+      sp = (int)blockIdx.x - __shfl(first, b, 64);
+      nparts = __shfl(parts, b, 64);
+    }
+    b = __builtin_amdgcn_readfirstlane(b);
+    sp = __builtin_amdgcn_readfirstlane(sp);
+    nparts = __builtin_amdgcn_readfirstlane(nparts);
+  }
   const int kch = (a.r_k + 63) / 64, vtl = (a.r_v + 31) / 32, ktiles = (a.t_max + 31) / 32;
   int n = a.n_keys[b];
   n = n < 0 ? 0 : (n > a.t_max ? a.t_max : n);
   const int ntiles = (n + 31) / 32;
-  const int tps = (ntiles + a.nsplit - 1) / a.nsplit;
+  const int tps = (ntiles + nparts - 1) / nparts;
   const int j0 = sp * tps, j1 = (j0 + tps < ntiles) ? j0 + tps : ntiles;
 
   float m_run = -1e30f, l_run = 0.f;
@@ -243,7 +316,7 @@ __global__ void __launch_bounds__(512, 1) decode_core_kernel(DecodeCoreArgs a) {
 
   // ---- partial results of this part
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  const size_t slot = (size_t)b * a.nsplit + sp;
+  const size_t slot = blockIdx.x;          // = first slot of the sequence + part
   if (wave == 0 && g == 0) {
     a.stats[slot * 64 + l32] = m_run;
     a.stats[slot * 64 + 32 + l32] = l_tot;
@@ -266,54 +339,84 @@ __global__ void __launch_bounds__(512, 1) decode_core_kernel(DecodeCoreArgs a) {
 }
 
 // merge the parts of one sequence: u[b, h, :] = sum_s wgt_s U_s / sum_s wgt_s, wgt_s = l_s 2^(m_s - max m).
-// One workgroup per (64 ranks, sequence): the partial sums are read as they were written (32 heads contiguous per rank),
-// transposed through LDS and written as runs of 64 ranks per head.
+// One workgroup per (64 ranks, sequence): the partial sums are read as they were written (32 heads contiguous per rank,
+// 16 bytes = 8 heads per lane; the first 16 parts are requested before the weights are worked out, so the two waits
+// overlap), transposed through LDS and written as runs of 64 ranks per head.
 __global__ void __launch_bounds__(256) decode_merge_kernel(const float* __restrict__ stats, const _Float16* __restrict__ upart,
-                                                           int nsplit, int H, int r_v, float* u_out) {
+                                                           const int32_t* __restrict__ n_keys, int B, int t_max, int nsplit, int H,
+                                                           int r_v, float* u_out) {
   __shared__ float tile[32][65];
   __shared__ float wgt[32][32];               // [part][head], normalised weights
   __shared__ float st[32][64];                // the parts' statistics
   const int r0 = 64 * blockIdx.x, b = blockIdx.y;
-  const size_t slot0 = (size_t)b * nsplit;
-  for (int i = threadIdx.x; i < nsplit * 64; i += 256) st[i >> 6][i & 63] = stats[slot0 * 64 + i];
+  int np, first_slot;
+  {
+    int parts, first;
+    decode_parts_of_lane(n_keys, B, t_max, nsplit, threadIdx.x & 63, parts, first);
+    np = B > 64 ? nsplit : __shfl(parts, b, 64);
+    first_slot = B > 64 ? b * nsplit : __shfl(first, b, 64);
+    np = __builtin_amdgcn_readfirstlane(np);
+    first_slot = __builtin_amdgcn_readfirstlane(first_slot);
+  }
+  const size_t slot0 = (size_t)first_slot;
+  // thread -> (rank rl, 8 heads from h0)
+  const int rl = threadIdx.x >> 2, h0 = 8 * (threadIdx.x & 3), rho = r0 + rl;
+  h8 x[16];
+#pragma unroll
+  for (int s = 0; s < 16; ++s) {
+    x[s] = h8{};
+    if (s < np && rho < r_v) x[s] = *(const h8*)&upart[((slot0 + s) * r_v + rho) * 32 + h0];
+  }
+  for (int i = threadIdx.x; i < np * 64; i += 256) st[i >> 6][i & 63] = stats[slot0 * 64 + i];
   __syncthreads();
   if (threadIdx.x < 32) {
     const int h = threadIdx.x;
     float M = -1e30f;
-    for (int s = 0; s < nsplit; ++s)
+    for (int s = 0; s < np; ++s)
       if (st[s][32 + h] > 0.f) M = fmaxf(M, st[s][h]);
     float tot = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
+    for (int s = 0; s < np; ++s) {
       const float l = st[s][32 + h];
       const float w = l > 0.f ? l * exp2f(st[s][h] - M) : 0.f;
       wgt[s][h] = w;
       tot += w;
     }
     const float inv = tot > 0.f ? 1.0f / tot : 0.f;
-    for (int s = 0; s < nsplit; ++s) wgt[s][h] *= inv;
+    for (int s = 0; s < np; ++s) wgt[s][h] *= inv;
   }
   __syncthreads();
-  const int h = threadIdx.x & 31;
-  for (int k = 0; k < 8; ++k) {
-    const int rl = (threadIdx.x >> 5) + 8 * k, rho = r0 + rl;
-    float acc = 0.f;
-    if (rho < r_v) {
-      // fixed order.  Every part's slot is read (independent requests, all in flight together); a part without keys has
-      // weight 0 and whatever its slot holds is discarded by the select, not multiplied.
-#pragma unroll 8
-      for (int s = 0; s < nsplit; ++s) {
-        const float w = wgt[s][h];
-        const float x = (float)upart[((slot0 + s) * r_v + rho) * 32 + h];
-        acc += w > 0.f ? w * x : 0.f;
+  {
+    // fixed order.  A part without keys has weight 0 and whatever its slot holds is discarded by the select, not multiplied.
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+      if (s < np) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float w = wgt[s][h0 + e];
+          acc[e] += w > 0.f ? w * (float)x[s][e] : 0.f;
+        }
       }
     }
-    tile[h][rl] = acc;
+    for (int s = 16; s < np; ++s) {
+      h8 y = {};
+      if (rho < r_v) y = *(const h8*)&upart[((slot0 + s) * r_v + rho) * 32 + h0];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float w = wgt[s][h0 + e];
+        acc[e] += w > 0.f ? w * (float)y[e] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) tile[h0 + e][rl] = acc[e];
   }
   __syncthreads();
-  const int rl = threadIdx.x & 63;
+  const int rl2 = threadIdx.x & 63;
   for (int k = 0; k < 8; ++k) {
     const int hh = (threadIdx.x >> 6) + 4 * k;
-    if (hh < H && r0 + rl < r_v) u_out[((size_t)b * H + hh) * r_v + r0 + rl] = tile[hh][rl];
+    if (hh < H && r0 + rl2 < r_v) u_out[((size_t)b * H + hh) * r_v + r0 + rl2] = tile[hh][rl2];
   }
 }
 
@@ -434,8 +537,10 @@ hipError_t launch_decode_core(const DecodeCoreArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_decode_merge(const float* stats, const void* upart, int B, int nsplit, int H, int r_v, float* u_out, hipStream_t s) {
-  hipLaunchKernelGGL(decode_merge_kernel, dim3((r_v + 63) / 64, B), dim3(256), 0, s, stats, (const _Float16*)upart, nsplit, H, r_v, u_out);
+hipError_t launch_decode_merge(const float* stats, const void* upart, const int32_t* n_keys, int B, int t_max, int nsplit, int H, int r_v,
+                               float* u_out, hipStream_t s) {
+  hipLaunchKernelGGL(decode_merge_kernel, dim3((r_v + 63) / 64, B), dim3(256), 0, s, stats, (const _Float16*)upart, n_keys, B, t_max, nsplit,
+                     H, r_v, u_out);
   return hipGetLastError();
 }
 

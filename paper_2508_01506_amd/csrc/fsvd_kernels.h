@@ -121,15 +121,16 @@ struct DecodeCoreArgs {
   const void* vcache;     // per sequence: P_v^T in operand order (decode_vcache_seq_bytes)
   const int32_t* n_keys;  // device [B]: valid keys of each sequence
   int B, t_max, r_k, r_v, nsplit;
-  float* stats;           // [B][nsplit][64]: running maximum (32 heads) | sum (32 heads)
-  _Float16* upart;        // [B][nsplit][r_v][32 heads]: U / l
+  float* stats;           // [B * nsplit slots][64]: running maximum (32 heads) | sum (32 heads); slot = workgroup
+  _Float16* upart;        // [B * nsplit slots][r_v][32 heads]: U / l
 };
 hipError_t launch_decode_cache_write(const void* src, const int32_t* t_start, int B, int t_max, int r, int n_new, int which,
                                      void* cache, hipStream_t s);
 hipError_t launch_decode_absorb(const void* q, const void* Vk, int w_dt, int B, int D, int H, int r_k, float scale, void* W,
                                 hipStream_t s);
 hipError_t launch_decode_core(const DecodeCoreArgs& a, hipStream_t s);
-hipError_t launch_decode_merge(const float* stats, const void* upart, int B, int nsplit, int H, int r_v, float* u_out, hipStream_t s);
+hipError_t launch_decode_merge(const float* stats, const void* upart, const int32_t* n_keys, int B, int t_max, int nsplit, int H, int r_v,
+                               float* u_out, hipStream_t s);
 hipError_t launch_decode_value(const float* u, const void* Vv, const void* bv, int w_dt, int B, int D, int H, int r_v, void* ctx,
                                hipStream_t s);
 hipError_t launch_decode_append(const void* pk, const void* pv, const int32_t* t_len, int B, int t_max, int r_k, int r_v,
