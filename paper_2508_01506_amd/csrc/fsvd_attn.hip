@@ -431,7 +431,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
           float m = s[qt][0];
 #pragma unroll
           for (int v = 1; v < 16; ++v) m = fmaxf(m, s[qt][v]);
-          mx[qt] = fmaxf(m, __shfl_xor(m, 32, 64));
+          mx[qt] = halves_max(m);
           raise = raise || (mx[qt] > 8.0f);
         }
         if (__any(raise)) {
@@ -493,7 +493,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_core_kernel(AttnCoreArgs
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
       const int q = qw + 32 * qt + l32;
-      const float l = l_run[qt] + __shfl_xor(l_run[qt], 32, 64);
+      const float l = halves_sum(l_run[qt]);
       const float inv = l > 0.f ? 1.0f / l : 0.f;
       if (q < M) {
         const int tok = tok0 + q;

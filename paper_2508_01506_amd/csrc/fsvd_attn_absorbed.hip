@@ -35,16 +35,6 @@ constexpr float kLog2eA = 1.4426950408889634f;
 __device__ __forceinline__ int fm_unit_off(int tok, int kchunks, int o) {
   return ((tok >> 5) * kchunks + (o >> 3)) * kFmChunkBytes + (o & 3) * kFmStepBytes + ((((o >> 2) & 1) << 5) + (tok & 31)) * 16;
 }
-// both halves of the wavefront combined: lane l and lane l ^ 32 receive op(x[l % 32], x[l % 32 + 32])
-__device__ __forceinline__ float halves_max(float x) {
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float halves_sum(float x) {
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
 // KS: matrix-core steps of 16 ranks that cover the largest of r_q, r_k, r_v (1..4); smaller ranks leave zero operands
 // wavefronts per SIMD the register budget is set for (= workgroups per compute unit): what the LDS tiles leave room for
 constexpr int abs_occupancy(int DH, int KS) { return KS <= 2 ? 4 : (DH == 128 ? 2 : 3); }

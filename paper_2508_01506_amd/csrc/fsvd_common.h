@@ -164,6 +164,17 @@ __device__ __forceinline__ f4v raw_to_f4(u2 raw) {
   return o;
 }
 
+// The two halves of a wavefront combined: lanes l and l ^ 32 both receive op(x[l % 32], x[l % 32 + 32]).  One
+// v_permlane32_swap exchanges the upper half of one register with the lower half of another: no LDS round trip.
+__device__ __forceinline__ float halves_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float halves_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Fragment-major ("FM") layout of an fp16 activation A[T, K] that will be an MFMA operand.
 // Tokens are grouped in tiles of 32 and the contraction axis in chunks of 64; one (tile, chunk)

@@ -278,7 +278,7 @@ __global__ void __launch_bounds__(512, 1) decode_core_kernel(DecodeCoreArgs a) {
       float mx = s[0];
 #pragma unroll
       for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[v]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      mx = halves_max(mx);
       if (__any(mx > m_run + 8.0f)) {                      // lazily raised reference maximum, as in the prefill kernel
         const float m_new = fmaxf(m_run, mx);
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
@@ -315,7 +315,7 @@ __global__ void __launch_bounds__(512, 1) decode_core_kernel(DecodeCoreArgs a) {
   }
 
   // ---- partial results of this part
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float l_tot = halves_sum(l_run);
   const size_t slot = blockIdx.x;          // = first slot of the sequence + part
   if (wave == 0 && g == 0) {
     a.stats[slot * 64 + l32] = m_run;

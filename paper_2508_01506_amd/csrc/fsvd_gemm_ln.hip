@@ -196,7 +196,7 @@ __global__ void __launch_bounds__(512, 1) linear_ln_kernel(LinearLnArgs a) {
         }
       }
     }
-    sum += __shfl_xor(sum, 32, 64);
+    sum = halves_sum(sum);
     if (g == 0) red[wave][32 * mt + l32] = sum;
   }
   __syncthreads();
@@ -219,7 +219,7 @@ __global__ void __launch_bounds__(512, 1) linear_ln_kernel(LinearLnArgs a) {
         const float dlt = acc[mt][j][v] - mean[mt];
         sq = fmaf(dlt, dlt, sq);
       }
-    sq += __shfl_xor(sq, 32, 64);
+    sq = halves_sum(sq);
     if (g == 0) red[wave][32 * mt + l32] = sq;
   }
   __syncthreads();
