@@ -723,6 +723,24 @@ def test_no_bias_custom_scale_and_activations(fb):
         assert rel_err(got, ref) < TOL_LAYER
 
 
+@pytest.mark.parametrize("name", ["ph_tiny_r16", "ph_tiny_d128_r48_causal"])
+def test_per_head_factors_without_biases_and_with_a_caller_scale(fb, name):
+    """The absorbed schedule folds b_q into the absorbed queries and adds b_v at the end: absent biases must read as
+    zeros there too, and a caller's softmax scale must reach the absorbed queries."""
+    w = W.get_workload(name)
+    inp = W.make_inputs(w)
+    dev = fb.to_device(inp, DEV)
+    for n in ("q", "k", "v", "o"):
+        inp[n]["b"] = None
+        dev[n].b = None
+    dev["desc"] = fb.make_desc(w.B, w.M, w.D, w.H, w.F, dev["X"].dtype, softmax_scale=0.07, key_len=dev["key_len"],
+                               causal=(w.mask == "causal"), norm=w.norm, ln_eps=w.ln_eps)
+    got = gpu_call(dev, "attention").cpu().numpy()
+    ref = O.attention_per_head(inp["X"], inp["q"], inp["k"], inp["v"], inp["o"], w.H, inp["causal"], inp["key_len"], 0.07)
+    assert np.isfinite(got).all()
+    assert rel_err(got, ref) < attn_block_tol(w, ref)
+
+
 @pytest.mark.parametrize("odt,eps", [(torch.float16, 2.0 ** -11), (torch.bfloat16, 2.0 ** -8)])
 def test_sixteen_bit_outputs_round_the_fp32_result(fb, odt, eps):
     w, inp, dev = workload("tiny_pad", fb)
