@@ -37,7 +37,7 @@ __device__ __forceinline__ int fm_unit_off(int tok, int kchunks, int o) {
 }
 // KS: matrix-core steps of 16 ranks that cover the largest of r_q, r_k, r_v (1..4); smaller ranks leave zero operands
 // wavefronts per SIMD the register budget is set for (= workgroups per compute unit): what the LDS tiles leave room for
-constexpr int abs_occupancy(int DH, int KS) { return KS <= 2 ? 4 : (DH == 128 ? 2 : 3); }
+constexpr int abs_occupancy(int DH, int KS) { return KS <= 2 ? 4 : ((DH == 128 && KS == 4) ? 2 : 3); }
 
 template <int DH, int WT, int KS>
 __global__ void __launch_bounds__(kAbsThreads, abs_occupancy(DH, KS)) attn_absorbed_kernel(AttnCoreArgs a, int nqb) {
@@ -132,60 +132,82 @@ __global__ void __launch_bounds__(kAbsThreads, abs_occupancy(DH, KS)) attn_absor
   // Row / column c of a 32-rank tile of M_h stands for rank 32 tile + sigma(c), sigma = c with bits 2 and 3 swapped:
   // accumulator register v of lane group g is row 8 (v / 4) + 4 g + v % 4, so registers 8 t .. 8 t + 7 are then the 8
   // consecutive ranks 16 t + 8 g .. of the tile: one fragment-major unit of P_q (for M_h's rows) or P_k (for W's rows).
+  // M_h is the same for the whole workgroup: its 32 x 32 tiles are dealt to the wavefronts (tile (tq, tk) to wavefront
+  // 2 tq + tk, so that not every wavefront of every workgroup asks the L2 for the same few lines of V_q and V_k at the
+  // same moment), handed over through LDS as ready operands, and every wavefront multiplies them with its own queries.
   h8 wq[KS];
   {
-    constexpr int DSB = (NT == 2 && WT == DT_BF16) ? 2 : (DST < 4 ? DST : 4);   // contraction steps whose operands are requested together
+    constexpr int DSB = DST < 4 ? DST : 4;     // contraction steps whose operands are requested together
+    u4* const mfl = (u4*)pv;                   // [tk][step s][lane]: M_h operands (the P_v tile is not in use yet)
+    f4v* const wbl = (f4v*)(mfl + NT * KS * 64);   // [tk][quad][lane]: b_q (V_k^h)^T, rows r_k, the same in every column
+    static_assert(NT * KS * 64 * 16 + NT * 4 * 64 * 16 <= kAbsBKV * PVS * 2, "the hand-over must fit in the P_v tile");
     const float qs = a.scale * kLog2eA;
-    const int sig = (l32 & ~12) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
-    const rsrc_t rsVq = rsrc_at(a.Vq, (long long)a.H * rq * DH * 2, 0);
-    const rsrc_t rsVk = rsrc_at(a.Vk, (long long)a.H * rk * DH * 2, 0);
-    const rsrc_t rsBq = rsrc_at(a.bq, a.bq ? (long long)D * 2 : 0, 0);
-#pragma unroll
-    for (int tk = 0; tk < NT; ++tk) {
-      f16v macc[NT], wacc = zero16();
-#pragma unroll
-      for (int tq = 0; tq < NT; ++tq) macc[tq] = zero16();
+    const int tq = wave >> 1, tk = wave & 1;
+    if (tq < NT && tk < NT) {
+      const int sig = (l32 & ~12) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
+      const rsrc_t rsVq = rsrc_at(a.Vq, (long long)a.H * rq * DH * 2, 0);
+      const rsrc_t rsVk = rsrc_at(a.Vk, (long long)a.H * rk * DH * 2, 0);
+      const rsrc_t rsBq = rsrc_at(a.bq, a.bq ? (long long)D * 2 : 0, 0);
+      const int rowq = 32 * tq + sig, rowk = 32 * tk + sig;
+      f16v macc = zero16(), bacc = zero16();
 #pragma unroll
       for (int d0 = 0; d0 < DST; d0 += DSB) {
-        if (d0 > 0) __builtin_amdgcn_sched_barrier(0);
-        u4 vq_raw[NT][DSB], vk_raw[DSB], bq_raw[DSB];
+        u4 vq_raw[DSB], vk_raw[DSB], bq_raw[DSB];
 #pragma unroll
         for (int ds = 0; ds < DSB; ++ds) {
           const int dof = (16 * (d0 + ds) + 8 * g) * 2;
-          const int rowk = 32 * tk + sig;
           vk_raw[ds] = buf_load16(rsVk, rowk < rk ? (h * rk + rowk) * DH * 2 + dof : kOobOffset);
-          bq_raw[ds] = buf_load16(rsBq, col0 * 2 + dof);                             // zeros without a bias
-#pragma unroll
-          for (int tq = 0; tq < NT; ++tq) {
-            const int rowq = 32 * tq + sig;
-            vq_raw[tq][ds] = buf_load16(rsVq, rowq < rq ? (h * rq + rowq) * DH * 2 + dof : kOobOffset);
-          }
+          vq_raw[ds] = buf_load16(rsVq, rowq < rq ? (h * rq + rowq) * DH * 2 + dof : kOobOffset);
+          bq_raw[ds] = buf_load16(rsBq, tq == 0 ? col0 * 2 + dof : kOobOffset);      // zeros without a bias
         }
 #pragma unroll
         for (int ds = 0; ds < DSB; ++ds) {
           const h8 vk = raw_to_h8<WT>(vk_raw[ds]);
-          wacc = mfma32(vk, raw_to_h8<WT>(bq_raw[ds]), wacc);                      // b_q (V_k^h)^T, the same in every column
-#pragma unroll
-          for (int tq = 0; tq < NT; ++tq) macc[tq] = mfma32(raw_to_h8<WT>(vq_raw[tq][ds]), vk, macc[tq]);     // rows r_q, cols r_k
+          macc = mfma32(raw_to_h8<WT>(vq_raw[ds]), vk, macc);                        // rows r_q, cols r_k
+          if (tq == 0) bacc = mfma32(vk, raw_to_h8<WT>(bq_raw[ds]), bacc);           // rows r_k, every column the same
         }
-      }
-#pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        h8 mf;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) mf[i] = (_Float16)macc[s >> 1][8 * (s & 1) + i];
-        wacc = mfma32(mf, __builtin_bit_cast(h8, pq_raw[s]), wacc);                 // rows r_k, cols queries
       }
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        if (2 * tk + t < KS) {
+        if (2 * tq + t < KS) {
+          h8 mf;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) mf[i] = (_Float16)macc[8 * t + i];
+          mfl[(tk * KS + 2 * tq + t) * 64 + lane] = __builtin_bit_cast(u4, mf);
+        }
+      }
+      if (tq == 0) {
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+          f4v x;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) x[e] = bacc[4 * qd + e];
+          wbl[(tk * 4 + qd) * 64 + lane] = x;
+        }
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int tk2 = 0; tk2 < NT; ++tk2) {
+      f16v wacc;
+#pragma unroll
+      for (int qd = 0; qd < 4; ++qd) {
+        const f4v x = wbl[(tk2 * 4 + qd) * 64 + lane];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) wacc[4 * qd + e] = x[e];
+      }
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+        wacc = mfma32(__builtin_bit_cast(h8, mfl[(tk2 * KS + s) * 64 + lane]), __builtin_bit_cast(h8, pq_raw[s]), wacc);   // rows r_k, cols queries
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        if (2 * tk2 + t < KS) {
           h8 r;
 #pragma unroll
           for (int i = 0; i < 8; ++i) r[i] = (_Float16)(wacc[8 * t + i] * qs);
-          wq[2 * tk + t] = r;
+          wq[2 * tk2 + t] = r;
         }
       }
-      __builtin_amdgcn_sched_barrier(0);       // keep the next tile's operand requests behind this tile's products
     }
   }
 
