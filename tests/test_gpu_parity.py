@@ -677,6 +677,28 @@ def test_single_token_sequences(fb):
         assert rel_err(gpu_call(dev, part).cpu().numpy(), oracle_call(inp, part)) < tol_for(w, part) * 2
 
 
+@pytest.mark.parametrize("name", ["ph_tiny_r16", "ph_tiny_d128_r64"])
+def test_per_head_factors_edge_sequences(fb, name):
+    """The absorbed schedule on single-token sequences, on lengths that end one key into a tile or a step, with one
+    visible key, and with a causal mask on top of the padding."""
+    for M in (1, 33, 129):
+        w = W.get_workload(name, B=3, M=M, min_len=1)
+        inp, dev = _run_custom(fb, w)
+        for part in ("attention", "layer"):
+            ref = oracle_call(inp, part)
+            tol = attn_block_tol(w, ref) if part == "attention" else TOL_LAYER
+            assert rel_err(gpu_call(dev, part).cpu().numpy(), ref) < tol * (2 if M == 1 else 1)
+    w = W.get_workload(name, B=3, M=300, min_len=1)
+    def mut(inp):
+        inp["key_len"][:] = [1, 300, 129]
+        inp["causal"] = True
+    inp, dev = _run_custom(fb, w, mut)
+    got = gpu_call(dev, "attention").cpu().numpy()
+    ref = oracle_call(inp, "attention")
+    assert np.isfinite(got).all()
+    assert rel_err(got, ref) < max(attn_block_tol(w, ref), TOL["attention_causal"])
+
+
 def test_key_len_one_and_full(fb):
     w = W.get_workload("tiny_pad")
     def mut(inp):
