@@ -763,6 +763,38 @@ def test_per_head_factors_without_biases_and_with_a_caller_scale(fb, name):
     assert rel_err(got, ref) < attn_block_tol(w, ref)
 
 
+@pytest.mark.parametrize("name,weights", [("cfg1_bert_base_b2_m128", "tiled"), ("tiny_causal_d128", "row"),
+                                          ("ph_tiny_r48_causal", "row")])
+def test_layer_replays_from_a_hip_graph(fb, name, weights):
+    """The library only enqueues kernels on the caller's stream (no allocation, no memset, no host synchronisation), so
+    a layer call with a caller workspace can be captured into a HIP graph: every replay on new inputs in the same
+    buffers must equal the eager call on those inputs, with eager work and synchronisations between the replays."""
+    w, inp, dev = workload(name, fb, weights)
+    per_head = isinstance(dev["q"], fb.HeadFactor)
+    layer = fb.fsvd_layer_heads if per_head else fb.fsvd_layer
+    size = fb.fsvd_layer_heads_workspace if per_head else fb.fsvd_layer_workspace
+    ranks = [dev[n].rank for n in ("q", "k", "v", "o", "w1", "w2")]
+    ws = torch.empty(size(dev["desc"], *ranks), dtype=torch.uint8, device=DEV)
+    x = dev["X"].clone()
+    out = torch.empty(x.shape, dtype=torch.float32, device=DEV)
+    args = (dev["q"], dev["k"], dev["v"], dev["o"], dev["ln1_gamma"], dev["ln1_beta"], dev["w1"], dev["w2"],
+            dev["ln2_gamma"], dev["ln2_beta"])
+    layer(dev["desc"], x, *args, out=out, workspace=ws)            # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        layer(dev["desc"], x, *args, out=out, workspace=ws)
+    gen = torch.Generator(device=DEV).manual_seed(11)
+    for k in range(3):
+        x.copy_(torch.randn(x.shape, generator=gen, device=DEV).to(x.dtype))
+        want = layer(dev["desc"], x, *args)
+        torch.cuda.synchronize()
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), k
+
+
 @pytest.mark.parametrize("odt,eps", [(torch.float16, 2.0 ** -11), (torch.bfloat16, 2.0 ** -8)])
 def test_sixteen_bit_outputs_round_the_fp32_result(fb, odt, eps):
     w, inp, dev = workload("tiny_pad", fb)
