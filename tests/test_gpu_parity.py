@@ -334,6 +334,39 @@ def test_layer_with_grouped_head_factors_encoder_shapes(fb, name):
         assert rel_err(got[b:b + 1], oracle_call(one, "layer")) < TOL_LAYER
 
 
+def test_absorbed_and_rebuilding_schedules_agree_on_seeded_random_shapes(fb, monkeypatch):
+    """A sweep of seeded shapes (head count, head width, per-head rank, sequence length, mask, storage type) through both
+    schedules of the per-head core: the rank windows then straddle the 64-rank chunks of the concatenated axis in every
+    possible way and the sequences end at every position of a key tile and a key step.  The two kernels share no code
+    after the rank projections, so their agreement to the hand-off noise of two blocks is a check of both; every fourth
+    shape is also compared with the oracle."""
+    rng = np.random.default_rng(20250801)
+    for case in range(16):
+        d_h = int(rng.choice([64, 128]))
+        H = int(rng.integers(1, 7))
+        r = int(rng.choice([16, 32, 48, 64]))
+        M = int(rng.integers(1, 420))
+        B = int(rng.integers(1, 4))
+        mask = str(rng.choice(["none", "padding", "causal"]))
+        dtype = str(rng.choice(["fp16", "bf16"]))
+        w = W.Workload(name=f"sweep{case}", seed=9000 + case, B=B, M=M, D=H * d_h, H=H, F=2 * H * d_h, r_attn=32, r_ffn=32,
+                       dtype=dtype, mask=mask, min_len=1, r_head=r)
+        inp = W.make_inputs(w)
+        dev = fb.to_device(inp, DEV)
+        absorbed = gpu_call(dev, "attention").cpu().numpy()
+        monkeypatch.setenv("FSVD_ATTN_ABSORBED", "0")
+        rebuilt = gpu_call(dev, "attention").cpu().numpy()
+        monkeypatch.delenv("FSVD_ATTN_ABSORBED")
+        tag = (case, H, d_h, r, B, M, mask, dtype)
+        assert np.isfinite(absorbed).all() and np.isfinite(rebuilt).all(), tag
+        rms = float(np.sqrt(np.mean(rebuilt.astype(np.float64) ** 2)))
+        tol = 1.5 * max(TOL["attention_causal" if mask == "causal" else "attention"], 1.0e-3 / rms)
+        assert rel_err(absorbed, rebuilt) < tol, tag
+        if case % 4 == 0:
+            ref = oracle_call(inp, "attention")
+            assert rel_err(absorbed, ref) < max(attn_block_tol(w, ref), TOL["attention_causal"] if mask == "causal" else 0.0), tag
+
+
 @pytest.mark.parametrize("ranks", [(32, 16, 48), (16, 64, 32), (64, 48, 16)])
 @pytest.mark.parametrize("name", ["ph_tiny_d128_r64", "ph_bert_base_b16_m512_r64"])
 def test_per_head_factors_with_three_different_ranks(fb, name, ranks):
