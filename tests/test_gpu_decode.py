@@ -169,3 +169,43 @@ def test_decode_core_rank_space_context(fb):
         a = O.softmax_rows(s.T)
         ref = a @ Pv[b, :n].astype(np.float64)
         assert rel_err(got[b], ref) < 3e-3, b
+
+
+@pytest.mark.parametrize("case", ["one_long_rest_empty", "all_equal", "single_sequence", "sixty_four_ragged", "more_than_sixty_four",
+                                  "all_empty_but_last"])
+def test_decode_core_balanced_split_over_ragged_batches(fb, case):
+    """The pass over the cache deals its workgroups to the sequences in proportion to their key tiles (and falls back to
+    equal parts above 64 sequences): batches whose lengths are as uneven as they can be, against the plain softmax."""
+    rng = np.random.default_rng(sum(map(ord, case)))
+    H, D, r_k, r_v, t_max = 8, 512, 128, 96, 700
+    lens = {
+        "one_long_rest_empty": [700] + [0] * 15,
+        "all_equal": [333] * 8,
+        "single_sequence": [640],
+        "sixty_four_ragged": [int(x) for x in np.random.default_rng(5).integers(0, 701, size=64)],
+        "more_than_sixty_four": [int(x) for x in np.random.default_rng(6).integers(0, 701, size=80)],
+        "all_empty_but_last": [0] * 31 + [97],
+    }[case]
+    B = len(lens)
+    lens = np.array(lens, np.int32)
+    Pk = rng.standard_normal((B, t_max, r_k)).astype(np.float16)
+    Pv = rng.standard_normal((B, t_max, r_v)).astype(np.float16)
+    Wq = (rng.standard_normal((B, H, r_k)) * 0.15).astype(np.float16)
+    kc, vc = fb.fsvd_decode_new_caches(B, t_max, r_k, r_v, DEV)
+    zero = torch.zeros(B, dtype=torch.int32, device=DEV)
+    fb.fsvd_decode_cache_write(kc, 0, t_max, torch.from_numpy(Pk).to(DEV), zero)
+    fb.fsvd_decode_cache_write(vc, 1, t_max, torch.from_numpy(Pv).to(DEV), zero)
+    Wpad = np.zeros((B, 32, r_k), np.float16)
+    Wpad[:, :H] = Wq
+    Wfm = torch.cat([fb.fsvd_pack_fm(torch.from_numpy(Wpad[b]).to(DEV)) for b in range(B)])
+    d = fb.make_desc(B, t_max, D, H, 16, torch.float16)
+    got = fb.fsvd_decode_attention_core(d, r_k, r_v, Wfm, kc, vc, torch.from_numpy(lens).to(DEV)).cpu().numpy()
+    assert np.isfinite(got).all()
+    for b in range(B):
+        n = int(lens[b])
+        if n == 0:
+            assert not got[b].any(), b            # no keys: the context is zero
+            continue
+        s = Pk[b, :n].astype(np.float64) @ Wq[b].astype(np.float64).T * np.log(2.0)
+        ref = O.softmax_rows(s.T) @ Pv[b, :n].astype(np.float64)
+        assert rel_err(got[b], ref) < 6e-3, (case, b, n)      # the attention-block bound: probabilities and u are fp16 hand-offs
